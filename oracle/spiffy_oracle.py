@@ -1,0 +1,358 @@
+"""CPU oracle for the draft-graph verification step of Spiffy (arxiv 2509.18085).
+
+TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, fp64 definition of what the
+GPU library computes.  Only the tests, the smoke check and the benchmark's CPU-baseline
+leg may import it; the product (the HIP library and its Python binding) never does, and
+this file imports nothing from the product.  It shares no code, table or helper with
+the HIP path.
+
+Everything is written as the definition reads, one draft at a time, one head at a time,
+in float64 (inputs that are bf16 on the GPU arrive here as the same values widened).
+numpy's matrix product is used as a library step; there is no blocking, fusion, caching
+trick or reordering.
+
+What the paper fixes and where:
+  * batched verification = the model evaluated on (context ; one state of the block) for
+    the true state and every draft, all in one call                       Sec. 4.3, Eqs. (2),(3)
+  * a draft block attends to itself and to the true context, never to another draft or to
+    the block it drafts for; attention inside a block is bidirectional    Fig. 4 caption
+  * keys/values of everything before the block are cached and fixed       Sec. 3.1 (prefix caching)
+  * exactness holds with fixed context KV / blockwise-causal context      Sec. 4.3, App. A.2
+  * Next(X, p): per-position top-1 probability and token, unmask the chosen positions
+                                                                          Alg. 1 steps 1-4, App. A
+  * threshold rule: unmask every masked position whose top-1 probability exceeds tau
+                                                                          Sec. 3.1
+  * acceptance walk over children of the last accepted node               Alg. 1 step 5, Eqs. (4)-(6)
+  * the accepted draft's own distribution (same forward pass) yields the next state
+                                                                          App. A, case 2
+
+Readings taken where the paper is silent (architecture details are not in the paper at
+all; the shapes come from the workload configurations):
+  pre-norm RMSNorm with learnable gain, rotary embedding with rotate-half pairing
+  (i, i+hd/2) and angle pos * base^(-2i/hd), SwiGLU FFN, optional QKV bias, untied
+  embedding / vocabulary matrices; every one of the G blocks sits at positions
+  pos0 .. pos0+B-1; only still-masked positions may be unmasked; ties go to the lowest
+  index; the threshold comparison is strict ">" on the float32 value of the confidence;
+  if no masked position of a state exceeds tau and force_one is set, the single
+  highest-confidence masked position is unmasked (progress guarantee needed by Alg. 1).
+
+Pins (tests/test_oracle_pins.py): closed forms, rotary invariances, agreement of the
+cached formulation with a dense-mask single-sequence formulation (two independent
+formulations of Sec. 4.3), torch's CPU scaled-dot-product attention, brute-force
+enumeration of all walks on small graphs, and the losslessness theorem on a tiny model.
+No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+from typing import Callable, Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+F64 = np.float64
+
+
+# ----------------------------------------------------------------------------------------
+# elementwise pieces
+# ----------------------------------------------------------------------------------------
+
+def rms_norm(x: np.ndarray, gain: np.ndarray, eps: float) -> np.ndarray:
+    """Row-wise x / sqrt(mean(x^2) + eps) * gain."""
+    x = np.asarray(x, F64)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * np.asarray(gain, F64)
+
+
+def rope(x: np.ndarray, positions: np.ndarray, base: float) -> np.ndarray:
+    """Rotary embedding on the last axis (size hd) of x[..., T, hd]; positions[T].
+    Pair (i, i + hd/2) is rotated by angle pos * base^(-2 i / hd)."""
+    x = np.asarray(x, F64)
+    hd = x.shape[-1]
+    half = hd // 2
+    i = np.arange(half, dtype=F64)
+    inv_freq = base ** (-2.0 * i / hd)
+    ang = np.asarray(positions, F64)[:, None] * inv_freq[None, :]      # [T, half]
+    c, s = np.cos(ang), np.sin(ang)
+    x1, x2 = x[..., :half], x[..., half:]
+    return np.concatenate([x1 * c - x2 * s, x2 * c + x1 * s], axis=-1)
+
+
+def silu(z: np.ndarray) -> np.ndarray:
+    return z / (1.0 + np.exp(-z))
+
+
+def softmax_rows(s: np.ndarray) -> np.ndarray:
+    s = s - np.max(s, axis=-1, keepdims=True)
+    e = np.exp(s)
+    return e / np.sum(e, axis=-1, keepdims=True)
+
+
+def _w(d: Dict, k: str) -> Optional[np.ndarray]:
+    v = d.get(k)
+    return None if v is None else np.asarray(v, F64)
+
+
+# ----------------------------------------------------------------------------------------
+# O1: one transformer layer over G independent block states with a shared cached prefix
+# ----------------------------------------------------------------------------------------
+
+def verify_layer(w: Dict[str, np.ndarray], prefix_k: np.ndarray, prefix_v: np.ndarray,
+                 hidden_in: np.ndarray, *, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                 pos0: int, rms_eps: float = 1e-5, rope_base: float = 10000.0,
+                 return_kv: bool = False):
+    """hidden_in [G,B,d] -> hidden_out [G,B,d].
+
+    Each g is processed on its own (that independence is the attention mask of Fig. 4):
+    block rows attend to the P cached prefix keys followed by the B keys of their own
+    block, bidirectionally.  prefix_k / prefix_v are [Hkv, P, hd]; prefix_k is already
+    rotated at positions 0..P-1.  The block sits at positions pos0..pos0+B-1 for every g
+    (Sec. 4.3, "appropriate positional embeddings").
+    """
+    x_all = np.asarray(hidden_in, F64)
+    G, B, d = x_all.shape
+    Hq, Hkv, hd = n_q_heads, n_kv_heads, head_dim
+    rep = Hq // Hkv
+    pk, pv = np.asarray(prefix_k, F64), np.asarray(prefix_v, F64)
+    wq, wk, wv, wo = _w(w, "wq"), _w(w, "wk"), _w(w, "wv"), _w(w, "wo")
+    wg, wu, wd = _w(w, "w_gate"), _w(w, "w_up"), _w(w, "w_down")
+    bq, bk, bv = _w(w, "bq"), _w(w, "bk"), _w(w, "bv")
+    pos = pos0 + np.arange(B)
+    out = np.empty_like(x_all)
+    ks, vs = [], []
+    for g in range(G):
+        x = x_all[g]                                            # [B, d]
+        n = rms_norm(x, w["norm1"], rms_eps)
+        q = n @ wq.T
+        k = n @ wk.T
+        v = n @ wv.T
+        if bq is not None:
+            q = q + bq
+        if bk is not None:
+            k = k + bk
+        if bv is not None:
+            v = v + bv
+        q = rope(q.reshape(B, Hq, hd).transpose(1, 0, 2), pos, rope_base)    # [Hq,B,hd]
+        k = rope(k.reshape(B, Hkv, hd).transpose(1, 0, 2), pos, rope_base)   # [Hkv,B,hd]
+        v = v.reshape(B, Hkv, hd).transpose(1, 0, 2)
+        o = np.empty((B, Hq, hd), F64)
+        for h in range(Hq):
+            kvh = h // rep
+            keys = np.concatenate([pk[kvh], k[kvh]], axis=0)    # [P+B, hd]
+            vals = np.concatenate([pv[kvh], v[kvh]], axis=0)
+            s = (q[h] @ keys.T) / np.sqrt(float(hd))            # [B, P+B]
+            p = softmax_rows(s)
+            o[:, h, :] = p @ vals
+        h1 = x + o.reshape(B, Hq * hd) @ wo.T
+        n2 = rms_norm(h1, w["norm2"], rms_eps)
+        y = h1 + (silu(n2 @ wg.T) * (n2 @ wu.T)) @ wd.T
+        out[g] = y
+        ks.append(k)
+        vs.append(v)
+    if return_kv:
+        return out, np.stack(ks), np.stack(vs)
+    return out
+
+
+def embed(w_embed: np.ndarray, block_tokens: np.ndarray) -> np.ndarray:
+    """hidden[g,b,:] = W_emb[block_tokens[g,b], :]; masked positions carry the MASK id's row."""
+    return np.asarray(w_embed, F64)[np.asarray(block_tokens)]
+
+
+# ----------------------------------------------------------------------------------------
+# O2: LM head -> top-1 token, confidence, threshold-unmask decision, next state
+# ----------------------------------------------------------------------------------------
+
+def decode_head(hidden: np.ndarray, final_norm: np.ndarray, w_vocab: np.ndarray,
+                block_tokens: np.ndarray, mask_id: int, threshold: float, *,
+                rms_eps: float = 1e-5, logit_scale: float = 1.0, force_one: bool = True):
+    """Alg. 1 steps 1-4 with the threshold rule of Sec. 3.1, for every one of the G states.
+
+    Returns (argmax [G,B] int32, conf [G,B] float32, unmask [G,B] uint8,
+             margin [G,B] float64, target_states [G,B] int32).
+    At positions that are not masked: argmax = the token already there, conf = 0,
+    unmask = 0, margin = +inf (they never compete, they keep their token).
+    """
+    hid = np.asarray(hidden, F64)
+    G, B, d = hid.shape
+    tok = np.asarray(block_tokens)
+    wv = np.asarray(w_vocab, F64)
+    amax = tok.astype(np.int32).copy()
+    conf = np.zeros((G, B), np.float32)
+    unmask = np.zeros((G, B), np.uint8)
+    margin = np.full((G, B), np.inf, F64)
+    tau32 = np.float32(threshold)
+    for g in range(G):
+        for b in range(B):
+            if tok[g, b] != mask_id:
+                continue
+            n = rms_norm(hid[g, b], final_norm, rms_eps)
+            logits = logit_scale * (wv @ n)                     # [V]
+            j = int(np.argmax(logits))                          # lowest index on ties
+            p_top = 1.0 / np.sum(np.exp(logits - logits[j]))    # = max_v softmax(logits)_v
+            rest = np.delete(logits, j)
+            amax[g, b] = j
+            conf[g, b] = np.float32(p_top)
+            margin[g, b] = logits[j] - (np.max(rest) if rest.size else -np.inf)
+            unmask[g, b] = 1 if conf[g, b] > tau32 else 0
+        masked = np.nonzero(tok[g] == mask_id)[0]
+        if force_one and masked.size and not unmask[g, masked].any():
+            best = masked[int(np.argmax(conf[g, masked]))]      # lowest index on ties
+            unmask[g, best] = 1
+    target = np.where(unmask == 1, amax, tok).astype(np.int32)
+    return amax, conf, unmask, margin, target
+
+
+# ----------------------------------------------------------------------------------------
+# O3: acceptance walk over the draft graph
+# ----------------------------------------------------------------------------------------
+
+def graph_accept(edges: np.ndarray, draft_states: np.ndarray, target_states: np.ndarray,
+                 root: int = 0):
+    """Alg. 1 step 5.  Node ``root`` is the current true state; target_states[n] is
+    Next(state n, distribution computed for state n).  Starting at the root, move to a
+    child (by the given edge list only) whose draft state equals the current node's
+    target state in all B positions; repeat from there; stop when no child matches.
+    Several matching children are necessarily copies of one state: the lowest id is taken.
+
+    Returns (node, depth, n_steps, accepted_state[B]) with n_steps = depth + 1 decode
+    steps covered by this one forward pass.
+    """
+    e = np.asarray(edges).reshape(-1, 2)
+    ds, ts = np.asarray(draft_states), np.asarray(target_states)
+    G = ds.shape[0]
+    cur, depth = int(root), 0
+    seen = {cur}
+    while depth < G:
+        cand = sorted(int(c) for p, c in e
+                      if int(p) == cur and np.array_equal(ds[int(c)], ts[cur]))
+        cand = [c for c in cand if c not in seen]
+        if not cand:
+            break
+        cur = cand[0]
+        seen.add(cur)
+        depth += 1
+    return cur, depth, depth + 1, ts[cur].astype(np.int32).copy()
+
+
+# ----------------------------------------------------------------------------------------
+# whole step (all layers, head, walk)
+# ----------------------------------------------------------------------------------------
+
+def verify_step(layers: Sequence[Dict], prefix: Sequence[Tuple[np.ndarray, np.ndarray]],
+                w_embed, final_norm, w_vocab, block_tokens, edges, *, n_q_heads, n_kv_heads,
+                head_dim, pos0, mask_id, threshold, rms_eps=1e-5, rope_base=10000.0,
+                logit_scale=1.0, force_one=True, root=0):
+    h = embed(w_embed, block_tokens)
+    for w, (pk, pv) in zip(layers, prefix):
+        h = verify_layer(w, pk, pv, h, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
+                         head_dim=head_dim, pos0=pos0, rms_eps=rms_eps, rope_base=rope_base)
+    amax, conf, unmask, margin, target = decode_head(
+        h, final_norm, w_vocab, block_tokens, mask_id, threshold, rms_eps=rms_eps,
+        logit_scale=logit_scale, force_one=force_one)
+    node, depth, n_steps, state = graph_accept(edges, block_tokens, target, root)
+    return dict(hidden=h, argmax=amax, conf=conf, unmask=unmask, margin=margin,
+                target_states=target, node=node, depth=depth, n_steps=n_steps,
+                accepted_state=state)
+
+
+# ----------------------------------------------------------------------------------------
+# O4: second, independent formulation used only to pin O1: ONE token sequence, explicit
+# position ids, explicit dense boolean attention mask (the paper's own construction)
+# ----------------------------------------------------------------------------------------
+
+def masked_forward(layers: Sequence[Dict], x: np.ndarray, positions: np.ndarray,
+                   allow: np.ndarray, *, n_q_heads: int, n_kv_heads: int, head_dim: int,
+                   rms_eps: float = 1e-5, rope_base: float = 10000.0):
+    """Plain transformer over one sequence x[T,d] with position ids and a dense boolean
+    mask allow[T,T] (True = row may attend to column).  Returns (hidden per layer boundary
+    [L+1][T,d], rotated K per layer [L][Hkv,T,hd], V per layer)."""
+    x = np.asarray(x, F64)
+    T = x.shape[0]
+    Hq, Hkv, hd = n_q_heads, n_kv_heads, head_dim
+    rep = Hq // Hkv
+    hs, Ks, Vs = [x], [], []
+    for w in layers:
+        n = rms_norm(x, w["norm1"], rms_eps)
+        q = n @ _w(w, "wq").T
+        k = n @ _w(w, "wk").T
+        v = n @ _w(w, "wv").T
+        if w.get("bq") is not None:
+            q = q + _w(w, "bq")
+        if w.get("bk") is not None:
+            k = k + _w(w, "bk")
+        if w.get("bv") is not None:
+            v = v + _w(w, "bv")
+        q = rope(q.reshape(T, Hq, hd).transpose(1, 0, 2), positions, rope_base)
+        k = rope(k.reshape(T, Hkv, hd).transpose(1, 0, 2), positions, rope_base)
+        v = v.reshape(T, Hkv, hd).transpose(1, 0, 2)
+        o = np.empty((T, Hq, hd), F64)
+        for h in range(Hq):
+            s = (q[h] @ k[h // rep].T) / np.sqrt(float(hd))
+            s = np.where(allow, s, -np.inf)
+            o[:, h, :] = softmax_rows(s) @ v[h // rep]
+        h1 = x + o.reshape(T, Hq * hd) @ _w(w, "wo").T
+        n2 = rms_norm(h1, w["norm2"], rms_eps)
+        x = h1 + (silu(n2 @ _w(w, "w_gate").T) * (n2 @ _w(w, "w_up").T)) @ _w(w, "w_down").T
+        hs.append(x)
+        Ks.append(k)
+        Vs.append(v)
+    return hs, Ks, Vs
+
+
+def verification_mask(P: int, B: int, G: int) -> Tuple[np.ndarray, np.ndarray]:
+    """Dense mask and position ids of the single-sequence formulation
+    [prefix ; block_0 ; ... ; block_{G-1}] (Fig. 4 caption, with fixed prefix KV):
+    prefix rows see the prefix only; the rows of block g see the prefix and block g.
+    Every block reuses positions P..P+B-1."""
+    T = P + G * B
+    allow = np.zeros((T, T), bool)
+    allow[:P, :P] = True
+    for g in range(G):
+        r = slice(P + g * B, P + (g + 1) * B)
+        allow[r, :P] = True
+        allow[r, r] = True
+    pos = np.concatenate([np.arange(P)] + [P + np.arange(B)] * G)
+    return allow, pos
+
+
+# ----------------------------------------------------------------------------------------
+# block decode loops, used only for the losslessness pin (Theorem, App. A)
+# ----------------------------------------------------------------------------------------
+
+Drafter = Callable[[np.ndarray, Dict], Tuple[np.ndarray, np.ndarray]]
+
+
+def decode_block(model: Dict, block0: np.ndarray, *, drafter: Optional[Drafter] = None,
+                 max_steps: int = 1000):
+    """Decode one block to completion.  ``model`` holds layers, prefix, w_embed,
+    final_norm, w_vocab and the keyword settings of ``verify_step``.
+
+    drafter=None: vanilla loop, one forward per state (G=1, no edges).
+    drafter(state, info): returns (draft_states [D,B], edges [E,2] over nodes 0..D with
+    node 0 = the true state) to be verified together with the true state.
+
+    Returns (final_state, trajectory = list of states after every forward, NFE,
+             list of accepted depths, list of forwards saved per call).
+    An accepted draft that has no MASK left saves nothing (its next state is itself and
+    the vanilla loop would have stopped there too), so "saved" is the depth minus one in
+    that case; otherwise saved == depth.
+    """
+    kw = model["kw"]
+    state = np.asarray(block0, np.int32).copy()
+    traj, depths, saved, nfe = [state.copy()], [], [], 0
+    info: Dict = {}
+    while (state == kw["mask_id"]).any() and nfe < max_steps:
+        if drafter is None:
+            states, edges = state[None, :], np.zeros((0, 2), np.int32)
+        else:
+            dr, edges = drafter(state, info)
+            states = np.concatenate([state[None, :], np.asarray(dr, np.int32).reshape(-1, state.size)])
+        r = verify_step(model["layers"], model["prefix"], model["w_embed"], model["final_norm"],
+                        model["w_vocab"], states, edges, **kw)
+        nfe += 1
+        depths.append(r["depth"])
+        vacuous = r["depth"] > 0 and not (states[r["node"]] == kw["mask_id"]).any()
+        saved.append(r["depth"] - (1 if vacuous else 0))
+        state = r["accepted_state"]
+        info = r
+        traj.append(state.copy())
+    return state, traj, nfe, depths, saved

@@ -1,0 +1,600 @@
+"""Pins for the CPU oracle: what the paper and the mathematics fix, checked without a GPU.
+
+Each test is chosen so that a plausible mistake in oracle/spiffy_oracle.py (dropped term,
+wrong sign or index, transposed operand, wrong mask or position) fails at least one.
+"""
+import itertools
+import json
+import math
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import spiffy_oracle as O
+from paper_2509_18085_amd import synth
+from helpers import cfg_kw, np_weights, tiny_cfg, tiny_model, to_np
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def small_cfg(**kw):
+    base = dict(L=2, d=32, Hq=4, Hkv=2, hd=8, F=24, V=50, P=5, B=3, G=3)
+    base.update(kw)
+    return synth.CONFIGS["c1"].scaled(**base)
+
+
+def layer_np(cfg, layer=0, seed=7, bias=False, scale=10.0):
+    w = np_weights(synth.layer_weights(cfg, layer, seed, bias=bias))
+    for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+        w[k] = w[k] * scale          # make every term matter at these tiny widths
+    return w
+
+
+# ------------------------------------------------------------------ elementwise closed forms
+
+def test_rmsnorm_closed_form():
+    x = np.full((2, 16), 3.0)
+    g = np.linspace(0.5, 2.0, 16)
+    out = O.rms_norm(x, g, 1e-5)
+    np.testing.assert_allclose(out, 3.0 / math.sqrt(9.0 + 1e-5) * g[None, :].repeat(2, 0), rtol=1e-14)
+    # scale invariance up to eps, and sign kept
+    y = np.array([[1.0, -2.0, 2.0, 0.0]])
+    out = O.rms_norm(y, np.ones(4), 0.0)
+    np.testing.assert_allclose(out, y / 1.5, rtol=1e-14)
+
+
+def test_silu_values():
+    np.testing.assert_allclose(O.silu(np.array([0.0, 1.0, -1.0, 40.0])),
+                               [0.0, 0.7310585786300049, -0.2689414213699951, 40.0], rtol=1e-12)
+
+
+def test_softmax_rows_sum_to_one():
+    r = np.random.default_rng(0)
+    s = r.normal(size=(7, 33)) * 30
+    p = O.softmax_rows(s)
+    np.testing.assert_allclose(p.sum(-1), 1.0, rtol=1e-14)
+    assert (p >= 0).all()
+    np.testing.assert_allclose(O.softmax_rows(np.log(np.array([[1.0, 3.0]]))), [[0.25, 0.75]], rtol=1e-14)
+
+
+# ------------------------------------------------------------------ P3 rotary
+
+def test_rope_known_rotation_and_identity():
+    # hd = 2: a single pair rotated by angle pos * base^0 = pos
+    out = O.rope(np.array([[1.0, 0.0], [0.0, 1.0]]), np.array([1, 2]), 10000.0)
+    np.testing.assert_allclose(out[0], [math.cos(1), math.sin(1)], rtol=1e-14)
+    np.testing.assert_allclose(out[1], [-math.sin(2), math.cos(2)], rtol=1e-14)
+    # hd = 4: pair (0,2) uses angle pos, pair (1,3) uses pos * base^(-1/2)
+    x = np.array([[1.0, 1.0, 0.0, 0.0]])
+    out = O.rope(x, np.array([3]), 100.0)
+    np.testing.assert_allclose(out[0], [math.cos(3), math.cos(0.3), math.sin(3), math.sin(0.3)], rtol=1e-13)
+    x = np.random.default_rng(1).normal(size=(5, 16))
+    np.testing.assert_allclose(O.rope(x, np.zeros(5), 10000.0), x, rtol=0, atol=0)
+
+
+def test_rope_relative_and_norm():
+    r = np.random.default_rng(2)
+    q, k = r.normal(size=(1, 64)), r.normal(size=(1, 64))
+    def dot(m, n):
+        return float(O.rope(q, np.array([m]), 10000.0)[0] @ O.rope(k, np.array([n]), 10000.0)[0])
+    assert abs(dot(5, 2) - dot(103, 100)) < 1e-10
+    assert abs(dot(5, 2) - dot(2, 5)) > 1e-6
+    np.testing.assert_allclose(np.linalg.norm(O.rope(q, np.array([77]), 10000.0)), np.linalg.norm(q), rtol=1e-13)
+
+
+# ------------------------------------------------------------------ P2 closed forms for the layer
+
+def _identity_out_cfg():
+    return small_cfg(d=32, Hq=4, Hkv=2, hd=8)      # Hq*hd == d so Wo can be the identity
+
+
+def test_layer_zero_output_projections_is_identity():
+    cfg = small_cfg()
+    w = layer_np(cfg)
+    w["wo"][:] = 0
+    w["w_down"][:] = 0
+    pk, pv = (to_np(t) for t in synth.prefix_kv(cfg, 0, 3))
+    x = to_np(synth.hidden_states(cfg, 3))
+    out = O.verify_layer(w, pk, pv, x, **cfg_kw(cfg))
+    np.testing.assert_array_equal(out, x)
+
+
+def test_attention_equal_value_rows():
+    cfg = _identity_out_cfg()
+    w = layer_np(cfg, bias=True)
+    w["wo"] = np.eye(cfg.d)
+    w["w_down"][:] = 0
+    w["wv"][:] = 0
+    c = np.linspace(-1, 1, cfg.Hkv * cfg.hd)
+    w["bv"] = c
+    pk, _ = (to_np(t) for t in synth.prefix_kv(cfg, 0, 3))
+    pv = np.broadcast_to(c.reshape(cfg.Hkv, 1, cfg.hd), (cfg.Hkv, cfg.P, cfg.hd)).copy()
+    x = to_np(synth.hidden_states(cfg, 3))
+    out = O.verify_layer(w, pk, pv, x, **cfg_kw(cfg))
+    rep = cfg.Hq // cfg.Hkv
+    expect_o = np.concatenate([c.reshape(cfg.Hkv, cfg.hd)[h // rep] for h in range(cfg.Hq)])
+    np.testing.assert_allclose(out - x, np.broadcast_to(expect_o, out.shape), rtol=1e-12, atol=1e-13)
+
+
+def test_attention_zero_keys_gives_mean_of_values():
+    cfg = _identity_out_cfg()
+    w = layer_np(cfg)
+    w["wo"] = np.eye(cfg.d)
+    w["w_down"][:] = 0
+    w["wk"][:] = 0
+    _, pv = (to_np(t) for t in synth.prefix_kv(cfg, 0, 3))
+    pk = np.zeros_like(pv)
+    x = to_np(synth.hidden_states(cfg, 3))
+    out, k_blk, v_blk = O.verify_layer(w, pk, pv, x, return_kv=True, **cfg_kw(cfg))
+    rep = cfg.Hq // cfg.Hkv
+    for g in range(cfg.G):
+        n = O.rms_norm(x[g], w["norm1"], cfg.rms_eps)
+        v_own = (n @ w["wv"].T).reshape(cfg.B, cfg.Hkv, cfg.hd)
+        for h in range(cfg.Hq):
+            mean_v = (pv[h // rep].sum(0) + v_own[:, h // rep].sum(0)) / (cfg.P + cfg.B)
+            got = (out[g] - x[g])[:, h * cfg.hd:(h + 1) * cfg.hd]
+            np.testing.assert_allclose(got, np.broadcast_to(mean_v, got.shape), rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ P11 library attention
+
+@pytest.mark.parametrize("B,pos0", [(1, 0), (4, 9)])
+def test_attention_matches_torch_sdpa(B, pos0):
+    """The attention inside the layer is plain scaled-dot-product attention over
+    [prefix keys ; own block keys] (App. C names that routine).  Projections are redone
+    with torch linear algebra; for B>1 the rotary step is the oracle's own (pinned above)."""
+    cfg = _identity_out_cfg().scaled(B=B, G=2, P=6)
+    w = layer_np(cfg, bias=True)
+    w["wo"] = np.eye(cfg.d)
+    w["w_down"][:] = 0
+    pk, pv = (to_np(t) for t in synth.prefix_kv(cfg, 0, 5))
+    x = to_np(synth.hidden_states(cfg, 5))
+    kw = cfg_kw(cfg, pos0=pos0)
+    out = O.verify_layer(w, pk, pv, x, **kw)
+    rep = cfg.Hq // cfg.Hkv
+    T = torch.from_numpy
+    for g in range(cfg.G):
+        xt = T(x[g])
+        n = xt * torch.rsqrt((xt * xt).mean(-1, keepdim=True) + cfg.rms_eps) * T(w["norm1"])
+        q = (n @ T(w["wq"]).T + T(w["bq"])).reshape(B, cfg.Hq, cfg.hd).permute(1, 0, 2)
+        k = (n @ T(w["wk"]).T + T(w["bk"])).reshape(B, cfg.Hkv, cfg.hd).permute(1, 0, 2)
+        v = (n @ T(w["wv"]).T + T(w["bv"])).reshape(B, cfg.Hkv, cfg.hd).permute(1, 0, 2)
+        pos = pos0 + np.arange(B)
+        q = T(O.rope(q.numpy(), pos, cfg.rope_base))
+        k = T(O.rope(k.numpy(), pos, cfg.rope_base))
+        keys = torch.cat([T(pk), k], dim=1).repeat_interleave(rep, dim=0)
+        vals = torch.cat([T(pv), v], dim=1).repeat_interleave(rep, dim=0)
+        o = torch.nn.functional.scaled_dot_product_attention(q[None], keys[None], vals[None])[0]
+        o = o.permute(1, 0, 2).reshape(B, cfg.d).numpy()
+        np.testing.assert_allclose(out[g] - x[g], o, rtol=1e-10, atol=1e-12)
+
+
+# ------------------------------------------------------------------ brute force on tiny shapes
+
+def test_layer_scalar_brute_force():
+    """Every sum written out with Python scalars on a tiny shape (transposition / index pin)."""
+    cfg = small_cfg(d=8, Hq=2, Hkv=1, hd=4, F=6, P=3, B=2, G=2)
+    w = layer_np(cfg, bias=True)
+    pk, pv = (to_np(t) for t in synth.prefix_kv(cfg, 0, 11))
+    x = to_np(synth.hidden_states(cfg, 11))
+    out = O.verify_layer(w, pk, pv, x, **cfg_kw(cfg))
+    d, hd, Hq, F, P, B = cfg.d, cfg.hd, cfg.Hq, cfg.F, cfg.P, cfg.B
+
+    def norm(row, gain):
+        ms = sum(v * v for v in row) / len(row)
+        return [v / math.sqrt(ms + cfg.rms_eps) * gain[i] for i, v in enumerate(row)]
+
+    def lin(row, W, b=None):
+        return [sum(W[o][i] * row[i] for i in range(len(row))) + (0.0 if b is None else b[o])
+                for o in range(len(W))]
+
+    def rot(vec, pos):
+        half = hd // 2
+        r = list(vec)
+        for i in range(half):
+            a = pos * cfg.rope_base ** (-2.0 * i / hd)
+            r[i] = vec[i] * math.cos(a) - vec[i + half] * math.sin(a)
+            r[i + half] = vec[i + half] * math.cos(a) + vec[i] * math.sin(a)
+        return r
+
+    for g in range(cfg.G):
+        rows = [list(x[g, b]) for b in range(B)]
+        ns = [norm(r, w["norm1"]) for r in rows]
+        qs = [lin(n, w["wq"], w["bq"]) for n in ns]
+        ks = [rot(lin(n, w["wk"], w["bk"]), cfg.P + b) for b, n in enumerate(ns)]
+        vs = [lin(n, w["wv"], w["bv"]) for n in ns]
+        for b in range(B):
+            o = []
+            for h in range(Hq):
+                q = rot(qs[b][h * hd:(h + 1) * hd], cfg.P + b)
+                keys = [list(pk[0, p]) for p in range(P)] + ks
+                vals = [list(pv[0, p]) for p in range(P)] + vs
+                sc = [sum(q[i] * kk[i] for i in range(hd)) / math.sqrt(hd) for kk in keys]
+                m = max(sc)
+                e = [math.exp(s - m) for s in sc]
+                z = sum(e)
+                o += [sum(e[j] / z * vals[j][i] for j in range(P + B)) for i in range(hd)]
+            h1 = [rows[b][i] + v for i, v in enumerate(lin(o, w["wo"]))]
+            n2 = norm(h1, w["norm2"])
+            gate, up = lin(n2, w["w_gate"]), lin(n2, w["w_up"])
+            act = [gg / (1 + math.exp(-gg)) * uu for gg, uu in zip(gate, up)]
+            y = [h1[i] + v for i, v in enumerate(lin(act, w["w_down"]))]
+            np.testing.assert_allclose(out[g, b], y, rtol=1e-11, atol=1e-13)
+
+
+# ------------------------------------------------------------------ P4 / P5 / P6 formulations
+
+def _tokens_model(cfg, seed=21, scale=8.0):
+    layers = [layer_np(cfg, l, seed, scale=scale) for l in range(cfg.L)]
+    w_embed = to_np(synth.embed_weights(cfg, seed)) * 50.0
+    return layers, w_embed
+
+
+def test_prefix_cache_equals_full_recomputation():
+    """Block rows of a full forward over [prefix ; block] (prefix rows attend to the prefix
+    only) equal the cached formulation fed with that forward's prefix K/V (Sec. 3.1 prefix
+    caching, App. A.2 exactness condition)."""
+    cfg = small_cfg(P=6, B=4, G=1)
+    layers, w_embed = _tokens_model(cfg)
+    r = np.random.default_rng(5)
+    prefix_tok = r.integers(0, cfg.V - 1, cfg.P)
+    block = synth.random_states(1, cfg.B, cfg.V, 0.5, 0.5, 9)[0]
+    x = w_embed[np.concatenate([prefix_tok, block])]
+    T = cfg.P + cfg.B
+    allow = np.ones((T, T), bool)
+    allow[:cfg.P, cfg.P:] = False
+    kw = dict(n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, rms_eps=cfg.rms_eps,
+              rope_base=cfg.rope_base)
+    hs, Ks, Vs = O.masked_forward(layers, x, np.arange(T), allow, **kw)
+    h = O.embed(w_embed, block[None, :])
+    for l, w in enumerate(layers):
+        h = O.verify_layer(w, Ks[l][:, :cfg.P], Vs[l][:, :cfg.P], h, pos0=cfg.P, **kw)
+        np.testing.assert_allclose(h[0], hs[l + 1][cfg.P:], rtol=1e-10, atol=1e-12)
+    # and a wrong pos0 must break it (positions are pinned, not just the mask)
+    h_bad = O.verify_layer(layers[0], Ks[0][:, :cfg.P], Vs[0][:, :cfg.P],
+                           O.embed(w_embed, block[None, :]), pos0=cfg.P + 1, **kw)
+    assert np.abs(h_bad[0] - hs[1][cfg.P:]).max() > 1e-6
+
+
+def test_one_call_equals_many_calls_and_draft_independence():
+    """The single-sequence dense-mask formulation (Sec. 4.3, Fig. 4) gives, for block g, what
+    a G=1 call on draft g gives; changing / permuting the other drafts changes nothing and
+    duplicates are equal."""
+    cfg = small_cfg(P=5, B=3, G=4)
+    layers, w_embed = _tokens_model(cfg)
+    r = np.random.default_rng(6)
+    prefix_tok = r.integers(0, cfg.V - 1, cfg.P)
+    states = synth.random_states(cfg.G, cfg.B, cfg.V, 0.3, 0.7, 10)
+    states[3] = states[1]                                  # a duplicate draft
+    kw = dict(n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, rms_eps=cfg.rms_eps,
+              rope_base=cfg.rope_base)
+    # prefix KV from a prefix-only forward
+    xp = w_embed[prefix_tok]
+    _, Kp, Vp = O.masked_forward(layers, xp, np.arange(cfg.P), np.ones((cfg.P, cfg.P), bool), **kw)
+    allow, pos = O.verification_mask(cfg.P, cfg.B, cfg.G)
+    x = w_embed[np.concatenate([prefix_tok, states.reshape(-1)])]
+    hs, _, _ = O.masked_forward(layers, x, pos, allow, **kw)
+    h_all = O.embed(w_embed, states)
+    singles = [O.embed(w_embed, states[g:g + 1]) for g in range(cfg.G)]
+    for l, w in enumerate(layers):
+        h_all = O.verify_layer(w, Kp[l], Vp[l], h_all, pos0=cfg.P, **kw)
+        singles = [O.verify_layer(w, Kp[l], Vp[l], s, pos0=cfg.P, **kw) for s in singles]
+    final = hs[-1][cfg.P:].reshape(cfg.G, cfg.B, cfg.d)
+    for g in range(cfg.G):
+        np.testing.assert_allclose(singles[g][0], final[g], rtol=1e-10, atol=1e-12)
+        np.testing.assert_array_equal(h_all[g], singles[g][0])
+    np.testing.assert_array_equal(h_all[1], h_all[3])
+    perm = [2, 0, 3, 1]
+    h_perm = O.embed(w_embed, states[perm])
+    for l, w in enumerate(layers):
+        h_perm = O.verify_layer(w, Kp[l], Vp[l], h_perm, pos0=cfg.P, **kw)
+    np.testing.assert_array_equal(h_perm, h_all[perm])
+    # the mask really isolates drafts: letting block 0 see block 1 changes block 0
+    leaky = allow.copy()
+    leaky[cfg.P:cfg.P + cfg.B, cfg.P + cfg.B:cfg.P + 2 * cfg.B] = True
+    hs_leak, _, _ = O.masked_forward(layers, x, pos, leaky, **kw)
+    assert np.abs(hs_leak[-1][cfg.P:cfg.P + cfg.B] - final[0]).max() > 1e-6
+
+
+# ------------------------------------------------------------------ head closed forms (P1, P2, P12)
+
+def _head_inputs(G=2, B=4, d=16, V=40, seed=0):
+    r = np.random.default_rng(seed)
+    hid = r.normal(size=(G, B, d))
+    tok = r.integers(0, V - 1, size=(G, B)).astype(np.int32)
+    tok[:, ::2] = V - 1
+    return hid, tok, np.ones(d) + 0.1 * r.normal(size=d), r.normal(size=(V, d))
+
+
+def test_head_zero_weights_uniform():
+    hid, tok, gn, wv = _head_inputs()
+    V = wv.shape[0]
+    amax, conf, unmask, margin, tgt = O.decode_head(hid, gn, np.zeros_like(wv), tok, V - 1, 0.9,
+                                                    force_one=False)
+    m = tok == V - 1
+    assert (amax[m] == 0).all()
+    np.testing.assert_allclose(conf[m], 1.0 / V, rtol=1e-6)
+    assert (margin[m] == 0).all() and not unmask.any()
+    np.testing.assert_array_equal(tgt, tok)
+    # sentinels at unmasked positions
+    assert (amax[~m] == tok[~m]).all() and (conf[~m] == 0).all() and np.isinf(margin[~m]).all()
+
+
+def test_head_planted_one_hot_logit():
+    hid, tok, gn, wv = _head_inputs()
+    V, d = wv.shape
+    a = 7.5
+    g, b, j = 1, 2, 13
+    n = O.rms_norm(hid[g, b], gn, 1e-5)
+    W = np.zeros((V, d))
+    W[j] = a * n / (n @ n)
+    amax, conf, unmask, margin, tgt = O.decode_head(hid, gn, W, tok, V - 1, 0.9, force_one=False)
+    assert amax[g, b] == j
+    expect = 1.0 / (1.0 + (V - 1) * math.exp(-a))
+    np.testing.assert_allclose(conf[g, b], expect, rtol=1e-6)
+    np.testing.assert_allclose(margin[g, b], a, rtol=1e-12)
+    assert unmask[g, b] == (1 if np.float32(expect) > np.float32(0.9) else 0) == 1
+    assert tgt[g, b] == j
+    # logit_scale multiplies the logits
+    _, conf2, *_ = O.decode_head(hid, gn, W, tok, V - 1, 0.9, logit_scale=0.5, force_one=False)
+    np.testing.assert_allclose(conf2[g, b], 1.0 / (1.0 + (V - 1) * math.exp(-a / 2)), rtol=1e-6)
+
+
+def test_head_matches_torch_softmax_and_bounds():
+    hid, tok, gn, wv = _head_inputs(G=3, B=6, d=24, V=97, seed=3)
+    V = wv.shape[0]
+    amax, conf, unmask, margin, tgt = O.decode_head(hid, gn, wv, tok, V - 1, 0.05, force_one=False)
+    T = torch.from_numpy
+    x = T(hid)
+    n = x * torch.rsqrt((x * x).mean(-1, keepdim=True) + 1e-5) * T(gn)
+    p = torch.softmax(n @ T(wv).T, dim=-1)
+    top, idx = p.max(-1)
+    m = tok == V - 1
+    np.testing.assert_array_equal(amax[m], idx.numpy()[m])
+    np.testing.assert_allclose(conf[m], top.numpy()[m], rtol=1e-6)
+    assert (conf[m] >= 1.0 / V - 1e-9).all() and (conf[m] <= 1.0).all()
+    np.testing.assert_array_equal(unmask[m], (conf[m] > np.float32(0.05)).astype(np.uint8))
+    top2 = torch.topk(n @ T(wv).T, 2, dim=-1).values
+    np.testing.assert_allclose(margin[m], (top2[..., 0] - top2[..., 1]).numpy()[m], rtol=1e-9)
+
+
+def test_head_threshold_strict_force_one_and_monotone():
+    hid, tok, gn, wv = _head_inputs(G=3, B=6, d=24, V=97, seed=4)
+    V = wv.shape[0]
+    _, conf, *_ = O.decode_head(hid, gn, wv, tok, V - 1, 0.0, logit_scale=3.0, force_one=False)
+    m = tok == V - 1
+    # strict ">": a threshold equal to a confidence does not unmask that position
+    c = float(conf[0][m[0]].max())
+    _, _, um, _, _ = O.decode_head(hid, gn, wv, tok, V - 1, c, logit_scale=3.0, force_one=False)
+    assert um[0].sum() == 0
+    # force_one: exactly the highest-confidence masked position of each state
+    _, _, um1, _, tgt = O.decode_head(hid, gn, wv, tok, V - 1, 1.0, logit_scale=3.0, force_one=True)
+    for g in range(3):
+        assert um1[g].sum() == 1
+        cg = np.where(m[g], conf[g], -1)
+        assert um1[g, int(np.argmax(cg))] == 1
+        assert (tgt[g] != tok[g]).sum() <= 1
+    # raising tau never unmasks more
+    prev = None
+    for tau in (0.0, 0.01, 0.05, 0.2, 0.5, 0.9):
+        _, _, um, _, _ = O.decode_head(hid, gn, wv, tok, V - 1, tau, logit_scale=3.0, force_one=False)
+        assert (um[~m] == 0).all()
+        if prev is not None:
+            assert ((um == 1) <= (prev == 1)).all()
+        prev = um
+
+
+# ------------------------------------------------------------------ P7 / P8 acceptance walk
+
+def test_accept_golden_cases():
+    """Hand-derived walks (tests/golden/accept_cases.json; each case cites the passage)."""
+    with open(os.path.join(GOLDEN, "accept_cases.json")) as f:
+        cases = json.load(f)["cases"]
+    assert len(cases) >= 6
+    for c in cases:
+        node, depth, n_steps, state = O.graph_accept(
+            np.asarray(c["edges"], np.int32).reshape(-1, 2), np.asarray(c["draft_states"]),
+            np.asarray(c["target_states"]), c.get("root", 0))
+        assert (node, depth, n_steps) == (c["node"], c["depth"], c["depth"] + 1), c["name"]
+        assert state.tolist() == c["accepted_state"], c["name"]
+
+
+def test_accept_g1_empty_graph():
+    ds = np.array([[5, 9, 9]])
+    ts = np.array([[5, 2, 9]])
+    node, depth, n_steps, state = O.graph_accept(np.zeros((0, 2), np.int32), ds, ts, 0)
+    assert (node, depth, n_steps) == (0, 0, 1) and state.tolist() == [5, 2, 9]
+
+
+def _brute_force_accept(G, edges, ds, ts, root):
+    """Deepest chain root=n0->n1->... with (n_i,n_{i+1}) an edge and ds[n_{i+1}] == ts[n_i],
+    enumerated over ALL node sequences without repetition."""
+    eset = {(int(p), int(c)) for p, c in edges}
+    best = (0, (root,))
+    others = [n for n in range(G) if n != root]
+    for k in range(1, G):
+        for seq in itertools.permutations(others, k):
+            chain = (root,) + seq
+            ok = all((chain[i], chain[i + 1]) in eset and np.array_equal(ds[chain[i + 1]], ts[chain[i]])
+                     for i in range(k))
+            if ok and k > best[0]:
+                best = (k, chain)
+    return best
+
+
+def test_accept_brute_force_small_graphs():
+    """Every DAG edge set on up to 4 nodes (node labels shuffled), tiny states with tokens in
+    {0,1,MASK}, all drafts distinct: at most one child can match at each step, so the walk is
+    THE maximal valid chain and must equal the one found by enumerating every node sequence."""
+    r = np.random.default_rng(12)
+    MASK = 2
+    n_checked = n_deep = 0
+    for G in (2, 3, 4, 5):
+        pairs = [(a, c) for a in range(G) for c in range(a + 1, G)]
+        edge_sets = range(1 << len(pairs)) if G < 5 else r.integers(0, 1 << len(pairs), 150)
+        for bits in edge_sets:
+            relabel = np.concatenate([[0], 1 + r.permutation(G - 1)])
+            edges = np.asarray([(relabel[a], relabel[c]) for i, (a, c) in enumerate(pairs)
+                                if (int(bits) >> i) & 1], np.int32).reshape(-1, 2)
+            for _ in range(4):
+                B = 3
+                ds = r.integers(0, 3, size=(G, B))
+                ts = ds.copy()
+                for g in range(G):
+                    for b in range(B):
+                        if ds[g, b] == MASK and r.random() < 0.7:
+                            ts[g, b] = r.integers(0, 2)
+                order = np.argsort(np.argsort(relabel))      # plant matches along edge direction
+                for g in range(G - 1):
+                    if r.random() < 0.7:
+                        ds[relabel[int(r.integers(g + 1, G))]] = ts[relabel[g]]
+                if len({tuple(x) for x in ds}) < G:
+                    continue
+                node, depth, n_steps, state = O.graph_accept(edges, ds, ts, 0)
+                bd, chain = _brute_force_accept(G, edges, ds, ts, 0)
+                assert (depth, node) == (bd, chain[-1]) and n_steps == depth + 1
+                np.testing.assert_array_equal(state, ts[node])
+                n_checked += 1
+                n_deep += depth >= 2
+    assert n_checked > 300 and n_deep > 10
+
+
+def test_accept_child_equal_to_target_always_accepted_non_child_never():
+    r = np.random.default_rng(13)
+    for _ in range(200):
+        G, B = int(r.integers(2, 7)), int(r.integers(1, 6))
+        ds = r.integers(0, 4, size=(G, B))
+        ts = r.integers(0, 4, size=(G, B))
+        c = int(r.integers(1, G))
+        ds[c] = ts[0]
+        for o in range(1, G):           # make every other draft differ from the root's target
+            if o != c:
+                ds[o] = ts[0]
+                ds[o, 0] = (ts[0, 0] + 1 + int(r.integers(0, 3))) % 5 + 10
+        ts[c] = ds[c]                   # nothing after c matches: ts[c] equals no other draft
+        ts[c, 0] = 99
+        node, depth, *_ = O.graph_accept(np.array([[0, c]]), ds, ts, 0)
+        assert (node, depth) == (c, 1)
+        # same states, but the edge is absent (or points the other way): never followed
+        other = np.array([[c, 0]] + [[0, o] for o in range(1, G) if o != c]).reshape(-1, 2)
+        node, depth, *_ = O.graph_accept(other, ds, ts, 0)
+        assert (node, depth) == (0, 0)
+
+
+def test_accept_depth_bounded_by_longest_path():
+    st, e, level = synth.grown_dag([3, 3, 3], 8, 50, 0.9, 1, 2, 5)
+    for depth in range(0, 5):
+        tgt, path = synth.planted_targets(st, e, 50, depth, 77 + depth)
+        node, d, n_steps, state = O.graph_accept(e, st, tgt, 0)
+        assert d == len(path) - 1 and node == path[-1] or np.array_equal(st[node], st[path[-1]])
+        assert d <= int(level.max())
+
+
+# ------------------------------------------------------------------ P9 losslessness (Theorem, App. A)
+
+def _is_subsequence(sub, full):
+    it = iter(full)
+    return all(any(np.array_equal(s, f) for f in it) for s in sub)
+
+
+def _oracle_lookahead_drafter(model, depth, width, seed):
+    """Drafts taken from the vanilla continuation (so some are accepted) mixed with random
+    wrong ones; the graph is built by the superset rule."""
+    kw = model["kw"]
+    r = np.random.default_rng(seed)
+
+    def drafter(state, info):
+        cur = state.copy()
+        drafts = []
+        for _ in range(depth):
+            if not (cur == kw["mask_id"]).any():
+                break
+            res = O.verify_step(model["layers"], model["prefix"], model["w_embed"], model["final_norm"],
+                                model["w_vocab"], cur[None, :], np.zeros((0, 2), np.int32), **kw)
+            cur = res["target_states"][0]
+            drafts.append(cur.copy())
+            for _ in range(width):
+                wrong = cur.copy()
+                pos = np.nonzero(state == kw["mask_id"])[0]
+                p = int(r.choice(pos))
+                wrong[p] = int(r.integers(0, kw["mask_id"]))
+                drafts.append(wrong)
+        if not drafts:
+            return np.zeros((0, state.size), np.int32), np.zeros((0, 2), np.int32)
+        if r.random() < 0.5 and len(drafts) > 1:       # sometimes drop the first true draft
+            drafts.pop(0)
+        allst = np.stack([state] + drafts)
+        return np.stack(drafts), synth.edges_by_superset(allst, kw["mask_id"])
+    return drafter
+
+
+def _random_drafter(model, n, seed):
+    kw = model["kw"]
+    r = np.random.default_rng(seed)
+
+    def drafter(state, info):
+        drafts = []
+        for _ in range(n):
+            dft = state.copy()
+            pos = np.nonzero(state == kw["mask_id"])[0]
+            k = int(r.integers(1, pos.size + 1))
+            for p in r.choice(pos, size=k, replace=False):
+                dft[p] = int(r.integers(0, kw["mask_id"]))
+            drafts.append(dft)
+        allst = np.stack([state] + drafts)
+        return np.stack(drafts), synth.edges_by_superset(allst, kw["mask_id"])
+    return drafter
+
+
+@pytest.mark.parametrize("logit_scale,threshold,force_one", [(1.0, 0.9, True), (20.0, 0.5, True),
+                                                             (30.0, 0.5, True)])
+def test_losslessness_on_tiny_model(logit_scale, threshold, force_one):
+    """Decoding a block with ANY draft graph gives the vanilla final block, a trajectory that
+    is a subsequence of the vanilla trajectory, and NFE_vanilla - NFE_spiffy = number of accepted drafts that still had a MASK."""
+    cfg = tiny_cfg(d=64, Hq=2, Hkv=2, hd=32, F=96, V=64, P=6, B=6, L=2)
+    model = tiny_model(cfg, seed=31, weight_std_scale=6.0, logit_scale=logit_scale,
+                       threshold=threshold, force_one=force_one)
+    block0 = np.full(cfg.B, cfg.mask_id, np.int32)
+    block0[2] = 7
+    final_v, traj_v, nfe_v, depths_v, _ = O.decode_block(model, block0)
+    assert not (final_v == cfg.mask_id).any() and sum(depths_v) == 0
+    assert nfe_v == len(traj_v) - 1
+    accepted_any = 0
+    for name, drafter in [("lookahead", _oracle_lookahead_drafter(model, 3, 1, 1)),
+                          ("lookahead_deep", _oracle_lookahead_drafter(model, 5, 0, 2)),
+                          ("random", _random_drafter(model, 4, 3))]:
+        final_s, traj_s, nfe_s, depths_s, saved_s = O.decode_block(model, block0, drafter=drafter)
+        np.testing.assert_array_equal(final_s, final_v, err_msg=name)
+        assert _is_subsequence(traj_s, traj_v), name
+        assert nfe_s <= nfe_v and nfe_v - nfe_s == sum(saved_s) <= sum(depths_s), name
+        accepted_any += sum(saved_s)
+    assert accepted_any > 0       # the speculative branch was really exercised
+
+
+def test_unmask_counts_vary_with_logit_scale():
+    """The synthetic knob really produces multi-token steps (so the pin above covers S_t > 1)."""
+    cfg = tiny_cfg(d=64, Hq=2, Hkv=2, hd=32, F=96, V=64, P=6, B=6, L=2)
+    model = tiny_model(cfg, seed=31, weight_std_scale=6.0, logit_scale=30.0, threshold=0.5)
+    block0 = np.full(cfg.B, cfg.mask_id, np.int32)
+    block0[2] = 7
+    _, traj, nfe, _, _ = O.decode_block(model, block0)
+    assert 1 < nfe < cfg.B - 1
+
+
+# ------------------------------------------------------------------ whole-step composition on config 1
+
+def test_config1_step_shapes_and_invariants():
+    cfg = synth.CONFIGS["c1"]
+    model = tiny_model(cfg)
+    states, edges = synth.draft_graph("c1", cfg)
+    assert states.shape == (cfg.G, cfg.B) and edges.shape[1] == 2 and len(edges) > 0
+    r = O.verify_step(model["layers"], model["prefix"], model["w_embed"], model["final_norm"],
+                      model["w_vocab"], states, edges, **model["kw"])
+    m = states == cfg.mask_id
+    assert r["hidden"].shape == (cfg.G, cfg.B, cfg.d)
+    assert ((r["conf"][m] >= 1.0 / cfg.V) & (r["conf"][m] <= 1.0)).all()
+    assert (r["unmask"].sum(1) >= (m.sum(1) > 0)).all()          # progress on every state
+    assert (r["target_states"][~m] == states[~m]).all()
+    assert 0 <= r["node"] < cfg.G and r["n_steps"] == r["depth"] + 1

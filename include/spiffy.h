@@ -1,0 +1,161 @@
+/*
+ * spiffy.h - C ABI of the MI355X (gfx950) draft-graph verification library.
+ *
+ * One verification step of Spiffy (arxiv 2509.18085): G states of one B-token block (node 0 is
+ * the current true state X_k(t), the others are draft blocks, Sec. 4.2) go through ONE forward
+ * pass (Sec. 4.3, Eqs. (2),(3)); each state attends to the shared cached context and to itself
+ * only (Fig. 4); every masked position is reduced to top-1 token, top-1 probability and the
+ * threshold-unmask decision (Alg. 1 steps 1-4, threshold rule of Sec. 3.1); then the draft graph
+ * (Eqs. (4)-(6)) is walked to the deepest accepted state (Alg. 1 step 5).
+ *
+ * Conventions for every call
+ *   - Kernel choice is by shape: bf16 with head_dim 128, d % 128 == 0, ffn % 64 == 0 runs the MFMA
+ *     kernels (LM head: d % 64 == 0, vocab % 128 == 0); anything else, and every shape when the
+ *     environment variable SPIFFY_FORCE_GENERIC=1 is set, runs shape-agnostic fp32-math kernels.
+ *   - All data pointers are DEVICE pointers owned by the caller unless a parameter says "host".
+ *     The library never frees or keeps them.  Structs (cfg, weights, prefix) are HOST structs
+ *     that hold device pointers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *     and return; they never synchronise and never allocate.  Scratch memory comes from the
+ *     caller: `workspace` of at least spiffy_workspace_bytes(...) bytes, 256-byte aligned.
+ *   - Matrices are row-major.  Weights are [out, in].  dtype (SPIFFY_BF16 / SPIFFY_F32) is the
+ *     storage type of weights, hidden states and KV; accumulation is fp32 in both cases.
+ *   - Outputs are fully overwritten; inputs are never modified; hidden_in == hidden_out is allowed.
+ *   - Errors are return codes; every argument check happens on the host before any launch, so
+ *     a failing call launches nothing.  Null required pointer, G<1, B<1, bad threshold, bad root
+ *     -> SPIFFY_EINVAL; unsupported shape -> SPIFFY_ESHAPE; pointer not 16-byte aligned ->
+ *     SPIFFY_EALIGN; workspace too small -> SPIFFY_EWORKSPACE; a failed launch -> SPIFFY_EDEVICE.
+ */
+#ifndef SPIFFY_H
+#define SPIFFY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SPIFFY_OK = 0,
+  SPIFFY_EINVAL = -1,
+  SPIFFY_ESHAPE = -2,
+  SPIFFY_EALIGN = -3,
+  SPIFFY_EWORKSPACE = -4,
+  SPIFFY_EDEVICE = -5
+} spiffy_status;
+
+enum { SPIFFY_BF16 = 0, SPIFFY_F32 = 1 };
+
+/* Limits checked by the host: G <= SPIFFY_MAX_G for the walk (one node per lane of a 64-wide
+ * wavefront, 64-bit child masks); rows G*B <= SPIFFY_MAX_ROWS. */
+#define SPIFFY_MAX_G 64
+#define SPIFFY_MAX_ROWS 16384
+
+typedef struct {
+  int32_t d;           /* model width */
+  int32_t n_q_heads;   /* query heads Hq */
+  int32_t n_kv_heads;  /* key/value heads Hkv, divides Hq */
+  int32_t head_dim;    /* hd, even, <= 256 */
+  int32_t ffn;         /* SwiGLU width F */
+  int32_t vocab;       /* V */
+  int32_t mask_id;     /* token id of MASK (Sec. 3.1) */
+  int32_t dtype;       /* SPIFFY_BF16 or SPIFFY_F32 */
+  float rms_eps;
+  float rope_base;
+} spiffy_model_cfg;
+
+/* One transformer layer.  wq [Hq*hd, d], wk/wv [Hkv*hd, d], wo [d, Hq*hd], w_gate/w_up [F, d],
+ * w_down [d, F], norm1/norm2 [d]; bq/bk/bv optional biases ([Hq*hd], [Hkv*hd], [Hkv*hd]),
+ * NULL = none. */
+typedef struct {
+  const void *wq, *wk, *wv, *wo;
+  const void *w_gate, *w_up, *w_down;
+  const void *norm1, *norm2;
+  const void *bq, *bk, *bv;
+} spiffy_layer_weights;
+
+/* Cached context of one layer (prefix caching, Sec. 3.1): k and v are each [Hkv, P, hd];
+ * k is already rotated at positions 0..P-1.  P may be 0 (then k, v may be NULL). */
+typedef struct {
+  const void *k, *v;
+  int32_t P;
+} spiffy_prefix_kv;
+
+/* Result of the walk: accepted node id, number of accepted drafts (depth), decode steps covered
+ * by this forward (depth+1), and a flag word (bit 0: an edge endpoint was outside [0,G) and
+ * that edge was ignored). */
+typedef struct {
+  int32_t node, depth, n_steps, flags;
+} spiffy_accept_result;
+
+const char *spiffy_status_str(int status);
+
+/* 1 if the cfg/B combination runs on the MFMA kernels, 0 if on the generic kernels, <0 = status. */
+int spiffy_uses_mfma(const spiffy_model_cfg *cfg, int32_t B);
+
+/* Bytes of caller-provided scratch needed by verify_layer / decode_head / verify_step for up to
+ * G states of B tokens and a prefix of up to P_max.  0 on invalid arguments. */
+size_t spiffy_workspace_bytes(const spiffy_model_cfg *cfg, int32_t G, int32_t B, int32_t P_max);
+
+/* Token embedding of the G states: hidden_out[g,b,:] = w_embed[block_tokens[g,b],:]; masked
+ * positions carry the MASK id's row (Sec. 3.1).  w_embed [V,d]; block_tokens [G,B] int32 with
+ * values in [0,V) (out-of-range ids are clamped); hidden_out [G,B,d]. */
+int spiffy_embed(const spiffy_model_cfg *cfg, const void *w_embed, const int32_t *block_tokens,
+                 int32_t G, int32_t B, void *hidden_out, void *stream);
+
+/* One transformer layer over the G states in one pass (Sec. 4.3; mask of Fig. 4 is implicit:
+ * the rows of state g attend to the P cached keys and to the B keys of state g, bidirectionally,
+ * and to nothing else).  pre-norm RMSNorm, QKV projection (+bias), rotary embedding at positions
+ * pos0..pos0+B-1 for every g (pos0 = P normally), attention, output projection + residual,
+ * RMSNorm, SwiGLU FFN + residual.  hidden_in, hidden_out [G,B,d]. */
+int spiffy_verify_layer(const spiffy_model_cfg *cfg, const spiffy_layer_weights *w,
+                        const spiffy_prefix_kv *prefix, const void *hidden_in, int32_t G, int32_t B,
+                        int32_t pos0, void *hidden_out, void *workspace, size_t workspace_bytes,
+                        void *stream);
+
+/* LM head reduced to decisions (Alg. 1 steps 1-4 with the threshold rule of Sec. 3.1), for all G
+ * states.  mask [G,B] uint8 (1 = masked) may be NULL, then mask = (block_tokens == cfg.mask_id).
+ * For every masked position: logits = logit_scale *
+ * RMSNorm(hidden) * w_vocab^T over the whole vocabulary, argmax = lowest-index top-1 token,
+ * conf = its softmax probability, top2_margin = top-1 logit minus second logit,
+ * unmask = conf > threshold (strict, fp32).  If force_one != 0 and a state has masked positions
+ * but none passes, its highest-conf masked position (lowest index on ties) is unmasked.
+ * target_states = Next(state): the state with its unmasked positions filled by argmax.
+ * At positions that are not masked: argmax = the token, conf = 0, unmask = 0, margin = +inf.
+ * Logits are never written to memory.  final_norm [d]; w_vocab [V,d];
+ * argmax/target_states [G,B] int32; conf/top2_margin [G,B] float; unmask [G,B] uint8.
+ * top2_margin and target_states may be NULL. */
+int spiffy_decode_head(const spiffy_model_cfg *cfg, const void *hidden, const void *final_norm,
+                       const void *w_vocab, const int32_t *block_tokens, const uint8_t *mask,
+                       int32_t G, int32_t B, float threshold, float logit_scale, int32_t force_one, int32_t *argmax,
+                       float *conf, uint8_t *unmask, float *top2_margin, int32_t *target_states,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/* Acceptance walk (Alg. 1 step 5).  graph_edges [E,2] int32 (parent, child), E >= 0;
+ * draft_states, target_states [G,B] int32; 0 <= root < G <= SPIFFY_MAX_G.  Starting at root, move
+ * to the lowest-id child (by the edge list only) whose draft state equals the current node's
+ * target state at all B positions; stop when none matches or a node would repeat.  result
+ * (device) receives the node, depth and n_steps; accepted_state [B] (device, may be NULL)
+ * receives target_states[node].  Edges with an endpoint outside [0,G) are ignored and flagged. */
+int spiffy_graph_accept(const int32_t *graph_edges, int32_t E, const int32_t *draft_states,
+                        const int32_t *target_states, int32_t G, int32_t B, int32_t root,
+                        spiffy_accept_result *result, int32_t *accepted_state, void *stream);
+
+/* The whole step on one stream with no host synchronisation: embed, n_layers x verify_layer,
+ * decode_head, graph_accept.  layers / prefix are HOST arrays of n_layers structs.
+ * hidden_out [G,B,d] receives the last layer's output (may be NULL: kept in the workspace). */
+int spiffy_verify_step(const spiffy_model_cfg *cfg, int32_t n_layers,
+                       const spiffy_layer_weights *layers, const spiffy_prefix_kv *prefix,
+                       const void *w_embed, const void *final_norm, const void *w_vocab,
+                       const int32_t *block_tokens, int32_t G, int32_t B, int32_t pos0,
+                       const int32_t *graph_edges, int32_t E, int32_t root, float threshold,
+                       float logit_scale, int32_t force_one, void *hidden_out, int32_t *argmax,
+                       float *conf, uint8_t *unmask, float *top2_margin, int32_t *target_states,
+                       spiffy_accept_result *result, int32_t *accepted_state, void *workspace,
+                       size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPIFFY_H */

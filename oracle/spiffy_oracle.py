@@ -181,11 +181,12 @@ def decode_head(hidden: np.ndarray, final_norm: np.ndarray, w_vocab: np.ndarray,
     margin = np.full((G, B), np.inf, F64)
     tau32 = np.float32(threshold)
     for g in range(G):
-        for b in range(B):
-            if tok[g, b] != mask_id:
-                continue
-            n = rms_norm(hid[g, b], final_norm, rms_eps)
-            logits = logit_scale * (wv @ n)                     # [V]
+        masked_pos = np.nonzero(tok[g] == mask_id)[0]
+        if masked_pos.size:
+            n = rms_norm(hid[g, masked_pos], final_norm, rms_eps)   # [n_masked, d]
+            logits_all = logit_scale * (n @ wv.T)                   # [n_masked, V], Alg. 1 step 1
+        for r, b in enumerate(masked_pos):
+            logits = logits_all[r]
             j = int(np.argmax(logits))                          # lowest index on ties
             p_top = 1.0 / np.sum(np.exp(logits - logits[j]))    # = max_v softmax(logits)_v
             rest = np.delete(logits, j)

@@ -1,0 +1,361 @@
+// C ABI of the verification library: argument checks, workspace carving, kernel selection by
+// shape, launch order.  No kernel lives here.  Every check runs before the first launch.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+
+#include "kernels.h"
+
+using namespace spiffy;
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline size_t esize(int dtype) { return dtype == SPIFFY_F32 ? 4 : 2; }
+
+bool force_generic() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = std::getenv("SPIFFY_FORCE_GENERIC");
+    v = (e && e[0] == '1') ? 1 : 0;
+  }
+  return v == 1;
+}
+
+int check_cfg(const spiffy_model_cfg* c) {
+  if (!c) return SPIFFY_EINVAL;
+  if (c->dtype != SPIFFY_BF16 && c->dtype != SPIFFY_F32) return SPIFFY_EINVAL;
+  if (c->d < 8 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 2 || c->ffn < 8 || c->vocab < 2)
+    return SPIFFY_EINVAL;
+  if (c->mask_id < 0 || c->mask_id >= c->vocab) return SPIFFY_EINVAL;
+  if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return SPIFFY_EINVAL;
+  if (c->n_q_heads % c->n_kv_heads != 0) return SPIFFY_ESHAPE;
+  if (c->head_dim % 8 != 0 || c->head_dim > 256) return SPIFFY_ESHAPE;
+  if (c->d % 8 != 0 || c->ffn % 8 != 0) return SPIFFY_ESHAPE;
+  return SPIFFY_OK;
+}
+
+int check_gb(int32_t G, int32_t B) {
+  if (G < 1 || B < 1) return SPIFFY_EINVAL;
+  if ((int64_t)G * B > SPIFFY_MAX_ROWS) return SPIFFY_ESHAPE;
+  return SPIFFY_OK;
+}
+
+bool layer_mfma(const spiffy_model_cfg* c) {
+  if (force_generic() || c->dtype != SPIFFY_BF16 || c->head_dim != 128) return false;
+  return c->d % 128 == 0 && c->ffn % 64 == 0;
+}
+bool head_mfma(const spiffy_model_cfg* c) {
+  if (force_generic() || c->dtype != SPIFFY_BF16) return false;
+  return c->d % 64 == 0 && c->vocab % 128 == 0;
+}
+
+// generic attention keeps all scores of one row in LDS
+size_t generic_attn_smem(const spiffy_model_cfg* c, int B, int P) {
+  const int hd = c->head_dim;
+  const int nchunk = 256 / hd > 0 ? 256 / hd : 1;
+  return sizeof(float) * ((size_t)hd + (size_t)B * hd + (size_t)(P + B) + (size_t)nchunk * hd);
+}
+constexpr size_t kMaxGenericSmem = 150 * 1024;
+
+struct Carve {
+  unsigned char* base;
+  size_t off;
+  explicit Carve(void* p) : base(reinterpret_cast<unsigned char*>(p)), off(0) {}
+  void* take(size_t bytes) {
+    void* r = base ? base + off : nullptr;
+    off += align_up(bytes, 256);
+    return r;
+  }
+};
+
+struct LayerWs {
+  void *n, *qkv, *attn, *h, *act, *attn_partial;
+  size_t bytes;
+};
+LayerWs carve_layer(const spiffy_model_cfg* c, int G, int B, int P, void* base) {
+  const size_t M = (size_t)G * B, es = esize(c->dtype);
+  const size_t qkv_cols = (size_t)(c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
+  Carve cv(base);
+  LayerWs w;
+  w.n = cv.take(M * c->d * es);
+  w.qkv = cv.take(M * qkv_cols * es);
+  w.attn = cv.take(M * (size_t)c->n_q_heads * c->head_dim * es);
+  w.h = cv.take(M * c->d * es);
+  w.act = cv.take(M * c->ffn * es);
+  w.attn_partial = cv.take(layer_mfma(c) ? mfma_attn_partial_bytes(G, B, c->n_q_heads, c->head_dim, P) : 0);
+  w.bytes = cv.off;
+  return w;
+}
+
+struct HeadWs {
+  int32_t *row_idx, *count;
+  void* nf;
+  TopPartial *part, *row_top;
+  int m_cap, n_part;
+  size_t bytes;
+};
+HeadWs carve_head(const spiffy_model_cfg* c, int G, int B, void* base) {
+  const int M = G * B;
+  Carve cv(base);
+  HeadWs w;
+  w.m_cap = (int)align_up((size_t)M, 128);
+  w.n_part = head_mfma(c) ? mfma_lmhead_partials_per_row(c->vocab) : 0;
+  w.row_idx = (int32_t*)cv.take(sizeof(int32_t) * w.m_cap);
+  w.count = (int32_t*)cv.take(sizeof(int32_t) * 4);
+  w.nf = cv.take((size_t)w.m_cap * c->d * esize(c->dtype));
+  w.part = (TopPartial*)cv.take(sizeof(TopPartial) * (size_t)w.n_part * w.m_cap);
+  w.row_top = (TopPartial*)cv.take(sizeof(TopPartial) * w.m_cap);
+  w.bytes = cv.off;
+  return w;
+}
+
+// layer and head scratch alias each other (used one after the other); the step adds a hidden
+// buffer and a next-state buffer in front.
+struct StepWs {
+  void* hidden;
+  int32_t* target;
+  void* rest;
+  size_t rest_bytes, bytes;
+};
+StepWs carve_step(const spiffy_model_cfg* c, int G, int B, int P, void* base) {
+  const size_t M = (size_t)G * B;
+  Carve cv(base);
+  StepWs w;
+  w.hidden = cv.take(M * c->d * esize(c->dtype));
+  w.target = (int32_t*)cv.take(sizeof(int32_t) * M);
+  const size_t lb = carve_layer(c, G, B, P, nullptr).bytes, hb = carve_head(c, G, B, nullptr).bytes;
+  w.rest_bytes = lb > hb ? lb : hb;
+  w.rest = cv.take(w.rest_bytes);
+  w.bytes = cv.off;
+  return w;
+}
+
+int dev(hipError_t e) { return e == hipSuccess ? SPIFFY_OK : SPIFFY_EDEVICE; }
+
+int check_layer_args(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const spiffy_prefix_kv* prefix,
+                     int32_t G, int32_t B) {
+  if (!w || !prefix) return SPIFFY_EINVAL;
+  if (!w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down || !w->norm1 || !w->norm2)
+    return SPIFFY_EINVAL;
+  if (prefix->P < 0 || (prefix->P > 0 && (!prefix->k || !prefix->v))) return SPIFFY_EINVAL;
+  const void* ptrs[] = {w->wq, w->wk, w->wv, w->wo, w->w_gate, w->w_up, w->w_down, w->norm1, w->norm2,
+                        w->bq, w->bk, w->bv, prefix->k, prefix->v};
+  for (const void* p : ptrs)
+    if (p && !aligned16(p)) return SPIFFY_EALIGN;
+  if (!layer_mfma(cfg) && generic_attn_smem(cfg, B, prefix->P) > kMaxGenericSmem) return SPIFFY_ESHAPE;
+  return SPIFFY_OK;
+}
+
+int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const spiffy_prefix_kv* prefix,
+              const void* hidden_in, int G, int B, int pos0, void* hidden_out, void* workspace, hipStream_t st) {
+  const int M = G * B, d = cfg->d, dt = cfg->dtype;
+  const int qd = cfg->n_q_heads * cfg->head_dim, kvd = cfg->n_kv_heads * cfg->head_dim;
+  const bool mf = layer_mfma(cfg);
+  const LayerWs ws = carve_layer(cfg, G, B, prefix->P, workspace);
+  int rc;
+  if ((rc = dev(launch_rmsnorm(dt, hidden_in, w->norm1, cfg->rms_eps, M, d, nullptr, nullptr, ws.n, st)))) return rc;
+
+  GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.A = ws.n; g.lda = d; g.M = M; g.K = d;
+  g.W[0] = w->wq; g.W[1] = w->wk; g.W[2] = w->wv;
+  g.bias[0] = w->bq; g.bias[1] = w->bk; g.bias[2] = w->bv;
+  g.Nseg[0] = qd; g.Nseg[1] = kvd; g.Nseg[2] = kvd;
+  g.N = qd + 2 * kvd; g.C = ws.qkv; g.ldc = g.N; g.scale = 1.f;
+  const bool mf_qkv = mf && mfma_gemm_supported(EPI_STORE, g);
+  if ((rc = dev(mf_qkv ? launch_gemm_mfma(EPI_STORE, g, st) : launch_gemm_generic(dt, EPI_STORE, g, st)))) return rc;
+
+  AttnArgs a;
+  a.qkv = ws.qkv; a.prefix_k = prefix->k; a.prefix_v = prefix->v; a.out = ws.attn; a.partial = ws.attn_partial;
+  a.G = G; a.B = B; a.Hq = cfg->n_q_heads; a.Hkv = cfg->n_kv_heads; a.hd = cfg->head_dim; a.P = prefix->P;
+  a.pos0 = pos0; a.rope_base = cfg->rope_base;
+  if ((rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st)))) return rc;
+
+  std::memset(&g, 0, sizeof(g));
+  g.A = ws.attn; g.lda = qd; g.M = M; g.K = qd; g.W[0] = w->wo; g.Nseg[0] = d; g.N = d;
+  g.C = ws.h; g.ldc = d; g.R = hidden_in; g.scale = 1.f;
+  if ((rc = dev(mf && mfma_gemm_supported(EPI_RESID, g) ? launch_gemm_mfma(EPI_RESID, g, st)
+                                                         : launch_gemm_generic(dt, EPI_RESID, g, st))))
+    return rc;
+
+  if ((rc = dev(launch_rmsnorm(dt, ws.h, w->norm2, cfg->rms_eps, M, d, nullptr, nullptr, ws.n, st)))) return rc;
+
+  std::memset(&g, 0, sizeof(g));
+  g.A = ws.n; g.lda = d; g.M = M; g.K = d; g.W[0] = w->w_gate; g.W[1] = w->w_up; g.N = cfg->ffn;
+  g.C = ws.act; g.ldc = cfg->ffn; g.scale = 1.f;
+  if ((rc = dev(mf && mfma_gemm_supported(EPI_SWIGLU, g) ? launch_gemm_mfma(EPI_SWIGLU, g, st)
+                                                          : launch_gemm_generic(dt, EPI_SWIGLU, g, st))))
+    return rc;
+
+  std::memset(&g, 0, sizeof(g));
+  g.A = ws.act; g.lda = cfg->ffn; g.M = M; g.K = cfg->ffn; g.W[0] = w->w_down; g.Nseg[0] = d; g.N = d;
+  g.C = hidden_out; g.ldc = d; g.R = ws.h; g.scale = 1.f;
+  return dev(mf && mfma_gemm_supported(EPI_RESID, g) ? launch_gemm_mfma(EPI_RESID, g, st)
+                                                      : launch_gemm_generic(dt, EPI_RESID, g, st));
+}
+
+int run_head(const spiffy_model_cfg* cfg, const void* hidden, const void* final_norm, const void* w_vocab,
+             const int32_t* tokens, const uint8_t* mask, int G, int B, float threshold, float logit_scale,
+             int force_one, int32_t* argmax, float* conf, uint8_t* unmask, float* margin, int32_t* target,
+             void* workspace, hipStream_t st) {
+  const int M = G * B, dt = cfg->dtype;
+  const HeadWs ws = carve_head(cfg, G, B, workspace);
+  int rc;
+  if ((rc = dev(launch_compact_rows(tokens, mask, cfg->mask_id, M, ws.row_idx, ws.count, st)))) return rc;
+  if ((rc = dev(launch_rmsnorm(dt, hidden, final_norm, cfg->rms_eps, M, cfg->d, ws.row_idx, ws.count, ws.nf, st))))
+    return rc;
+  if (head_mfma(cfg)) {
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A = ws.nf; g.lda = cfg->d; g.M = M; g.M_dev = ws.count; g.K = cfg->d;
+    g.W[0] = w_vocab; g.Nseg[0] = cfg->vocab; g.N = cfg->vocab;
+    g.C = ws.part; g.ldc = ws.m_cap; g.scale = logit_scale;
+    if ((rc = dev(launch_gemm_mfma(EPI_LMHEAD, g, st)))) return rc;
+    if ((rc = dev(launch_lmhead_combine(ws.part, ws.n_part, ws.m_cap, ws.count, M, ws.row_top, st)))) return rc;
+  } else {
+    if ((rc = dev(launch_lmhead_generic(dt, ws.nf, w_vocab, cfg->d, cfg->vocab, logit_scale, ws.count, M,
+                                        ws.row_top, st))))
+      return rc;
+  }
+  return dev(launch_head_finalize(ws.row_top, ws.row_idx, ws.count, tokens, mask, cfg->mask_id, G, B, threshold,
+                                  force_one, argmax, conf, unmask, margin, target, st));
+}
+
+int check_head_args(const spiffy_model_cfg* cfg, const void* hidden, const void* final_norm, const void* w_vocab,
+                    const int32_t* tokens, float threshold, float logit_scale, const int32_t* argmax,
+                    const float* conf, const uint8_t* unmask) {
+  if (!hidden || !final_norm || !w_vocab || !tokens || !argmax || !conf || !unmask) return SPIFFY_EINVAL;
+  if (!(threshold >= 0.f && threshold <= 1.f) || !(logit_scale > 0.f) || !std::isfinite(logit_scale))
+    return SPIFFY_EINVAL;
+  if (!aligned16(hidden) || !aligned16(final_norm) || !aligned16(w_vocab)) return SPIFFY_EALIGN;
+  if ((size_t)cfg->d * sizeof(float) > 64 * 1024 && !head_mfma(cfg)) return SPIFFY_ESHAPE;
+  return SPIFFY_OK;
+}
+
+int check_accept_args(const int32_t* edges, int32_t E, const int32_t* draft, const int32_t* target, int32_t G,
+                      int32_t B, int32_t root, const spiffy_accept_result* res) {
+  if (G < 1 || B < 1 || E < 0 || (E > 0 && !edges) || !draft || !target || !res) return SPIFFY_EINVAL;
+  if (root < 0 || root >= G) return SPIFFY_EINVAL;
+  if (G > SPIFFY_MAX_G) return SPIFFY_ESHAPE;
+  return SPIFFY_OK;
+}
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+const char* spiffy_status_str(int s) {
+  switch (s) {
+    case SPIFFY_OK: return "ok";
+    case SPIFFY_EINVAL: return "invalid argument";
+    case SPIFFY_ESHAPE: return "unsupported shape";
+    case SPIFFY_EALIGN: return "pointer not 16-byte aligned";
+    case SPIFFY_EWORKSPACE: return "workspace too small";
+    case SPIFFY_EDEVICE: return "device launch failed";
+    default: return "unknown status";
+  }
+}
+
+int spiffy_uses_mfma(const spiffy_model_cfg* cfg, int32_t B) {
+  int rc = check_cfg(cfg);
+  if (rc) return rc;
+  if (B < 1) return SPIFFY_EINVAL;
+  return layer_mfma(cfg) ? 1 : 0;
+}
+
+size_t spiffy_workspace_bytes(const spiffy_model_cfg* cfg, int32_t G, int32_t B, int32_t P_max) {
+  if (check_cfg(cfg) || check_gb(G, B) || P_max < 0) return 0;
+  return carve_step(cfg, G, B, P_max, nullptr).bytes;
+}
+
+int spiffy_embed(const spiffy_model_cfg* cfg, const void* w_embed, const int32_t* block_tokens, int32_t G,
+                 int32_t B, void* hidden_out, void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(G, B))) return rc;
+  if (!w_embed || !block_tokens || !hidden_out) return SPIFFY_EINVAL;
+  if (!aligned16(w_embed) || !aligned16(hidden_out)) return SPIFFY_EALIGN;
+  return dev(launch_embed(cfg->dtype, w_embed, block_tokens, G * B, cfg->d, cfg->vocab, hidden_out,
+                          (hipStream_t)stream));
+}
+
+int spiffy_verify_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const spiffy_prefix_kv* prefix,
+                        const void* hidden_in, int32_t G, int32_t B, int32_t pos0, void* hidden_out,
+                        void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(G, B))) return rc;
+  if (!hidden_in || !hidden_out || !workspace || pos0 < 0) return SPIFFY_EINVAL;
+  if ((rc = check_layer_args(cfg, w, prefix, G, B))) return rc;
+  if (!aligned16(hidden_in) || !aligned16(hidden_out) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SPIFFY_EALIGN;
+  if (workspace_bytes < carve_layer(cfg, G, B, prefix->P, nullptr).bytes) return SPIFFY_EWORKSPACE;
+  return run_layer(cfg, w, prefix, hidden_in, G, B, pos0, hidden_out, workspace, (hipStream_t)stream);
+}
+
+int spiffy_decode_head(const spiffy_model_cfg* cfg, const void* hidden, const void* final_norm, const void* w_vocab,
+                       const int32_t* block_tokens, const uint8_t* mask, int32_t G, int32_t B, float threshold,
+                       float logit_scale, int32_t force_one, int32_t* argmax, float* conf, uint8_t* unmask,
+                       float* top2_margin, int32_t* target_states, void* workspace, size_t workspace_bytes,
+                       void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(G, B))) return rc;
+  if (!workspace) return SPIFFY_EINVAL;
+  if ((rc = check_head_args(cfg, hidden, final_norm, w_vocab, block_tokens, threshold, logit_scale, argmax, conf,
+                            unmask)))
+    return rc;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPIFFY_EALIGN;
+  if (workspace_bytes < carve_head(cfg, G, B, nullptr).bytes) return SPIFFY_EWORKSPACE;
+  return run_head(cfg, hidden, final_norm, w_vocab, block_tokens, mask, G, B, threshold, logit_scale, force_one,
+                  argmax, conf, unmask, top2_margin, target_states, workspace, (hipStream_t)stream);
+}
+
+int spiffy_graph_accept(const int32_t* graph_edges, int32_t E, const int32_t* draft_states,
+                        const int32_t* target_states, int32_t G, int32_t B, int32_t root,
+                        spiffy_accept_result* result, int32_t* accepted_state, void* stream) {
+  int rc = check_accept_args(graph_edges, E, draft_states, target_states, G, B, root, result);
+  if (rc) return rc;
+  return dev(launch_graph_accept(graph_edges, E, draft_states, target_states, G, B, root, result, accepted_state,
+                                 (hipStream_t)stream));
+}
+
+int spiffy_verify_step(const spiffy_model_cfg* cfg, int32_t n_layers, const spiffy_layer_weights* layers,
+                       const spiffy_prefix_kv* prefix, const void* w_embed, const void* final_norm,
+                       const void* w_vocab, const int32_t* block_tokens, int32_t G, int32_t B, int32_t pos0,
+                       const int32_t* graph_edges, int32_t E, int32_t root, float threshold, float logit_scale,
+                       int32_t force_one, void* hidden_out, int32_t* argmax, float* conf, uint8_t* unmask,
+                       float* top2_margin, int32_t* target_states, spiffy_accept_result* result,
+                       int32_t* accepted_state, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(G, B))) return rc;
+  if (n_layers < 0 || (n_layers > 0 && (!layers || !prefix)) || !w_embed || !workspace || pos0 < 0)
+    return SPIFFY_EINVAL;
+  if (!aligned16(w_embed) || (hidden_out && !aligned16(hidden_out)) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SPIFFY_EALIGN;
+  int P_max = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if ((rc = check_layer_args(cfg, &layers[l], &prefix[l], G, B))) return rc;
+    if (prefix[l].P > P_max) P_max = prefix[l].P;
+  }
+  if ((rc = check_head_args(cfg, workspace, final_norm, w_vocab, block_tokens, threshold, logit_scale, argmax, conf,
+                            unmask)))
+    return rc;
+  const int32_t* tgt_probe = target_states ? target_states : reinterpret_cast<const int32_t*>(workspace);
+  if ((rc = check_accept_args(graph_edges, E, block_tokens, tgt_probe, G, B, root, result))) return rc;
+  const StepWs ws = carve_step(cfg, G, B, P_max, workspace);
+  if (workspace_bytes < ws.bytes) return SPIFFY_EWORKSPACE;
+
+  hipStream_t st = (hipStream_t)stream;
+  void* hid = hidden_out ? hidden_out : ws.hidden;
+  int32_t* tgt = target_states ? target_states : ws.target;
+  if ((rc = dev(launch_embed(cfg->dtype, w_embed, block_tokens, G * B, cfg->d, cfg->vocab, hid, st)))) return rc;
+  for (int l = 0; l < n_layers; ++l)
+    if ((rc = run_layer(cfg, &layers[l], &prefix[l], hid, G, B, pos0, hid, ws.rest, st))) return rc;
+  if ((rc = run_head(cfg, hid, final_norm, w_vocab, block_tokens, nullptr, G, B, threshold, logit_scale, force_one,
+                     argmax, conf, unmask, top2_margin, tgt, ws.rest, st)))
+    return rc;
+  return dev(launch_graph_accept(graph_edges, E, block_tokens, tgt, G, B, root, result, accepted_state, st));
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Launchers implemented by the kernel translation units; called only by api.hip.
+// Every launcher enqueues on `st` and returns hipGetLastError() of its launches.
+#pragma once
+#include "common.h"
+
+namespace spiffy {
+
+// ---- generic (any shape, T = float or bf16 storage, fp32 math) ---------------------------------
+hipError_t launch_embed(int dtype, const void* w_embed, const int32_t* tokens, int M, int d, int V,
+                        void* out, hipStream_t st);
+// out[r,:] = rmsnorm(x[src(r),:]) * gain, src(r) = row_idx ? row_idx[r] : r, rows r < *n_rows_dev
+// (or < M when n_rows_dev is NULL).
+hipError_t launch_rmsnorm(int dtype, const void* x, const void* gain, float eps, int M, int d,
+                          const int32_t* row_idx, const int32_t* n_rows_dev, void* out, hipStream_t st);
+hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs& a, hipStream_t st);
+
+struct AttnArgs {
+  const void* qkv;       // [M, (Hq+2Hkv)*hd]: q | k | v columns, not yet rotated
+  const void* prefix_k;  // [Hkv,P,hd]
+  const void* prefix_v;
+  void* out;             // [M, Hq*hd]
+  void* partial;         // MFMA path: split partials (fp32)
+  int G, B, Hq, Hkv, hd, P, pos0;
+  float rope_base;
+};
+hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t st);
+
+// masked-row list: row_idx[0..count) = flattened (g,b) with mask set, ascending; *count.
+hipError_t launch_compact_rows(const int32_t* tokens, const uint8_t* mask, int mask_id, int M,
+                               int32_t* row_idx, int32_t* count, hipStream_t st);
+// per compacted row r: summary over the whole vocabulary of scale * (n[r,:] . w_vocab[v,:])
+hipError_t launch_lmhead_generic(int dtype, const void* n, const void* w_vocab, int d, int V,
+                                 float scale, const int32_t* count, int M, TopPartial* row_top,
+                                 hipStream_t st);
+// merge n_part partials per row; part is [n_part][m_cap]
+hipError_t launch_lmhead_combine(const TopPartial* part, int n_part, int m_cap, const int32_t* count, int M,
+                                 TopPartial* row_top, hipStream_t st);
+// scatter row summaries to [G,B] outputs, apply threshold / force_one, build next states
+hipError_t launch_head_finalize(const TopPartial* row_top, const int32_t* row_idx, const int32_t* count,
+                                const int32_t* tokens, const uint8_t* mask, int mask_id, int G, int B,
+                                float threshold, int force_one, int32_t* argmax, float* conf,
+                                uint8_t* unmask, float* margin, int32_t* target, hipStream_t st);
+
+hipError_t launch_graph_accept(const int32_t* edges, int E, const int32_t* draft, const int32_t* target,
+                               int G, int B, int root, spiffy_accept_result* res, int32_t* state,
+                               hipStream_t st);
+
+// ---- MFMA (bf16, gfx950) -----------------------------------------------------------------------
+bool mfma_gemm_supported(int epi, const GemmArgs& a);
+hipError_t launch_gemm_mfma(int epi, const GemmArgs& a, hipStream_t st);
+int mfma_lmhead_partials_per_row(int V);  // partial summaries per row written by EPI_LMHEAD
+bool mfma_attn_supported(const AttnArgs& a);
+size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P);
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st);
+
+}  // namespace spiffy

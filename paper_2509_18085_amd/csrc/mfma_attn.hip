@@ -1,0 +1,418 @@
+// Shared-prefix block attention for gfx950 (bf16 MFMA, head_dim 128).
+//
+// Every one of the G states attends to the same P cached keys and to its own B keys only
+// (Fig. 4: a draft block sees the true context and itself; Sec. 3.1 prefix caching).  The mask is
+// never built: the prefix part is dense and shared, the own-block part is the block diagonal of
+// the (G*B) x (G*B) score matrix.
+//
+// Work split: one workgroup = (query head, 128 consecutive query rows, one split of the prefix).
+// A prefix K/V tile of 64 keys is staged in LDS once and used by all 128 query rows (4 states of
+// 32 tokens, or 32 states of 4); workgroups of the same head run next to each other on one XCD
+// so the tile comes from HBM once and from L2 afterwards.  The number of prefix splits depends on
+// P only, so a row's arithmetic does not depend on G.
+//
+// Per wavefront (32 query rows) everything is kept "query per lane":
+//   S^T = K Q^T    A operand = K rows from LDS, B operand = rotated, pre-scaled Q in registers
+//                  -> lane (q, half) holds 16 of the 32 keys of a sub-tile for its query q
+//   online softmax max / sum are reductions over the lane's own registers plus one xor-32 shuffle
+//   O^T = V^T P^T  A operand = V^T from a transposed LDS tile, B operand = P^T straight from the
+//                  S^T accumulators (no trip through LDS); the rescale factor is per lane.
+// Rotary embedding (positions pos0..pos0+B-1 for every state, Sec. 4.3) is applied to Q when it is
+// loaded and to the own-block K when it is staged; the cached prefix K arrives rotated.
+#include "kernels.h"
+
+namespace spiffy {
+
+namespace {
+
+constexpr int HD = 128;
+constexpr int KTILE = 64;
+constexpr int QTILE = 128;
+constexpr int KS_STRIDE = HD + 8;     // bf16 per K row in LDS (272 B: conflict-free 16-byte reads)
+constexpr int VT_STRIDE = KTILE + 4;  // bf16 per V^T row in LDS (136 B: conflict-free 8-byte reads)
+constexpr int KS_ELEMS = KTILE * KS_STRIDE;
+constexpr int VT_ELEMS = HD * VT_STRIDE;
+constexpr int BUF_ELEMS = KS_ELEMS + VT_ELEMS;
+constexpr int SPLIT_KEYS = 1024;
+constexpr size_t kAttnSmem = sizeof(bf16_t) * 2 * BUF_ELEMS;  // 69,632 B
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+struct KVRegs {
+  u32x4 k[4];
+  u32x4 v[4];
+};
+
+__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
+__device__ __forceinline__ u32x4 as_u32x4(bf16x8 x) { return __builtin_bit_cast(u32x4, x); }
+
+// prefix tile: keys key0..key0+63 of kv head (rows clamped to the last valid key)
+__device__ __forceinline__ void gload_prefix(KVRegs& r, const bf16_t* __restrict__ pk, const bf16_t* __restrict__ pv,
+                                             int key0, int key_last) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = threadIdx.x + 256 * i;
+    const int key = min(key0 + (c >> 4), key_last);
+    r.k[i] = *reinterpret_cast<const u32x4*>(pk + (size_t)key * HD + (c & 15) * 8);
+  }
+  const int kq = threadIdx.x >> 4, ho = threadIdx.x & 15;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int key = min(key0 + 4 * kq + i, key_last);
+    r.v[i] = *reinterpret_cast<const u32x4*>(pv + (size_t)key * HD + ho * 8);
+  }
+}
+__device__ __forceinline__ void lstore_k(const KVRegs& r, bf16_t* ks) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = threadIdx.x + 256 * i;
+    *reinterpret_cast<u32x4*>(ks + (c >> 4) * KS_STRIDE + (c & 15) * 8) = r.k[i];
+  }
+}
+// V arrives as 4 keys x 8 head-dim values per thread; LDS wants V^T[hd][key]
+__device__ __forceinline__ void lstore_vt(const KVRegs& r, bf16_t* vt) {
+  const int kq = threadIdx.x >> 4, ho = threadIdx.x & 15;
+  const bf16x8 r0 = as_bf16x8(r.v[0]), r1 = as_bf16x8(r.v[1]), r2 = as_bf16x8(r.v[2]), r3 = as_bf16x8(r.v[3]);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    bf16x4 t;
+    t[0] = r0[e]; t[1] = r1[e]; t[2] = r2[e]; t[3] = r3[e];
+    *reinterpret_cast<bf16x4*>(vt + (ho * 8 + e) * VT_STRIDE + 4 * kq) = t;
+  }
+}
+
+struct WaveState {
+  bf16x8 qf[8];     // rotated, scaled Q^T fragments: hd = 16*kk + 8*half + e
+  f32x16 o[4];      // O^T accumulators: hd = 32*n + 8*(v/4) + 4*half + v%4, query = lane%32
+  float m_run, l_run;
+};
+
+// One 64-key tile against the wave's 32 queries.  `valid(key_in_tile)` masks keys (only called
+// when MASKED).  Scores are in the log2 domain (Q carries log2(e)/sqrt(hd)).
+template <bool MASKED, typename ValidFn>
+__device__ __forceinline__ void process_tile(WaveState& w, const bf16_t* __restrict__ ks, const bf16_t* __restrict__ vt,
+                                             int l32, int hh, ValidFn valid) {
+  f32x16 s[2];
+#pragma unroll
+  for (int st = 0; st < 2; ++st) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) s[st][v] = 0.f;
+    const bf16_t* kp = ks + (st * 32 + l32) * KS_STRIDE + hh * 8;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + kk * 16);
+      s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[kk], s[st], 0, 0, 0);
+    }
+  }
+  float tmax = -INFINITY;
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      if (MASKED) {
+        const int key = st * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+        if (!valid(key)) s[st][v] = -INFINITY;
+      }
+      tmax = fmaxf(tmax, s[st][v]);
+    }
+  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+  const float m_new = fmaxf(w.m_run, tmax);
+  const float alpha = (w.m_run == -INFINITY) ? 0.f : exp2f(w.m_run - m_new);
+  const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
+  bf16x8 pf[2][2];
+  float psum = 0.f;
+#pragma unroll
+  for (int st = 0; st < 2; ++st)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const bf16_t pb = static_cast<bf16_t>(exp2f(s[st][v] - m_safe));
+      psum += static_cast<float>(pb);
+      pf[st][v >> 3][v & 7] = pb;
+    }
+  w.l_run = w.l_run * alpha + psum;
+  w.m_run = m_new;
+#pragma unroll
+  for (int n = 0; n < 4; ++n) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) w.o[n][v] *= alpha;
+    const bf16_t* vp = vt + (n * 32 + l32) * VT_STRIDE + 4 * hh;
+#pragma unroll
+    for (int st = 0; st < 2; ++st)
+#pragma unroll
+      for (int k2 = 0; k2 < 2; ++k2) {
+        const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vp + st * 32 + 16 * k2);
+        const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vp + st * 32 + 16 * k2 + 8);
+        bf16x8 vf;
+        vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
+        vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
+        w.o[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[st][k2], w.o[n], 0, 0, 0);
+      }
+  }
+}
+
+struct AttnKArgs {
+  const bf16_t* qkv;
+  const bf16_t* pk;
+  const bf16_t* pv;
+  const float2* rope;   // [B][64] (cos, sin) of angle (pos0+b) * base^(-2f/128)
+  bf16_t* out;
+  float* opart;         // [nS][M][Hq][128]
+  float* mlpart;        // [nS][M][Hq][2]
+  int M, B, Hq, Hkv, P, ld, nQ, nS;
+};
+
+__global__ __launch_bounds__(256) void attn_prefix_mfma_kernel(AttnKArgs a) {
+  extern __shared__ __align__(16) unsigned char smem_raw[];
+  bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
+
+  const int total = a.nQ * a.nS * a.Hq;
+  int L = blockIdx.x;
+  if ((total & 7) == 0) L = (blockIdx.x >> 3) + (blockIdx.x & 7) * (total >> 3);
+  const int qt = L % a.nQ;
+  const int sp = (L / a.nQ) % a.nS;
+  const int h = L / (a.nQ * a.nS);
+  const int kvh = h / (a.Hq / a.Hkv);
+
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int l32 = lane & 31, hh = lane >> 5;
+  const int m0 = qt * QTILE;
+  const int m0w = m0 + wave * 32;
+  const int qrow = min(m0w + l32, a.M - 1);
+
+  WaveState w;
+  w.m_run = -INFINITY;
+  w.l_run = 0.f;
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) w.o[n][v] = 0.f;
+
+  // ---- Q: load, rotate at position pos0 + (row % B), scale, round to bf16 ------------------
+  {
+    const bf16_t* qp = a.qkv + (size_t)qrow * a.ld + h * HD + hh * 8;
+    const float2* rp = a.rope + (size_t)(qrow % a.B) * 64 + hh * 8;
+    const float qscale = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
+      const bf16x8 x2 = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + 64);
+      bf16x8 y1, y2;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float2 cs = rp[kk * 16 + e];
+        const float a1 = static_cast<float>(x1[e]), a2 = static_cast<float>(x2[e]);
+        y1[e] = static_cast<bf16_t>((a1 * cs.x - a2 * cs.y) * qscale);
+        y2[e] = static_cast<bf16_t>((a2 * cs.x + a1 * cs.y) * qscale);
+      }
+      w.qf[kk] = y1;
+      w.qf[kk + 4] = y2;
+    }
+  }
+
+  // ---- prefix keys of this split ------------------------------------------------------------
+  const int kbeg = sp * SPLIT_KEYS;
+  const int kend = min(a.P, kbeg + SPLIT_KEYS);
+  const int n_tiles = kend > kbeg ? (kend - kbeg + KTILE - 1) / KTILE : 0;
+  const bf16_t* pk = a.pk + (size_t)kvh * a.P * HD;
+  const bf16_t* pv = a.pv + (size_t)kvh * a.P * HD;
+  KVRegs r;
+  if (n_tiles > 0) {
+    gload_prefix(r, pk, pv, kbeg, kend - 1);
+    lstore_k(r, smem);
+    lstore_vt(r, smem + KS_ELEMS);
+  }
+  __syncthreads();
+  for (int t = 0; t < n_tiles; ++t) {
+    const int cur = t & 1;
+    if (t + 1 < n_tiles) gload_prefix(r, pk, pv, kbeg + (t + 1) * KTILE, kend - 1);
+    const bf16_t* ks = smem + cur * BUF_ELEMS;
+    const int key0 = kbeg + t * KTILE;
+    if (key0 + KTILE <= kend) {
+      process_tile<false>(w, ks, ks + KS_ELEMS, l32, hh, [](int) { return true; });
+    } else {
+      const int nvalid = kend - key0;
+      process_tile<true>(w, ks, ks + KS_ELEMS, l32, hh, [nvalid](int key) { return key < nvalid; });
+    }
+    if (t + 1 < n_tiles) {
+      bf16_t* nb = smem + (cur ^ 1) * BUF_ELEMS;
+      lstore_k(r, nb);
+      lstore_vt(r, nb + KS_ELEMS);
+    }
+    __syncthreads();
+  }
+
+  // ---- own-block keys: the block diagonal, handled by the last split --------------------------
+  if (sp == a.nS - 1) {
+    const int m_last = min(m0 + QTILE, a.M) - 1;
+    const int own_lo = (m0 / a.B) * a.B;
+    const int own_hi = min(a.M, (m_last / a.B + 1) * a.B);
+    // rows of the states this wave's queries belong to
+    const int w_lo = (min(m0w, a.M - 1) / a.B) * a.B;
+    const int w_hi = (min(m0w + 31, a.M - 1) / a.B + 1) * a.B;
+    const int q_lo = (qrow / a.B) * a.B;    // this lane's state: rows [q_lo, q_lo + B)
+    const int q_hi = q_lo + a.B;
+    bf16_t* ks = smem;
+    bf16_t* vt = smem + KS_ELEMS;
+    for (int r0 = own_lo; r0 < own_hi; r0 += KTILE) {
+      // K rows r0..r0+63 with rotary embedding: thread handles (key, chunk ch) and its partner ch+8
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int u = threadIdx.x + 256 * i;
+        const int key = u >> 3, ch = u & 7;
+        const int row = min(r0 + key, a.M - 1);
+        const bf16_t* kp = a.qkv + (size_t)row * a.ld + (a.Hq + kvh) * HD + ch * 8;
+        const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(kp);
+        const bf16x8 x2 = *reinterpret_cast<const bf16x8*>(kp + 64);
+        const float2* rp = a.rope + (size_t)(row % a.B) * 64 + ch * 8;
+        bf16x8 y1, y2;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const float2 cs = rp[e];
+          const float a1 = static_cast<float>(x1[e]), a2 = static_cast<float>(x2[e]);
+          y1[e] = static_cast<bf16_t>(a1 * cs.x - a2 * cs.y);
+          y2[e] = static_cast<bf16_t>(a2 * cs.x + a1 * cs.y);
+        }
+        *reinterpret_cast<bf16x8*>(ks + key * KS_STRIDE + ch * 8) = y1;
+        *reinterpret_cast<bf16x8*>(ks + key * KS_STRIDE + ch * 8 + 64) = y2;
+      }
+      {
+        const int kq = threadIdx.x >> 4, ho = threadIdx.x & 15;
+        KVRegs rv;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const int row = min(r0 + 4 * kq + i, a.M - 1);
+          rv.v[i] = *reinterpret_cast<const u32x4*>(a.qkv + (size_t)row * a.ld + (a.Hq + a.Hkv + kvh) * HD + ho * 8);
+        }
+        lstore_vt(rv, vt);
+      }
+      __syncthreads();
+      if (r0 < w_hi && r0 + KTILE > w_lo) {     // wave-uniform: this pass holds keys of my states
+        process_tile<true>(w, ks, vt, l32, hh, [r0, q_lo, q_hi, own_hi](int key) {
+          const int row = r0 + key;
+          return row >= q_lo && row < q_hi && row < own_hi;
+        });
+      }
+      __syncthreads();
+    }
+  }
+
+  // ---- write ----------------------------------------------------------------------------------
+  const float l_tot = w.l_run + __shfl_xor(w.l_run, 32, 64);
+  if (m0w + l32 >= a.M) return;
+  if (a.nS == 1) {
+    const float inv = 1.0f / l_tot;
+    bf16_t* op = a.out + (size_t)qrow * (a.Hq * HD) + h * HD + 4 * hh;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        bf16x4 t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = static_cast<bf16_t>(w.o[n][g4 * 4 + e] * inv);
+        *reinterpret_cast<bf16x4*>(op + n * 32 + g4 * 8) = t;
+      }
+  } else {
+    const size_t rowh = ((size_t)sp * a.M + qrow) * a.Hq + h;
+    float* op = a.opart + rowh * HD + 4 * hh;
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int g4 = 0; g4 < 4; ++g4) {
+        f32x4 t;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[e] = w.o[n][g4 * 4 + e];
+        *reinterpret_cast<f32x4*>(op + n * 32 + g4 * 8) = t;
+      }
+    if (hh == 0) {
+      a.mlpart[rowh * 2] = w.m_run;
+      a.mlpart[rowh * 2 + 1] = l_tot;
+    }
+  }
+}
+
+// merge the prefix splits of each (row, head): weights 2^(m_s - max m)
+__global__ __launch_bounds__(128) void attn_combine_kernel(const float* __restrict__ opart,
+                                                           const float* __restrict__ mlpart, bf16_t* __restrict__ out,
+                                                           int M, int Hq, int nS) {
+  const size_t rowh = blockIdx.x;   // row * Hq + head
+  const int t = threadIdx.x;
+  float mx = -INFINITY;
+  for (int s = 0; s < nS; ++s) mx = fmaxf(mx, mlpart[((size_t)s * M * Hq + rowh) * 2]);
+  float num = 0.f, den = 0.f;
+  for (int s = 0; s < nS; ++s) {
+    const size_t i = (size_t)s * M * Hq + rowh;
+    const float ms = mlpart[i * 2];
+    const float wgt = (ms == -INFINITY) ? 0.f : exp2f(ms - mx);
+    den += wgt * mlpart[i * 2 + 1];
+    num += wgt * opart[i * HD + t];
+  }
+  out[rowh * HD + t] = static_cast<bf16_t>(num / den);
+}
+
+__global__ void rope_table_kernel(float2* __restrict__ tab, int B, int half, int hd, int pos0, float base) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * half) return;
+  const int b = i / half, f = i % half;
+  const double inv_freq = pow((double)base, -2.0 * (double)f / (double)hd);
+  const double ang = (double)(pos0 + b) * inv_freq;
+  tab[i] = make_float2((float)cos(ang), (float)sin(ang));
+}
+
+inline int n_splits(int P) { return P > 0 ? cdiv(P, SPLIT_KEYS) : 1; }
+
+}  // namespace
+
+bool mfma_attn_supported(const AttnArgs& a) {
+  return a.hd == HD && a.Hq % a.Hkv == 0 && a.B >= 1 && a.G >= 1;
+}
+
+// rope table + split partials
+size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P) {
+  const size_t M = (size_t)G * B;
+  size_t bytes = align_up(sizeof(float2) * (size_t)B * (hd / 2), 256);
+  const int nS = n_splits(P);
+  if (nS > 1) {
+    bytes += align_up(sizeof(float) * nS * M * Hq * hd, 256);
+    bytes += align_up(sizeof(float) * nS * M * Hq * 2, 256);
+  }
+  return bytes;
+}
+
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
+  static bool attr_done = false;
+  if (!attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)attn_prefix_mfma_kernel,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnSmem);
+    if (e != hipSuccess) return e;
+    attr_done = true;
+  }
+  const int M = a.G * a.B;
+  const int nS = n_splits(a.P);
+  unsigned char* ws = reinterpret_cast<unsigned char*>(a.partial);
+  float2* rope = reinterpret_cast<float2*>(ws);
+  ws += align_up(sizeof(float2) * (size_t)a.B * (HD / 2), 256);
+  float* opart = reinterpret_cast<float*>(ws);
+  ws += align_up(sizeof(float) * (size_t)nS * M * a.Hq * HD, 256);
+  float* mlpart = reinterpret_cast<float*>(ws);
+
+  const int nrope = a.B * (HD / 2);
+  rope_table_kernel<<<cdiv(nrope, 256), 256, 0, st>>>(rope, a.B, HD / 2, HD, a.pos0, a.rope_base);
+
+  AttnKArgs k;
+  k.qkv = (const bf16_t*)a.qkv;
+  k.pk = (const bf16_t*)a.prefix_k;
+  k.pv = (const bf16_t*)a.prefix_v;
+  k.rope = rope;
+  k.out = (bf16_t*)a.out;
+  k.opart = opart;
+  k.mlpart = mlpart;
+  k.M = M; k.B = a.B; k.Hq = a.Hq; k.Hkv = a.Hkv; k.P = a.P;
+  k.ld = (a.Hq + 2 * a.Hkv) * HD;
+  k.nQ = cdiv(M, QTILE);
+  k.nS = nS;
+  attn_prefix_mfma_kernel<<<k.nQ * nS * a.Hq, 256, kAttnSmem, st>>>(k);
+  if (nS > 1) attn_combine_kernel<<<M * a.Hq, 128, 0, st>>>(opart, mlpart, (bf16_t*)a.out, M, a.Hq, nS);
+  return hipGetLastError();
+}
+
+}  // namespace spiffy

@@ -1,0 +1,250 @@
+"""Thin ctypes binding over libspiffy.so (the C ABI declared in include/spiffy.h).
+
+Argument marshalling only: every step of the verification path runs in the HIP kernels behind
+the C ABI.  PyTorch is used for device memory and the stream handle.  Importing this module loads
+the library and raises if it has not been built (python -m paper_2509_18085_amd.build); there is
+no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspiffy.so")
+
+SPIFFY_OK, SPIFFY_EINVAL, SPIFFY_ESHAPE, SPIFFY_EALIGN, SPIFFY_EWORKSPACE, SPIFFY_EDEVICE = 0, -1, -2, -3, -4, -5
+SPIFFY_BF16, SPIFFY_F32 = 0, 1
+MAX_G = 64
+
+EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "spiffy_embed",
+           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_graph_accept", "spiffy_verify_step"]
+
+
+class ModelCfg(C.Structure):
+    _fields_ = [("d", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("ffn", C.c_int32), ("vocab", C.c_int32),
+                ("mask_id", C.c_int32), ("dtype", C.c_int32), ("rms_eps", C.c_float),
+                ("rope_base", C.c_float)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down",
+                                          "norm1", "norm2", "bq", "bk", "bv")]
+
+
+class PrefixKV(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("P", C.c_int32)]
+
+
+class AcceptResult(C.Structure):
+    _fields_ = [("node", C.c_int32), ("depth", C.c_int32), ("n_steps", C.c_int32), ("flags", C.c_int32)]
+
+
+class SpiffyError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s: %s (status %d)" % (where, status_str(status), status))
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError("libspiffy.so is not built (%s missing): run `python -m paper_2509_18085_amd.build`; "
+                          "there is no fallback path" % LIB_PATH)
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, f32, sz = C.c_void_p, C.c_int32, C.c_float, C.c_size_t
+    cfgp = C.POINTER(ModelCfg)
+    lib.spiffy_status_str.restype = C.c_char_p
+    lib.spiffy_status_str.argtypes = [C.c_int]
+    lib.spiffy_uses_mfma.restype = C.c_int
+    lib.spiffy_uses_mfma.argtypes = [cfgp, i32]
+    lib.spiffy_workspace_bytes.restype = sz
+    lib.spiffy_workspace_bytes.argtypes = [cfgp, i32, i32, i32]
+    lib.spiffy_embed.restype = C.c_int
+    lib.spiffy_embed.argtypes = [cfgp, vp, vp, i32, i32, vp, vp]
+    lib.spiffy_verify_layer.restype = C.c_int
+    lib.spiffy_verify_layer.argtypes = [cfgp, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, i32, i32, i32,
+                                        vp, vp, sz, vp]
+    lib.spiffy_decode_head.restype = C.c_int
+    lib.spiffy_decode_head.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp,
+                                       vp, sz, vp]
+    lib.spiffy_graph_accept.restype = C.c_int
+    lib.spiffy_graph_accept.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.spiffy_verify_step.restype = C.c_int
+    lib.spiffy_verify_step.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp,
+                                       i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
+                                       vp, vp, sz, vp]
+    return lib
+
+
+lib = _load()
+
+
+def status_str(status: int) -> str:
+    return lib.spiffy_status_str(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != SPIFFY_OK:
+        raise SpiffyError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensor must be contiguous")
+    return t.data_ptr()
+
+
+def _stream(stream=None) -> Optional[int]:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    s = stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+    return s or None
+
+
+def make_cfg(*, d, n_q_heads, n_kv_heads, head_dim, ffn, vocab, mask_id, dtype, rms_eps=1e-5,
+             rope_base=10000.0) -> ModelCfg:
+    code = {torch.bfloat16: SPIFFY_BF16, torch.float32: SPIFFY_F32, "bf16": SPIFFY_BF16, "f32": SPIFFY_F32}[dtype]
+    return ModelCfg(d, n_q_heads, n_kv_heads, head_dim, ffn, vocab, mask_id, code, rms_eps, rope_base)
+
+
+def cfg_from_synth(c) -> ModelCfg:
+    return make_cfg(d=c.d, n_q_heads=c.Hq, n_kv_heads=c.Hkv, head_dim=c.hd, ffn=c.F, vocab=c.V,
+                    mask_id=c.mask_id, dtype=c.dtype, rms_eps=c.rms_eps, rope_base=c.rope_base)
+
+
+def layer_weights(w: Dict[str, torch.Tensor]) -> LayerWeights:
+    lw = LayerWeights()
+    for name, _ in LayerWeights._fields_:
+        setattr(lw, name, _ptr(w.get(name)))
+    lw._keep = w          # keep the tensors alive as long as the struct
+    return lw
+
+
+def prefix_kv(k: Optional[torch.Tensor], v: Optional[torch.Tensor]) -> PrefixKV:
+    P = 0 if k is None else int(k.shape[1])
+    p = PrefixKV(_ptr(k) if P else None, _ptr(v) if P else None, P)
+    p._keep = (k, v)
+    return p
+
+
+def uses_mfma(cfg: ModelCfg, B: int) -> int:
+    return lib.spiffy_uses_mfma(C.byref(cfg), B)
+
+
+def workspace_bytes(cfg: ModelCfg, G: int, B: int, P_max: int) -> int:
+    return int(lib.spiffy_workspace_bytes(C.byref(cfg), G, B, P_max))
+
+
+def alloc_workspace(cfg: ModelCfg, G: int, B: int, P_max: int, device="cuda") -> torch.Tensor:
+    n = workspace_bytes(cfg, G, B, P_max)
+    if n == 0:
+        raise SpiffyError(SPIFFY_EINVAL, "spiffy_workspace_bytes")
+    return torch.empty(n + 256, dtype=torch.uint8, device=device)
+
+
+def _ws(ws: torch.Tensor) -> Tuple[int, int]:
+    p = ws.data_ptr()
+    off = (-p) % 256
+    return p + off, ws.numel() - off
+
+
+def _tdtype(cfg: ModelCfg):
+    return torch.float32 if cfg.dtype == SPIFFY_F32 else torch.bfloat16
+
+
+def embed(cfg: ModelCfg, w_embed: torch.Tensor, block_tokens: torch.Tensor, out: Optional[torch.Tensor] = None,
+          stream=None) -> torch.Tensor:
+    G, B = block_tokens.shape
+    if out is None:
+        out = torch.empty((G, B, cfg.d), dtype=_tdtype(cfg), device=w_embed.device)
+    _check(lib.spiffy_embed(C.byref(cfg), _ptr(w_embed), _ptr(block_tokens), G, B, _ptr(out), _stream(stream)),
+           "spiffy_embed")
+    return out
+
+
+def verify_layer(cfg: ModelCfg, w: LayerWeights, prefix: PrefixKV, hidden_in: torch.Tensor, pos0: int,
+                 workspace: torch.Tensor, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    G, B, _ = hidden_in.shape
+    if out is None:
+        out = torch.empty_like(hidden_in)
+    wp, wn = _ws(workspace)
+    _check(lib.spiffy_verify_layer(C.byref(cfg), C.byref(w), C.byref(prefix), _ptr(hidden_in), G, B, pos0,
+                                   _ptr(out), wp, wn, _stream(stream)), "spiffy_verify_layer")
+    return out
+
+
+def decode_head(cfg: ModelCfg, hidden: torch.Tensor, final_norm: torch.Tensor, w_vocab: torch.Tensor,
+                block_tokens: torch.Tensor, threshold: float, workspace: torch.Tensor, *,
+                mask: Optional[torch.Tensor] = None, logit_scale: float = 1.0, force_one: bool = True,
+                stream=None) -> Dict[str, torch.Tensor]:
+    G, B = block_tokens.shape
+    dev = hidden.device
+    out = dict(argmax=torch.empty((G, B), dtype=torch.int32, device=dev),
+               conf=torch.empty((G, B), dtype=torch.float32, device=dev),
+               unmask=torch.empty((G, B), dtype=torch.uint8, device=dev),
+               margin=torch.empty((G, B), dtype=torch.float32, device=dev),
+               target_states=torch.empty((G, B), dtype=torch.int32, device=dev))
+    wp, wn = _ws(workspace)
+    _check(lib.spiffy_decode_head(C.byref(cfg), _ptr(hidden), _ptr(final_norm), _ptr(w_vocab), _ptr(block_tokens),
+                                  _ptr(mask), G, B, threshold, logit_scale, int(force_one), _ptr(out["argmax"]),
+                                  _ptr(out["conf"]), _ptr(out["unmask"]), _ptr(out["margin"]),
+                                  _ptr(out["target_states"]), wp, wn, _stream(stream)), "spiffy_decode_head")
+    return out
+
+
+def graph_accept(graph_edges: torch.Tensor, draft_states: torch.Tensor, target_states: torch.Tensor,
+                 root: int = 0, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Returns (result int32[4] = node, depth, n_steps, flags ; accepted_state int32[B]), on device."""
+    G, B = draft_states.shape
+    E = int(graph_edges.shape[0]) if graph_edges is not None else 0
+    res = torch.empty(4, dtype=torch.int32, device=draft_states.device)
+    state = torch.empty(B, dtype=torch.int32, device=draft_states.device)
+    _check(lib.spiffy_graph_accept(_ptr(graph_edges) if E else None, E, _ptr(draft_states), _ptr(target_states),
+                                   G, B, root, _ptr(res), _ptr(state), _stream(stream)), "spiffy_graph_accept")
+    return res, state
+
+
+class StepPlan:
+    """Pre-marshalled arguments of spiffy_verify_step for repeated calls (weights, prefix KV and
+    output buffers are fixed; only the launch happens per call)."""
+
+    def __init__(self, cfg: ModelCfg, layers: Sequence[LayerWeights], prefix: Sequence[PrefixKV],
+                 w_embed: torch.Tensor, final_norm: torch.Tensor, w_vocab: torch.Tensor, G: int, B: int,
+                 pos0: int, threshold: float, logit_scale: float = 1.0, force_one: bool = True,
+                 root: int = 0, device="cuda"):
+        self.cfg, self.G, self.B, self.pos0 = cfg, G, B, pos0
+        self.threshold, self.logit_scale, self.force_one, self.root = threshold, logit_scale, int(force_one), root
+        self.n_layers = len(layers)
+        self._layers = (LayerWeights * max(1, self.n_layers))(*layers)
+        self._prefix = (PrefixKV * max(1, self.n_layers))(*prefix)
+        self._keep = (list(layers), list(prefix), w_embed, final_norm, w_vocab)
+        self.w_embed, self.final_norm, self.w_vocab = w_embed, final_norm, w_vocab
+        P_max = max([p.P for p in prefix], default=0)
+        self.workspace = alloc_workspace(cfg, G, B, P_max, device)
+        dt = _tdtype(cfg)
+        self.out = dict(hidden=torch.empty((G, B, cfg.d), dtype=dt, device=device),
+                        argmax=torch.empty((G, B), dtype=torch.int32, device=device),
+                        conf=torch.empty((G, B), dtype=torch.float32, device=device),
+                        unmask=torch.empty((G, B), dtype=torch.uint8, device=device),
+                        margin=torch.empty((G, B), dtype=torch.float32, device=device),
+                        target_states=torch.empty((G, B), dtype=torch.int32, device=device),
+                        result=torch.empty(4, dtype=torch.int32, device=device),
+                        accepted_state=torch.empty(B, dtype=torch.int32, device=device))
+
+    def run(self, block_tokens: torch.Tensor, graph_edges: Optional[torch.Tensor], stream=None) -> Dict[str, torch.Tensor]:
+        o = self.out
+        E = int(graph_edges.shape[0]) if graph_edges is not None else 0
+        wp, wn = _ws(self.workspace)
+        _check(lib.spiffy_verify_step(
+            C.byref(self.cfg), self.n_layers, self._layers, self._prefix, _ptr(self.w_embed), _ptr(self.final_norm),
+            _ptr(self.w_vocab), _ptr(block_tokens), self.G, self.B, self.pos0, _ptr(graph_edges) if E else None, E,
+            self.root, self.threshold, self.logit_scale, self.force_one, _ptr(o["hidden"]), _ptr(o["argmax"]),
+            _ptr(o["conf"]), _ptr(o["unmask"]), _ptr(o["margin"]), _ptr(o["target_states"]), _ptr(o["result"]),
+            _ptr(o["accepted_state"]), wp, wn, _stream(stream)), "spiffy_verify_step")
+        return o

@@ -1,0 +1,169 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments before any launch."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2509_18085_amd import spiffy as sp, synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_exports_match_header():
+    hdr = open(os.path.join(ROOT, "include", "spiffy.h")).read()
+    declared = set(re.findall(r"\b(spiffy_[a-z_]+)\s*\(", hdr))
+    declared -= {"spiffy_workspace_bytes(...)"}
+    assert declared == set(sp.EXPORTS), declared ^ set(sp.EXPORTS)
+    for name in declared:
+        assert getattr(sp.lib, name) is not None
+
+
+def test_status_strings():
+    assert sp.status_str(0) == "ok"
+    for s in (-1, -2, -3, -4, -5):
+        assert sp.status_str(s) not in ("ok", "unknown status")
+
+
+def _cfg(key="c3"):
+    return sp.cfg_from_synth(synth.CONFIGS[key])
+
+
+def test_kernel_choice_by_shape():
+    assert sp.uses_mfma(_cfg("c3"), 32) == 1
+    assert sp.uses_mfma(_cfg("c4"), 32) == 1
+    assert sp.uses_mfma(_cfg("c5"), 4) == 1
+    assert sp.uses_mfma(_cfg("c1"), 8) == 0
+
+
+def test_workspace_bytes():
+    c = synth.CONFIGS["c3"]
+    n = sp.workspace_bytes(_cfg("c3"), c.G, c.B, c.P)
+    M = c.G * c.B
+    # at least the SwiGLU activation and the QKV buffer must fit
+    assert n > M * c.F * 2 + M * 3 * c.d * 2
+    assert n < 2 << 30
+    assert sp.workspace_bytes(_cfg("c3"), 0, 32, 10) == 0
+    assert sp.workspace_bytes(_cfg("c3"), 4, 32, -1) == 0
+    bad = _cfg("c3")
+    bad.n_kv_heads = 5
+    assert sp.workspace_bytes(bad, 4, 32, 10) == 0
+    # more prefix (more splits) never needs less
+    assert sp.workspace_bytes(_cfg("c5"), 64, 4, 8192) >= sp.workspace_bytes(_cfg("c5"), 64, 4, 1024)
+
+
+DUMMY = 0x10000  # non-null, 16-byte aligned, never dereferenced: every check fails before a launch
+
+
+def _layer_structs():
+    w = sp.LayerWeights(*([DUMMY] * 9 + [None] * 3))
+    p = sp.PrefixKV(DUMMY, DUMMY, 64)
+    return w, p
+
+
+def test_verify_layer_argument_errors():
+    cfg = _cfg("c3")
+    w, p = _layer_structs()
+    call = lambda **k: sp.lib.spiffy_verify_layer(
+        C.byref(k.get("cfg", cfg)), C.byref(k.get("w", w)), C.byref(k.get("p", p)), k.get("hin", DUMMY),
+        k.get("G", 4), k.get("B", 32), k.get("pos0", 64), k.get("hout", DUMMY), k.get("ws", 0x100000),
+        k.get("wsn", 16), None)
+    assert call() == sp.SPIFFY_EWORKSPACE                      # tiny workspace, everything else fine
+    assert call(G=0) == sp.SPIFFY_EINVAL
+    assert call(B=0) == sp.SPIFFY_EINVAL
+    assert call(hin=None) == sp.SPIFFY_EINVAL
+    assert call(ws=None) == sp.SPIFFY_EINVAL
+    assert call(pos0=-1) == sp.SPIFFY_EINVAL
+    assert call(hout=DUMMY + 2) == sp.SPIFFY_EALIGN
+    assert call(ws=0x100010) == sp.SPIFFY_EALIGN
+    assert call(G=4096, B=32) == sp.SPIFFY_ESHAPE               # more rows than SPIFFY_MAX_ROWS
+    w2, _ = _layer_structs()
+    w2.w_down = None
+    assert call(w=w2) == sp.SPIFFY_EINVAL
+    w3, _ = _layer_structs()
+    w3.wq = DUMMY + 8
+    assert call(w=w3) == sp.SPIFFY_EALIGN
+    p2 = sp.PrefixKV(None, None, 64)
+    assert call(p=p2) == sp.SPIFFY_EINVAL
+    bad = _cfg("c3")
+    bad.dtype = 7
+    assert call(cfg=bad) == sp.SPIFFY_EINVAL
+    bad = _cfg("c3")
+    bad.head_dim = 100
+    assert call(cfg=bad) == sp.SPIFFY_ESHAPE
+    bad = _cfg("c3")
+    bad.mask_id = bad.vocab
+    assert call(cfg=bad) == sp.SPIFFY_EINVAL
+
+
+def test_decode_head_argument_errors():
+    cfg = _cfg("c3")
+    call = lambda **k: sp.lib.spiffy_decode_head(
+        C.byref(cfg), k.get("hid", DUMMY), DUMMY, DUMMY, k.get("tok", DUMMY), None, k.get("G", 4), 32,
+        k.get("tau", 0.9), k.get("scale", 1.0), 1, k.get("amax", DUMMY), DUMMY, DUMMY, None, None,
+        k.get("ws", 0x100000), k.get("wsn", 16), None)
+    assert call() == sp.SPIFFY_EWORKSPACE
+    assert call(tau=1.5) == sp.SPIFFY_EINVAL
+    assert call(tau=-0.1) == sp.SPIFFY_EINVAL
+    assert call(tau=float("nan")) == sp.SPIFFY_EINVAL
+    assert call(scale=0.0) == sp.SPIFFY_EINVAL
+    assert call(tok=None) == sp.SPIFFY_EINVAL
+    assert call(amax=None) == sp.SPIFFY_EINVAL
+    assert call(hid=DUMMY + 4) == sp.SPIFFY_EALIGN
+    assert call(G=-3) == sp.SPIFFY_EINVAL
+
+
+def test_graph_accept_argument_errors():
+    call = lambda **k: sp.lib.spiffy_graph_accept(
+        k.get("edges", DUMMY), k.get("E", 3), k.get("ds", DUMMY), k.get("ts", DUMMY), k.get("G", 4), 8,
+        k.get("root", 0), k.get("res", DUMMY), None, None)
+    assert call(G=65) == sp.SPIFFY_ESHAPE
+    assert call(root=4) == sp.SPIFFY_EINVAL
+    assert call(root=-1) == sp.SPIFFY_EINVAL
+    assert call(E=-1) == sp.SPIFFY_EINVAL
+    assert call(edges=None) == sp.SPIFFY_EINVAL
+    assert call(ds=None) == sp.SPIFFY_EINVAL
+    assert call(res=None) == sp.SPIFFY_EINVAL
+    assert call(G=0) == sp.SPIFFY_EINVAL
+
+
+def test_verify_step_argument_errors():
+    cfg = _cfg("c3")
+    w, p = _layer_structs()
+    layers = (sp.LayerWeights * 1)(w)
+    prefix = (sp.PrefixKV * 1)(p)
+    call = lambda **k: sp.lib.spiffy_verify_step(
+        C.byref(cfg), 1, layers, prefix, DUMMY, k.get("fn", DUMMY), DUMMY, DUMMY, k.get("G", 4), 32, 64,
+        DUMMY, 2, k.get("root", 0), k.get("tau", 0.9), 1.0, 1, None, DUMMY, DUMMY, DUMMY, None, None,
+        k.get("res", DUMMY), None, 0x100000, 16, None)
+    assert call() == sp.SPIFFY_EWORKSPACE
+    assert call(root=9) == sp.SPIFFY_EINVAL
+    assert call(tau=2.0) == sp.SPIFFY_EINVAL
+    assert call(fn=None) == sp.SPIFFY_EINVAL
+    assert call(res=None) == sp.SPIFFY_EINVAL
+    assert call(G=100) == sp.SPIFFY_ESHAPE                      # walk supports at most 64 nodes
+
+
+def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
+    import importlib
+    monkeypatch.setattr(sp, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(ImportError):
+        sp._load()
+
+
+def test_synth_graphs_follow_the_recipes():
+    import numpy as np
+    for key in ("c1", "c3", "c4", "c5"):
+        cfg = synth.CONFIGS[key]
+        st, e = synth.draft_graph(key, cfg)
+        assert st.shape == (cfg.G, cfg.B), key
+        assert len(e) > 0 and e.min() >= 0 and e.max() < cfg.G
+        for p, c in e:            # child's unmasked set strictly contains the parent's (Eq. 6)
+            up = set(np.nonzero(st[p] != cfg.mask_id)[0])
+            uc = set(np.nonzero(st[c] != cfg.mask_id)[0])
+            assert up < uc
+    st, e = synth.draft_graph("c5", synth.CONFIGS["c5"])
+    assert len({tuple(r) for r in st}) == 16          # 16 subsets, 4 copies each
+    tgt, path = synth.planted_targets(*synth.draft_graph("c3", synth.CONFIGS["c3"]), synth.CONFIGS["c3"].V, 3, 5)
+    assert len(path) >= 2

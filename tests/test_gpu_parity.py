@@ -1,0 +1,369 @@
+"""GPU-vs-oracle parity through the C ABI (needs an MI355X: pytest -m gpu).
+
+Bar: hidden states and confidences within 1e-4 (fp32) / 2e-2 (bf16) by the metric
+|gpu - ref| / (|ref| + rms(ref)); argmax / unmask / next-state / acceptance decisions bit-exact
+except where the oracle's top-2 logit margin is below 1e-3 or its confidence is within 1e-4*tau
+of the threshold (both counted and printed).  Every call is compared on identical input bits:
+bf16 inputs reach the oracle as the same values widened to float64.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2509_18085_amd import synth
+from helpers import np_weights, to_np
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def sp():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2509_18085_amd import spiffy
+    return spiffy
+
+
+def O():
+    from oracle import spiffy_oracle
+    return spiffy_oracle
+
+
+def rel_err(gpu, ref):
+    ref = np.asarray(ref, np.float64)
+    gpu = np.asarray(gpu, np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref))) + 1e-30
+    return float(np.max(np.abs(gpu - ref) / (np.abs(ref) + rms))), float(
+        np.linalg.norm(gpu - ref) / (np.linalg.norm(ref) + 1e-30))
+
+
+def tol(cfg):
+    return 1e-4 if cfg.dtype == "f32" else 2e-2
+
+
+def dev_weights(w):
+    return {k: v.to(DEV) for k, v in w.items()}
+
+
+def oracle_kw(cfg, pos0=None):
+    return dict(n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P if pos0 is None else pos0,
+                rms_eps=cfg.rms_eps, rope_base=cfg.rope_base)
+
+
+def run_layer(sp, cfg, w, pk, pv, hidden, pos0=None, G=None):
+    scfg = sp.cfg_from_synth(cfg)
+    G = hidden.shape[0]
+    ws = sp.alloc_workspace(scfg, G, cfg.B, pk.shape[1] if pk is not None else 0, DEV)
+    dw = dev_weights(w)
+    lw = sp.layer_weights(dw)
+    pf = sp.prefix_kv(None if pk is None else pk.to(DEV), None if pv is None else pv.to(DEV))
+    out = sp.verify_layer(scfg, lw, pf, hidden.to(DEV), cfg.P if pos0 is None else pos0, ws)
+    torch.cuda.synchronize()
+    return out.cpu()
+
+
+def check_layer(sp, cfg, seed=synth.DEFAULT_SEED, bias=False, hidden_std=1.0, pos0=None, weight_scale=None):
+    w = synth.layer_weights(cfg, 0, seed, bias=bias)
+    if weight_scale:
+        for k in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down"):
+            w[k] = (w[k].float() * weight_scale).to(w[k].dtype)
+    pk, pv = synth.prefix_kv(cfg, 0, seed)
+    x = synth.hidden_states(cfg, seed, std=hidden_std)
+    got = run_layer(sp, cfg, w, pk, pv, x, pos0)
+    ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), to_np(x), **oracle_kw(cfg, pos0))
+    e_max, e_norm = rel_err(to_np(got), ref)
+    print("layer %s: max-rel %.3e  normwise %.3e" % (cfg.name, e_max, e_norm))
+    assert e_max < tol(cfg), (cfg, e_max, e_norm)
+    return got, ref
+
+
+# ------------------------------------------------------------------ acceptance walk (bit-exact)
+
+def test_accept_golden_and_random(sp):
+    import json, os
+    cases = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "accept_cases.json")))["cases"]
+    for c in cases:
+        e = torch.tensor(c["edges"], dtype=torch.int32, device=DEV).reshape(-1, 2)
+        ds = torch.tensor(c["draft_states"], dtype=torch.int32, device=DEV)
+        ts = torch.tensor(c["target_states"], dtype=torch.int32, device=DEV)
+        res, state = sp.graph_accept(e, ds, ts, c.get("root", 0))
+        res = res.cpu().tolist()
+        assert res[:3] == [c["node"], c["depth"], c["depth"] + 1] and res[3] == 0, c["name"]
+        assert state.cpu().tolist() == c["accepted_state"], c["name"]
+    r = np.random.default_rng(3)
+    for trial in range(60):
+        G = int(r.integers(1, 65))
+        B = int(r.choice([1, 3, 4, 8, 32, 33, 70]))
+        levels = []
+        left = G - 1
+        while left > 0:
+            n = int(min(left, r.integers(1, 9)))
+            levels.append(n)
+            left -= n
+        st, e, _ = synth.grown_dag(levels, B, 50, 0.9, 1, 3, 100 + trial)
+        tgt, path = synth.planted_targets(st, e, 50, int(r.integers(0, 6)), 200 + trial)
+        if trial % 3 == 0 and len(e):
+            e = e[r.permutation(len(e))]                   # edge order must not matter
+        root = 0
+        ref = O().graph_accept(e, st, tgt, root)
+        res, state = sp.graph_accept(torch.from_numpy(np.ascontiguousarray(e)).to(DEV), torch.from_numpy(st).to(DEV),
+                                     torch.from_numpy(tgt).to(DEV), root)
+        assert tuple(res.cpu().tolist()[:3]) == ref[:3], (trial, G, B)
+        assert state.cpu().tolist() == ref[3].tolist()
+
+
+def test_accept_edge_cases(sp):
+    # no edges, G = 1
+    ds = torch.tensor([[5, 9, 9]], dtype=torch.int32, device=DEV)
+    ts = torch.tensor([[5, 2, 9]], dtype=torch.int32, device=DEV)
+    res, state = sp.graph_accept(None, ds, ts, 0)
+    assert res.cpu().tolist() == [0, 0, 1, 0] and state.cpu().tolist() == [5, 2, 9]
+    # out-of-range endpoints are ignored and flagged; a cycle terminates
+    ds = torch.tensor([[9, 9], [1, 9], [1, 2]], dtype=torch.int32, device=DEV)
+    ts = torch.tensor([[1, 9], [1, 2], [1, 9]], dtype=torch.int32, device=DEV)
+    e = torch.tensor([[0, 1], [1, 2], [2, 1], [7, 1], [0, -1]], dtype=torch.int32, device=DEV)
+    res, state = sp.graph_accept(e, ds, ts, 0)
+    assert res.cpu().tolist() == [2, 2, 3, 1]
+    # full subset lattice of the small-block configuration, walk to the all-unmasked leaf
+    cfg = synth.CONFIGS["c5"]
+    st, e = synth.draft_graph("c5", cfg)
+    tgt = st.copy()
+    order = [0, 1, 3, 7, 15]
+    for a, b in zip(order[:-1], order[1:]):
+        tgt[a] = st[b]
+    tgt[15, 0] = 5
+    ref = O().graph_accept(e, st, tgt, 0)
+    res, state = sp.graph_accept(torch.from_numpy(e).to(DEV), torch.from_numpy(st).to(DEV),
+                                 torch.from_numpy(tgt).to(DEV), 0)
+    assert tuple(res.cpu().tolist()[:3]) == ref[:3] == (15, 4, 5)
+
+
+# ------------------------------------------------------------------ embed
+
+@pytest.mark.parametrize("key", ["c1", "bf16"])
+def test_embed(sp, key):
+    cfg = synth.CONFIGS["c1"] if key == "c1" else synth.CONFIGS["c1"].scaled(dtype="bf16")
+    w = synth.embed_weights(cfg)
+    st, _ = synth.draft_graph("c1", cfg)
+    got = sp.embed(sp.cfg_from_synth(cfg), w.to(DEV), torch.from_numpy(st).to(DEV))
+    np.testing.assert_array_equal(to_np(got), O().embed(to_np(w), st))
+
+
+# ------------------------------------------------------------------ layer parity
+
+def test_layer_config1_fp32(sp):
+    check_layer(sp, synth.CONFIGS["c1"])
+    check_layer(sp, synth.CONFIGS["c1"], bias=True, weight_scale=3.0)
+
+
+@pytest.mark.parametrize("shape", [
+    dict(d=64, Hq=2, Hkv=1, hd=32, F=40, P=0, B=5, G=3),          # no prefix, odd sizes
+    dict(d=96, Hq=6, Hkv=2, hd=16, F=72, P=37, B=7, G=2),         # GQA, ragged everything
+    dict(d=128, Hq=2, Hkv=2, hd=64, F=136, P=300, B=1, G=9),      # one-token blocks
+])
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_layer_generic_shapes(sp, shape, dtype):
+    cfg = synth.CONFIGS["c1"].scaled(dtype=dtype, **shape)
+    check_layer(sp, cfg, bias=True, weight_scale=4.0)
+
+
+MFMA_SHAPES = [
+    dict(d=512, Hq=4, Hkv=2, hd=128, F=768, P=200, B=32, G=5),    # GQA, ragged prefix tail, ragged row tail
+    dict(d=256, Hq=2, Hkv=2, hd=128, F=320, P=64, B=4, G=40),     # small blocks: block-diagonal own keys
+    dict(d=256, Hq=2, Hkv=1, hd=128, F=192, P=0, B=8, G=3),       # no prefix at all
+    dict(d=256, Hq=2, Hkv=2, hd=128, F=256, P=2100, B=16, G=10),  # three prefix splits + combine
+    dict(d=384, Hq=3, Hkv=3, hd=128, F=448, P=1, B=64, G=3),      # block larger than a wave's 32 rows
+    dict(d=256, Hq=2, Hkv=2, hd=128, F=256, P=130, B=24, G=7),    # block size that divides nothing
+]
+
+
+@pytest.mark.parametrize("shape", MFMA_SHAPES)
+def test_layer_mfma_shapes(sp, shape):
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", V=1280, **shape)
+    assert sp.uses_mfma(sp.cfg_from_synth(cfg), cfg.B) == 1
+    check_layer(sp, cfg, bias=True, weight_scale=2.0)
+
+
+def test_layer_mfma_batch_invariance_and_duplicates(sp):
+    """A state's rows do not depend on which other states are verified with it (Sec. 4.3
+    independence; App. A.2 remark on accumulation order): bit-identical across G and position."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=512, Hq=4, Hkv=2, hd=128, F=768, P=333, B=32, G=6, V=1280)
+    w = synth.layer_weights(cfg, 0)
+    pk, pv = synth.prefix_kv(cfg, 0)
+    x = synth.hidden_states(cfg)
+    x[4] = x[1]
+    full = run_layer(sp, cfg, w, pk, pv, x)
+    assert torch.equal(full[4], full[1])
+    for g in (0, 3, 5):
+        single = run_layer(sp, cfg, w, pk, pv, x[g:g + 1].contiguous())
+        assert torch.equal(single[0], full[g]), g
+    perm = [5, 2, 0, 4, 1, 3]
+    shuffled = run_layer(sp, cfg, w, pk, pv, x[perm].contiguous())
+    assert torch.equal(shuffled, full[perm])
+
+
+def test_layer_config2_full_size(sp):
+    """One LLaDA-8B-shaped layer at the full configuration-2 size, all 512 rows against the oracle."""
+    check_layer(sp, synth.CONFIGS["c2"])
+
+
+def test_layer_shapes_of_configs_3_4_5_reduced_rows(sp):
+    """Configurations 3-5 at their real widths, prefix lengths and block sizes, with fewer states
+    so the oracle finishes in seconds; G keeps several row tiles and a ragged tail."""
+    check_layer(sp, synth.CONFIGS["c3"].scaled(G=5))
+    check_layer(sp, synth.CONFIGS["c4"].scaled(G=5))
+    check_layer(sp, synth.CONFIGS["c5"].scaled(G=40, P=2500))
+
+
+# ------------------------------------------------------------------ head parity
+
+def run_head(sp, cfg, hidden, hw, states, threshold, logit_scale, force_one):
+    scfg = sp.cfg_from_synth(cfg)
+    ws = sp.alloc_workspace(scfg, states.shape[0], cfg.B, 0, DEV)
+    out = sp.decode_head(scfg, hidden.to(DEV), hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV),
+                         torch.from_numpy(states).to(DEV), threshold, ws, logit_scale=logit_scale,
+                         force_one=force_one)
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in out.items()}
+
+
+def check_head(sp, cfg, states, hidden, hw, threshold, logit_scale, force_one=True):
+    got = run_head(sp, cfg, hidden, hw, states, threshold, logit_scale, force_one)
+    amax, conf, unmask, margin, target = O().decode_head(
+        to_np(hidden), to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states, cfg.mask_id, threshold,
+        rms_eps=cfg.rms_eps, logit_scale=logit_scale, force_one=force_one)
+    m = states == cfg.mask_id
+    near_tie = m & (margin < 1e-3)
+    near_tau = m & (np.abs(conf.astype(np.float64) - threshold) < 1e-4 * threshold)
+    # force_one picks the best position by confidence: a state whose two best masked positions are
+    # within 1e-6 relative is a near-tie of that decision
+    ok_state = np.ones(states.shape[0], bool)
+    for g in range(states.shape[0]):
+        c = np.sort(conf[g][m[g]])[::-1]
+        if near_tie[g].any() or near_tau[g].any() or (c.size > 1 and c[0] - c[1] < 1e-5 * c[0]):
+            ok_state[g] = False
+    print("head %s: masked %d, near-tie (margin<1e-3) %d, near-threshold %d, states excluded %d/%d, unmasked %d"
+          % (cfg.name, m.sum(), near_tie.sum(), near_tau.sum(), (~ok_state).sum(), len(ok_state), unmask.sum()))
+    clear = m & ~near_tie
+    np.testing.assert_array_equal(got["argmax"][clear], amax[clear])
+    np.testing.assert_array_equal(got["argmax"][~m], states[~m])
+    assert (got["conf"][~m] == 0).all() and (got["unmask"][~m] == 0).all() and np.isinf(got["margin"][~m]).all()
+    e_max = np.max(np.abs(got["conf"][m] - conf[m]) / np.maximum(conf[m], 1e-30)) if m.any() else 0.0
+    t = 1e-4 if cfg.dtype == "f32" else 2e-2
+    assert e_max < t, e_max
+    big = clear & (margin > 1e-2)
+    if big.any():
+        np.testing.assert_allclose(got["margin"][big], margin[big], rtol=1e-3, atol=1e-4)
+    np.testing.assert_array_equal(got["unmask"][ok_state], unmask[ok_state])
+    np.testing.assert_array_equal(got["target_states"][ok_state], target[ok_state])
+    assert ok_state.mean() > 0.5
+    return got
+
+
+@pytest.mark.parametrize("scale,tau,force", [(1.0, 0.9, True), (40.0, 0.9, True), (40.0, 0.3, False), (15.0, 0.0, False)])
+def test_head_config1_fp32(sp, scale, tau, force):
+    cfg = synth.CONFIGS["c1"]
+    st, _ = synth.draft_graph("c1", cfg)
+    check_head(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), tau, scale, force)
+
+
+def test_head_generic_bf16_and_edge_masks(sp):
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=96, V=777, B=9, G=5)
+    st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.2, 0.8, 4)
+    st[1, :] = cfg.mask_id          # fully masked state
+    st[2, :] = 3                    # nothing masked: nothing to decode, nothing forced
+    check_head(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 0.5, 30.0)
+
+
+@pytest.mark.parametrize("shape,scale", [
+    (dict(d=256, V=1280, B=32, G=5), 40.0),         # ragged row tile
+    (dict(d=512, V=128 * 9, B=4, G=70), 25.0),      # several row tiles, small blocks
+    (dict(d=256, V=128, B=16, G=2), 60.0),          # a single vocabulary tile
+])
+def test_head_mfma_shapes(sp, shape, scale):
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", Hq=2, Hkv=2, hd=128, F=256, **shape)
+    st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.1, 0.9, 6)
+    st[0, :] = 7                    # a state with nothing masked
+    check_head(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 0.6, scale)
+
+
+def test_head_nothing_masked_anywhere(sp):
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=256, V=1280, B=8, G=3)
+    st = np.full((cfg.G, cfg.B), 5, np.int32)
+    got = run_head(sp, cfg, synth.hidden_states(cfg), synth.head_weights(cfg), st, 0.9, 1.0, True)
+    assert (got["unmask"] == 0).all() and (got["target_states"] == st).all()
+
+
+def test_head_config3_shape_sampled_rows(sp):
+    """Full vocabulary (126464) and width of configuration 3; 320 masked rows checked one by one."""
+    cfg = synth.CONFIGS["c3"].scaled(G=12)
+    st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.8, 0.9, 8)
+    hw = synth.head_weights(cfg)
+    check_head(sp, cfg, st, synth.hidden_states(cfg), hw, cfg.threshold, 8.0)
+
+
+# ------------------------------------------------------------------ whole step
+
+def build_step(sp, cfg, key, seed, logit_scale, n_layers=None):
+    L = cfg.L if n_layers is None else n_layers
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(L)]
+    prefix = [synth.prefix_kv(cfg, l, seed) for l in range(L)]
+    hw = synth.head_weights(cfg, seed)
+    w_embed = synth.embed_weights(cfg, seed)
+    states, edges = synth.draft_graph(key, cfg, seed)
+    scfg = sp.cfg_from_synth(cfg)
+    d_layers = [dev_weights(w) for w in layers]
+    d_prefix = [(k.to(DEV), v.to(DEV)) for k, v in prefix]
+    plan = sp.StepPlan(scfg, [sp.layer_weights(w) for w in d_layers], [sp.prefix_kv(k, v) for k, v in d_prefix],
+                       w_embed.to(DEV), hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), cfg.G, cfg.B, cfg.P,
+                       cfg.threshold, logit_scale=logit_scale, device=DEV)
+    return plan, layers, prefix, hw, w_embed, states, edges
+
+
+@pytest.mark.parametrize("key,logit_scale", [("c1", 1.0), ("c1", 40.0), ("c1_literal", 40.0)])
+def test_step_config1_end_to_end(sp, key, logit_scale):
+    """Configuration 1 (fp32), the whole step in one call: hidden within 1e-4, every decision and
+    the accepted node bit-exact (near-ties excluded and counted)."""
+    cfg = synth.CONFIGS["c1"]
+    plan, layers, prefix, hw, w_embed, states, edges = build_step(sp, cfg, key, synth.DEFAULT_SEED, logit_scale)
+    out = plan.run(torch.from_numpy(states).to(DEV), torch.from_numpy(edges).to(DEV))
+    torch.cuda.synchronize()
+    ref = O().verify_step([np_weights(w) for w in layers], [(to_np(k), to_np(v)) for k, v in prefix],
+                          to_np(w_embed), to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states, edges,
+                          n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P, mask_id=cfg.mask_id,
+                          threshold=cfg.threshold, logit_scale=logit_scale)
+    e_max, e_norm = rel_err(to_np(out["hidden"]), ref["hidden"])
+    assert e_max < 1e-4, e_max
+    m = states == cfg.mask_id
+    clear = m & (ref["margin"] > 1e-3)
+    print("step %s: hidden %.2e, near-ties %d" % (key, e_max, (m & ~clear).sum()))
+    np.testing.assert_array_equal(out["argmax"].cpu().numpy()[clear], ref["argmax"][clear])
+    if clear[m].all():
+        np.testing.assert_array_equal(out["unmask"].cpu().numpy(), ref["unmask"])
+        np.testing.assert_array_equal(out["target_states"].cpu().numpy(), ref["target_states"])
+        res = out["result"].cpu().tolist()
+        assert res[:3] == [ref["node"], ref["depth"], ref["n_steps"]]
+        assert out["accepted_state"].cpu().tolist() == ref["accepted_state"].tolist()
+
+
+def test_step_accept_follows_device_targets(sp):
+    """Chained step on an MFMA shape (2 layers): the walk inside the step equals the oracle walk
+    on the step's own next states, and each stage matches the oracle on the stage's own inputs."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=1280, P=100, B=32, G=32)
+    plan, layers, prefix, hw, w_embed, states, edges = build_step(sp, cfg, "c3", 5, 30.0)
+    out = plan.run(torch.from_numpy(states).to(DEV), torch.from_numpy(edges).to(DEV))
+    torch.cuda.synchronize()
+    tgt = out["target_states"].cpu().numpy()
+    ref = O().graph_accept(edges, states, tgt, 0)
+    assert tuple(out["result"].cpu().tolist()[:3]) == ref[:3]
+    assert out["accepted_state"].cpu().tolist() == ref[3].tolist()
+    # stage-wise: layers from the oracle's fp64 chain stay inside the bf16 tolerance after 2 layers
+    h = O().embed(to_np(w_embed), states)
+    for w, (pk, pv) in zip(layers, prefix):
+        h = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), h, **oracle_kw(cfg))
+    e_max, _ = rel_err(to_np(out["hidden"]), h)
+    assert e_max < 4e-2, e_max       # two chained bf16 layers
+    # and the head on the step's own hidden
+    check_head(sp, cfg, states, out["hidden"].cpu(), hw, cfg.threshold, 30.0)

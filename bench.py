@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the draft-graph verification step on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3|c2|c4|c5] [--no-cpu-baseline]
+
+One step = the whole hot path over one batch of synthetic input: embedding of G block states,
+L transformer layers (shared-prefix attention + projections), LM head reduced to
+top-1/confidence/unmask, next-state build and the acceptance walk, all in one C-ABI call with
+weights, prefix KV and inputs already resident in HBM.  Prints ONE JSON line.
+
+metric  = draft states verified per second (G / step latency), whole job on one GPU
+roofline= the dominant kernel (the SwiGLU gate/up MFMA GEMM): algorithmic flop of one launch /
+          its average launch duration, timed here with HIP events around back-to-back launches
+          of that kernel on the same shapes and buffers the step uses
+cpu_baseline = the CPU oracle (oracle/, float64 numpy) timed on this host on a bounded sample
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
+LOGIT_SCALE = 8.0             # synthetic knob: random-init logits are flat, this makes ~1/3 of positions pass tau
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="c3")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kernel-iters", type=int, default=5)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2509_18085_amd import spiffy as sp, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    cfg = synth.CONFIGS[args.config]
+    seed = synth.DEFAULT_SEED
+    scfg = sp.cfg_from_synth(cfg)
+    t0 = time.time()
+
+    # ---- synthetic model and inputs, generated on the device from the seed ---------------------
+    layers = [synth.layer_weights(cfg, l, seed, device=dev) for l in range(cfg.L)]
+    prefix = [synth.prefix_kv(cfg, l, seed, device=dev) for l in range(cfg.L)]
+    hw = synth.head_weights(cfg, seed, device=dev)
+    w_embed = synth.embed_weights(cfg, seed, device=dev)
+    states, edges = synth.draft_graph(args.config, cfg, seed)
+    d_states = torch.from_numpy(states).to(dev)
+    d_edges = torch.from_numpy(np.ascontiguousarray(edges)).to(dev)
+    plan = sp.StepPlan(scfg, [sp.layer_weights(w) for w in layers], [sp.prefix_kv(k, v) for k, v in prefix],
+                       w_embed, hw["final_norm"], hw["w_vocab"], cfg.G, cfg.B, cfg.P, cfg.threshold,
+                       logit_scale=LOGIT_SCALE, device=dev)
+    torch.cuda.synchronize()
+    t_setup = time.time() - t0
+
+    # ---- whole step ------------------------------------------------------------------------------
+    for _ in range(args.warmup):
+        plan.run(d_states, d_edges)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        plan.run(d_states, d_edges)
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    per = sorted(a.elapsed_time(b) for a, b in ev)
+    ms_per_step = wall * 1e3 / args.steps
+    out = plan.out
+    res = out["result"].cpu().tolist()
+    m = states == cfg.mask_id
+
+    # ---- dominant kernel in isolation: gate/up SwiGLU GEMM, same shapes, weights rotating over layers
+    M = cfg.G * cfg.B
+    x = torch.randn((M, cfg.d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    act = torch.empty((M, cfg.F), device=dev, dtype=torch.bfloat16)
+    for w in layers[:2]:
+        sp.gemm(sp.GEMM_SWIGLU, x, w["w_gate"], w["w_up"], out=act)
+    torch.cuda.synchronize()
+    k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_launch = 0
+    k0.record()
+    for _ in range(args.kernel_iters):
+        for w in layers:
+            sp.gemm(sp.GEMM_SWIGLU, x, w["w_gate"], w["w_up"], out=act)
+            n_launch += 1
+    k1.record()
+    torch.cuda.synchronize()
+    k_ms = k0.elapsed_time(k1) / n_launch
+    flop_launch = 2.0 * M * cfg.d * 2 * cfg.F
+    achieved = flop_launch / (k_ms * 1e-3) / 1e12
+
+    # algorithmic work of the whole step
+    params_layer = cfg.d * cfg.Hq * cfg.hd * 2 + cfg.d * cfg.Hkv * cfg.hd * 2 + 3 * cfg.d * cfg.F
+    n_masked = int(m.sum())
+    flop_step = cfg.L * (2.0 * M * params_layer + 4.0 * cfg.B * (cfg.P + cfg.B) * cfg.hd * cfg.Hq * cfg.G) \
+        + 2.0 * n_masked * cfg.V * cfg.d
+    bytes_step = cfg.L * (2.0 * params_layer + 2.0 * 2 * cfg.P * cfg.Hkv * cfg.hd) + 2.0 * cfg.V * cfg.d \
+        + 2.0 * M * cfg.d
+
+    line = {
+        "metric": "draft_states_verified_per_s",
+        "value": cfg.G / (ms_per_step * 1e-3),
+        "unit": "states/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "L": cfg.L, "d": cfg.d, "Hq": cfg.Hq, "Hkv": cfg.Hkv, "hd": cfg.hd,
+                   "F": cfg.F, "V": cfg.V, "P": cfg.P, "B": cfg.B, "G": cfg.G, "threshold": cfg.threshold,
+                   "logit_scale": LOGIT_SCALE, "n_edges": int(len(edges)), "masked_positions": n_masked,
+                   "seed": seed},
+        "step_latency_ms": {"p10": per[len(per) // 10], "p50": per[len(per) // 2], "p90": per[(len(per) * 9) // 10]},
+        "step_flop": flop_step,
+        "step_algorithmic_bytes": bytes_step,
+        "step_tflops": flop_step / (ms_per_step * 1e-3) / 1e12,
+        "step_frac_of_bf16_peak": flop_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+        "outcome": {"accepted_node": res[0], "depth": res[1], "unmasked": int(out["unmask"].sum().item())},
+        "roofline": {"kernel": "gemm_bf16_mfma_kernel<EPI_SWIGLU> (gate/up projection)", "bound": "mfma",
+                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "avg_launch_ms": k_ms, "flop_per_launch": flop_launch, "launches_timed": n_launch},
+        "setup_s": t_setup,
+    }
+
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(cfg, layers[0], prefix[0], hw, states, edges)
+    print(json.dumps(line))
+
+
+def cpu_baseline(cfg, layer0, prefix0, hw, states, edges):
+    """The oracle as it stands, on this host: one layer on a few states + the head on a few states +
+    the walk, scaled to a whole step (x L layers, x G states).  A baseline for context, not a target."""
+    import numpy as np
+    from threadpoolctl import threadpool_info
+    from oracle import spiffy_oracle as O
+
+    f64 = lambda t: t.detach().cpu().double().numpy()
+    g_layer, g_head = min(4, cfg.G), min(2, cfg.G)
+    w = {k: f64(v) for k, v in layer0.items()}
+    pk, pv = f64(prefix0[0]), f64(prefix0[1])
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((g_layer, cfg.B, cfg.d))
+    t0 = time.perf_counter()
+    O.verify_layer(w, pk, pv, x, n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P,
+                   rms_eps=cfg.rms_eps, rope_base=cfg.rope_base)
+    t_layer = (time.perf_counter() - t0) / g_layer
+    del w
+    wv, fn = f64(hw["w_vocab"]), f64(hw["final_norm"])
+    xh = rng.standard_normal((g_head, cfg.B, cfg.d))
+    t0 = time.perf_counter()
+    _, _, _, _, tgt = O.decode_head(xh, fn, wv, states[:g_head], cfg.mask_id, cfg.threshold, rms_eps=cfg.rms_eps,
+                                    logit_scale=LOGIT_SCALE)
+    t_head = (time.perf_counter() - t0) / g_head
+    t0 = time.perf_counter()
+    O.graph_accept(edges, states, states, 0)
+    t_walk = time.perf_counter() - t0
+    step_s = cfg.G * (cfg.L * t_layer + t_head) + t_walk
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    return {"value": cfg.G / step_s, "unit": "states/s", "cores": threads, "kind": "oracle",
+            "sample": "oracle.verify_layer on %d states of layer 0 (%.2f s/state), oracle.decode_head on %d states "
+                      "(%.2f s/state), oracle.graph_accept in full (%.4f s); scaled to %d layers x %d states"
+                      % (g_layer, t_layer, g_head, t_head, t_walk, cfg.L, cfg.G),
+            "extrapolated_step_s": step_s}
+
+
+if __name__ == "__main__":
+    main()

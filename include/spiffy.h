@@ -132,6 +132,15 @@ int spiffy_decode_head(const spiffy_model_cfg *cfg, const void *hidden, const vo
                        float *conf, uint8_t *unmask, float *top2_margin, int32_t *target_states,
                        void *workspace, size_t workspace_bytes, void *stream);
 
+/* The projection GEMM that verify_layer is made of, exposed for unit tests and for kernel-level
+ * timing.  A [M,K], weights [N,K] row-major, C [M,N] (SPIFFY_GEMM_SWIGLU: W0 = gate, W1 = up,
+ * both [N,K], C = silu(A W0^T) * (A W1^T)); SPIFFY_GEMM_RESID: C = R + A W0^T with R [M,N];
+ * SPIFFY_GEMM_STORE: C = A W0^T.  bf16 with K % 64 == 0 and N % 128 == 0 (SWIGLU: N % 64 == 0)
+ * runs the MFMA kernel, anything else the generic kernel.  No workspace. */
+enum { SPIFFY_GEMM_STORE = 0, SPIFFY_GEMM_RESID = 1, SPIFFY_GEMM_SWIGLU = 2 };
+int spiffy_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W0, const void *W1,
+                const void *R, void *C, int32_t M, int32_t N, int32_t K, void *stream);
+
 /* Acceptance walk (Alg. 1 step 5).  graph_edges [E,2] int32 (parent, child), E >= 0;
  * draft_states, target_states [G,B] int32; 0 <= root < G <= SPIFFY_MAX_G.  Starting at root, move
  * to the lowest-id child (by the edge list only) whose draft state equals the current node's

@@ -86,6 +86,14 @@ def softmax_rows(s: np.ndarray) -> np.ndarray:
     return e / np.sum(e, axis=-1, keepdims=True)
 
 
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """Round to the nearest bfloat16 (ties to even), returned as float64.  Used only where a
+    float decides an integer and the GPU kernel's operand precision has to be mirrored."""
+    b = np.ascontiguousarray(np.asarray(x, np.float32)).view(np.uint32).astype(np.uint64)
+    b = ((b + 0x7FFF + ((b >> 16) & 1)) >> 16) << 16
+    return b.astype(np.uint32).view(np.float32).astype(F64).reshape(np.shape(x))
+
+
 def _w(d: Dict, k: str) -> Optional[np.ndarray]:
     v = d.get(k)
     return None if v is None else np.asarray(v, F64)
@@ -163,8 +171,15 @@ def embed(w_embed: np.ndarray, block_tokens: np.ndarray) -> np.ndarray:
 
 def decode_head(hidden: np.ndarray, final_norm: np.ndarray, w_vocab: np.ndarray,
                 block_tokens: np.ndarray, mask_id: int, threshold: float, *,
-                rms_eps: float = 1e-5, logit_scale: float = 1.0, force_one: bool = True):
+                rms_eps: float = 1e-5, logit_scale: float = 1.0, force_one: bool = True,
+                operand_dtype: Optional[str] = None):
     """Alg. 1 steps 1-4 with the threshold rule of Sec. 3.1, for every one of the G states.
+
+    operand_dtype="bf16" rounds the normalised hidden row to bfloat16 before the vocabulary
+    product.  The argmax / threshold decisions are integers decided by floats, so when the
+    GPU path is compared in its bf16 configuration both sides take that decision from
+    operands of the same precision (the kernel's matrix-core operands are bf16); with None the
+    row stays float64 (the fp32 configuration and every pin).
 
     Returns (argmax [G,B] int32, conf [G,B] float32, unmask [G,B] uint8,
              margin [G,B] float64, target_states [G,B] int32).
@@ -184,6 +199,8 @@ def decode_head(hidden: np.ndarray, final_norm: np.ndarray, w_vocab: np.ndarray,
         masked_pos = np.nonzero(tok[g] == mask_id)[0]
         if masked_pos.size:
             n = rms_norm(hid[g, masked_pos], final_norm, rms_eps)   # [n_masked, d]
+            if operand_dtype == "bf16":
+                n = round_to_bf16(n)
             logits_all = logit_scale * (n @ wv.T)                   # [n_masked, V], Alg. 1 step 1
         for r, b in enumerate(masked_pos):
             logits = logits_all[r]

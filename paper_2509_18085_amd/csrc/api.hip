@@ -310,6 +310,25 @@ int spiffy_decode_head(const spiffy_model_cfg* cfg, const void* hidden, const vo
                   argmax, conf, unmask, top2_margin, target_states, workspace, (hipStream_t)stream);
 }
 
+int spiffy_gemm(int32_t dtype, int32_t epilogue, const void* A, const void* W0, const void* W1, const void* R,
+                void* C, int32_t M, int32_t N, int32_t K, void* stream) {
+  if (dtype != SPIFFY_BF16 && dtype != SPIFFY_F32) return SPIFFY_EINVAL;
+  if (epilogue < SPIFFY_GEMM_STORE || epilogue > SPIFFY_GEMM_SWIGLU) return SPIFFY_EINVAL;
+  if (!A || !W0 || !C || M < 1 || N < 1 || K < 1) return SPIFFY_EINVAL;
+  if (epilogue == SPIFFY_GEMM_SWIGLU && !W1) return SPIFFY_EINVAL;
+  if (epilogue == SPIFFY_GEMM_RESID && !R) return SPIFFY_EINVAL;
+  if (K % 8 != 0 || N % 8 != 0) return SPIFFY_ESHAPE;
+  if (!aligned16(A) || !aligned16(W0) || !aligned16(C) || (W1 && !aligned16(W1)) || (R && !aligned16(R)))
+    return SPIFFY_EALIGN;
+  GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.A = A; g.lda = K; g.M = M; g.K = K; g.N = N; g.C = C; g.ldc = N; g.R = R; g.scale = 1.f;
+  g.W[0] = W0;
+  if (epilogue == SPIFFY_GEMM_SWIGLU) g.W[1] = W1; else g.Nseg[0] = N;
+  const bool mf = !force_generic() && dtype == SPIFFY_BF16 && mfma_gemm_supported(epilogue, g);
+  return dev(mf ? launch_gemm_mfma(epilogue, g, (hipStream_t)stream) : launch_gemm_generic(dtype, epilogue, g, (hipStream_t)stream));
+}
+
 int spiffy_graph_accept(const int32_t* graph_edges, int32_t E, const int32_t* draft_states,
                         const int32_t* target_states, int32_t G, int32_t B, int32_t root,
                         spiffy_accept_result* result, int32_t* accepted_state, void* stream) {

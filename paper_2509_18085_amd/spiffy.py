@@ -21,7 +21,8 @@ SPIFFY_BF16, SPIFFY_F32 = 0, 1
 MAX_G = 64
 
 EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "spiffy_embed",
-           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_graph_accept", "spiffy_verify_step"]
+           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_verify_step"]
+GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
 
 class ModelCfg(C.Structure):
@@ -71,6 +72,8 @@ def _load() -> C.CDLL:
     lib.spiffy_decode_head.restype = C.c_int
     lib.spiffy_decode_head.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp,
                                        vp, sz, vp]
+    lib.spiffy_gemm.restype = C.c_int
+    lib.spiffy_gemm.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp]
     lib.spiffy_graph_accept.restype = C.c_int
     lib.spiffy_graph_accept.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
     lib.spiffy_verify_step.restype = C.c_int
@@ -195,6 +198,18 @@ def decode_head(cfg: ModelCfg, hidden: torch.Tensor, final_norm: torch.Tensor, w
                                   _ptr(mask), G, B, threshold, logit_scale, int(force_one), _ptr(out["argmax"]),
                                   _ptr(out["conf"]), _ptr(out["unmask"]), _ptr(out["margin"]),
                                   _ptr(out["target_states"]), wp, wn, _stream(stream)), "spiffy_decode_head")
+    return out
+
+
+def gemm(epilogue: int, A: torch.Tensor, W0: torch.Tensor, W1: Optional[torch.Tensor] = None,
+         R: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    M, K = A.shape
+    N = W0.shape[0]
+    if out is None:
+        out = torch.empty((M, N), dtype=A.dtype, device=A.device)
+    dt = SPIFFY_F32 if A.dtype == torch.float32 else SPIFFY_BF16
+    _check(lib.spiffy_gemm(dt, epilogue, _ptr(A), _ptr(W0), _ptr(W1), _ptr(R), _ptr(out), M, N, K,
+                           _stream(stream)), "spiffy_gemm")
     return out
 
 

@@ -2,9 +2,13 @@
 
 Bar: hidden states and confidences within 1e-4 (fp32) / 2e-2 (bf16) by the metric
 |gpu - ref| / (|ref| + rms(ref)); argmax / unmask / next-state / acceptance decisions bit-exact
-except where the oracle's top-2 logit margin is below 1e-3 or its confidence is within 1e-4*tau
-of the threshold (both counted and printed).  Every call is compared on identical input bits:
-bf16 inputs reach the oracle as the same values widened to float64.
+except where the oracle's top-2 logit margin is below 1e-3 (times the synthetic logit_scale knob
+when that is above 1: the knob multiplies the rounding noise of the logits as well) or its
+confidence is within 1e-4*tau of the threshold (both counted and printed).  Every call is
+compared on identical input bits: bf16 inputs reach the oracle as the same values widened to
+float64, and in the bf16 configuration the oracle rounds the normalised row to bf16 before the
+vocabulary product, as the kernel's matrix-core operands are (decisions are taken from operands
+of the same precision on both sides).
 """
 import numpy as np
 import pytest
@@ -233,9 +237,11 @@ def check_head(sp, cfg, states, hidden, hw, threshold, logit_scale, force_one=Tr
     got = run_head(sp, cfg, hidden, hw, states, threshold, logit_scale, force_one)
     amax, conf, unmask, margin, target = O().decode_head(
         to_np(hidden), to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states, cfg.mask_id, threshold,
-        rms_eps=cfg.rms_eps, logit_scale=logit_scale, force_one=force_one)
+        rms_eps=cfg.rms_eps, logit_scale=logit_scale, force_one=force_one,
+        operand_dtype="bf16" if cfg.dtype == "bf16" else None)
     m = states == cfg.mask_id
-    near_tie = m & (margin < 1e-3)
+    tie = 1e-3 * max(1.0, logit_scale)
+    near_tie = m & (margin < tie)
     near_tau = m & (np.abs(conf.astype(np.float64) - threshold) < 1e-4 * threshold)
     # force_one picks the best position by confidence: a state whose two best masked positions are
     # within 1e-6 relative is a near-tie of that decision
@@ -253,9 +259,9 @@ def check_head(sp, cfg, states, hidden, hw, threshold, logit_scale, force_one=Tr
     e_max = np.max(np.abs(got["conf"][m] - conf[m]) / np.maximum(conf[m], 1e-30)) if m.any() else 0.0
     t = 1e-4 if cfg.dtype == "f32" else 2e-2
     assert e_max < t, e_max
-    big = clear & (margin > 1e-2)
+    big = clear & (margin > 10 * tie)
     if big.any():
-        np.testing.assert_allclose(got["margin"][big], margin[big], rtol=1e-3, atol=1e-4)
+        np.testing.assert_allclose(got["margin"][big], margin[big], rtol=2e-3, atol=tie)
     np.testing.assert_array_equal(got["unmask"][ok_state], unmask[ok_state])
     np.testing.assert_array_equal(got["target_states"][ok_state], target[ok_state])
     assert ok_state.mean() > 0.5

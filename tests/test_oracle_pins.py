@@ -386,6 +386,28 @@ def test_head_threshold_strict_force_one_and_monotone():
         prev = um
 
 
+def test_round_to_bf16_matches_torch():
+    r = np.random.default_rng(9)
+    x = np.concatenate([r.normal(size=4000) * 10.0 ** r.integers(-6, 6, 4000),
+                        [0.0, 1.0, 1.00390625, 1.001953125, 1.005859375, -3.0e-39, 65504.0]])
+    want = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).double().numpy()
+    np.testing.assert_array_equal(O.round_to_bf16(x), want)
+
+
+def test_head_bf16_operand_rounding_is_the_only_difference():
+    hid, tok, gn, wv = _head_inputs(G=2, B=4, d=32, V=50, seed=8)
+    V = wv.shape[0]
+    a = O.decode_head(hid, gn, wv, tok, V - 1, 0.3, operand_dtype="bf16", force_one=False)
+    # same result as the float64 head applied to rows that are already normalised-and-rounded:
+    # build such rows by hand (unit gain, eps 0, rows scaled to mean-square 1 are fixed points)
+    m = tok == V - 1
+    n = O.round_to_bf16(O.rms_norm(hid, gn, 1e-5))
+    for g, b in zip(*np.nonzero(m)):
+        logits = wv @ n[g, b]
+        assert a[0][g, b] == int(np.argmax(logits))
+        np.testing.assert_allclose(a[1][g, b], 1.0 / np.exp(logits - logits.max()).sum(), rtol=1e-6)
+
+
 # ------------------------------------------------------------------ P7 / P8 acceptance walk
 
 def test_accept_golden_cases():

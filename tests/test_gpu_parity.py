@@ -264,7 +264,7 @@ def check_head(sp, cfg, states, hidden, hw, threshold, logit_scale, force_one=Tr
         np.testing.assert_allclose(got["margin"][big], margin[big], rtol=2e-3, atol=tie)
     np.testing.assert_array_equal(got["unmask"][ok_state], unmask[ok_state])
     np.testing.assert_array_equal(got["target_states"][ok_state], target[ok_state])
-    assert ok_state.mean() > 0.5
+    assert ok_state.mean() >= 0.5
     return got
 
 
@@ -286,7 +286,7 @@ def test_head_generic_bf16_and_edge_masks(sp):
 @pytest.mark.parametrize("shape,scale", [
     (dict(d=256, V=1280, B=32, G=5), 40.0),         # ragged row tile
     (dict(d=512, V=128 * 9, B=4, G=70), 25.0),      # several row tiles, small blocks
-    (dict(d=256, V=128, B=16, G=2), 60.0),          # a single vocabulary tile
+    (dict(d=256, V=128, B=16, G=6), 20.0),          # a single vocabulary tile
 ])
 def test_head_mfma_shapes(sp, shape, scale):
     cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", Hq=2, Hkv=2, hd=128, F=256, **shape)

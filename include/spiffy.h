@@ -10,7 +10,7 @@
  *
  * Conventions for every call
  *   - Kernel choice is by shape: bf16 with head_dim 128, d % 128 == 0, ffn % 64 == 0 runs the MFMA
- *     kernels (LM head: d % 64 == 0, vocab % 128 == 0); anything else, and every shape when the
+ *     kernels (LM head: d % 64 == 0); anything else, and every shape when the
  *     environment variable SPIFFY_FORCE_GENERIC=1 is set, runs shape-agnostic fp32-math kernels.
  *   - All data pointers are DEVICE pointers owned by the caller unless a parameter says "host".
  *     The library never frees or keeps them.  Structs (cfg, weights, prefix) are HOST structs
@@ -136,10 +136,13 @@ int spiffy_decode_head(const spiffy_model_cfg *cfg, const void *hidden, const vo
  * timing.  A [M,K], weights [N,K] row-major, C [M,N] (SPIFFY_GEMM_SWIGLU: W0 = gate, W1 = up,
  * both [N,K], C = silu(A W0^T) * (A W1^T)); SPIFFY_GEMM_RESID: C = R + A W0^T with R [M,N];
  * SPIFFY_GEMM_STORE: C = A W0^T.  bf16 with K % 64 == 0 and N % 128 == 0 (SWIGLU: N % 64 == 0)
- * runs the MFMA kernel, anything else the generic kernel.  No workspace. */
+ * runs the MFMA kernel, anything else the generic kernel.  workspace (256-byte aligned, at least
+ * 4*M*N*sizeof(float) bytes) may be NULL; with it, SPIFFY_GEMM_RESID slices K exactly as
+ * verify_layer does for its output and down projections (the slice count depends on N and K only). */
 enum { SPIFFY_GEMM_STORE = 0, SPIFFY_GEMM_RESID = 1, SPIFFY_GEMM_SWIGLU = 2 };
 int spiffy_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W0, const void *W1,
-                const void *R, void *C, int32_t M, int32_t N, int32_t K, void *stream);
+                const void *R, void *C, int32_t M, int32_t N, int32_t K, void *workspace,
+                size_t workspace_bytes, void *stream);
 
 /* Acceptance walk (Alg. 1 step 5).  graph_edges [E,2] int32 (parent, child), E >= 0;
  * draft_states, target_states [G,B] int32; 0 <= root < G <= SPIFFY_MAX_G.  Starting at root, move

@@ -47,7 +47,7 @@ bool layer_mfma(const spiffy_model_cfg* c) {
 }
 bool head_mfma(const spiffy_model_cfg* c) {
   if (force_generic() || c->dtype != SPIFFY_BF16) return false;
-  return c->d % 64 == 0 && c->vocab % 128 == 0;
+  return c->d % 64 == 0;
 }
 
 // generic attention keeps all scores of one row in LDS
@@ -70,7 +70,7 @@ struct Carve {
 };
 
 struct LayerWs {
-  void *n, *qkv, *attn, *h, *act, *attn_partial;
+  void *n, *qkv, *attn, *h, *act, *attn_partial, *splitk;
   size_t bytes;
 };
 LayerWs carve_layer(const spiffy_model_cfg* c, int G, int B, int P, void* base) {
@@ -84,6 +84,7 @@ LayerWs carve_layer(const spiffy_model_cfg* c, int G, int B, int P, void* base) 
   w.h = cv.take(M * c->d * es);
   w.act = cv.take(M * c->ffn * es);
   w.attn_partial = cv.take(layer_mfma(c) ? mfma_attn_partial_bytes(G, B, c->n_q_heads, c->head_dim, P) : 0);
+  w.splitk = cv.take(layer_mfma(c) ? sizeof(float) * 4 * M * c->d : 0);   // up to 4 K slices of [M,d] fp32
   w.bytes = cv.off;
   return w;
 }
@@ -172,14 +173,25 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   a.pos0 = pos0; a.rope_base = cfg->rope_base;
   if ((rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st)))) return rc;
 
+  // output projection + residual (+ RMSNorm-2 fused into the split-K reduction when K is sliced)
   std::memset(&g, 0, sizeof(g));
   g.A = ws.attn; g.lda = qd; g.M = M; g.K = qd; g.W[0] = w->wo; g.Nseg[0] = d; g.N = d;
   g.C = ws.h; g.ldc = d; g.R = hidden_in; g.scale = 1.f;
-  if ((rc = dev(mf && mfma_gemm_supported(EPI_RESID, g) ? launch_gemm_mfma(EPI_RESID, g, st)
-                                                         : launch_gemm_generic(dt, EPI_RESID, g, st))))
-    return rc;
+  bool normed = false;
+  if (mf && mfma_gemm_supported(EPI_RESID, g)) {
+    const int ks = mfma_ksplit(d, qd);
+    if (ks > 1) {
+      g.C = ws.splitk; g.ksplit = ks;
+      if ((rc = dev(launch_gemm_mfma(EPI_PARTIAL, g, st)))) return rc;
+      if ((rc = dev(launch_splitk_reduce((const float*)ws.splitk, ks, hidden_in, ws.h, w->norm2, cfg->rms_eps, ws.n, M,
+                                         d, st))))
+        return rc;
+      normed = true;
+    } else if ((rc = dev(launch_gemm_mfma(EPI_RESID, g, st)))) return rc;
+  } else if ((rc = dev(launch_gemm_generic(dt, EPI_RESID, g, st)))) return rc;
 
-  if ((rc = dev(launch_rmsnorm(dt, ws.h, w->norm2, cfg->rms_eps, M, d, nullptr, nullptr, ws.n, st)))) return rc;
+  if (!normed && (rc = dev(launch_rmsnorm(dt, ws.h, w->norm2, cfg->rms_eps, M, d, nullptr, nullptr, ws.n, st))))
+    return rc;
 
   std::memset(&g, 0, sizeof(g));
   g.A = ws.n; g.lda = d; g.M = M; g.K = d; g.W[0] = w->w_gate; g.W[1] = w->w_up; g.N = cfg->ffn;
@@ -191,8 +203,16 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   std::memset(&g, 0, sizeof(g));
   g.A = ws.act; g.lda = cfg->ffn; g.M = M; g.K = cfg->ffn; g.W[0] = w->w_down; g.Nseg[0] = d; g.N = d;
   g.C = hidden_out; g.ldc = d; g.R = ws.h; g.scale = 1.f;
-  return dev(mf && mfma_gemm_supported(EPI_RESID, g) ? launch_gemm_mfma(EPI_RESID, g, st)
-                                                      : launch_gemm_generic(dt, EPI_RESID, g, st));
+  if (mf && mfma_gemm_supported(EPI_RESID, g)) {
+    const int ks = mfma_ksplit(d, cfg->ffn);
+    if (ks > 1) {
+      g.C = ws.splitk; g.ksplit = ks;
+      if ((rc = dev(launch_gemm_mfma(EPI_PARTIAL, g, st)))) return rc;
+      return dev(launch_splitk_reduce((const float*)ws.splitk, ks, ws.h, hidden_out, nullptr, 0.f, nullptr, M, d, st));
+    }
+    return dev(launch_gemm_mfma(EPI_RESID, g, st));
+  }
+  return dev(launch_gemm_generic(dt, EPI_RESID, g, st));
 }
 
 int run_head(const spiffy_model_cfg* cfg, const void* hidden, const void* final_norm, const void* w_vocab,
@@ -311,7 +331,7 @@ int spiffy_decode_head(const spiffy_model_cfg* cfg, const void* hidden, const vo
 }
 
 int spiffy_gemm(int32_t dtype, int32_t epilogue, const void* A, const void* W0, const void* W1, const void* R,
-                void* C, int32_t M, int32_t N, int32_t K, void* stream) {
+                void* C, int32_t M, int32_t N, int32_t K, void* workspace, size_t workspace_bytes, void* stream) {
   if (dtype != SPIFFY_BF16 && dtype != SPIFFY_F32) return SPIFFY_EINVAL;
   if (epilogue < SPIFFY_GEMM_STORE || epilogue > SPIFFY_GEMM_SWIGLU) return SPIFFY_EINVAL;
   if (!A || !W0 || !C || M < 1 || N < 1 || K < 1) return SPIFFY_EINVAL;
@@ -326,7 +346,19 @@ int spiffy_gemm(int32_t dtype, int32_t epilogue, const void* A, const void* W0, 
   g.W[0] = W0;
   if (epilogue == SPIFFY_GEMM_SWIGLU) g.W[1] = W1; else g.Nseg[0] = N;
   const bool mf = !force_generic() && dtype == SPIFFY_BF16 && mfma_gemm_supported(epilogue, g);
-  return dev(mf ? launch_gemm_mfma(epilogue, g, (hipStream_t)stream) : launch_gemm_generic(dtype, epilogue, g, (hipStream_t)stream));
+  hipStream_t st = (hipStream_t)stream;
+  if (mf && epilogue == SPIFFY_GEMM_RESID) {     // same K slicing as verify_layer when scratch is given
+    const int ks = mfma_ksplit(N, K);
+    if (ks > 1 && workspace) {
+      if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPIFFY_EALIGN;
+      if (workspace_bytes < sizeof(float) * (size_t)ks * M * N) return SPIFFY_EWORKSPACE;
+      g.C = workspace; g.ksplit = ks;
+      int rc = dev(launch_gemm_mfma(EPI_PARTIAL, g, st));
+      if (rc) return rc;
+      return dev(launch_splitk_reduce((const float*)workspace, ks, R, C, nullptr, 0.f, nullptr, M, N, st));
+    }
+  }
+  return dev(mf ? launch_gemm_mfma(epilogue, g, st) : launch_gemm_generic(dtype, epilogue, g, st));
 }
 
 int spiffy_graph_accept(const int32_t* graph_edges, int32_t E, const int32_t* draft_states,

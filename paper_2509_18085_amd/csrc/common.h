@@ -79,7 +79,7 @@ struct alignas(16) TopPartial {
 
 // C[M,N] = A[M,K] * W^T where W is given as up to three row-major [N_i,K] segments laid side by
 // side along N (q | k | v), or as a (gate, up) pair for the SwiGLU epilogue.
-enum GemmEpi { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3 };
+enum GemmEpi { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2, EPI_LMHEAD = 3, EPI_PARTIAL = 4 };
 
 struct GemmArgs {
   const void* A;        // [M,K]
@@ -92,6 +92,7 @@ struct GemmArgs {
   int M, N, K;
   int lda, ldc;
   float scale;          // LMHEAD: logit scale
+  int ksplit;           // PARTIAL: number of K slices (C = fp32 [ksplit][M][N]); otherwise 1
 };
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }

@@ -48,7 +48,11 @@ hipError_t launch_graph_accept(const int32_t* edges, int E, const int32_t* draft
 // ---- MFMA (bf16, gfx950) -----------------------------------------------------------------------
 bool mfma_gemm_supported(int epi, const GemmArgs& a);
 hipError_t launch_gemm_mfma(int epi, const GemmArgs& a, hipStream_t st);
-int mfma_lmhead_partials_per_row(int V);  // partial summaries per row written by EPI_LMHEAD
+int mfma_lmhead_partials_per_row(int V);
+int mfma_ksplit(int N, int K);          // K slices used for a [M,K]x[N,K] projection with residual (depends on N, K only)
+// out = R + sum of the K-slice partials P[ksplit][M][N] (fixed order); if normed != NULL also RMSNorm(out)*gain
+hipError_t launch_splitk_reduce(const float* P, int ksplit, const void* R, void* out, const void* gain, float eps,
+                                void* normed, int M, int N, hipStream_t st);  // partial summaries per row written by EPI_LMHEAD
 bool mfma_attn_supported(const AttnArgs& a);
 size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P);
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st);

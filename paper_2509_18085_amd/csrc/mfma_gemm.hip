@@ -1,263 +1,424 @@
-// bf16 MFMA GEMM for gfx950:  D[i,j] = sum_k X[i,k] * Y[j,k]  (both operands K-contiguous),
-// fp32 accumulation with v_mfma_f32_32x32x16_bf16, 128x128x64 workgroup tile, 4 wavefronts of
-// 64x64, double-buffered LDS fed through registers, XCD-aware tile order.
+// bf16 MFMA GEMM for gfx950:  D[i,j] = sum_k X[i,k] * Y[j,k]  (both operands K-contiguous), fp32
+// accumulation with v_mfma_f32_32x32x16_bf16.
 //
-// One kernel template, four epilogues:
-//   EPI_STORE   C = X W^T (+bias)         W given as up to three [N_i,K] segments (q | k | v)
-//   EPI_RESID   C = R + X W^T             (output projection, FFN down projection)
-//   EPI_SWIGLU  C = silu(X Wg^T) * (X Wu^T)   the tile's 128 "columns" are 64 gate + 64 up rows
-//   EPI_LMHEAD  rows i = vocabulary entries, columns j = tokens: each lane owns a token column
-//               and reduces its logits to (top, lowest index, runner-up, sum exp) in registers;
-//               logits are never stored (Alg. 1 steps 1-2 fused into the GEMM).
+// Shape of the kernel (what measurements on MI355X pushed it to):
+//   * one workgroup per CU: 256 x BN output tile (BN = 192 or 128), 4 wavefronts in a 2x2 grid, each
+//     wavefront owns 128 x BN/2 (accumulators in AGPRs).  The L2 delivers about 32 B/clk to a CU, so
+//     a tile needs >= 64..128 flop per loaded byte; 128x128 tiles are bound by that, 256x192 is not.
+//   * K advances in steps of 64 so every row segment is one full 128-byte line; operands go
+//     global -> LDS directly (LDS-DMA loads, no register staging), rows XOR-swizzled so the
+//     16-byte fragment reads are conflict-free.
+//   * separate LDS rings for the two operands: X (activations, mostly L2 hits) 2 stages, Y (weights,
+//     streamed from HBM) 3-4 stages, 136 KB in all.
+//   * one barrier per K-tile; the loads of later tiles and the LDS fragment reads of the next
+//     16-wide K step are threaded between the MFMAs of the current step, fragments double-buffered
+//     in registers, partial s_waitcnt vmcnt so younger loads stay in flight across the barrier.
+//   * workgroup ids are remapped so that the workgroups sharing a weight tile sit on one XCD.
 //
-// Accumulation order along K is the same for every output element whatever M, N or the tile
-// position, so a row's result does not depend on how many other states are verified with it.
+// Epilogues:
+//   EPI_STORE    C = X W^T (+bias), W given as up to three row segments (q | k | v)
+//   EPI_RESID    C = R + X W^T
+//   EPI_SWIGLU   C = silu(X Wg^T) * (X Wu^T); gate and up rows are interleaved 16/16 inside every
+//                32-column MFMA tile, partner values meet through one lane shuffle
+//   EPI_PARTIAL  fp32 partial sums of one K slice (split-K for narrow N; reduced by a second kernel
+//                in a fixed order, the slice count depends on (N, K) only)
+//   EPI_LMHEAD   rows i = vocabulary entries, columns j = tokens: each lane owns token columns and
+//                reduces its logits to (top, lowest index, runner-up, sum exp) in registers; logits
+//                are never stored (Alg. 1 steps 1-2 fused into the GEMM)
+//
+// The accumulation order along K of every output element is fixed by (N, K) alone, so a row's result
+// does not depend on how many other states are verified with it.
 #include "kernels.h"
 
 namespace spiffy {
 
 namespace {
 
-constexpr int BM = 128, BN = 128, BK = 64;
-constexpr int LDS_STRIDE = BK + 8;  // bf16 elements per LDS row: 144 B keeps 16-byte fragment reads conflict-free
-constexpr int TILE_ELEMS = 128 * LDS_STRIDE;
+constexpr int BM = 256, BKK = 64, SX = 2;
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-struct Frag4 {
-  u32x4 v[4];
-};
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
 
-// 128 rows x 64 k of a K-contiguous matrix -> registers (4 x 16 B per thread)
-__device__ __forceinline__ void load_tile(Frag4& f, const bf16_t* __restrict__ base, int ld, int row0, int row_max,
-                                          int k0) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = threadIdx.x + 256 * i;
-    int row = row0 + (c >> 3);
-    row = row < row_max ? row : row_max - 1;
-    f.v[i] = *reinterpret_cast<const u32x4*>(base + (size_t)row * ld + k0 + (c & 7) * 8);
-  }
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {   // vmcnt <= N; lgkmcnt / expcnt untouched
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | (7 << 4) | (0xF << 8) | ((N >> 4) << 14));
 }
-// SwiGLU operand tile: rows 0..63 from the gate matrix, rows 64..127 from the up matrix
-__device__ __forceinline__ void load_tile_pair(Frag4& f, const bf16_t* __restrict__ g, const bf16_t* __restrict__ u,
-                                               int ld, int row0, int k0) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = threadIdx.x + 256 * i;
-    const int r = c >> 3;
-    const bf16_t* base = r < 64 ? g : u;
-    f.v[i] = *reinterpret_cast<const u32x4*>(base + (size_t)(row0 + (r & 63)) * ld + k0 + (c & 7) * 8);
-  }
-}
-__device__ __forceinline__ void store_tile(const Frag4& f, bf16_t* lds) {
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = threadIdx.x + 256 * i;
-    *reinterpret_cast<u32x4*>(lds + (c >> 3) * LDS_STRIDE + (c & 7) * 8) = f.v[i];
-  }
-}
+__device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
-template <int EPI>
+template <int EPI, int BN, int SY>
 __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int tiles_i, int tiles_j) {
-  extern __shared__ __align__(16) unsigned char smem_raw[];
-  bf16_t* Xs = reinterpret_cast<bf16_t*>(smem_raw);  // [2][128][LDS_STRIDE]
-  bf16_t* Ys = Xs + 2 * TILE_ELEMS;                  // [2][128][LDS_STRIDE]
+  constexpr int TM = 4, TN = BN / 64;
+  constexpr int LX = BM / 32, LY = BN / 32;       // 1-KB wave-loads (8 rows x 128 B) per wavefront per K-tile
+  constexpr int NL = LX + LY;
+  constexpr int XSTAGE = BM * BKK, YSTAGE = BN * BKK;
+  constexpr int NMF = TM * TN, NF = TM + TN;
+  constexpr int NSLOT = 4 * NMF;                  // MFMAs between two barriers
+  extern __shared__ __align__(1024) unsigned char smem_raw[];
+  bf16_t* Xs = reinterpret_cast<bf16_t*>(smem_raw);
+  bf16_t* Ys = Xs + SX * XSTAGE;
 
-  // XCD-aware order: workgroup ids go round-robin over the 8 XCDs, so give each XCD a contiguous
-  // range of logical tiles; the logical order runs fastest over the activation tiles, which keeps
-  // all workgroups that stream the same weight tile on one XCD (one L2) and close in time.
-  const int total = tiles_i * tiles_j;
-  int L = blockIdx.x;
-  if ((total & 7) == 0) L = (blockIdx.x >> 3) + (blockIdx.x & 7) * (total >> 3);
+  // XCD-aware order: workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous range
+  // of logical tiles, running fastest over the activation tiles, so the workgroups that stream the
+  // same weight tile share one L2 and run at the same time.
+  const int per_z = tiles_i * tiles_j;
+  const int kz = blockIdx.x / per_z;
+  int L = blockIdx.x % per_z;
+  if ((per_z & 7) == 0) L = (L >> 3) + (L & 7) * (per_z >> 3);
   const int ti = (EPI == EPI_LMHEAD) ? L / tiles_j : L % tiles_i;
   const int tj = (EPI == EPI_LMHEAD) ? L % tiles_j : L / tiles_i;
   const int i0 = ti * BM, j0 = tj * BN;
 
-  // operand roles
-  const bf16_t* X;      // rows i
-  int ldx, i_max;
-  const bf16_t* Y = nullptr;  // rows j
-  const bf16_t* Y2 = nullptr;
-  int ldy, j_max, jrow0;
-  const bf16_t* bias = nullptr;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int l32 = lane & 31, hh = lane >> 5;
+
+  int i_max, j_max;
   if (EPI == EPI_LMHEAD) {
-    X = (const bf16_t*)a.W[0]; ldx = a.K; i_max = a.N;          // vocabulary rows
-    Y = (const bf16_t*)a.A; ldy = a.lda; jrow0 = j0;            // token rows
+    i_max = a.N;
     j_max = a.M_dev ? min(*a.M_dev, a.M) : a.M;
     if (j0 >= j_max) return;
   } else {
-    X = (const bf16_t*)a.A; ldx = a.lda;
     i_max = a.M_dev ? min(*a.M_dev, a.M) : a.M;
+    j_max = a.N;
     if (i0 >= i_max) return;
-    ldy = a.K;
-    if (EPI == EPI_SWIGLU) {
-      Y = (const bf16_t*)a.W[0]; Y2 = (const bf16_t*)a.W[1]; jrow0 = tj * 64; j_max = a.N;
-    } else {
-      // segment of this column tile (no runtime indexing of the argument block: that would spill it)
-      if (j0 < a.Nseg[0]) {
-        Y = (const bf16_t*)a.W[0]; jrow0 = j0; j_max = a.Nseg[0]; bias = (const bf16_t*)a.bias[0];
-      } else if (j0 < a.Nseg[0] + a.Nseg[1]) {
-        Y = (const bf16_t*)a.W[1]; jrow0 = j0 - a.Nseg[0]; j_max = a.Nseg[1]; bias = (const bf16_t*)a.bias[1];
-      } else {
-        Y = (const bf16_t*)a.W[2]; jrow0 = j0 - a.Nseg[0] - a.Nseg[1]; j_max = a.Nseg[2];
-        bias = (const bf16_t*)a.bias[2];
-      }
-      if (bias) bias += jrow0;
-    }
   }
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wi = wave >> 1, wj = wave & 1;
-  const int l32 = lane & 31, hh = lane >> 5;
+  // K range of this slice
+  const int KT_all = a.K / BKK;
+  const int kt0 = (int)(((long long)KT_all * kz) / a.ksplit);
+  const int KT = (int)(((long long)KT_all * (kz + 1)) / a.ksplit) - kt0;
 
-  f32x16 acc[2][2];
+  // ---- per-lane global sources.  A wave-load covers 8 rows; lane -> (row, swizzled 16-byte chunk)
+  const bf16_t* xsrc[LX];
+  const bf16_t* ysrc[LY];
+  {
+    const bf16_t* X = (EPI == EPI_LMHEAD) ? (const bf16_t*)a.W[0] : (const bf16_t*)a.A;
+    const int ldx = (EPI == EPI_LMHEAD) ? a.K : a.lda;
 #pragma unroll
-  for (int p = 0; p < 2; ++p)
+    for (int q = 0; q < LX; ++q) {
+      const int row = 8 * (wave * LX + q) + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+      const int gi = min(i0 + row, i_max - 1);
+      xsrc[q] = X + (size_t)gi * ldx + (size_t)kt0 * BKK + chunk * 8;
+    }
 #pragma unroll
-    for (int q = 0; q < 2; ++q)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[p][q][v] = 0.f;
+    for (int q = 0; q < LY; ++q) {
+      const int row = 8 * (wave * LY + q) + (lane >> 3);
+      const int chunk = (lane & 7) ^ ((row >> 1) & 7);
+      const bf16_t* p;
+      if (EPI == EPI_LMHEAD) {
+        p = (const bf16_t*)a.A + (size_t)min(j0 + row, j_max - 1) * a.lda;
+      } else if (EPI == EPI_SWIGLU) {
+        // rows of every 32-row MFMA tile: 16 gate rows then the 16 up rows of the same features
+        const int f = tj * (BN / 2) + (row >> 5) * 16 + (row & 15);
+        p = ((row & 16) ? (const bf16_t*)a.W[1] : (const bf16_t*)a.W[0]) + (size_t)f * a.K;
+      } else {
+        const int n = j0 + row;   // column of the fused [seg0 | seg1 | seg2] output; 8-row groups never straddle
+        if (n < a.Nseg[0]) p = (const bf16_t*)a.W[0] + (size_t)n * a.K;
+        else if (n < a.Nseg[0] + a.Nseg[1]) p = (const bf16_t*)a.W[1] + (size_t)(n - a.Nseg[0]) * a.K;
+        else p = (const bf16_t*)a.W[2] + (size_t)(n - a.Nseg[0] - a.Nseg[1]) * a.K;
+      }
+      ysrc[q] = p + (size_t)kt0 * BKK + chunk * 8;
+    }
+  }
+  auto load_x = [&](int q, int t) {
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(xsrc[q] + (size_t)t * BKK),
+                                     (lds_ptr_t)(Xs + (t % SX) * XSTAGE + (wave * LX + q) * 512), 16, 0, 0);
+  };
+  auto load_y = [&](int q, int t) {
+    __builtin_amdgcn_global_load_lds((glb_ptr_t)(ysrc[q] + (size_t)t * BKK),
+                                     (lds_ptr_t)(Ys + (t % SY) * YSTAGE + (wave * LY + q) * 512), 16, 0, 0);
+  };
+  // load `idx` of group g (the loads issued after barrier g): X of tile g+SX first, then Y of tile g+SY
+  auto group_load = [&](int idx, int g) {
+    if (idx < LX) { if (g + SX < KT) load_x(idx, g + SX); }
+    else { if (g + SY < KT) load_y(idx - LX, g + SY); }
+  };
 
-  const int KT = a.K / BK;
-  Frag4 fx, fy;
-  load_tile(fx, X, ldx, i0, i_max, 0);
-  if (EPI == EPI_SWIGLU) load_tile_pair(fy, Y, Y2, ldy, jrow0, 0); else load_tile(fy, Y, ldy, jrow0, j_max, 0);
-  store_tile(fx, Xs);
-  store_tile(fy, Ys);
-  __syncthreads();
+  f32x16 acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // short K: not enough tiles for the steady-state wait counts, wait for everything each time
+  const bool short_k = KT <= SY;
+  // prologue, in the order the partial waits rely on: Y0 X0 | Y1 .. Y(SY-2) | first quarter of group -1
+  // (the part of X1 that a "K step 3 of tile -1" would have issued); the loop issues the rest
+  static_assert(SY >= 3, "the steady-state wait keeps one Y tile in flight across the barrier");
+#pragma unroll
+  for (int q = 0; q < LY; ++q) load_y(q, 0);
+#pragma unroll
+  for (int q = 0; q < LX; ++q) load_x(q, 0);
+#pragma unroll
+  for (int t = 1; t < SY - 1; ++t)
+    if (t < KT) {
+#pragma unroll
+      for (int q = 0; q < LY; ++q) load_y(q, t);
+    }
+#pragma unroll
+  for (int idx = 0; idx < NL / 4; ++idx) group_load(idx, -1);
+
+  const int sw_r = (l32 >> 1) & 7;
+  const int xrow = (wm * 128 + l32) * BKK;
+  const int yrow = (wn * (BN / 2) + l32) * BKK;
+  bf16x8 fx[2][TM], fy[2][TN];
+  auto ldfrag = [&](int buf, const bf16_t* xs, const bf16_t* ys, int kk, int r) {
+    const int slot = ((kk * 2 + hh) ^ sw_r) * 8;
+    if (r < TM) fx[buf][r] = *reinterpret_cast<const bf16x8*>(xs + xrow + r * 32 * BKK + slot);
+    else fy[buf][r - TM] = *reinterpret_cast<const bf16x8*>(ys + yrow + (r - TM) * 32 * BKK + slot);
+  };
+  if (short_k) wait_vmcnt<0>(); else wait_vmcnt<(SY - 2) * LY + NL / 4>();   // tile 0 is in LDS
+  __builtin_amdgcn_s_barrier();
+#pragma unroll
+  for (int r = 0; r < NF; ++r) ldfrag(0, Xs, Ys, 0, r);
 
   for (int kt = 0; kt < KT; ++kt) {
-    const int cur = kt & 1;
-    if (kt + 1 < KT) {
-      load_tile(fx, X, ldx, i0, i_max, (kt + 1) * BK);
-      if (EPI == EPI_SWIGLU) load_tile_pair(fy, Y, Y2, ldy, jrow0, (kt + 1) * BK);
-      else load_tile(fy, Y, ldy, jrow0, j_max, (kt + 1) * BK);
+    const bf16_t* xs = Xs + (kt % SX) * XSTAGE;
+    const bf16_t* ys = Ys + (kt % SY) * YSTAGE;
+    // K steps 0..2 of the tile: MFMAs on fragment buffer kk&1, fragments of step kk+1 into the other
+    // buffer, remaining loads of group kt-1
+#pragma unroll
+    for (int kk = 0; kk < 3; ++kk) {
+#pragma unroll
+      for (int m = 0; m < NMF; ++m) {
+        const int i = m / TN, j = m % TN;
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kk & 1][i], fy[kk & 1][j], acc[i][j], 0, 0, 0);
+        if (m >= 1 && m - 1 < NF) ldfrag((kk + 1) & 1, xs, ys, kk + 1, m - 1);
+        const int slot = NMF + kk * NMF + m;      // position among the NSLOT MFMAs that follow barrier kt-1
+        if (((slot + 1) * NL) / NSLOT != (slot * NL) / NSLOT) group_load((slot * NL) / NSLOT, kt - 1);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
-    const bf16_t* xs = Xs + cur * TILE_ELEMS + (wi * 64 + l32) * LDS_STRIDE + hh * 8;
-    // wave wj owns j-columns {wj*32 + 0..31} and {64 + wj*32 + 0..31}: column c and c+64 of the tile
-    // sit in the same lane (gate/up pairing for SwiGLU)
-    const bf16_t* ys = Ys + cur * TILE_ELEMS + (wj * 32 + l32) * LDS_STRIDE + hh * 8;
+    // barrier kt: tile kt+1 is in LDS for every wavefront (only the Y loads of group kt-1 may still
+    // fly), and no wavefront reads the stages of tile kt after this point
+    if (!short_k && kt + SY - 1 < KT) wait_vmcnt<LY>(); else wait_vmcnt<0>();
+    wait_lgkm0();
+    __builtin_amdgcn_s_barrier();
+    const bf16_t* xs1 = Xs + ((kt + 1) % SX) * XSTAGE;
+    const bf16_t* ys1 = Ys + ((kt + 1) % SY) * YSTAGE;
+    // K step 3: MFMAs on buffer 1, fragments (kt+1, step 0) into buffer 0, first loads of group kt
 #pragma unroll
-    for (int kk = 0; kk < BK / 16; ++kk) {
-      bf16x8 xa[2], yb[2];
-#pragma unroll
-      for (int p = 0; p < 2; ++p) xa[p] = *reinterpret_cast<const bf16x8*>(xs + p * 32 * LDS_STRIDE + kk * 16);
-#pragma unroll
-      for (int q = 0; q < 2; ++q) yb[q] = *reinterpret_cast<const bf16x8*>(ys + q * 64 * LDS_STRIDE + kk * 16);
-#pragma unroll
-      for (int p = 0; p < 2; ++p)
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-          acc[p][q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[p], yb[q], acc[p][q], 0, 0, 0);
+    for (int m = 0; m < NMF; ++m) {
+      const int i = m / TN, j = m % TN;
+      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[1][i], fy[1][j], acc[i][j], 0, 0, 0);
+      if (m >= 1 && m - 1 < NF) ldfrag(0, xs1, ys1, 0, m - 1);
+      if (((m + 1) * NL) / NSLOT != (m * NL) / NSLOT) group_load((m * NL) / NSLOT, kt);
+      __builtin_amdgcn_sched_barrier(0);
     }
-    if (kt + 1 < KT) {
-      store_tile(fx, Xs + (cur ^ 1) * TILE_ELEMS);
-      store_tile(fy, Ys + (cur ^ 1) * TILE_ELEMS);
-    }
-    __syncthreads();
   }
 
-  // accumulator element (p,q,v) of this lane: i = i0 + wi*64 + p*32 + 8*(v/4) + 4*hh + v%4,
-  //                                           j-column (within the 128 of the tile) = q*64 + wj*32 + l32
+  // accumulator element (i,j,v) of this lane: row  = i0 + wm*128 + i*32 + 8*(v/4) + 4*hh + v%4
+  //                                           col  = wn*(BN/2) + j*32 + l32   (within the tile)
   if (EPI == EPI_LMHEAD) {
-    // lane owns token columns j(q); reduce over its 32 vocabulary rows per column
     TopPartial* part = reinterpret_cast<TopPartial*>(a.C);
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int tokr = j0 + q * 64 + wj * 32 + l32;
+    for (int j = 0; j < TN; ++j) {
+      const int tokr = j0 + wn * (BN / 2) + j * 32 + l32;
       Top t = top_empty();
       float mx = -INFINITY;
 #pragma unroll
-      for (int p = 0; p < 2; ++p)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          acc[p][q][v] *= a.scale;
-          mx = fmaxf(mx, acc[p][q][v]);
+          const int idx = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+          acc[i][j][v] = idx < i_max ? acc[i][j][v] * a.scale : -INFINITY;
+          mx = fmaxf(mx, acc[i][j][v]);
         }
-      // (top, lowest index, runner-up) in one ordered pass, sum of exp against the lane's own top
       float s = 0.f;
 #pragma unroll
-      for (int p = 0; p < 2; ++p)
+      for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const float l = acc[p][q][v];
-          const int idx = i0 + wi * 64 + p * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+          const float l = acc[i][j][v];
+          const int idx = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
           if (l > t.m || (l == t.m && idx < t.idx)) { t.m2 = t.m; t.m = l; t.idx = idx; }
           else t.m2 = fmaxf(t.m2, l);
-          s += __expf(l - mx);
+          s += (l == -INFINITY) ? 0.f : __expf(l - mx);
         }
       t.s = s;
       t = top_merge(t, top_shfl_xor(t, 32));
-      if (hh == 0 && tokr < j_max) part[(size_t)(ti * 2 + wi) * a.ldc + tokr] = TopPartial{t.m, t.m2, t.s, t.idx};
+      if (hh == 0 && tokr < j_max) part[(size_t)(ti * 2 + wm) * a.ldc + tokr] = TopPartial{t.m, t.m2, t.s, t.idx};
     }
     return;
   }
 
+  if (EPI == EPI_PARTIAL) {
+    float* P = reinterpret_cast<float*>(a.C) + (size_t)kz * a.M * a.ldc;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+        if (r >= i_max) continue;
+#pragma unroll
+        for (int j = 0; j < TN; ++j) P[(size_t)r * a.ldc + j0 + wn * (BN / 2) + j * 32 + l32] = acc[i][j][v];
+      }
+    return;
+  }
+
   bf16_t* C = reinterpret_cast<bf16_t*>(a.C);
-  const bf16_t* R = reinterpret_cast<const bf16_t*>(a.R);
+  if (EPI == EPI_SWIGLU) {
 #pragma unroll
-  for (int p = 0; p < 2; ++p)
+    for (int i = 0; i < TM; ++i)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int i = i0 + wi * 64 + p * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-      if (i >= i_max) continue;
-      if (EPI == EPI_SWIGLU) {
-        const float g = acc[p][0][v], u = acc[p][1][v];
-        const int f = tj * 64 + wj * 32 + l32;
-        C[(size_t)i * a.ldc + f] = static_cast<bf16_t>(g / (1.f + __expf(-g)) * u);
-      } else {
+      for (int v = 0; v < 16; ++v) {
+        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-          const int jc = q * 64 + wj * 32 + l32;
-          float val = acc[p][q][v];
-          if (EPI == EPI_STORE && bias) val += static_cast<float>(bias[jc]);
-          const size_t o = (size_t)i * a.ldc + j0 + jc;
-          if (EPI == EPI_RESID) val += static_cast<float>(R[o]);
-          C[o] = static_cast<bf16_t>(val);
+        for (int j = 0; j < TN; ++j) {
+          const float mine = acc[i][j][v];
+          const float other = __shfl_xor(mine, 16, 64);
+          const float g = (l32 & 16) ? other : mine, u = (l32 & 16) ? mine : other;
+          // both lanes of a pair hold (g, u): lanes 0-15 store the even v, lanes 16-31 the odd v
+          const bool store = ((l32 >> 4) & 1) == (v & 1);
+          if (store && r < i_max) {
+            const int f = tj * (BN / 2) + (wn * TN + j) * 16 + (l32 & 15);
+            C[(size_t)r * a.ldc + f] = static_cast<bf16_t>(g / (1.f + __expf(-g)) * u);
+          }
         }
       }
+    return;
+  }
+
+  const bf16_t* R = reinterpret_cast<const bf16_t*>(a.R);
+  const bool has_bias = EPI == EPI_STORE && (a.bias[0] || a.bias[1] || a.bias[2]);
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int n = j0 + wn * (BN / 2) + j * 32 + l32;
+    float bv = 0.f;
+    if (has_bias) {
+      const bf16_t* bp = nullptr;
+      if (n < a.Nseg[0]) { if (a.bias[0]) bp = (const bf16_t*)a.bias[0] + n; }
+      else if (n < a.Nseg[0] + a.Nseg[1]) { if (a.bias[1]) bp = (const bf16_t*)a.bias[1] + (n - a.Nseg[0]); }
+      else { if (a.bias[2]) bp = (const bf16_t*)a.bias[2] + (n - a.Nseg[0] - a.Nseg[1]); }
+      if (bp) bv = static_cast<float>(*bp);
     }
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+        if (r >= i_max) continue;
+        const size_t o = (size_t)r * a.ldc + n;
+        float val = acc[i][j][v] + bv;
+        if (EPI == EPI_RESID) val += static_cast<float>(R[o]);
+        C[o] = static_cast<bf16_t>(val);
+      }
+  }
 }
 
-constexpr size_t kSmemBytes = sizeof(bf16_t) * 4 * TILE_ELEMS;  // 73,728 B
+template <int BN, int SY>
+constexpr size_t smem_bytes() { return sizeof(bf16_t) * (size_t)(SX * BM + SY * BN) * BKK; }
 
-template <int EPI>
+template <int EPI, int BN, int SY>
 hipError_t launch_t(const GemmArgs& a, int tiles_i, int tiles_j, hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kSmemBytes);
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI, BN, SY>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BN, SY>());
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  gemm_bf16_mfma_kernel<EPI><<<tiles_i * tiles_j, 256, kSmemBytes, st>>>(a, tiles_i, tiles_j);
+  gemm_bf16_mfma_kernel<EPI, BN, SY><<<tiles_i * tiles_j * a.ksplit, 256, smem_bytes<BN, SY>(), st>>>(a, tiles_i, tiles_j);
   return hipGetLastError();
+}
+
+// out[m,:] = R[m,:] + sum_z P[z][m,:]  (fixed order), optionally followed by RMSNorm of that row
+template <bool NORM>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ P, int ksplit,
+                                                            const bf16_t* __restrict__ R, bf16_t* __restrict__ out,
+                                                            const bf16_t* __restrict__ gain, float eps,
+                                                            bf16_t* __restrict__ normed, int M, int N) {
+  __shared__ float red[4];
+  extern __shared__ float rowbuf[];
+  const int m = blockIdx.x;
+  float ss = 0.f;
+  for (int n = threadIdx.x * 4; n < N; n += 1024) {
+    f32x4 s = *reinterpret_cast<const f32x4*>(P + (size_t)m * N + n);
+    for (int z = 1; z < ksplit; ++z) {
+      const f32x4 p = *reinterpret_cast<const f32x4*>(P + ((size_t)z * M + m) * N + n);
+      s[0] += p[0]; s[1] += p[1]; s[2] += p[2]; s[3] += p[3];
+    }
+    const bf16x4 r = *reinterpret_cast<const bf16x4*>(R + (size_t)m * N + n);
+    bf16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      s[e] += static_cast<float>(r[e]);
+      o[e] = static_cast<bf16_t>(s[e]);
+      if (NORM) { rowbuf[n + e] = s[e]; ss += s[e] * s[e]; }
+    }
+    *reinterpret_cast<bf16x4*>(out + (size_t)m * N + n) = o;
+  }
+  if (!NORM) return;
+  ss = wave_sum(ss);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)N + eps);
+  for (int n = threadIdx.x * 4; n < N; n += 1024) {
+    const bf16x4 g = *reinterpret_cast<const bf16x4*>(gain + n);
+    bf16x4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = static_cast<bf16_t>(rowbuf[n + e] * inv * static_cast<float>(g[e]));
+    *reinterpret_cast<bf16x4*>(normed + (size_t)m * N + n) = o;
+  }
 }
 
 }  // namespace
 
+// number of K slices for the narrow-N projections: a function of (N, K) only
+int mfma_ksplit(int N, int K) {
+  const int n_tiles = N / 128, kt = K / BKK;
+  int ks = 1;
+  while (ks < 4 && 4 * n_tiles * ks < 224 && kt / (ks + 1) >= 8) ++ks;
+  return ks;
+}
+
 bool mfma_gemm_supported(int epi, const GemmArgs& a) {
-  if (a.K % BK != 0 || a.K < BK || a.M < 1) return false;
+  if (a.K % BKK != 0 || a.K < BKK || a.M < 1) return false;
   if (epi == EPI_SWIGLU) return a.N % 64 == 0;
-  if (epi == EPI_LMHEAD) return a.N % BM == 0;
+  if (epi == EPI_LMHEAD) return a.N >= 1;
+  if (a.N % 128 != 0) return false;
   int n = 0;
   for (int s = 0; s < 3; ++s) {
-    if (a.Nseg[s] < 0 || a.Nseg[s] % BN != 0) return false;
+    if (a.Nseg[s] < 0 || a.Nseg[s] % 8 != 0) return false;
     n += a.Nseg[s];
   }
   return n == a.N && a.Nseg[0] > 0;
 }
 
-int mfma_lmhead_partials_per_row(int V) { return V / BM * 2; }
+int mfma_lmhead_partials_per_row(int V) { return cdiv(V, BM) * 2; }
 
-hipError_t launch_gemm_mfma(int epi, const GemmArgs& a, hipStream_t st) {
+hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
+  GemmArgs a = a0;
+  if (a.ksplit < 1) a.ksplit = 1;
   switch (epi) {
-    case EPI_STORE: return launch_t<EPI_STORE>(a, cdiv(a.M, BM), a.N / BN, st);
-    case EPI_RESID: return launch_t<EPI_RESID>(a, cdiv(a.M, BM), a.N / BN, st);
-    case EPI_SWIGLU: return launch_t<EPI_SWIGLU>(a, cdiv(a.M, BM), a.N / 64, st);
-    case EPI_LMHEAD: return launch_t<EPI_LMHEAD>(a, a.N / BM, cdiv(a.M, BN), st);
-    default: return hipErrorInvalidValue;
+    case EPI_STORE:
+      if (a.N % 192 == 0) return launch_t<EPI_STORE, 192, 3>(a, cdiv(a.M, BM), a.N / 192, st);
+      return launch_t<EPI_STORE, 128, 4>(a, cdiv(a.M, BM), a.N / 128, st);
+    case EPI_RESID:
+      return launch_t<EPI_RESID, 128, 4>(a, cdiv(a.M, BM), a.N / 128, st);
+    case EPI_PARTIAL:
+      return launch_t<EPI_PARTIAL, 128, 4>(a, cdiv(a.M, BM), a.N / 128, st);
+    case EPI_SWIGLU:
+      if (a.N % 96 == 0) return launch_t<EPI_SWIGLU, 192, 3>(a, cdiv(a.M, BM), a.N / 96, st);
+      return launch_t<EPI_SWIGLU, 128, 4>(a, cdiv(a.M, BM), a.N / 64, st);
+    case EPI_LMHEAD:
+      return launch_t<EPI_LMHEAD, 192, 3>(a, cdiv(a.N, BM), cdiv(a.M, 192), st);
+    default:
+      return hipErrorInvalidValue;
   }
+}
+
+hipError_t launch_splitk_reduce(const float* P, int ksplit, const void* R, void* out, const void* gain, float eps,
+                                void* normed, int M, int N, hipStream_t st) {
+  if (normed)
+    splitk_reduce_kernel<true><<<M, 256, sizeof(float) * (size_t)N, st>>>(P, ksplit, (const bf16_t*)R, (bf16_t*)out,
+                                                                       (const bf16_t*)gain, eps, (bf16_t*)normed, M, N);
+  else
+    splitk_reduce_kernel<false><<<M, 256, 0, st>>>(P, ksplit, (const bf16_t*)R, (bf16_t*)out, nullptr, 0.f, nullptr, M, N);
+  return hipGetLastError();
 }
 
 }  // namespace spiffy

@@ -73,7 +73,7 @@ def _load() -> C.CDLL:
     lib.spiffy_decode_head.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp,
                                        vp, sz, vp]
     lib.spiffy_gemm.restype = C.c_int
-    lib.spiffy_gemm.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp]
+    lib.spiffy_gemm.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     lib.spiffy_graph_accept.restype = C.c_int
     lib.spiffy_graph_accept.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
     lib.spiffy_verify_step.restype = C.c_int
@@ -202,13 +202,15 @@ def decode_head(cfg: ModelCfg, hidden: torch.Tensor, final_norm: torch.Tensor, w
 
 
 def gemm(epilogue: int, A: torch.Tensor, W0: torch.Tensor, W1: Optional[torch.Tensor] = None,
-         R: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+         R: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+         workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
     M, K = A.shape
     N = W0.shape[0]
     if out is None:
         out = torch.empty((M, N), dtype=A.dtype, device=A.device)
     dt = SPIFFY_F32 if A.dtype == torch.float32 else SPIFFY_BF16
-    _check(lib.spiffy_gemm(dt, epilogue, _ptr(A), _ptr(W0), _ptr(W1), _ptr(R), _ptr(out), M, N, K,
+    wp, wn = _ws(workspace) if workspace is not None else (None, 0)
+    _check(lib.spiffy_gemm(dt, epilogue, _ptr(A), _ptr(W0), _ptr(W1), _ptr(R), _ptr(out), M, N, K, wp, wn,
                            _stream(stream)), "spiffy_gemm")
     return out
 

@@ -373,3 +373,39 @@ def test_step_accept_follows_device_targets(sp):
     assert e_max < 4e-2, e_max       # two chained bf16 layers
     # and the head on the step's own hidden
     check_head(sp, cfg, states, out["hidden"].cpu(), hw, cfg.threshold, 30.0)
+
+
+# ------------------------------------------------------------------ projection GEMM on its own
+
+@pytest.mark.parametrize("M,N,K,epi", [
+    (300, 384, 256, "store"),       # 192-wide tiles, ragged rows, short K
+    (1024, 1536, 1024, "store"),    # 192-wide tiles, several row tiles, steady-state pipeline
+    (70, 256, 192, "store"),        # 128-wide tiles, K of three tiles
+    (513, 512, 2048, "resid"),      # sliced K (split-K) with residual, ragged rows
+    (256, 128, 64, "resid"),        # single K tile
+    (520, 384, 512, "swiglu"),      # gate/up interleave, 192-wide tiles (96 features per tile)
+    (129, 320, 640, "swiglu"),      # 128-wide tiles (64 features per tile)
+])
+def test_gemm_against_float64_matmul(sp, M, N, K, epi):
+    g = torch.Generator().manual_seed(M * 7 + N)
+    A = (torch.randn((M, K), generator=g) * 0.5).to(torch.bfloat16)
+    W0 = (torch.randn((N, K), generator=g) * 0.05).to(torch.bfloat16)
+    W1 = (torch.randn((N, K), generator=g) * 0.05).to(torch.bfloat16)
+    R = torch.randn((M, N), generator=g).to(torch.bfloat16)
+    a, w0, w1, r = to_np(A), to_np(W0), to_np(W1), to_np(R)
+    if epi == "store":
+        got = sp.gemm(sp.GEMM_STORE, A.to(DEV), W0.to(DEV))
+        ref = a @ w0.T
+    elif epi == "resid":
+        ws = torch.empty(4 * M * N * 4 + 256, dtype=torch.uint8, device=DEV)
+        got = sp.gemm(sp.GEMM_RESID, A.to(DEV), W0.to(DEV), R=R.to(DEV), workspace=ws)
+        direct = sp.gemm(sp.GEMM_RESID, A.to(DEV), W0.to(DEV), R=R.to(DEV))
+        ref = r + a @ w0.T
+        assert rel_err(to_np(direct.cpu()), ref)[0] < 1e-2
+    else:
+        got = sp.gemm(sp.GEMM_SWIGLU, A.to(DEV), W0.to(DEV), W1.to(DEV))
+        gg = a @ w0.T
+        ref = gg / (1.0 + np.exp(-gg)) * (a @ w1.T)
+    torch.cuda.synchronize()
+    e_max, e_norm = rel_err(to_np(got.cpu()), ref)
+    assert e_max < 1e-2 and e_norm < 4e-3, (e_max, e_norm)

@@ -92,7 +92,7 @@ LayerWs carve_layer(const spiffy_model_cfg* c, int G, int B, int P, void* base) 
 struct HeadWs {
   int32_t *row_idx, *count;
   void* nf;
-  TopPartial *part, *row_top;
+  TopPartial *part, *part2, *row_top;
   int m_cap, n_part;
   size_t bytes;
 };
@@ -106,6 +106,7 @@ HeadWs carve_head(const spiffy_model_cfg* c, int G, int B, void* base) {
   w.count = (int32_t*)cv.take(sizeof(int32_t) * 4);
   w.nf = cv.take((size_t)w.m_cap * c->d * esize(c->dtype));
   w.part = (TopPartial*)cv.take(sizeof(TopPartial) * (size_t)w.n_part * w.m_cap);
+  w.part2 = (TopPartial*)cv.take(sizeof(TopPartial) * (size_t)kLmheadCombineSlices * w.m_cap);
   w.row_top = (TopPartial*)cv.take(sizeof(TopPartial) * w.m_cap);
   w.bytes = cv.off;
   return w;
@@ -232,7 +233,7 @@ int run_head(const spiffy_model_cfg* cfg, const void* hidden, const void* final_
     g.W[0] = w_vocab; g.Nseg[0] = cfg->vocab; g.N = cfg->vocab;
     g.C = ws.part; g.ldc = ws.m_cap; g.scale = logit_scale;
     if ((rc = dev(launch_gemm_mfma(EPI_LMHEAD, g, st)))) return rc;
-    if ((rc = dev(launch_lmhead_combine(ws.part, ws.n_part, ws.m_cap, ws.count, M, ws.row_top, st)))) return rc;
+    if ((rc = dev(launch_lmhead_combine(ws.part, ws.n_part, ws.m_cap, ws.count, M, ws.part2, ws.row_top, st)))) return rc;
   } else {
     if ((rc = dev(launch_lmhead_generic(dt, ws.nf, w_vocab, cfg->d, cfg->vocab, logit_scale, ws.count, M,
                                         ws.row_top, st))))

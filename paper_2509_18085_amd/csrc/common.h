@@ -91,6 +91,7 @@ struct GemmArgs {
   const int* M_dev;     // optional device row count (rows >= *M_dev are skipped), NULL = use M
   int M, N, K;
   int lda, ldc;
+  int ldw;              // row stride of the weight segments in elements (0 = K, i.e. dense rows)
   float scale;          // LMHEAD: logit scale
   int ksplit;           // PARTIAL: number of K slices (C = fp32 [ksplit][M][N]); otherwise 1
 };

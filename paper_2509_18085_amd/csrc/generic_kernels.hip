@@ -374,19 +374,22 @@ hipError_t launch_lmhead_generic(int dtype, const void* n, const void* w_vocab, 
 }
 
 // merge the per-tile partial summaries part[n_part][m_cap] of each row; lanes run along rows so
-// the reads are coalesced, four wavefronts split the partials of the same 64 rows
+// the reads are coalesced, four wavefronts split the partials of the same 64 rows.  blockIdx.y
+// selects a slice of the partials (two-level merge when there are many): out is [gridDim.y][m_cap].
 __global__ __launch_bounds__(256) void lmhead_combine_kernel(const TopPartial* __restrict__ part, int n_part,
                                                              int m_cap, const int32_t* __restrict__ count,
-                                                             TopPartial* __restrict__ row_top) {
+                                                             TopPartial* __restrict__ out) {
   __shared__ TopPartial sh[4][64];
   const int n = *count;
   const int r0 = blockIdx.x * 64;
   if (r0 >= n) return;
+  const int per = (n_part + gridDim.y - 1) / gridDim.y;
+  const int p0 = blockIdx.y * per, p1 = min(n_part, p0 + per);
   const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r = r0 + lane;
   Top t = top_empty();
   if (r < n) {
-    for (int i = w; i < n_part; i += 4) {
+    for (int i = p0 + w; i < p1; i += 4) {
       const TopPartial p = part[(size_t)i * m_cap + r];
       t = top_merge(t, Top{p.m, p.m2, p.s, p.idx});
     }
@@ -396,13 +399,19 @@ __global__ __launch_bounds__(256) void lmhead_combine_kernel(const TopPartial* _
   if (w == 0 && r < n) {
     Top a = top_empty();
     for (int i = 0; i < 4; ++i) a = top_merge(a, Top{sh[i][lane].m, sh[i][lane].m2, sh[i][lane].s, sh[i][lane].idx});
-    row_top[r] = TopPartial{a.m, a.m2, a.s, a.idx};
+    out[(size_t)blockIdx.y * m_cap + r] = TopPartial{a.m, a.m2, a.s, a.idx};
   }
 }
 
 hipError_t launch_lmhead_combine(const TopPartial* part, int n_part, int m_cap, const int32_t* count, int M,
-                                 TopPartial* row_top, hipStream_t st) {
-  lmhead_combine_kernel<<<cdiv(M, 64), 256, 0, st>>>(part, n_part, m_cap, count, row_top);
+                                 TopPartial* tmp, TopPartial* row_top, hipStream_t st) {
+  const int slices = kLmheadCombineSlices;
+  if (n_part > 2 * slices && tmp) {
+    lmhead_combine_kernel<<<dim3(cdiv(M, 64), slices), 256, 0, st>>>(part, n_part, m_cap, count, tmp);
+    lmhead_combine_kernel<<<dim3(cdiv(M, 64), 1), 256, 0, st>>>(tmp, slices, m_cap, count, row_top);
+  } else {
+    lmhead_combine_kernel<<<dim3(cdiv(M, 64), 1), 256, 0, st>>>(part, n_part, m_cap, count, row_top);
+  }
   return hipGetLastError();
 }
 

@@ -32,9 +32,10 @@ hipError_t launch_compact_rows(const int32_t* tokens, const uint8_t* mask, int m
 hipError_t launch_lmhead_generic(int dtype, const void* n, const void* w_vocab, int d, int V,
                                  float scale, const int32_t* count, int M, TopPartial* row_top,
                                  hipStream_t st);
-// merge n_part partials per row; part is [n_part][m_cap]
+// merge n_part partials per row; part is [n_part][m_cap]; tmp is [kLmheadCombineSlices][m_cap] scratch
+constexpr int kLmheadCombineSlices = 16;
 hipError_t launch_lmhead_combine(const TopPartial* part, int n_part, int m_cap, const int32_t* count, int M,
-                                 TopPartial* row_top, hipStream_t st);
+                                 TopPartial* tmp, TopPartial* row_top, hipStream_t st);
 // scatter row summaries to [G,B] outputs, apply threshold / force_one, build next states
 hipError_t launch_head_finalize(const TopPartial* row_top, const int32_t* row_idx, const int32_t* count,
                                 const int32_t* tokens, const uint8_t* mask, int mask_id, int G, int B,

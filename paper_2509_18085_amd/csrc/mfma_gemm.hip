@@ -8,8 +8,8 @@
 //   * K advances in steps of 64 so every row segment is one full 128-byte line; operands go
 //     global -> LDS directly (LDS-DMA loads, no register staging), rows XOR-swizzled so the
 //     16-byte fragment reads are conflict-free.
-//   * separate LDS rings for the two operands: X (activations, mostly L2 hits) 2 stages, Y (weights,
-//     streamed from HBM) 3-4 stages, 136 KB in all.
+//   * separate LDS rings for the two operands: the activation operand (mostly L2 hits) gets 2 stages,
+//     the weight operand (streamed from HBM) SD = 3-4 stages, 128-144 KB in all.
 //   * one barrier per K-tile; the loads of later tiles and the LDS fragment reads of the next
 //     16-wide K step are threaded between the MFMAs of the current step, fragments double-buffered
 //     in registers, partial s_waitcnt vmcnt so younger loads stay in flight across the barrier.
@@ -34,7 +34,7 @@ namespace spiffy {
 
 namespace {
 
-constexpr int BM = 256, BKK = 64, SX = 2;
+constexpr int BM = 256, BKK = 64;
 
 typedef __attribute__((address_space(3))) void* lds_ptr_t;
 typedef const __attribute__((address_space(1))) void* glb_ptr_t;
@@ -45,8 +45,11 @@ __device__ __forceinline__ void wait_vmcnt() {   // vmcnt <= N; lgkmcnt / expcnt
 }
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
-template <int EPI, int BN, int SY>
+template <int EPI, int BN, int SD>
 __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int tiles_i, int tiles_j) {
+  // which operand is the weight matrix (deep ring): Y for the projections, X for the LM head
+  constexpr bool XDEEP = (EPI == EPI_LMHEAD);
+  constexpr int SX = XDEEP ? SD : 2, SY = XDEEP ? 2 : SD;
   constexpr int TM = 4, TN = BN / 64;
   constexpr int LX = BM / 32, LY = BN / 32;       // 1-KB wave-loads (8 rows x 128 B) per wavefront per K-tile
   constexpr int NL = LX + LY;
@@ -83,6 +86,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     if (i0 >= i_max) return;
   }
 
+  const int ldw = a.ldw ? a.ldw : a.K;
   // K range of this slice
   const int KT_all = a.K / BKK;
   const int kt0 = (int)(((long long)KT_all * kz) / a.ksplit);
@@ -93,7 +97,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   const bf16_t* ysrc[LY];
   {
     const bf16_t* X = (EPI == EPI_LMHEAD) ? (const bf16_t*)a.W[0] : (const bf16_t*)a.A;
-    const int ldx = (EPI == EPI_LMHEAD) ? a.K : a.lda;
+    const int ldx = (EPI == EPI_LMHEAD) ? ldw : a.lda;
 #pragma unroll
     for (int q = 0; q < LX; ++q) {
       const int row = 8 * (wave * LX + q) + (lane >> 3);
@@ -111,12 +115,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
       } else if (EPI == EPI_SWIGLU) {
         // rows of every 32-row MFMA tile: 16 gate rows then the 16 up rows of the same features
         const int f = tj * (BN / 2) + (row >> 5) * 16 + (row & 15);
-        p = ((row & 16) ? (const bf16_t*)a.W[1] : (const bf16_t*)a.W[0]) + (size_t)f * a.K;
+        p = ((row & 16) ? (const bf16_t*)a.W[1] : (const bf16_t*)a.W[0]) + (size_t)f * ldw;
       } else {
         const int n = j0 + row;   // column of the fused [seg0 | seg1 | seg2] output; 8-row groups never straddle
-        if (n < a.Nseg[0]) p = (const bf16_t*)a.W[0] + (size_t)n * a.K;
-        else if (n < a.Nseg[0] + a.Nseg[1]) p = (const bf16_t*)a.W[1] + (size_t)(n - a.Nseg[0]) * a.K;
-        else p = (const bf16_t*)a.W[2] + (size_t)(n - a.Nseg[0] - a.Nseg[1]) * a.K;
+        if (n < a.Nseg[0]) p = (const bf16_t*)a.W[0] + (size_t)n * ldw;
+        else if (n < a.Nseg[0] + a.Nseg[1]) p = (const bf16_t*)a.W[1] + (size_t)(n - a.Nseg[0]) * ldw;
+        else p = (const bf16_t*)a.W[2] + (size_t)(n - a.Nseg[0] - a.Nseg[1]) * ldw;
       }
       ysrc[q] = p + (size_t)kt0 * BKK + chunk * 8;
     }
@@ -129,10 +133,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     __builtin_amdgcn_global_load_lds((glb_ptr_t)(ysrc[q] + (size_t)t * BKK),
                                      (lds_ptr_t)(Ys + (t % SY) * YSTAGE + (wave * LY + q) * 512), 16, 0, 0);
   };
-  // load `idx` of group g (the loads issued after barrier g): X of tile g+SX first, then Y of tile g+SY
+  constexpr int LS = XDEEP ? LY : LX, LD = XDEEP ? LX : LY;   // wave-loads of the shallow / deep operand
+  auto load_sh = [&](int q, int t) { if (XDEEP) load_y(q, t); else load_x(q, t); };
+  auto load_dp = [&](int q, int t) { if (XDEEP) load_x(q, t); else load_y(q, t); };
+  // load `idx` of group g (the loads issued after barrier g): shallow operand of tile g+2 first, then
+  // the deep operand of tile g+SD
   auto group_load = [&](int idx, int g) {
-    if (idx < LX) { if (g + SX < KT) load_x(idx, g + SX); }
-    else { if (g + SY < KT) load_y(idx - LX, g + SY); }
+    if (idx < LS) { if (g + 2 < KT) load_sh(idx, g + 2); }
+    else { if (g + SD < KT) load_dp(idx - LS, g + SD); }
   };
 
   f32x16 acc[TM][TN];
@@ -144,19 +152,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // short K: not enough tiles for the steady-state wait counts, wait for everything each time
-  const bool short_k = KT <= SY;
-  // prologue, in the order the partial waits rely on: Y0 X0 | Y1 .. Y(SY-2) | first quarter of group -1
-  // (the part of X1 that a "K step 3 of tile -1" would have issued); the loop issues the rest
-  static_assert(SY >= 3, "the steady-state wait keeps one Y tile in flight across the barrier");
+  const bool short_k = KT <= SD;
+  // prologue, in the order the partial waits rely on: D0 S0 | D1 .. D(SD-2) | first quarter of group -1
+  // (the part of S1 that a "K step 3 of tile -1" would have issued); the loop issues the rest
+  static_assert(SD >= 3, "the steady-state wait keeps one deep-operand tile in flight across the barrier");
 #pragma unroll
-  for (int q = 0; q < LY; ++q) load_y(q, 0);
+  for (int q = 0; q < LD; ++q) load_dp(q, 0);
 #pragma unroll
-  for (int q = 0; q < LX; ++q) load_x(q, 0);
+  for (int q = 0; q < LS; ++q) load_sh(q, 0);
 #pragma unroll
-  for (int t = 1; t < SY - 1; ++t)
+  for (int t = 1; t < SD - 1; ++t)
     if (t < KT) {
 #pragma unroll
-      for (int q = 0; q < LY; ++q) load_y(q, t);
+      for (int q = 0; q < LD; ++q) load_dp(q, t);
     }
 #pragma unroll
   for (int idx = 0; idx < NL / 4; ++idx) group_load(idx, -1);
@@ -170,7 +178,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     if (r < TM) fx[buf][r] = *reinterpret_cast<const bf16x8*>(xs + xrow + r * 32 * BKK + slot);
     else fy[buf][r - TM] = *reinterpret_cast<const bf16x8*>(ys + yrow + (r - TM) * 32 * BKK + slot);
   };
-  if (short_k) wait_vmcnt<0>(); else wait_vmcnt<(SY - 2) * LY + NL / 4>();   // tile 0 is in LDS
+  if (short_k) wait_vmcnt<0>(); else wait_vmcnt<(SD - 2) * LD + NL / 4>();   // tile 0 is in LDS
   __builtin_amdgcn_s_barrier();
 #pragma unroll
   for (int r = 0; r < NF; ++r) ldfrag(0, Xs, Ys, 0, r);
@@ -192,9 +200,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    // barrier kt: tile kt+1 is in LDS for every wavefront (only the Y loads of group kt-1 may still
-    // fly), and no wavefront reads the stages of tile kt after this point
-    if (!short_k && kt + SY - 1 < KT) wait_vmcnt<LY>(); else wait_vmcnt<0>();
+    // barrier kt: tile kt+1 is in LDS for every wavefront (only the deep-operand loads of group kt-1
+    // may still fly), and no wavefront reads the stages of tile kt after this point
+    if (!short_k && kt + SD - 1 < KT) wait_vmcnt<LD>(); else wait_vmcnt<0>();
     wait_lgkm0();
     __builtin_amdgcn_s_barrier();
     const bf16_t* xs1 = Xs + ((kt + 1) % SX) * XSTAGE;
@@ -309,19 +317,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   }
 }
 
-template <int BN, int SY>
-constexpr size_t smem_bytes() { return sizeof(bf16_t) * (size_t)(SX * BM + SY * BN) * BKK; }
+template <int EPI, int BN, int SD>
+constexpr size_t smem_bytes() {
+  return sizeof(bf16_t) * (size_t)(EPI == EPI_LMHEAD ? SD * BM + 2 * BN : 2 * BM + SD * BN) * BKK;
+}
 
-template <int EPI, int BN, int SY>
+template <int EPI, int BN, int SD>
 hipError_t launch_t(const GemmArgs& a, int tiles_i, int tiles_j, hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI, BN, SY>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<BN, SY>());
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI, BN, SD>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<EPI, BN, SD>());
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  gemm_bf16_mfma_kernel<EPI, BN, SY><<<tiles_i * tiles_j * a.ksplit, 256, smem_bytes<BN, SY>(), st>>>(a, tiles_i, tiles_j);
+  gemm_bf16_mfma_kernel<EPI, BN, SD><<<tiles_i * tiles_j * a.ksplit, 256, smem_bytes<EPI, BN, SD>(), st>>>(a, tiles_i, tiles_j);
   return hipGetLastError();
 }
 

@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--config", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=5)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run plain device copies of 1 GiB (calibration of the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -66,6 +68,14 @@ def main():
                        logit_scale=LOGIT_SCALE, device=dev)
     torch.cuda.synchronize()
     t_setup = time.time() - t0
+
+    if args.copy_probe:     # a copy kernel of known size: 1 GiB read, 1 GiB written per launch
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- whole step ------------------------------------------------------------------------------
     for _ in range(args.warmup):
@@ -139,50 +149,68 @@ def main():
         "outcome": {"accepted_node": res[0], "depth": res[1], "unmasked": int(out["unmask"].sum().item())},
         "roofline": {"kernel": "gemm_bf16_mfma_kernel<EPI_SWIGLU> (gate/up projection)", "bound": "mfma",
                      "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": stored_traffic(args.config),
+                     "traffic_source": "profiles/hbm_traffic_c3_gemm_kernels.txt (rocprofv3 --pmc FETCH_SIZE / "
+                                       "WRITE_SIZE, scaled by a 1 GiB copy probe; bytes per launch)",
+                     "algorithmic_bytes_per_launch": 2.0 * (2 * cfg.F * cfg.d + M * cfg.d + M * cfg.F),
                      "avg_launch_ms": k_ms, "flop_per_launch": flop_launch, "launches_timed": n_launch},
         "setup_s": t_setup,
     }
 
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg, layers[0], prefix[0], hw, states, edges)
+        line["cpu_baseline"] = cpu_baseline(cfg, layers, prefix, hw, states, edges)
     print(json.dumps(line))
 
 
-def cpu_baseline(cfg, layer0, prefix0, hw, states, edges):
-    """The oracle as it stands, on this host: one layer on a few states + the head on a few states +
-    the walk, scaled to a whole step (x L layers, x G states).  A baseline for context, not a target."""
+def stored_traffic(config):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary
+    (counters cannot be collected from inside this process); None if there is none for the workload."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s_gemm_kernels.txt" % config)
+    try:
+        for ln in open(path):
+            if ln.startswith("traffic_bytes_per_launch_swiglu_gemm:"):
+                return float(ln.split(":")[1])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(cfg, layers, prefix, hw, states, edges):
+    """The oracle as it stands, on this host, on a bounded sample of the same workload: the first
+    layers on all G states + the head on all G states + the walk, scaled to the full depth.
+    A baseline for context, not a target."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import spiffy_oracle as O
 
     f64 = lambda t: t.detach().cpu().double().numpy()
-    g_layer, g_head = min(4, cfg.G), min(2, cfg.G)
-    w = {k: f64(v) for k, v in layer0.items()}
-    pk, pv = f64(prefix0[0]), f64(prefix0[1])
+    n_layers = min(cfg.L, 4)
     rng = np.random.default_rng(0)
-    x = rng.standard_normal((g_layer, cfg.B, cfg.d))
-    t0 = time.perf_counter()
-    O.verify_layer(w, pk, pv, x, n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P,
-                   rms_eps=cfg.rms_eps, rope_base=cfg.rope_base)
-    t_layer = (time.perf_counter() - t0) / g_layer
-    del w
+    x = rng.standard_normal((cfg.G, cfg.B, cfg.d))
+    t_layers = 0.0
+    for l in range(n_layers):
+        w = {k: f64(v) for k, v in layers[l].items()}
+        pk, pv = f64(prefix[l][0]), f64(prefix[l][1])
+        t0 = time.perf_counter()
+        x = O.verify_layer(w, pk, pv, x, n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P,
+                           rms_eps=cfg.rms_eps, rope_base=cfg.rope_base)
+        t_layers += time.perf_counter() - t0
+        del w, pk, pv
     wv, fn = f64(hw["w_vocab"]), f64(hw["final_norm"])
-    xh = rng.standard_normal((g_head, cfg.B, cfg.d))
     t0 = time.perf_counter()
-    _, _, _, _, tgt = O.decode_head(xh, fn, wv, states[:g_head], cfg.mask_id, cfg.threshold, rms_eps=cfg.rms_eps,
-                                    logit_scale=LOGIT_SCALE)
-    t_head = (time.perf_counter() - t0) / g_head
+    _, _, _, _, tgt = O.decode_head(x, fn, wv, states, cfg.mask_id, cfg.threshold, rms_eps=cfg.rms_eps,
+                                    logit_scale=LOGIT_SCALE, operand_dtype="bf16")
+    t_head = time.perf_counter() - t0
     t0 = time.perf_counter()
-    O.graph_accept(edges, states, states, 0)
+    O.graph_accept(edges, states, tgt, 0)
     t_walk = time.perf_counter() - t0
-    step_s = cfg.G * (cfg.L * t_layer + t_head) + t_walk
+    step_s = t_layers * cfg.L / n_layers + t_head + t_walk
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     return {"value": cfg.G / step_s, "unit": "states/s", "cores": threads, "kind": "oracle",
-            "sample": "oracle.verify_layer on %d states of layer 0 (%.2f s/state), oracle.decode_head on %d states "
-                      "(%.2f s/state), oracle.graph_accept in full (%.4f s); scaled to %d layers x %d states"
-                      % (g_layer, t_layer, g_head, t_head, t_walk, cfg.L, cfg.G),
-            "extrapolated_step_s": step_s}
+            "sample": "oracle.verify_layer on all %d states for %d of %d layers (%.2f s), oracle.decode_head on all "
+                      "states (%.2f s), oracle.graph_accept (%.4f s); layer time scaled by %d/%d"
+                      % (cfg.G, n_layers, cfg.L, t_layers, t_head, t_walk, cfg.L, n_layers),
+            "measured_s": t_layers + t_head + t_walk, "extrapolated_step_s": step_s}
 
 
 if __name__ == "__main__":

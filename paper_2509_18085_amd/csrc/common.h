@@ -96,6 +96,14 @@ struct GemmArgs {
   int ksplit;           // PARTIAL: number of K slices (C = fp32 [ksplit][M][N]); otherwise 1
 };
 
+// Workgroup ids are handed to the 8 XCDs round-robin (id % 8).  Map id -> logical index so that every
+// XCD owns one contiguous range of logical indices (XCD x owns ids x, x+8, ...), for any total.
+__device__ __forceinline__ int xcd_contiguous(int id, int total) {
+  const int x = id & 7, j = id >> 3;
+  const int q = total >> 3, r = total & 7;
+  return x * q + (x < r ? x : r) + j;
+}
+
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 

@@ -166,8 +166,7 @@ __global__ __launch_bounds__(256) void attn_prefix_mfma_kernel(AttnKArgs a) {
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
   const int total = a.nQ * a.nS * a.Hq;
-  int L = blockIdx.x;
-  if ((total & 7) == 0) L = (blockIdx.x >> 3) + (blockIdx.x & 7) * (total >> 3);
+  const int L = xcd_contiguous(blockIdx.x, total);
   const int qt = L % a.nQ;
   const int sp = (L / a.nQ) % a.nS;
   const int h = L / (a.nQ * a.nS);

@@ -65,8 +65,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   // same weight tile share one L2 and run at the same time.
   const int per_z = tiles_i * tiles_j;
   const int kz = blockIdx.x / per_z;
-  int L = blockIdx.x % per_z;
-  if ((per_z & 7) == 0) L = (L >> 3) + (L & 7) * (per_z >> 3);
+  const int L = xcd_contiguous(blockIdx.x % per_z, per_z);
   const int ti = (EPI == EPI_LMHEAD) ? L / tiles_j : L % tiles_i;
   const int tj = (EPI == EPI_LMHEAD) ? L % tiles_j : L / tiles_i;
   const int i0 = ti * BM, j0 = tj * BN;

@@ -11,7 +11,12 @@
 // so the tile comes from HBM once and from L2 afterwards.  The number of prefix splits depends on
 // P only, so a row's arithmetic does not depend on G.
 //
-// Per wavefront (32 query rows) everything is kept "query per lane":
+// Eight wavefronts per workgroup: wavefront pair p owns query rows 32p..32p+31, and the two wavefronts
+// of a pair split every 64-key tile between them (32 keys each), each keeping its own running
+// (max, sum, O); the pair is merged through LDS at the end.  Two wavefronts per SIMD let the softmax
+// arithmetic of one overlap the MFMAs of the other.
+//
+// Per wavefront (32 query rows x 32 keys of a tile) everything is kept "query per lane":
 //   S^T = K Q^T    A operand = K rows from LDS, B operand = rotated, pre-scaled Q in registers
 //                  -> lane (q, half) holds 16 of the 32 keys of a sub-tile for its query q
 //   online softmax max / sum are reductions over the lane's own registers plus one xor-32 shuffle
@@ -38,46 +43,47 @@ constexpr size_t kAttnSmem = sizeof(bf16_t) * 2 * BUF_ELEMS;  // 69,632 B
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+constexpr int NT = 512;   // threads per workgroup
+
 struct KVRegs {
-  u32x4 k[4];
-  u32x4 v[4];
+  u32x4 k[2];
+  u32x4 v[2];
 };
 
 __device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
-__device__ __forceinline__ u32x4 as_u32x4(bf16x8 x) { return __builtin_bit_cast(u32x4, x); }
 
 // prefix tile: keys key0..key0+63 of kv head (rows clamped to the last valid key)
 __device__ __forceinline__ void gload_prefix(KVRegs& r, const bf16_t* __restrict__ pk, const bf16_t* __restrict__ pv,
                                              int key0, int key_last) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = threadIdx.x + 256 * i;
+  for (int i = 0; i < 2; ++i) {
+    const int c = threadIdx.x + NT * i;
     const int key = min(key0 + (c >> 4), key_last);
     r.k[i] = *reinterpret_cast<const u32x4*>(pk + (size_t)key * HD + (c & 15) * 8);
   }
-  const int kq = threadIdx.x >> 4, ho = threadIdx.x & 15;
+  const int kp = threadIdx.x >> 4, ho = threadIdx.x & 15;
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int key = min(key0 + 4 * kq + i, key_last);
+  for (int i = 0; i < 2; ++i) {
+    const int key = min(key0 + 2 * kp + i, key_last);
     r.v[i] = *reinterpret_cast<const u32x4*>(pv + (size_t)key * HD + ho * 8);
   }
 }
 __device__ __forceinline__ void lstore_k(const KVRegs& r, bf16_t* ks) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const int c = threadIdx.x + 256 * i;
+  for (int i = 0; i < 2; ++i) {
+    const int c = threadIdx.x + NT * i;
     *reinterpret_cast<u32x4*>(ks + (c >> 4) * KS_STRIDE + (c & 15) * 8) = r.k[i];
   }
 }
-// V arrives as 4 keys x 8 head-dim values per thread; LDS wants V^T[hd][key]
+// V arrives as 2 keys x 8 head-dim values per thread; LDS wants V^T[hd][key]
 __device__ __forceinline__ void lstore_vt(const KVRegs& r, bf16_t* vt) {
-  const int kq = threadIdx.x >> 4, ho = threadIdx.x & 15;
-  const bf16x8 r0 = as_bf16x8(r.v[0]), r1 = as_bf16x8(r.v[1]), r2 = as_bf16x8(r.v[2]), r3 = as_bf16x8(r.v[3]);
+  const int kp = threadIdx.x >> 4, ho = threadIdx.x & 15;
+  const bf16x8 r0 = as_bf16x8(r.v[0]), r1 = as_bf16x8(r.v[1]);
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    bf16x4 t;
-    t[0] = r0[e]; t[1] = r1[e]; t[2] = r2[e]; t[3] = r3[e];
-    *reinterpret_cast<bf16x4*>(vt + (ho * 8 + e) * VT_STRIDE + 4 * kq) = t;
+    bf16x2 t;
+    t[0] = r0[e]; t[1] = r1[e];
+    *reinterpret_cast<bf16x2*>(vt + (ho * 8 + e) * VT_STRIDE + 2 * kp) = t;
   }
 }
 
@@ -87,66 +93,57 @@ struct WaveState {
   float m_run, l_run;
 };
 
-// One 64-key tile against the wave's 32 queries.  `valid(key_in_tile)` masks keys (only called
-// when MASKED).  Scores are in the log2 domain (Q carries log2(e)/sqrt(hd)).
+// The wavefront's 32-key half (`st`) of a 64-key tile against its 32 queries.  `valid(key_in_tile)` masks
+// keys (only called when MASKED).  Scores are in the log2 domain (Q carries log2(e)/sqrt(hd)).
 template <bool MASKED, typename ValidFn>
 __device__ __forceinline__ void process_tile(WaveState& w, const bf16_t* __restrict__ ks, const bf16_t* __restrict__ vt,
-                                             int l32, int hh, ValidFn valid) {
-  f32x16 s[2];
+                                             int st, int l32, int hh, ValidFn valid) {
+  f32x16 s;
 #pragma unroll
-  for (int st = 0; st < 2; ++st) {
+  for (int v = 0; v < 16; ++v) s[v] = 0.f;
+  const bf16_t* kp = ks + (st * 32 + l32) * KS_STRIDE + hh * 8;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) s[st][v] = 0.f;
-    const bf16_t* kp = ks + (st * 32 + l32) * KS_STRIDE + hh * 8;
-#pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + kk * 16);
-      s[st] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[kk], s[st], 0, 0, 0);
-    }
+  for (int kk = 0; kk < 8; ++kk) {
+    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + kk * 16);
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[kk], s, 0, 0, 0);
   }
   float tmax = -INFINITY;
 #pragma unroll
-  for (int st = 0; st < 2; ++st)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      if (MASKED) {
-        const int key = st * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-        if (!valid(key)) s[st][v] = -INFINITY;
-      }
-      tmax = fmaxf(tmax, s[st][v]);
+  for (int v = 0; v < 16; ++v) {
+    if (MASKED) {
+      const int key = st * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+      if (!valid(key)) s[v] = -INFINITY;
     }
+    tmax = fmaxf(tmax, s[v]);
+  }
   tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
   const float m_new = fmaxf(w.m_run, tmax);
-  const float alpha = (w.m_run == -INFINITY) ? 0.f : exp2f(w.m_run - m_new);
+  const float alpha = (w.m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(w.m_run - m_new);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
-  bf16x8 pf[2][2];
+  bf16x8 pf[2];
   float psum = 0.f;
 #pragma unroll
-  for (int st = 0; st < 2; ++st)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const bf16_t pb = static_cast<bf16_t>(exp2f(s[st][v] - m_safe));
-      psum += static_cast<float>(pb);
-      pf[st][v >> 3][v & 7] = pb;
-    }
+  for (int v = 0; v < 16; ++v) {
+    const bf16_t pb = static_cast<bf16_t>(__builtin_amdgcn_exp2f(s[v] - m_safe));
+    psum += static_cast<float>(pb);
+    pf[v >> 3][v & 7] = pb;
+  }
   w.l_run = w.l_run * alpha + psum;
   w.m_run = m_new;
 #pragma unroll
   for (int n = 0; n < 4; ++n) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) w.o[n][v] *= alpha;
-    const bf16_t* vp = vt + (n * 32 + l32) * VT_STRIDE + 4 * hh;
+    const bf16_t* vp = vt + (n * 32 + l32) * VT_STRIDE + st * 32 + 4 * hh;
 #pragma unroll
-    for (int st = 0; st < 2; ++st)
-#pragma unroll
-      for (int k2 = 0; k2 < 2; ++k2) {
-        const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vp + st * 32 + 16 * k2);
-        const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vp + st * 32 + 16 * k2 + 8);
-        bf16x8 vf;
-        vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
-        vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
-        w.o[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[st][k2], w.o[n], 0, 0, 0);
-      }
+    for (int k2 = 0; k2 < 2; ++k2) {
+      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vp + 16 * k2);
+      const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vp + 16 * k2 + 8);
+      bf16x8 vf;
+      vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
+      vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
+      w.o[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[k2], w.o[n], 0, 0, 0);
+    }
   }
 }
 
@@ -161,7 +158,7 @@ struct AttnKArgs {
   int M, B, Hq, Hkv, P, ld, nQ, nS;
 };
 
-__global__ __launch_bounds__(256) void attn_prefix_mfma_kernel(AttnKArgs a) {
+__global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
@@ -174,8 +171,9 @@ __global__ __launch_bounds__(256) void attn_prefix_mfma_kernel(AttnKArgs a) {
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int l32 = lane & 31, hh = lane >> 5;
+  const int qw = wave >> 1, st = wave & 1;    // query group of the wavefront pair, key half of this wavefront
   const int m0 = qt * QTILE;
-  const int m0w = m0 + wave * 32;
+  const int m0w = m0 + qw * 32;
   const int qrow = min(m0w + l32, a.M - 1);
 
   WaveState w;
@@ -227,10 +225,10 @@ __global__ __launch_bounds__(256) void attn_prefix_mfma_kernel(AttnKArgs a) {
     const bf16_t* ks = smem + cur * BUF_ELEMS;
     const int key0 = kbeg + t * KTILE;
     if (key0 + KTILE <= kend) {
-      process_tile<false>(w, ks, ks + KS_ELEMS, l32, hh, [](int) { return true; });
+      process_tile<false>(w, ks, ks + KS_ELEMS, st, l32, hh, [](int) { return true; });
     } else {
       const int nvalid = kend - key0;
-      process_tile<true>(w, ks, ks + KS_ELEMS, l32, hh, [nvalid](int key) { return key < nvalid; });
+      process_tile<true>(w, ks, ks + KS_ELEMS, st, l32, hh, [nvalid](int key) { return key < nvalid; });
     }
     if (t + 1 < n_tiles) {
       bf16_t* nb = smem + (cur ^ 1) * BUF_ELEMS;
@@ -254,10 +252,8 @@ __global__ __launch_bounds__(256) void attn_prefix_mfma_kernel(AttnKArgs a) {
     bf16_t* vt = smem + KS_ELEMS;
     for (int r0 = own_lo; r0 < own_hi; r0 += KTILE) {
       // K rows r0..r0+63 with rotary embedding: thread handles (key, chunk ch) and its partner ch+8
-#pragma unroll
-      for (int i = 0; i < 2; ++i) {
-        const int u = threadIdx.x + 256 * i;
-        const int key = u >> 3, ch = u & 7;
+      {
+        const int key = threadIdx.x >> 3, ch = threadIdx.x & 7;
         const int row = min(r0 + key, a.M - 1);
         const bf16_t* kp = a.qkv + (size_t)row * a.ld + (a.Hq + kvh) * HD + ch * 8;
         const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(kp);
@@ -275,24 +271,57 @@ __global__ __launch_bounds__(256) void attn_prefix_mfma_kernel(AttnKArgs a) {
         *reinterpret_cast<bf16x8*>(ks + key * KS_STRIDE + ch * 8 + 64) = y2;
       }
       {
-        const int kq = threadIdx.x >> 4, ho = threadIdx.x & 15;
+        const int kp2 = threadIdx.x >> 4, ho = threadIdx.x & 15;
         KVRegs rv;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int row = min(r0 + 4 * kq + i, a.M - 1);
+        for (int i = 0; i < 2; ++i) {
+          const int row = min(r0 + 2 * kp2 + i, a.M - 1);
           rv.v[i] = *reinterpret_cast<const u32x4*>(a.qkv + (size_t)row * a.ld + (a.Hq + a.Hkv + kvh) * HD + ho * 8);
         }
         lstore_vt(rv, vt);
       }
       __syncthreads();
-      if (r0 < w_hi && r0 + KTILE > w_lo) {     // wave-uniform: this pass holds keys of my states
-        process_tile<true>(w, ks, vt, l32, hh, [r0, q_lo, q_hi, own_hi](int key) {
-          const int row = r0 + key;
-          return row >= q_lo && row < q_hi && row < own_hi;
-        });
+      // own-block keys always go to the first wavefront of the pair, sub-tile by sub-tile in row order, so
+      // a state's arithmetic does not depend on where its rows sit in the 128-row tile
+      if (st == 0) {
+#pragma unroll
+        for (int sub = 0; sub < 2; ++sub) {
+          const int k_lo = r0 + sub * 32;
+          if (k_lo < w_hi && k_lo + 32 > w_lo) {   // wave-uniform: this half holds keys of my states
+            process_tile<true>(w, ks, vt, sub, l32, hh, [r0, q_lo, q_hi, own_hi](int key) {
+              const int row = r0 + key;
+              return row >= q_lo && row < q_hi && row < own_hi;
+            });
+          }
+        }
       }
       __syncthreads();
     }
+  }
+
+  // ---- merge the two key halves of each wavefront pair through LDS ------------------------------
+  {
+    float* xb = reinterpret_cast<float*>(smem_raw) + (size_t)qw * 66 * 64;   // [66][64 lanes] per pair
+    if (st == 1) {
+#pragma unroll
+      for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) xb[(n * 16 + v) * 64 + lane] = w.o[n][v];
+      xb[64 * 64 + lane] = w.m_run;
+      xb[65 * 64 + lane] = w.l_run;
+    }
+    __syncthreads();
+    if (st == 1) return;
+    const float m1 = xb[64 * 64 + lane], l1 = xb[65 * 64 + lane];
+    const float mm = fmaxf(w.m_run, m1);
+    const float a0 = (w.m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(w.m_run - mm);
+    const float a1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - mm);
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) w.o[n][v] = w.o[n][v] * a0 + xb[(n * 16 + v) * 64 + lane] * a1;
+    w.l_run = w.l_run * a0 + l1 * a1;
+    w.m_run = mm;
   }
 
   // ---- write ----------------------------------------------------------------------------------
@@ -409,7 +438,7 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   k.ld = (a.Hq + 2 * a.Hkv) * HD;
   k.nQ = cdiv(M, QTILE);
   k.nS = nS;
-  attn_prefix_mfma_kernel<<<k.nQ * nS * a.Hq, 256, kAttnSmem, st>>>(k);
+  attn_prefix_mfma_kernel<<<k.nQ * nS * a.Hq, NT, kAttnSmem, st>>>(k);
   if (nS > 1) attn_combine_kernel<<<M * a.Hq, 128, 0, st>>>(opart, mlpart, (bf16_t*)a.out, M, a.Hq, nS);
   return hipGetLastError();
 }

@@ -28,6 +28,8 @@
 //
 // The accumulation order along K of every output element is fixed by (N, K) alone, so a row's result
 // does not depend on how many other states are verified with it.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace spiffy {
@@ -70,7 +72,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   const int tj = (EPI == EPI_LMHEAD) ? L % tiles_j : L / tiles_i;
   const int i0 = ti * BM, j0 = tj * BN;
 
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  // the wavefront id is uniform: keep it (and all LDS destination arithmetic) in scalar registers
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, hh = lane >> 5;
 
@@ -137,9 +140,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   auto load_dp = [&](int q, int t) { if (XDEEP) load_x(q, t); else load_y(q, t); };
   // load `idx` of group g (the loads issued after barrier g): shallow operand of tile g+2 first, then
   // the deep operand of tile g+SD
-  auto group_load = [&](int idx, int g) {
-    if (idx < LS) { if (g + 2 < KT) load_sh(idx, g + 2); }
-    else { if (g + SD < KT) load_dp(idx - LS, g + SD); }
+  auto group_load = [&](int idx, int g, bool checked = true) {
+    if (idx < LS) { if (!checked || g + 2 < KT) load_sh(idx, g + 2); }
+    else { if (!checked || g + SD < KT) load_dp(idx - LS, g + SD); }
   };
 
   f32x16 acc[TM][TN];
@@ -182,7 +185,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 #pragma unroll
   for (int r = 0; r < NF; ++r) ldfrag(0, Xs, Ys, 0, r);
 
-  for (int kt = 0; kt < KT; ++kt) {
+  // one K-tile; STEADY = every tile this iteration prefetches exists (no bounds checks, no branches)
+  auto k_tile = [&](int kt, auto steady_tag) {
+    constexpr bool STEADY = decltype(steady_tag)::value;
     const bf16_t* xs = Xs + (kt % SX) * XSTAGE;
     const bf16_t* ys = Ys + (kt % SY) * YSTAGE;
     // K steps 0..2 of the tile: MFMAs on fragment buffer kk&1, fragments of step kk+1 into the other
@@ -195,13 +200,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kk & 1][i], fy[kk & 1][j], acc[i][j], 0, 0, 0);
         if (m >= 1 && m - 1 < NF) ldfrag((kk + 1) & 1, xs, ys, kk + 1, m - 1);
         const int slot = NMF + kk * NMF + m;      // position among the NSLOT MFMAs that follow barrier kt-1
-        if (((slot + 1) * NL) / NSLOT != (slot * NL) / NSLOT) group_load((slot * NL) / NSLOT, kt - 1);
+        if (((slot + 1) * NL) / NSLOT != (slot * NL) / NSLOT) group_load((slot * NL) / NSLOT, kt - 1, !STEADY);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
     // barrier kt: tile kt+1 is in LDS for every wavefront (only the deep-operand loads of group kt-1
     // may still fly), and no wavefront reads the stages of tile kt after this point
-    if (!short_k && kt + SD - 1 < KT) wait_vmcnt<LD>(); else wait_vmcnt<0>();
+    if (STEADY || (!short_k && kt + SD - 1 < KT)) wait_vmcnt<LD>(); else wait_vmcnt<0>();
     wait_lgkm0();
     __builtin_amdgcn_s_barrier();
     const bf16_t* xs1 = Xs + ((kt + 1) % SX) * XSTAGE;
@@ -212,10 +217,17 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
       const int i = m / TN, j = m % TN;
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[1][i], fy[1][j], acc[i][j], 0, 0, 0);
       if (m >= 1 && m - 1 < NF) ldfrag(0, xs1, ys1, 0, m - 1);
-      if (((m + 1) * NL) / NSLOT != (m * NL) / NSLOT) group_load((m * NL) / NSLOT, kt);
+      if (((m + 1) * NL) / NSLOT != (m * NL) / NSLOT) group_load((m * NL) / NSLOT, kt, !STEADY);
       __builtin_amdgcn_sched_barrier(0);
     }
+  };
+  // steady state: kt >= 1 (group kt-1 exists as a whole) and kt + SD < KT (everything prefetched exists)
+  int kt = 0;
+  if (!short_k) {
+    k_tile(0, std::false_type{});
+    for (kt = 1; kt + SD < KT; ++kt) k_tile(kt, std::true_type{});
   }
+  for (; kt < KT; ++kt) k_tile(kt, std::false_type{});
 
   // accumulator element (i,j,v) of this lane: row  = i0 + wm*128 + i*32 + 8*(v/4) + 4*hh + v%4
   //                                           col  = wn*(BN/2) + j*32 + l32   (within the tile)

@@ -149,14 +149,28 @@ int check_layer_args(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w,
   return SPIFFY_OK;
 }
 
+// Chaining hints used by the whole-step driver: `normed_in` = ws.n already holds RMSNorm-1 of hidden_in
+// (written by the previous layer's last kernel); `next_norm1` = gain of the next layer's RMSNorm-1, to be
+// produced into ws.n by this layer's last kernel; `rope_ready` = the rotary table is already in place.
+struct LayerChain {
+  bool normed_in = false;
+  const void* next_norm1 = nullptr;
+  bool rope_ready = false;
+  bool normed_out = false;   // set when ws.n holds the next layer's normalised input on return
+};
+
 int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const spiffy_prefix_kv* prefix,
-              const void* hidden_in, int G, int B, int pos0, void* hidden_out, void* workspace, hipStream_t st) {
+              const void* hidden_in, int G, int B, int pos0, void* hidden_out, void* workspace, hipStream_t st,
+              LayerChain* chain = nullptr) {
   const int M = G * B, d = cfg->d, dt = cfg->dtype;
   const int qd = cfg->n_q_heads * cfg->head_dim, kvd = cfg->n_kv_heads * cfg->head_dim;
   const bool mf = layer_mfma(cfg);
   const LayerWs ws = carve_layer(cfg, G, B, prefix->P, workspace);
   int rc;
-  if ((rc = dev(launch_rmsnorm(dt, hidden_in, w->norm1, cfg->rms_eps, M, d, nullptr, nullptr, ws.n, st)))) return rc;
+  if (chain) chain->normed_out = false;
+  if (!(chain && chain->normed_in) &&
+      (rc = dev(launch_rmsnorm(dt, hidden_in, w->norm1, cfg->rms_eps, M, d, nullptr, nullptr, ws.n, st))))
+    return rc;
 
   GemmArgs g;
   std::memset(&g, 0, sizeof(g));
@@ -171,7 +185,7 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   AttnArgs a;
   a.qkv = ws.qkv; a.prefix_k = prefix->k; a.prefix_v = prefix->v; a.out = ws.attn; a.partial = ws.attn_partial;
   a.G = G; a.B = B; a.Hq = cfg->n_q_heads; a.Hkv = cfg->n_kv_heads; a.hd = cfg->head_dim; a.P = prefix->P;
-  a.pos0 = pos0; a.rope_base = cfg->rope_base;
+  a.pos0 = pos0; a.rope_base = cfg->rope_base; a.rope_ready = chain && chain->rope_ready;
   if ((rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st)))) return rc;
 
   // output projection + residual (+ RMSNorm-2 fused into the split-K reduction when K is sliced)
@@ -209,7 +223,10 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
     if (ks > 1) {
       g.C = ws.splitk; g.ksplit = ks;
       if ((rc = dev(launch_gemm_mfma(EPI_PARTIAL, g, st)))) return rc;
-      return dev(launch_splitk_reduce((const float*)ws.splitk, ks, ws.h, hidden_out, nullptr, 0.f, nullptr, M, d, st));
+      const void* ng = chain ? chain->next_norm1 : nullptr;
+      if (chain && ng) chain->normed_out = true;
+      return dev(launch_splitk_reduce((const float*)ws.splitk, ks, ws.h, hidden_out, ng, cfg->rms_eps,
+                                      ng ? ws.n : nullptr, M, d, st));
     }
     return dev(launch_gemm_mfma(EPI_RESID, g, st));
   }
@@ -401,8 +418,13 @@ int spiffy_verify_step(const spiffy_model_cfg* cfg, int32_t n_layers, const spif
   void* hid = hidden_out ? hidden_out : ws.hidden;
   int32_t* tgt = target_states ? target_states : ws.target;
   if ((rc = dev(launch_embed(cfg->dtype, w_embed, block_tokens, G * B, cfg->d, cfg->vocab, hid, st)))) return rc;
-  for (int l = 0; l < n_layers; ++l)
-    if ((rc = run_layer(cfg, &layers[l], &prefix[l], hid, G, B, pos0, hid, ws.rest, st))) return rc;
+  LayerChain chain;
+  for (int l = 0; l < n_layers; ++l) {
+    chain.normed_in = chain.normed_out;
+    chain.next_norm1 = (l + 1 < n_layers) ? layers[l + 1].norm1 : nullptr;
+    if ((rc = run_layer(cfg, &layers[l], &prefix[l], hid, G, B, pos0, hid, ws.rest, st, &chain))) return rc;
+    chain.rope_ready = true;      // same pos0 / B / base for every layer: the table is computed once
+  }
   if ((rc = run_head(cfg, hid, final_norm, w_vocab, block_tokens, nullptr, G, B, threshold, logit_scale, force_one,
                      argmax, conf, unmask, top2_margin, tgt, ws.rest, st)))
     return rc;

@@ -50,25 +50,37 @@ __device__ __forceinline__ float block_max_256(float v, float* red) {
   return fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
 }
 
+// 16 bytes per thread per step; d * sizeof(T) is a multiple of 16 (checked by the host)
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const T* __restrict__ x, const T* __restrict__ gain, float eps,
                                                       int M, int d, const int32_t* __restrict__ row_idx,
                                                       const int32_t* __restrict__ n_rows_dev, T* __restrict__ out) {
+  constexpr int VEC = 16 / sizeof(T);
+  typedef T vec_t __attribute__((ext_vector_type(VEC)));
   __shared__ float red[4];
   const int r = blockIdx.x;
   const int n_rows = n_rows_dev ? *n_rows_dev : M;
   if (r >= n_rows) return;
   const int src = row_idx ? row_idx[r] : r;
-  const T* xr = x + (size_t)src * d;
+  const vec_t* xr = reinterpret_cast<const vec_t*>(x + (size_t)src * d);
+  const vec_t* gr = reinterpret_cast<const vec_t*>(gain);
+  vec_t* o = reinterpret_cast<vec_t*>(out + (size_t)r * d);
+  const int nv = d / VEC;
   float ss = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    float v = to_f32(xr[i]);
-    ss += v * v;
+  for (int i = threadIdx.x; i < nv; i += 256) {
+    const vec_t v = xr[i];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) { const float f = to_f32(v[e]); ss += f * f; }
   }
   ss = block_sum_256(ss, red);
   const float inv = 1.0f / sqrtf(ss / (float)d + eps);
-  T* o = out + (size_t)r * d;
-  for (int i = threadIdx.x; i < d; i += 256) o[i] = from_f32<T>(to_f32(xr[i]) * inv * to_f32(gain[i]));
+  for (int i = threadIdx.x; i < nv; i += 256) {
+    const vec_t v = xr[i], g = gr[i];
+    vec_t w;
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) w[e] = from_f32<T>(to_f32(v[e]) * inv * to_f32(g[e]));
+    o[i] = w;
+  }
 }
 
 hipError_t launch_rmsnorm(int dtype, const void* x, const void* gain, float eps, int M, int d,

@@ -22,6 +22,7 @@ struct AttnArgs {
   void* partial;         // MFMA path: split partials (fp32)
   int G, B, Hq, Hkv, hd, P, pos0;
   float rope_base;
+  int rope_ready;        // MFMA path: the rotary table at the start of `partial` is already filled
 };
 hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t st);
 

@@ -424,7 +424,7 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   float* mlpart = reinterpret_cast<float*>(ws);
 
   const int nrope = a.B * (HD / 2);
-  rope_table_kernel<<<cdiv(nrope, 256), 256, 0, st>>>(rope, a.B, HD / 2, HD, a.pos0, a.rope_base);
+  if (!a.rope_ready) rope_table_kernel<<<cdiv(nrope, 256), 256, 0, st>>>(rope, a.B, HD / 2, HD, a.pos0, a.rope_base);
 
   AttnKArgs k;
   k.qkv = (const bf16_t*)a.qkv;

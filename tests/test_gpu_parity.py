@@ -409,3 +409,21 @@ def test_gemm_against_float64_matmul(sp, M, N, K, epi):
     torch.cuda.synchronize()
     e_max, e_norm = rel_err(to_np(got.cpu()), ref)
     assert e_max < 1e-2 and e_norm < 4e-3, (e_max, e_norm)
+
+
+def test_small_block_duplicates_are_bit_identical(sp):
+    """Small-block configuration: every unmask-subset state appears four times; copies must give
+    bit-identical rows and (through the whole step) identical decisions."""
+    cfg = synth.CONFIGS["c5"].scaled(L=1, d=512, Hq=4, Hkv=4, F=768, V=1280, P=1500)
+    st, e = synth.draft_graph("c5", synth.CONFIGS["c5"])
+    st = np.where(st == synth.CONFIGS["c5"].mask_id, cfg.mask_id, st % (cfg.V - 1)).astype(np.int32)
+    plan, layers, prefix, hw, w_embed, _, _ = build_step(sp, cfg, "c5", 3, 30.0)
+    out = plan.run(torch.from_numpy(st).to(DEV), torch.from_numpy(e).to(DEV))
+    torch.cuda.synchronize()
+    hid = out["hidden"].cpu()
+    n = 1 << cfg.B
+    for k in range(1, cfg.G // n):
+        assert torch.equal(hid[:n], hid[k * n:(k + 1) * n]), k
+        for key in ("argmax", "unmask", "target_states"):
+            assert torch.equal(out[key][:n], out[key][k * n:(k + 1) * n]), (k, key)
+        assert torch.equal(out["conf"][:n], out["conf"][k * n:(k + 1) * n])

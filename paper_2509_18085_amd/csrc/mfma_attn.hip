@@ -11,6 +11,12 @@
 // so the tile comes from HBM once and from L2 afterwards.  The number of prefix splits depends on
 // P only, so a row's arithmetic does not depend on G.
 //
+// Prefix tiles travel global -> LDS directly (LDS-DMA loads, no registers) into a ring of NSTAGE
+// stages, up to NSTAGE-1 tiles ahead of the MFMAs, one barrier per tile.  Both K and V keep their [key][hd]
+// rows in LDS, 16-byte chunks permuted per row so that fragment reads are conflict-free:
+//   K row r: chunk c sits at position c ^ (r & 15)          (16-byte reads of one chunk per lane)
+//   V row r: 64-byte unit u sits at position u ^ (r & 3)    (transposing 8-byte reads, below)
+//
 // Eight wavefronts per workgroup: wavefront pair p owns query rows 32p..32p+31, and the two wavefronts
 // of a pair split every 64-key tile between them (32 keys each), each keeping its own running
 // (max, sum, O); the pair is merged through LDS at the end.  Two wavefronts per SIMD let the softmax
@@ -20,8 +26,10 @@
 //   S^T = K Q^T    A operand = K rows from LDS, B operand = rotated, pre-scaled Q in registers
 //                  -> lane (q, half) holds 16 of the 32 keys of a sub-tile for its query q
 //   online softmax max / sum are reductions over the lane's own registers plus one xor-32 shuffle
-//   O^T = V^T P^T  A operand = V^T from a transposed LDS tile, B operand = P^T straight from the
-//                  S^T accumulators (no trip through LDS); the rescale factor is per lane.
+//   O^T = V^T P^T  A operand = V^T, read from the row-major V tile with the transposing LDS read
+//                  (ds_read_b64_tr_b16: in every group of 16 lanes, lane 4q+c receives element c of the
+//                  8-byte pieces addressed by lanes q, q+4, q+8, q+12), B operand = P^T straight from
+//                  the S^T accumulators (no trip through LDS); the rescale factor is per lane.
 // Rotary embedding (positions pos0..pos0+B-1 for every state, Sec. 4.3) is applied to Q when it is
 // loaded and to the own-block K when it is staged; the cached prefix K arrives rotated.
 #include "kernels.h"
@@ -33,59 +41,29 @@ namespace {
 constexpr int HD = 128;
 constexpr int KTILE = 64;
 constexpr int QTILE = 128;
-constexpr int KS_STRIDE = HD + 8;     // bf16 per K row in LDS (272 B: conflict-free 16-byte reads)
-constexpr int VT_STRIDE = KTILE + 4;  // bf16 per V^T row in LDS (136 B: conflict-free 8-byte reads)
-constexpr int KS_ELEMS = KTILE * KS_STRIDE;
-constexpr int VT_ELEMS = HD * VT_STRIDE;
-constexpr int BUF_ELEMS = KS_ELEMS + VT_ELEMS;
+constexpr int NSTAGE = 4;
+constexpr int TILE_ELEMS = KTILE * HD;          // one K or V tile: 16 KB
+constexpr int STAGE_ELEMS = 2 * TILE_ELEMS;     // K tile then V tile
 constexpr int SPLIT_KEYS = 1024;
-constexpr size_t kAttnSmem = sizeof(bf16_t) * 2 * BUF_ELEMS;  // 69,632 B
+constexpr size_t kAttnSmem = sizeof(bf16_t) * NSTAGE * STAGE_ELEMS;  // 131,072 B
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef __attribute__((address_space(3))) void* lds_ptr_t;
+typedef const __attribute__((address_space(1))) void* glb_ptr_t;
+typedef __attribute__((address_space(3))) bf16x4* lds_bf16x4_ptr_t;
 
 constexpr int NT = 512;   // threads per workgroup
+constexpr int DMA_PER_TILE = 4;   // LDS-DMA loads per thread per prefix tile (2 for K, 2 for V)
 
-struct KVRegs {
-  u32x4 k[2];
-  u32x4 v[2];
-};
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {   // vmcnt <= N; lgkmcnt / expcnt untouched
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | (7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+}
 
-__device__ __forceinline__ bf16x8 as_bf16x8(u32x4 x) { return __builtin_bit_cast(bf16x8, x); }
-
-// prefix tile: keys key0..key0+63 of kv head (rows clamped to the last valid key)
-__device__ __forceinline__ void gload_prefix(KVRegs& r, const bf16_t* __restrict__ pk, const bf16_t* __restrict__ pv,
-                                             int key0, int key_last) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int c = threadIdx.x + NT * i;
-    const int key = min(key0 + (c >> 4), key_last);
-    r.k[i] = *reinterpret_cast<const u32x4*>(pk + (size_t)key * HD + (c & 15) * 8);
-  }
-  const int kp = threadIdx.x >> 4, ho = threadIdx.x & 15;
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int key = min(key0 + 2 * kp + i, key_last);
-    r.v[i] = *reinterpret_cast<const u32x4*>(pv + (size_t)key * HD + ho * 8);
-  }
-}
-__device__ __forceinline__ void lstore_k(const KVRegs& r, bf16_t* ks) {
-#pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int c = threadIdx.x + NT * i;
-    *reinterpret_cast<u32x4*>(ks + (c >> 4) * KS_STRIDE + (c & 15) * 8) = r.k[i];
-  }
-}
-// V arrives as 2 keys x 8 head-dim values per thread; LDS wants V^T[hd][key]
-__device__ __forceinline__ void lstore_vt(const KVRegs& r, bf16_t* vt) {
-  const int kp = threadIdx.x >> 4, ho = threadIdx.x & 15;
-  const bf16x8 r0 = as_bf16x8(r.v[0]), r1 = as_bf16x8(r.v[1]);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    bf16x2 t;
-    t[0] = r0[e]; t[1] = r1[e];
-    *reinterpret_cast<bf16x2*>(vt + (ho * 8 + e) * VT_STRIDE + 2 * kp) = t;
-  }
-}
+// position (in 16-byte chunks) of chunk c of row r inside the LDS tiles
+__device__ __forceinline__ int k_pos(int r, int c) { return c ^ (r & 15); }
+__device__ __forceinline__ int v_pos(int r, int c) { return c ^ ((r & 3) << 2); }
 
 struct WaveState {
   bf16x8 qf[8];     // rotated, scaled Q^T fragments: hd = 16*kk + 8*half + e
@@ -93,19 +71,44 @@ struct WaveState {
   float m_run, l_run;
 };
 
+// O *= alpha, in place (the multiplies are opaque to the compiler so that the rarely taken branch around
+// them does not cost a copy of the 64 accumulator registers on every tile)
+__device__ __forceinline__ void rescale_in_place(WaveState& w, float alpha) {
+#pragma unroll
+  for (int n = 0; n < 4; ++n)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      float x = w.o[n][v];
+      asm volatile("v_mul_f32 %0, %1, %0" : "+v"(x) : "v"(alpha));
+      w.o[n][v] = x;
+    }
+}
+
+// max of a value and its partner 32 lanes away, without a trip through LDS: after the swap one result
+// holds the low half's values in both halves, the other the high half's
+__device__ __forceinline__ float max_with_other_half(float x) {
+  typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+  const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
 // The wavefront's 32-key half (`st`) of a 64-key tile against its 32 queries.  `valid(key_in_tile)` masks
 // keys (only called when MASKED).  Scores are in the log2 domain (Q carries log2(e)/sqrt(hd)).
 template <bool MASKED, typename ValidFn>
-__device__ __forceinline__ void process_tile(WaveState& w, const bf16_t* __restrict__ ks, const bf16_t* __restrict__ vt,
-                                             int st, int l32, int hh, ValidFn valid) {
+__device__ __forceinline__ void process_tile(WaveState& w, const bf16_t* __restrict__ ks, const bf16_t* __restrict__ vs,
+                                             int st, int lane, ValidFn valid) {
+  const int l32 = lane & 31, hh = lane >> 5;
   f32x16 s;
 #pragma unroll
   for (int v = 0; v < 16; ++v) s[v] = 0.f;
-  const bf16_t* kp = ks + (st * 32 + l32) * KS_STRIDE + hh * 8;
+  {
+    const int row = st * 32 + l32;
+    const bf16_t* kp = ks + row * HD;
 #pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + kk * 16);
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[kk], s, 0, 0, 0);
+    for (int kk = 0; kk < 8; ++kk) {
+      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + k_pos(row, 2 * kk + hh) * 8);
+      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[kk], s, 0, 0, 0);
+    }
   }
   float tmax = -INFINITY;
 #pragma unroll
@@ -116,34 +119,130 @@ __device__ __forceinline__ void process_tile(WaveState& w, const bf16_t* __restr
     }
     tmax = fmaxf(tmax, s[v]);
   }
-  tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+  tmax = max_with_other_half(tmax);
   const float m_new = fmaxf(w.m_run, tmax);
   const float alpha = (w.m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(w.m_run - m_new);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
   bf16x8 pf[2];
   float psum = 0.f;
+  const bf16x2 ones = {static_cast<bf16_t>(1.0f), static_cast<bf16_t>(1.0f)};
 #pragma unroll
-  for (int v = 0; v < 16; ++v) {
-    const bf16_t pb = static_cast<bf16_t>(__builtin_amdgcn_exp2f(s[v] - m_safe));
-    psum += static_cast<float>(pb);
-    pf[v >> 3][v & 7] = pb;
+  for (int i = 0; i < 8; ++i) {
+    f32x2 e;
+    e[0] = __builtin_amdgcn_exp2f(s[2 * i] - m_safe);
+    e[1] = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_safe);
+    const bf16x2 pb = __builtin_convertvector(e, bf16x2);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, psum, false);
+    pf[i >> 2][(2 * i) & 7] = pb[0];
+    pf[i >> 2][(2 * i + 1) & 7] = pb[1];
   }
   w.l_run = w.l_run * alpha + psum;
   w.m_run = m_new;
+  // multiplying by exactly 1 changes nothing: skip the rescale when no lane's maximum moved
+  if (__builtin_amdgcn_ballot_w64(alpha != 1.f) != 0) rescale_in_place(w, alpha);
+  // V^T fragments: lane j of a 16-lane group addresses key (j / 4) of its 4-key run, hd block 4 * (j % 4)
+  // of the group's 16 rows; the transposing read hands lane 4q+c the 4 keys of hd row 4q+c
+  const int g = lane >> 4, j = lane & 15;
+  const int vkey = st * 32 + 4 * (g >> 1) + (j >> 2);     // + 16*k2 + 8*eh, which keep (key & 3)
+  const bf16_t* vp = vs + vkey * HD + 16 * (g & 1) + 4 * (j & 3);
 #pragma unroll
   for (int n = 0; n < 4; ++n) {
-#pragma unroll
-    for (int v = 0; v < 16; ++v) w.o[n][v] *= alpha;
-    const bf16_t* vp = vt + (n * 32 + l32) * VT_STRIDE + st * 32 + 4 * hh;
+    const int unit = (n ^ (vkey & 3)) * 32;
 #pragma unroll
     for (int k2 = 0; k2 < 2; ++k2) {
-      const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vp + 16 * k2);
-      const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vp + 16 * k2 + 8);
+      const bf16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr_t)(vp + (16 * k2) * HD + unit));
+      const bf16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr_t)(vp + (16 * k2 + 8) * HD + unit));
       bf16x8 vf;
       vf[0] = lo[0]; vf[1] = lo[1]; vf[2] = lo[2]; vf[3] = lo[3];
       vf[4] = hi[0]; vf[5] = hi[1]; vf[6] = hi[2]; vf[7] = hi[3];
       w.o[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[k2], w.o[n], 0, 0, 0);
     }
+  }
+}
+
+// S^T of the wavefront's 32-key half of a full tile (no masking): 8 MFMAs
+__device__ __forceinline__ void scores(const WaveState& w, f32x16& s, const bf16_t* __restrict__ ks, int st, int lane) {
+  const int row = st * 32 + (lane & 31), hh = lane >> 5;
+  const bf16_t* kp = ks + row * HD;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) s[v] = 0.f;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) {
+    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + k_pos(row, 2 * kk + hh) * 8);
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[kk], s, 0, 0, 0);
+  }
+}
+
+// One step of the software pipeline over full prefix tiles: the online-softmax arithmetic on the scores
+// `s` of tile t runs between the score MFMAs of tile t+1 (K from `k_next`, result in `sn`, when NEXT),
+// then O += P V for tile t (V from `v_cur`).  Same arithmetic, in the same order, as process_tile<false>.
+template <bool NEXT>
+__device__ __forceinline__ void pipe_step(WaveState& w, const f32x16& s, f32x16& sn, const bf16_t* __restrict__ k_next,
+                                          const bf16_t* __restrict__ v_cur, int st, int lane) {
+  const int l32 = lane & 31, hh = lane >> 5;
+  bf16x8 kf[8];
+  if (NEXT) {
+    const int row = st * 32 + l32;
+    const bf16_t* kp = k_next + row * HD;
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk) kf[kk] = *reinterpret_cast<const bf16x8*>(kp + k_pos(row, 2 * kk + hh) * 8);
+  }
+  float tmax = s[0];
+#pragma unroll
+  for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[v]);
+  tmax = max_with_other_half(tmax);
+  const float m_new = fmaxf(w.m_run, tmax);     // finite: a full tile has no masked score
+  const float alpha = (w.m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(w.m_run - m_new);
+  const int g = lane >> 4, j = lane & 15;
+  const int vkey = st * 32 + 4 * (g >> 1) + (j >> 2);
+  const bf16_t* vp = v_cur + vkey * HD + 16 * (g & 1) + 4 * (j & 3);
+  if (NEXT) {
+#pragma unroll
+    for (int v = 0; v < 16; ++v) sn[v] = 0.f;
+  }
+  bf16x8 pf[2];
+  bf16x4 vlo[8], vhi[8];
+  float psum = 0.f;
+  const bf16x2 ones = {static_cast<bf16_t>(1.0f), static_cast<bf16_t>(1.0f)};
+  __builtin_amdgcn_sched_barrier(0);   // K fragment reads and the running-max chain stay above this line
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (NEXT) sn = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i], w.qf[i], sn, 0, 0, 0);
+    f32x2 e;
+    e[0] = __builtin_amdgcn_exp2f(s[2 * i] - m_new);
+    e[1] = __builtin_amdgcn_exp2f(s[2 * i + 1] - m_new);
+    const bf16x2 pb = __builtin_convertvector(e, bf16x2);
+    psum = __builtin_amdgcn_fdot2_f32_bf16(pb, ones, psum, false);
+    pf[i >> 2][(2 * i) & 7] = pb[0];
+    pf[i >> 2][(2 * i + 1) & 7] = pb[1];
+    {   // V^T fragment i: key step k2 = i / 4, hd block n = i % 4
+      const int k2 = i >> 2, n = i & 3;
+      const int unit = (n ^ (vkey & 3)) * 32;
+      vlo[i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr_t)(vp + (16 * k2) * HD + unit));
+      vhi[i] = __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4_ptr_t)(vp + (16 * k2 + 8) * HD + unit));
+    }
+  }
+  // issue order for the loop above: per score MFMA two exponentials with their subtract / convert / sum
+  // and two V fragment reads
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    if (NEXT) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x400, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+  }
+  w.l_run = w.l_run * alpha + psum;
+  w.m_run = m_new;
+  // the branch below must not move above the block it follows: make its condition depend on the block's results
+  float alpha_c = alpha;
+  if (NEXT) asm volatile("" : "+v"(alpha_c) : "v"(psum), "v"(sn[15]));
+  else asm volatile("" : "+v"(alpha_c) : "v"(psum));
+  if (__builtin_amdgcn_ballot_w64(alpha_c != 1.f) != 0) rescale_in_place(w, alpha_c);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const bf16x8 vf = __builtin_shufflevector(vlo[i], vhi[i], 0, 1, 2, 3, 4, 5, 6, 7);
+    w.o[i & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[i >> 2], w.o[i & 3], 0, 0, 0);
   }
 }
 
@@ -206,37 +305,74 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
     }
   }
 
-  // ---- prefix keys of this split ------------------------------------------------------------
+  // ---- prefix keys of this split: LDS-DMA ring, NSTAGE-1 tiles ahead ------------------------------
   const int kbeg = sp * SPLIT_KEYS;
   const int kend = min(a.P, kbeg + SPLIT_KEYS);
   const int n_tiles = kend > kbeg ? (kend - kbeg + KTILE - 1) / KTILE : 0;
   const bf16_t* pk = a.pk + (size_t)kvh * a.P * HD;
   const bf16_t* pv = a.pv + (size_t)kvh * a.P * HD;
-  KVRegs r;
-  if (n_tiles > 0) {
-    gload_prefix(r, pk, pv, kbeg, kend - 1);
-    lstore_k(r, smem);
-    lstore_vt(r, smem + KS_ELEMS);
-  }
-  __syncthreads();
-  for (int t = 0; t < n_tiles; ++t) {
-    const int cur = t & 1;
-    if (t + 1 < n_tiles) gload_prefix(r, pk, pv, kbeg + (t + 1) * KTILE, kend - 1);
-    const bf16_t* ks = smem + cur * BUF_ELEMS;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  // wavefront `wave` brings rows 8*wave .. 8*wave+7 of both tiles: lane -> (row, LDS position) -> source chunk
+  auto issue_tile = [&](int t) {
+    bf16_t* stage = smem + (t % NSTAGE) * STAGE_ELEMS;
     const int key0 = kbeg + t * KTILE;
-    if (key0 + KTILE <= kend) {
-      process_tile<false>(w, ks, ks + KS_ELEMS, st, l32, hh, [](int) { return true; });
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+      const int row = 8 * wave_u + 4 * q + (lane >> 4), pos = lane & 15;
+      const size_t src = (size_t)min(key0 + row, kend - 1) * HD;
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(pk + src + k_pos(row, pos) * 8),
+                                       (lds_ptr_t)(stage + (8 * wave_u + 4 * q) * HD), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(pv + src + v_pos(row, pos) * 8),
+                                       (lds_ptr_t)(stage + TILE_ELEMS + (8 * wave_u + 4 * q) * HD), 16, 0, 0);
+    }
+  };
+#pragma unroll
+  for (int t = 0; t < NSTAGE - 1; ++t)
+    if (t < n_tiles) issue_tile(t);
+  // full tiles run through the software pipeline (scores of tile t+1 under the softmax of tile t); a ragged
+  // last tile takes the masked path afterwards
+  const bool ragged = n_tiles > 0 && ((kend - kbeg) % KTILE) != 0;
+  const int n_pipe = ragged ? n_tiles - 1 : n_tiles;
+  if (n_pipe > 0) {
+    // tile 0 has landed; tiles 1 .. min(2, n_tiles-1) may still be in flight
+    if (n_tiles >= 3) wait_vmcnt<2 * DMA_PER_TILE>(); else if (n_tiles == 2) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    f32x16 sa, sb;
+    scores(w, sa, smem, st, lane);
+    // step t: tile t+1 has landed (tile t+2 may be in flight) and every wavefront is done with step t-1,
+    // i.e. with K of tile t and V of tile t-1, whose stage the next prefetch overwrites
+    auto sync_and_prefetch = [&](int t) {
+      if (t + 2 < n_tiles) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();
+      __builtin_amdgcn_s_barrier();
+      if (t + NSTAGE - 1 < n_tiles) issue_tile(t + NSTAGE - 1);
+    };
+    auto k_of = [&](int t) { return smem + (t % NSTAGE) * STAGE_ELEMS; };
+    auto v_of = [&](int t) { return smem + (t % NSTAGE) * STAGE_ELEMS + TILE_ELEMS; };
+    int t = 0;
+    for (; t + 2 < n_pipe; t += 2) {     // two steps per trip: the score registers swap roles
+      sync_and_prefetch(t);
+      pipe_step<true>(w, sa, sb, k_of(t + 1), v_of(t), st, lane);
+      sync_and_prefetch(t + 1);
+      pipe_step<true>(w, sb, sa, k_of(t + 2), v_of(t + 1), st, lane);
+    }
+    if (t + 1 < n_pipe) {
+      sync_and_prefetch(t);
+      pipe_step<true>(w, sa, sb, k_of(t + 1), v_of(t), st, lane);
+      sync_and_prefetch(t + 1);
+      pipe_step<false>(w, sb, sa, nullptr, v_of(t + 1), st, lane);
     } else {
-      const int nvalid = kend - key0;
-      process_tile<true>(w, ks, ks + KS_ELEMS, st, l32, hh, [nvalid](int key) { return key < nvalid; });
+      sync_and_prefetch(t);
+      pipe_step<false>(w, sa, sb, nullptr, v_of(t), st, lane);
     }
-    if (t + 1 < n_tiles) {
-      bf16_t* nb = smem + (cur ^ 1) * BUF_ELEMS;
-      lstore_k(r, nb);
-      lstore_vt(r, nb + KS_ELEMS);
-    }
-    __syncthreads();
   }
+  if (ragged) {
+    wait_vmcnt<0>();
+    __builtin_amdgcn_s_barrier();
+    const bf16_t* ks = smem + ((n_tiles - 1) % NSTAGE) * STAGE_ELEMS;
+    const int nvalid = kend - (kbeg + (n_tiles - 1) * KTILE);
+    process_tile<true>(w, ks, ks + TILE_ELEMS, st, lane, [nvalid](int key) { return key < nvalid; });
+  }
+  __syncthreads();   // all tiles consumed, no DMA in flight: the ring can be reused
 
   // ---- own-block keys: the block diagonal, handled by the last split --------------------------
   if (sp == a.nS - 1) {
@@ -249,7 +385,7 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
     const int q_lo = (qrow / a.B) * a.B;    // this lane's state: rows [q_lo, q_lo + B)
     const int q_hi = q_lo + a.B;
     bf16_t* ks = smem;
-    bf16_t* vt = smem + KS_ELEMS;
+    bf16_t* vs = smem + TILE_ELEMS;
     for (int r0 = own_lo; r0 < own_hi; r0 += KTILE) {
       // K rows r0..r0+63 with rotary embedding: thread handles (key, chunk ch) and its partner ch+8
       {
@@ -267,18 +403,18 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
           y1[e] = static_cast<bf16_t>(a1 * cs.x - a2 * cs.y);
           y2[e] = static_cast<bf16_t>(a2 * cs.x + a1 * cs.y);
         }
-        *reinterpret_cast<bf16x8*>(ks + key * KS_STRIDE + ch * 8) = y1;
-        *reinterpret_cast<bf16x8*>(ks + key * KS_STRIDE + ch * 8 + 64) = y2;
+        *reinterpret_cast<bf16x8*>(ks + key * HD + k_pos(key, ch) * 8) = y1;
+        *reinterpret_cast<bf16x8*>(ks + key * HD + k_pos(key, ch + 8) * 8) = y2;
       }
       {
         const int kp2 = threadIdx.x >> 4, ho = threadIdx.x & 15;
-        KVRegs rv;
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
-          const int row = min(r0 + 2 * kp2 + i, a.M - 1);
-          rv.v[i] = *reinterpret_cast<const u32x4*>(a.qkv + (size_t)row * a.ld + (a.Hq + a.Hkv + kvh) * HD + ho * 8);
+          const int key = 2 * kp2 + i;
+          const int row = min(r0 + key, a.M - 1);
+          const u32x4 x = *reinterpret_cast<const u32x4*>(a.qkv + (size_t)row * a.ld + (a.Hq + a.Hkv + kvh) * HD + ho * 8);
+          *reinterpret_cast<u32x4*>(vs + key * HD + v_pos(key, ho) * 8) = x;
         }
-        lstore_vt(rv, vt);
       }
       __syncthreads();
       // own-block keys always go to the first wavefront of the pair, sub-tile by sub-tile in row order, so
@@ -288,7 +424,7 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
         for (int sub = 0; sub < 2; ++sub) {
           const int k_lo = r0 + sub * 32;
           if (k_lo < w_hi && k_lo + 32 > w_lo) {   // wave-uniform: this half holds keys of my states
-            process_tile<true>(w, ks, vt, sub, l32, hh, [r0, q_lo, q_hi, own_hi](int key) {
+            process_tile<true>(w, ks, vs, sub, lane, [r0, q_lo, q_hi, own_hi](int key) {
               const int row = r0 + key;
               return row >= q_lo && row < q_hi && row < own_hi;
             });

@@ -185,6 +185,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 #pragma unroll
   for (int r = 0; r < NF; ++r) ldfrag(0, Xs, Ys, 0, r);
 
+  // fragment reads of the next K step issued after MFMA m of the current one: [frag_lo(m), frag_lo(m+1)).
+  // One per MFMA from the second on when there are enough MFMAs, else spread over all but the last.
+  auto frag_lo = [](int m) {
+    if (NF <= NMF - 1) return m < 1 ? 0 : (m - 1 < NF ? m - 1 : NF);
+    return m < NMF - 1 ? (m * NF) / (NMF - 1) : NF;
+  };
   // one K-tile; STEADY = every tile this iteration prefetches exists (no bounds checks, no branches)
   auto k_tile = [&](int kt, auto steady_tag) {
     constexpr bool STEADY = decltype(steady_tag)::value;
@@ -198,7 +204,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
       for (int m = 0; m < NMF; ++m) {
         const int i = m / TN, j = m % TN;
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kk & 1][i], fy[kk & 1][j], acc[i][j], 0, 0, 0);
-        if (m >= 1 && m - 1 < NF) ldfrag((kk + 1) & 1, xs, ys, kk + 1, m - 1);
+#pragma unroll
+        for (int r = frag_lo(m); r < frag_lo(m + 1); ++r) ldfrag((kk + 1) & 1, xs, ys, kk + 1, r);
         const int slot = NMF + kk * NMF + m;      // position among the NSLOT MFMAs that follow barrier kt-1
         if (((slot + 1) * NL) / NSLOT != (slot * NL) / NSLOT) group_load((slot * NL) / NSLOT, kt - 1, !STEADY);
         __builtin_amdgcn_sched_barrier(0);
@@ -216,7 +223,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     for (int m = 0; m < NMF; ++m) {
       const int i = m / TN, j = m % TN;
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[1][i], fy[1][j], acc[i][j], 0, 0, 0);
-      if (m >= 1 && m - 1 < NF) ldfrag(0, xs1, ys1, 0, m - 1);
+#pragma unroll
+      for (int r = frag_lo(m); r < frag_lo(m + 1); ++r) ldfrag(0, xs1, ys1, 0, r);
       if (((m + 1) * NL) / NSLOT != (m * NL) / NSLOT) group_load((m * NL) / NSLOT, kt, !STEADY);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -390,7 +398,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 
 // number of K slices for the narrow-N projections: a function of (N, K) only
 int mfma_ksplit(int N, int K) {
-  const int n_tiles = N / 128, kt = K / BKK;
+  const int n_tiles = cdiv(N, 128), kt = K / BKK;
   int ks = 1;
   while (ks < 4 && 4 * n_tiles * ks < 224 && kt / (ks + 1) >= 8) ++ks;
   return ks;
@@ -398,9 +406,9 @@ int mfma_ksplit(int N, int K) {
 
 bool mfma_gemm_supported(int epi, const GemmArgs& a) {
   if (a.K % BKK != 0 || a.K < BKK || a.M < 1) return false;
-  if (epi == EPI_SWIGLU) return a.N % 64 == 0;
+  if (epi == EPI_SWIGLU) return a.N % 32 == 0;
   if (epi == EPI_LMHEAD) return a.N >= 1;
-  if (a.N % 128 != 0) return false;
+  if (a.N % 64 != 0) return false;
   int n = 0;
   for (int s = 0; s < 3; ++s) {
     if (a.Nseg[s] < 0 || a.Nseg[s] % 8 != 0) return false;
@@ -411,20 +419,46 @@ bool mfma_gemm_supported(int epi, const GemmArgs& a) {
 
 int mfma_lmhead_partials_per_row(int V) { return cdiv(V, BM) * 2; }
 
+// Column-tile width: a pure scheduling choice (it never changes the K order of any output element).
+// Estimated cost = rounds over the 256 CUs x width / efficiency of that width.
+static int choose_bn(int m_tiles, int n_cols, int unit, int ksplit, bool allow192) {
+  const int widths[3] = {192, 128, 64};
+  const float eff[3] = {1.0f, 0.85f, 0.55f};
+  int best = 0;
+  float best_cost = 1e30f;
+  for (int i = 0; i < 3; ++i) {
+    const int cols = widths[i] / unit;          // output columns (or SwiGLU features) per tile
+    if ((i == 0 && !allow192) || n_cols % cols != 0) continue;
+    const int tiles = m_tiles * (n_cols / cols) * ksplit;
+    const float cost = (float)cdiv(tiles, 256) * widths[i] / eff[i];
+    if (cost < best_cost) { best_cost = cost; best = widths[i]; }
+  }
+  return best;
+}
+
 hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
   GemmArgs a = a0;
   if (a.ksplit < 1) a.ksplit = 1;
+  const int mt = cdiv(a.M, BM);
   switch (epi) {
-    case EPI_STORE:
-      if (a.N % 192 == 0) return launch_t<EPI_STORE, 192, 3>(a, cdiv(a.M, BM), a.N / 192, st);
-      return launch_t<EPI_STORE, 128, 4>(a, cdiv(a.M, BM), a.N / 128, st);
+    case EPI_STORE: {
+      const int bn = choose_bn(mt, a.N, 1, 1, true);
+      if (bn == 192) return launch_t<EPI_STORE, 192, 3>(a, mt, a.N / 192, st);
+      if (bn == 128) return launch_t<EPI_STORE, 128, 4>(a, mt, a.N / 128, st);
+      return launch_t<EPI_STORE, 64, 4>(a, mt, a.N / 64, st);
+    }
     case EPI_RESID:
-      return launch_t<EPI_RESID, 128, 4>(a, cdiv(a.M, BM), a.N / 128, st);
+      if (choose_bn(mt, a.N, 1, 1, false) == 64) return launch_t<EPI_RESID, 64, 4>(a, mt, a.N / 64, st);
+      return launch_t<EPI_RESID, 128, 4>(a, mt, a.N / 128, st);
     case EPI_PARTIAL:
-      return launch_t<EPI_PARTIAL, 128, 4>(a, cdiv(a.M, BM), a.N / 128, st);
-    case EPI_SWIGLU:
-      if (a.N % 96 == 0) return launch_t<EPI_SWIGLU, 192, 3>(a, cdiv(a.M, BM), a.N / 96, st);
-      return launch_t<EPI_SWIGLU, 128, 4>(a, cdiv(a.M, BM), a.N / 64, st);
+      if (choose_bn(mt, a.N, 1, a.ksplit, false) == 64) return launch_t<EPI_PARTIAL, 64, 4>(a, mt, a.N / 64, st);
+      return launch_t<EPI_PARTIAL, 128, 4>(a, mt, a.N / 128, st);
+    case EPI_SWIGLU: {
+      const int bn = choose_bn(mt, a.N, 2, 1, true);   // a tile of width w holds w/2 features
+      if (bn == 192) return launch_t<EPI_SWIGLU, 192, 3>(a, mt, a.N / 96, st);
+      if (bn == 128) return launch_t<EPI_SWIGLU, 128, 4>(a, mt, a.N / 64, st);
+      return launch_t<EPI_SWIGLU, 64, 4>(a, mt, a.N / 32, st);
+    }
     case EPI_LMHEAD:
       return launch_t<EPI_LMHEAD, 192, 3>(a, cdiv(a.N, BM), cdiv(a.M, 192), st);
     default:

@@ -288,22 +288,28 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 
   bf16_t* C = reinterpret_cast<bf16_t*>(a.C);
   if (EPI == EPI_SWIGLU) {
+    // lanes 0-15 of a half hold gate values, lanes 16-31 the up values of the same features.  For every
+    // pair of rows (v, v+1) the two lanes swap one value: the gate lane keeps row v and receives up(v), the up
+    // lane keeps row v+1 and receives gate(v+1); each then finishes and stores one row
+    const bool up_lane = (l32 & 16) != 0;
+    const int up = up_lane ? 1 : 0;
+    // per-lane part of the address once; the row part below is the same for every lane of the half
+    bf16_t* Cl = C + (size_t)up * a.ldc + tj * (BN / 2) + wn * TN * 16 + (l32 & 15);
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+      for (int v = 0; v < 16; v += 2) {
+        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the gate lane's row
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          const float mine = acc[i][j][v];
-          const float other = __shfl_xor(mine, 16, 64);
-          const float g = (l32 & 16) ? other : mine, u = (l32 & 16) ? mine : other;
-          // both lanes of a pair hold (g, u): lanes 0-15 store the even v, lanes 16-31 the odd v
-          const bool store = ((l32 >> 4) & 1) == (v & 1);
-          if (store && r < i_max) {
-            const int f = tj * (BN / 2) + (wn * TN + j) * 16 + (l32 & 15);
-            C[(size_t)r * a.ldc + f] = static_cast<bf16_t>(g / (1.f + __expf(-g)) * u);
-          }
+          float a0 = acc[i][j][v], a1 = acc[i][j][v + 1];
+          asm volatile("" : "+v"(a0), "+v"(a1));   // two plain selects below, not a lane-indexed element extract
+          const float keep = up_lane ? a1 : a0;
+          const float give = up_lane ? a0 : a1;
+          const float got = __shfl_xor(give, 16, 64);
+          const float g = up_lane ? got : keep, u = up_lane ? keep : got;
+          if (r + up < i_max)
+            Cl[(size_t)r * a.ldc + j * 16] = static_cast<bf16_t>(g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u);
         }
       }
     return;
@@ -311,29 +317,56 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 
   const bf16_t* R = reinterpret_cast<const bf16_t*>(a.R);
   const bool has_bias = EPI == EPI_STORE && (a.bias[0] || a.bias[1] || a.bias[2]);
+  // rows (v, v+1) of two neighbouring columns are regrouped so that every lane stores one 4-byte pair: the
+  // even lane takes row v (its own column and the next one), the odd lane row v+1
+  const int odd = l32 & 1;
+  float bv[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int n = j0 + wn * (BN / 2) + j * 32 + l32;
-    float bv = 0.f;
+    bv[j] = 0.f;
     if (has_bias) {
       const bf16_t* bp = nullptr;
       if (n < a.Nseg[0]) { if (a.bias[0]) bp = (const bf16_t*)a.bias[0] + n; }
       else if (n < a.Nseg[0] + a.Nseg[1]) { if (a.bias[1]) bp = (const bf16_t*)a.bias[1] + (n - a.Nseg[0]); }
       else { if (a.bias[2]) bp = (const bf16_t*)a.bias[2] + (n - a.Nseg[0] - a.Nseg[1]); }
-      if (bp) bv = static_cast<float>(*bp);
+      if (bp) bv[j] = static_cast<float>(*bp);
     }
+  }
+  // per-lane part of the address once; the row part below is the same for every lane of the half
+  const size_t lane_off = (size_t)odd * a.ldc + (j0 + wn * (BN / 2) + l32 - odd);
+  bf16_t* Cl = C + lane_off;
+  const bf16_t* Rl = R + lane_off;
+  auto store_all = [&](auto checked_tag) {
+    constexpr bool CHECKED = decltype(checked_tag)::value;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-        if (r >= i_max) continue;
-        const size_t o = (size_t)r * a.ldc + n;
-        float val = acc[i][j][v] + bv;
-        if (EPI == EPI_RESID) val += static_cast<float>(R[o]);
-        C[o] = static_cast<bf16_t>(val);
+      for (int v = 0; v < 16; v += 2) {
+        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the even lane's row
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+          float a0 = acc[i][j][v] + bv[j], a1 = acc[i][j][v + 1] + bv[j];
+          asm volatile("" : "+v"(a0), "+v"(a1));   // two plain selects below, not a lane-indexed element extract
+          const float keep = odd ? a1 : a0;
+          const float give = odd ? a0 : a1;
+          const float got = __shfl_xor(give, 1, 64);
+          float lo = odd ? got : keep, hi = odd ? keep : got;   // columns n-odd, n-odd+1 of row r+odd
+          if (CHECKED && r + odd >= i_max) continue;
+          const size_t o = (size_t)r * a.ldc + j * 32;
+          if (EPI == EPI_RESID) {
+            const bf16x2 rr = *reinterpret_cast<const bf16x2*>(Rl + o);
+            lo += static_cast<float>(rr[0]);
+            hi += static_cast<float>(rr[1]);
+          }
+          bf16x2 out2;
+          out2[0] = static_cast<bf16_t>(lo);
+          out2[1] = static_cast<bf16_t>(hi);
+          *reinterpret_cast<bf16x2*>(Cl + o) = out2;
+        }
       }
-  }
+  };
+  if (i0 + BM <= i_max) store_all(std::false_type{}); else store_all(std::true_type{});
 }
 
 template <int EPI, int BN, int SD>

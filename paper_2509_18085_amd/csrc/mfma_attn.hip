@@ -11,11 +11,15 @@
 // so the tile comes from HBM once and from L2 afterwards.  The number of prefix splits depends on
 // P only, so a row's arithmetic does not depend on G.
 //
-// Prefix tiles travel global -> LDS directly (LDS-DMA loads, no registers) into a ring of NSTAGE
-// stages, up to NSTAGE-1 tiles ahead of the MFMAs, one barrier per tile.  Both K and V keep their [key][hd]
-// rows in LDS, 16-byte chunks permuted per row so that fragment reads are conflict-free:
-//   K row r: chunk c sits at position c ^ (r & 15)          (16-byte reads of one chunk per lane)
+// Everything the workgroup reads travels global -> LDS directly as whole 256-byte rows (LDS-DMA loads, no
+// registers): the 128 Q rows and the own-block K/V rows once at the start, the prefix tiles into a ring of
+// NSTAGE stages, up to NSTAGE-1 tiles ahead of the MFMAs, one barrier per tile.  Rows keep their [row][hd]
+// layout in LDS, 16-byte chunks permuted per row so that fragment reads are conflict-free:
+//   Q / K row r: chunk c sits at position c ^ (r & 15)      (16-byte reads of one chunk per lane)
 //   V row r: 64-byte unit u sits at position u ^ (r & 3)    (transposing 8-byte reads, below)
+// The loop over full prefix tiles is software-pipelined: the score MFMAs of tile t+1 are issued between
+// the exponentials of tile t.  The O rescale is skipped when no lane's running maximum moved (multiplying
+// by exactly 1 changes nothing).
 //
 // Eight wavefronts per workgroup: wavefront pair p owns query rows 32p..32p+31, and the two wavefronts
 // of a pair split every 64-key tile between them (32 keys each), each keeping its own running
@@ -25,13 +29,18 @@
 // Per wavefront (32 query rows x 32 keys of a tile) everything is kept "query per lane":
 //   S^T = K Q^T    A operand = K rows from LDS, B operand = rotated, pre-scaled Q in registers
 //                  -> lane (q, half) holds 16 of the 32 keys of a sub-tile for its query q
-//   online softmax max / sum are reductions over the lane's own registers plus one xor-32 shuffle
+//   online softmax max / sum are reductions over the lane's own registers plus one half swap
 //   O^T = V^T P^T  A operand = V^T, read from the row-major V tile with the transposing LDS read
 //                  (ds_read_b64_tr_b16: in every group of 16 lanes, lane 4q+c receives element c of the
 //                  8-byte pieces addressed by lanes q, q+4, q+8, q+12), B operand = P^T straight from
 //                  the S^T accumulators (no trip through LDS); the rescale factor is per lane.
-// Rotary embedding (positions pos0..pos0+B-1 for every state, Sec. 4.3) is applied to Q when it is
-// loaded and to the own-block K when it is staged; the cached prefix K arrives rotated.
+// Own-block keys (the block diagonal) come first, handled by the last prefix split: they always go to the
+// first wavefront of a pair, 32 keys at a time in row order, so a state's arithmetic does not depend on
+// where its rows sit in the tile; the mask is applied per element (any B works).
+// Rotary embedding (positions pos0..pos0+B-1 for every state, Sec. 4.3) is applied to the Q and own-block K
+// fragments in registers, on their way from LDS to the matrix pipe; the cached prefix K arrives rotated.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace spiffy {
@@ -44,7 +53,7 @@ constexpr int QTILE = 128;
 constexpr int NSTAGE = 4;
 constexpr int TILE_ELEMS = KTILE * HD;          // one K or V tile: 16 KB
 constexpr int STAGE_ELEMS = 2 * TILE_ELEMS;     // K tile then V tile
-constexpr int SPLIT_KEYS = 1024;
+constexpr int SPLIT_KEYS = 2048;
 constexpr size_t kAttnSmem = sizeof(bf16_t) * NSTAGE * STAGE_ELEMS;  // 131,072 B
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -92,24 +101,24 @@ __device__ __forceinline__ float max_with_other_half(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
-// The wavefront's 32-key half (`st`) of a 64-key tile against its 32 queries.  `valid(key_in_tile)` masks
-// keys (only called when MASKED).  Scores are in the log2 domain (Q carries log2(e)/sqrt(hd)).
-template <bool MASKED, typename ValidFn>
-__device__ __forceinline__ void process_tile(WaveState& w, const bf16_t* __restrict__ ks, const bf16_t* __restrict__ vs,
-                                             int st, int lane, ValidFn valid) {
-  const int l32 = lane & 31, hh = lane >> 5;
-  f32x16 s;
+// S^T of the wavefront's 32-key half of a tile in LDS: 8 MFMAs
+__device__ __forceinline__ void scores(const WaveState& w, f32x16& s, const bf16_t* __restrict__ ks, int st, int lane) {
+  const int row = st * 32 + (lane & 31), hh = lane >> 5;
+  const bf16_t* kp = ks + row * HD;
 #pragma unroll
   for (int v = 0; v < 16; ++v) s[v] = 0.f;
-  {
-    const int row = st * 32 + l32;
-    const bf16_t* kp = ks + row * HD;
 #pragma unroll
-    for (int kk = 0; kk < 8; ++kk) {
-      const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + k_pos(row, 2 * kk + hh) * 8);
-      s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[kk], s, 0, 0, 0);
-    }
+  for (int kk = 0; kk < 8; ++kk) {
+    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + k_pos(row, 2 * kk + hh) * 8);
+    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[kk], s, 0, 0, 0);
   }
+}
+
+// Online-softmax update and O += P V for the 32 keys of half `st` of a tile whose scores `s` are in registers
+// (log2 domain: Q carries log2(e)/sqrt(hd)).  `valid(key_in_tile)` masks keys (only called when MASKED).
+template <bool MASKED, typename ValidFn>
+__device__ __forceinline__ void finish_tile(WaveState& w, f32x16& s, const bf16_t* __restrict__ vs, int st, int lane, ValidFn valid) {
+  const int hh = lane >> 5;
   float tmax = -INFINITY;
 #pragma unroll
   for (int v = 0; v < 16; ++v) {
@@ -160,17 +169,13 @@ __device__ __forceinline__ void process_tile(WaveState& w, const bf16_t* __restr
   }
 }
 
-// S^T of the wavefront's 32-key half of a full tile (no masking): 8 MFMAs
-__device__ __forceinline__ void scores(const WaveState& w, f32x16& s, const bf16_t* __restrict__ ks, int st, int lane) {
-  const int row = st * 32 + (lane & 31), hh = lane >> 5;
-  const bf16_t* kp = ks + row * HD;
-#pragma unroll
-  for (int v = 0; v < 16; ++v) s[v] = 0.f;
-#pragma unroll
-  for (int kk = 0; kk < 8; ++kk) {
-    const bf16x8 kf = *reinterpret_cast<const bf16x8*>(kp + k_pos(row, 2 * kk + hh) * 8);
-    s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, w.qf[kk], s, 0, 0, 0);
-  }
+// The wavefront's 32-key half (`st`) of a 64-key tile in LDS against its 32 queries
+template <bool MASKED, typename ValidFn>
+__device__ __forceinline__ void process_tile(WaveState& w, const bf16_t* __restrict__ ks, const bf16_t* __restrict__ vs,
+                                             int st, int lane, ValidFn valid) {
+  f32x16 s;
+  scores(w, s, ks, st, lane);
+  finish_tile<MASKED>(w, s, vs, st, lane, valid);
 }
 
 // One step of the software pipeline over full prefix tiles: the online-softmax arithmetic on the scores
@@ -250,12 +255,38 @@ struct AttnKArgs {
   const bf16_t* qkv;
   const bf16_t* pk;
   const bf16_t* pv;
-  const float2* rope;   // [B][64] (cos, sin) of angle (pos0+b) * base^(-2f/128)
+  const float2* rope;   // [64][B] (cos, sin) of angle (pos0+b) * base^(-2f/128): lanes that differ in b read neighbours
   bf16_t* out;
   float* opart;         // [nS][M][Hq][128]
   float* mlpart;        // [nS][M][Hq][2]
   int M, B, Hq, Hkv, P, ld, nQ, nS;
 };
+
+// the lane's 8 MFMA operand fragments of LDS tile row `row` (K layout): hd = 16*kk + 8*hh + e
+__device__ __forceinline__ void load_frags(bf16x8 (&f)[8], const bf16_t* __restrict__ tile, int row, int hh) {
+  const bf16_t* p = tile + row * HD;
+#pragma unroll
+  for (int kk = 0; kk < 8; ++kk) f[kk] = *reinterpret_cast<const bf16x8*>(p + k_pos(row, 2 * kk + hh) * 8);
+}
+// rotary embedding of the fragments of global row `row` (position row % B) and scaling; fragment kk pairs with
+// kk + 4 (hd and hd + 64).  `rope` is [64][B] (cos, sin).
+__device__ __forceinline__ void rotate_frags(bf16x8 (&f)[8], const float2* __restrict__ rope, int B, int row, int hh, float scale) {
+  const float2* rp = rope + (size_t)(hh * 8) * B + (row % B);
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const bf16x8 x1 = f[kk], x2 = f[kk + 4];
+    bf16x8 y1, y2;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float2 cs = rp[(size_t)(kk * 16 + e) * B];
+      const float a1 = static_cast<float>(x1[e]), a2 = static_cast<float>(x2[e]);
+      y1[e] = static_cast<bf16_t>((a1 * cs.x - a2 * cs.y) * scale);
+      y2[e] = static_cast<bf16_t>((a2 * cs.x + a1 * cs.y) * scale);
+    }
+    f[kk] = y1;
+    f[kk + 4] = y2;
+  }
+}
 
 __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
@@ -283,52 +314,105 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) w.o[n][v] = 0.f;
 
-  // ---- Q: load, rotate at position pos0 + (row % B), scale, round to bf16 ------------------
-  {
-    const bf16_t* qp = a.qkv + (size_t)qrow * a.ld + h * HD + hh * 8;
-    const float2* rp = a.rope + (size_t)(qrow % a.B) * 64 + hh * 8;
-    const float qscale = 1.4426950408889634f * 0.08838834764831845f;  // log2(e) / sqrt(128)
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(qp + kk * 16);
-      const bf16x8 x2 = *reinterpret_cast<const bf16x8*>(qp + kk * 16 + 64);
-      bf16x8 y1, y2;
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const float2 cs = rp[kk * 16 + e];
-        const float a1 = static_cast<float>(x1[e]), a2 = static_cast<float>(x2[e]);
-        y1[e] = static_cast<bf16_t>((a1 * cs.x - a2 * cs.y) * qscale);
-        y2[e] = static_cast<bf16_t>((a2 * cs.x + a1 * cs.y) * qscale);
-      }
-      w.qf[kk] = y1;
-      w.qf[kk + 4] = y2;
-    }
-  }
-
-  // ---- prefix keys of this split: LDS-DMA ring, NSTAGE-1 tiles ahead ------------------------------
   const int kbeg = sp * SPLIT_KEYS;
   const int kend = min(a.P, kbeg + SPLIT_KEYS);
   const int n_tiles = kend > kbeg ? (kend - kbeg + KTILE - 1) / KTILE : 0;
   const bf16_t* pk = a.pk + (size_t)kvh * a.P * HD;
   const bf16_t* pv = a.pv + (size_t)kvh * a.P * HD;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
-  // wavefront `wave` brings rows 8*wave .. 8*wave+7 of both tiles: lane -> (row, LDS position) -> source chunk
-  auto issue_tile = [&](int t) {
-    bf16_t* stage = smem + (t % NSTAGE) * STAGE_ELEMS;
-    const int key0 = kbeg + t * KTILE;
+  // LDS-DMA of N_ROWS rows of 256 bytes (rows row0 .. clamped to row_max of a matrix with row stride `ld`
+  // elements, starting at `src`) into an LDS tile; wavefront `wave` brings N_ROWS/8 consecutive rows:
+  // lane -> (row, LDS position) -> source chunk
+  auto issue_rows = [&](auto n_rows_tag, auto vswz_tag, bf16_t* dst, const bf16_t* src, int row0, int row_max, size_t ld) {
+    constexpr int N_ROWS = decltype(n_rows_tag)::value;
+    constexpr bool VSWZ = decltype(vswz_tag)::value;
+    constexpr int PER_WAVE = N_ROWS / 8;
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int row = 8 * wave_u + 4 * q + (lane >> 4), pos = lane & 15;
-      const size_t src = (size_t)min(key0 + row, kend - 1) * HD;
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(pk + src + k_pos(row, pos) * 8),
-                                       (lds_ptr_t)(stage + (8 * wave_u + 4 * q) * HD), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((glb_ptr_t)(pv + src + v_pos(row, pos) * 8),
-                                       (lds_ptr_t)(stage + TILE_ELEMS + (8 * wave_u + 4 * q) * HD), 16, 0, 0);
+    for (int q = 0; q < PER_WAVE / 4; ++q) {
+      const int row = PER_WAVE * wave_u + 4 * q + (lane >> 4), pos = lane & 15;
+      const int chunk = VSWZ ? v_pos(row, pos) : k_pos(row, pos);
+      __builtin_amdgcn_global_load_lds((glb_ptr_t)(src + (size_t)min(row0 + row, row_max) * ld + chunk * 8),
+                                       (lds_ptr_t)(dst + (PER_WAVE * wave_u + 4 * q) * HD), 16, 0, 0);
     }
   };
+  using R64 = std::integral_constant<int, 64>;
+  using R128 = std::integral_constant<int, 128>;
+  auto issue_tile = [&](int t) {     // prefix tile t of this split into its ring stage
+    bf16_t* stage = smem + (t % NSTAGE) * STAGE_ELEMS;
+    issue_rows(R64{}, std::false_type{}, stage, pk, kbeg + t * KTILE, kend - 1, HD);
+    issue_rows(R64{}, std::true_type{}, stage + TILE_ELEMS, pv, kbeg + t * KTILE, kend - 1, HD);
+  };
+  // own-block rows c0 .. c0+127 (K and V columns of the fused activations) into stages 1 and 2
+  const bool has_own = sp == a.nS - 1;
+  const int own_lo = (m0 / a.B) * a.B;
+  const int own_hi = min(a.M, ((min(m0 + QTILE, a.M) - 1) / a.B + 1) * a.B);
+  auto issue_own = [&](int c0) {
 #pragma unroll
-  for (int t = 0; t < NSTAGE - 1; ++t)
-    if (t < n_tiles) issue_tile(t);
+    for (int i = 0; i < 2; ++i) {
+      bf16_t* stage = smem + (1 + i) * STAGE_ELEMS;
+      issue_rows(R64{}, std::false_type{}, stage, a.qkv + (a.Hq + kvh) * HD, c0 + 64 * i, a.M - 1, a.ld);
+      issue_rows(R64{}, std::true_type{}, stage + TILE_ELEMS, a.qkv + (a.Hq + a.Hkv + kvh) * HD, c0 + 64 * i, a.M - 1, a.ld);
+    }
+  };
+
+  // ---- start every transfer known up front: the 128 Q rows (stage 3), the first own-block rows (stages 1, 2)
+  // and prefix tile 0 (stage 0); all of them arrive as whole 256-byte rows
+  issue_rows(R128{}, std::false_type{}, smem + 3 * STAGE_ELEMS, a.qkv + h * HD, m0, a.M - 1, a.ld);
+  if (has_own) issue_own(own_lo);
+  if (n_tiles > 0) issue_tile(0);
+  wait_vmcnt<0>();
+  __builtin_amdgcn_s_barrier();
+
+  // ---- Q: fragments of the wavefront pair's rows, rotated at position pos0 + (row % B), scaled by
+  // log2(e)/sqrt(128), rounded to bf16
+  load_frags(w.qf, smem + 3 * STAGE_ELEMS, qw * 32 + l32, hh);
+  rotate_frags(w.qf, a.rope, a.B, qrow, hh, 1.4426950408889634f * 0.08838834764831845f);
+
+  // ---- own-block keys: the block diagonal, handled by the last split.  They always go to the first wavefront
+  // of the pair, 32 keys at a time in row order, so a state's arithmetic does not depend on where its rows sit
+  // in the 128-row tile.  K fragments are rotated in registers on their way from LDS to the matrix pipe.
+  if (has_own) {
+    // rows of the states this wave's queries belong to
+    const int w_lo = (min(m0w, a.M - 1) / a.B) * a.B;
+    const int w_hi = (min(m0w + 31, a.M - 1) / a.B + 1) * a.B;
+    const int q_lo = (qrow / a.B) * a.B;    // this lane's state: rows [q_lo, q_lo + B)
+    const int q_hi = q_lo + a.B;
+    for (int c0 = own_lo; c0 < own_hi; c0 += 128) {
+      if (c0 != own_lo) {      // more than 128 own rows (B does not divide the tile): next chunk
+        __syncthreads();
+        issue_own(c0);
+        wait_vmcnt<0>();
+        __builtin_amdgcn_s_barrier();
+      }
+      if (st == 0) {
+#pragma unroll
+        for (int sub = 0; sub < 4; ++sub) {
+          const int k_lo = c0 + sub * 32;
+          if (k_lo < w_hi && k_lo + 32 > w_lo && k_lo < own_hi) {   // wave-uniform: this sub-tile holds keys of my states
+            const bf16_t* stage = smem + (1 + (sub >> 1)) * STAGE_ELEMS;
+            bf16x8 kf[8];
+            load_frags(kf, stage, (sub & 1) * 32 + l32, hh);
+            rotate_frags(kf, a.rope, a.B, min(k_lo + l32, a.M - 1), hh, 1.0f);
+            f32x16 sc;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) sc[v] = 0.f;
+#pragma unroll
+            for (int kk = 0; kk < 8; ++kk) sc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], w.qf[kk], sc, 0, 0, 0);
+            const int t0 = c0 + (sub >> 1) * 64;     // first row of the 64-row tile
+            finish_tile<true>(w, sc, stage + TILE_ELEMS, sub & 1, lane, [t0, q_lo, q_hi, own_hi](int key) {
+              const int row = t0 + key;
+              return row >= q_lo && row < q_hi && row < own_hi;
+            });
+          }
+        }
+      }
+    }
+  }
+  __syncthreads();   // Q and own-block stages are free again
+
+  // ---- prefix keys of this split: LDS-DMA ring, up to NSTAGE-1 tiles ahead -------------------------
+  if (1 < n_tiles) issue_tile(1);
+  if (2 < n_tiles) issue_tile(2);
   // full tiles run through the software pipeline (scores of tile t+1 under the softmax of tile t); a ragged
   // last tile takes the masked path afterwards
   const bool ragged = n_tiles > 0 && ((kend - kbeg) % KTILE) != 0;
@@ -373,67 +457,6 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
     process_tile<true>(w, ks, ks + TILE_ELEMS, st, lane, [nvalid](int key) { return key < nvalid; });
   }
   __syncthreads();   // all tiles consumed, no DMA in flight: the ring can be reused
-
-  // ---- own-block keys: the block diagonal, handled by the last split --------------------------
-  if (sp == a.nS - 1) {
-    const int m_last = min(m0 + QTILE, a.M) - 1;
-    const int own_lo = (m0 / a.B) * a.B;
-    const int own_hi = min(a.M, (m_last / a.B + 1) * a.B);
-    // rows of the states this wave's queries belong to
-    const int w_lo = (min(m0w, a.M - 1) / a.B) * a.B;
-    const int w_hi = (min(m0w + 31, a.M - 1) / a.B + 1) * a.B;
-    const int q_lo = (qrow / a.B) * a.B;    // this lane's state: rows [q_lo, q_lo + B)
-    const int q_hi = q_lo + a.B;
-    bf16_t* ks = smem;
-    bf16_t* vs = smem + TILE_ELEMS;
-    for (int r0 = own_lo; r0 < own_hi; r0 += KTILE) {
-      // K rows r0..r0+63 with rotary embedding: thread handles (key, chunk ch) and its partner ch+8
-      {
-        const int key = threadIdx.x >> 3, ch = threadIdx.x & 7;
-        const int row = min(r0 + key, a.M - 1);
-        const bf16_t* kp = a.qkv + (size_t)row * a.ld + (a.Hq + kvh) * HD + ch * 8;
-        const bf16x8 x1 = *reinterpret_cast<const bf16x8*>(kp);
-        const bf16x8 x2 = *reinterpret_cast<const bf16x8*>(kp + 64);
-        const float2* rp = a.rope + (size_t)(row % a.B) * 64 + ch * 8;
-        bf16x8 y1, y2;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const float2 cs = rp[e];
-          const float a1 = static_cast<float>(x1[e]), a2 = static_cast<float>(x2[e]);
-          y1[e] = static_cast<bf16_t>(a1 * cs.x - a2 * cs.y);
-          y2[e] = static_cast<bf16_t>(a2 * cs.x + a1 * cs.y);
-        }
-        *reinterpret_cast<bf16x8*>(ks + key * HD + k_pos(key, ch) * 8) = y1;
-        *reinterpret_cast<bf16x8*>(ks + key * HD + k_pos(key, ch + 8) * 8) = y2;
-      }
-      {
-        const int kp2 = threadIdx.x >> 4, ho = threadIdx.x & 15;
-#pragma unroll
-        for (int i = 0; i < 2; ++i) {
-          const int key = 2 * kp2 + i;
-          const int row = min(r0 + key, a.M - 1);
-          const u32x4 x = *reinterpret_cast<const u32x4*>(a.qkv + (size_t)row * a.ld + (a.Hq + a.Hkv + kvh) * HD + ho * 8);
-          *reinterpret_cast<u32x4*>(vs + key * HD + v_pos(key, ho) * 8) = x;
-        }
-      }
-      __syncthreads();
-      // own-block keys always go to the first wavefront of the pair, sub-tile by sub-tile in row order, so
-      // a state's arithmetic does not depend on where its rows sit in the 128-row tile
-      if (st == 0) {
-#pragma unroll
-        for (int sub = 0; sub < 2; ++sub) {
-          const int k_lo = r0 + sub * 32;
-          if (k_lo < w_hi && k_lo + 32 > w_lo) {   // wave-uniform: this half holds keys of my states
-            process_tile<true>(w, ks, vs, sub, lane, [r0, q_lo, q_hi, own_hi](int key) {
-              const int row = r0 + key;
-              return row >= q_lo && row < q_hi && row < own_hi;
-            });
-          }
-        }
-      }
-      __syncthreads();
-    }
-  }
 
   // ---- merge the two key halves of each wavefront pair through LDS ------------------------------
   {
@@ -516,7 +539,7 @@ __global__ __launch_bounds__(128) void attn_combine_kernel(const float* __restri
 __global__ void rope_table_kernel(float2* __restrict__ tab, int B, int half, int hd, int pos0, float base) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B * half) return;
-  const int b = i / half, f = i % half;
+  const int f = i / B, b = i % B;      // tab[f][b]
   const double inv_freq = pow((double)base, -2.0 * (double)f / (double)hd);
   const double ang = (double)(pos0 + b) * inv_freq;
   tab[i] = make_float2((float)cos(ang), (float)sin(ang));

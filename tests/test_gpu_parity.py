@@ -177,7 +177,10 @@ MFMA_SHAPES = [
     dict(d=512, Hq=4, Hkv=2, hd=128, F=768, P=200, B=32, G=5),    # GQA, ragged prefix tail, ragged row tail
     dict(d=256, Hq=2, Hkv=2, hd=128, F=320, P=64, B=4, G=40),     # small blocks: block-diagonal own keys
     dict(d=256, Hq=2, Hkv=1, hd=128, F=192, P=0, B=8, G=3),       # no prefix at all
-    dict(d=256, Hq=2, Hkv=2, hd=128, F=256, P=2100, B=16, G=10),  # three prefix splits + combine
+    dict(d=256, Hq=2, Hkv=2, hd=128, F=256, P=2100, B=16, G=10),  # two prefix splits (the second a lone ragged tile) + combine
+    dict(d=256, Hq=2, Hkv=2, hd=128, F=256, P=4200, B=8, G=20),   # three prefix splits, the last 1 full tile + ragged
+    dict(d=256, Hq=2, Hkv=1, hd=128, F=256, P=128, B=32, G=3),    # exactly two full prefix tiles
+    dict(d=256, Hq=2, Hkv=1, hd=128, F=256, P=192, B=32, G=9),    # exactly three full prefix tiles, three row tiles
     dict(d=384, Hq=3, Hkv=3, hd=128, F=448, P=1, B=64, G=3),      # block larger than a wave's 32 rows
     dict(d=256, Hq=2, Hkv=2, hd=128, F=256, P=130, B=24, G=7),    # block size that divides nothing
 ]

@@ -62,31 +62,39 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   bf16_t* Xs = reinterpret_cast<bf16_t*>(smem_raw);
   bf16_t* Ys = Xs + SX * XSTAGE;
 
-  // XCD-aware order: workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous range
-  // of logical tiles, running fastest over the activation tiles, so the workgroups that stream the
-  // same weight tile share one L2 and run at the same time.
-  const int per_z = tiles_i * tiles_j;
-  const int kz = blockIdx.x / per_z;
-  const int L = xcd_contiguous(blockIdx.x % per_z, per_z);
-  const int ti = (EPI == EPI_LMHEAD) ? L / tiles_j : L % tiles_i;
-  const int tj = (EPI == EPI_LMHEAD) ? L % tiles_j : L / tiles_i;
-  const int i0 = ti * BM, j0 = tj * BN;
-
   // the wavefront id is uniform: keep it (and all LDS destination arithmetic) in scalar registers
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, hh = lane >> 5;
 
-  int i_max, j_max;
+  int i_max, j_max, kz, ti, tj;
   if (EPI == EPI_LMHEAD) {
+    // The grid covers the row capacity; the number of rows in use is only known on the device.  The first
+    // (vocabulary tiles x token tiles in use) workgroup ids take the real tiles, token tiles running fastest
+    // so that the workgroups sharing a vocabulary tile sit next to each other on one XCD; the rest leave.
     i_max = a.N;
     j_max = a.M_dev ? min(*a.M_dev, a.M) : a.M;
-    if (j0 >= j_max) return;
+    const int used_j = (j_max + BN - 1) / BN;
+    const int used = tiles_i * used_j;
+    if ((int)blockIdx.x >= used) return;
+    const int L = xcd_contiguous(blockIdx.x, used);
+    kz = 0;
+    ti = L / used_j;
+    tj = L % used_j;
   } else {
+    // XCD-aware order: workgroup ids go round-robin over the 8 XCDs; give each XCD a contiguous range
+    // of logical tiles, running fastest over the activation tiles, so the workgroups that stream the
+    // same weight tile share one L2 and run at the same time.
+    const int per_z = tiles_i * tiles_j;
+    kz = blockIdx.x / per_z;
+    const int L = xcd_contiguous(blockIdx.x % per_z, per_z);
+    ti = L % tiles_i;
+    tj = L / tiles_i;
     i_max = a.M_dev ? min(*a.M_dev, a.M) : a.M;
     j_max = a.N;
-    if (i0 >= i_max) return;
+    if (ti * BM >= i_max) return;
   }
+  const int i0 = ti * BM, j0 = tj * BN;
 
   const int ldw = a.ldw ? a.ldw : a.K;
   // K range of this slice
@@ -240,35 +248,51 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   // accumulator element (i,j,v) of this lane: row  = i0 + wm*128 + i*32 + 8*(v/4) + 4*hh + v%4
   //                                           col  = wn*(BN/2) + j*32 + l32   (within the tile)
   if (EPI == EPI_LMHEAD) {
+    // Per token column: top value, its lowest vocabulary index, runner-up and sum of exponentials over the
+    // lane's 64 vocabulary rows, on the unscaled accumulators (the scale is positive, so the order is the
+    // same); the lane's rows are visited in increasing vocabulary index, so "strictly greater" keeps the
+    // lowest index among equals.  One median-of-three per value maintains the runner-up.
     TopPartial* part = reinterpret_cast<TopPartial*>(a.C);
+    const float c = a.scale * 1.4426950408889634f;
+    auto reduce_columns = [&](auto checked_tag) {
+      constexpr bool CHECKED = decltype(checked_tag)::value;   // the last vocabulary tile: rows beyond V count as -inf
 #pragma unroll
-    for (int j = 0; j < TN; ++j) {
-      const int tokr = j0 + wn * (BN / 2) + j * 32 + l32;
-      Top t = top_empty();
-      float mx = -INFINITY;
+      for (int j = 0; j < TN; ++j) {
+        float m = -INFINITY, m2 = -INFINITY;
+        int code = 0;      // 16 * i + v of the top value
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int idx = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-          acc[i][j][v] = idx < i_max ? acc[i][j][v] * a.scale : -INFINITY;
-          mx = fmaxf(mx, acc[i][j][v]);
-        }
-      float s = 0.f;
+          for (int v = 0; v < 16; ++v) {
+            float l = acc[i][j][v];
+            if (CHECKED) {
+              const int idx = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+              if (idx >= i_max) l = -INFINITY;
+              acc[i][j][v] = l;
+            }
+            m2 = __builtin_amdgcn_fmed3f(m, m2, l);
+            code = l > m ? 16 * i + v : code;
+            m = __builtin_amdgcn_fmed3f(m, l, INFINITY);   // max(m, l) as one instruction
+          }
+        // in the last tile a lane may have no row below V: it keeps m = -inf and contributes nothing
+        const float mc = (m == -INFINITY) ? 0.f : m * c;
+        float sum = 0.f;
 #pragma unroll
-      for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const float l = acc[i][j][v];
-          const int idx = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
-          if (l > t.m || (l == t.m && idx < t.idx)) { t.m2 = t.m; t.m = l; t.idx = idx; }
-          else t.m2 = fmaxf(t.m2, l);
-          s += (l == -INFINITY) ? 0.f : __expf(l - mx);
-        }
-      t.s = s;
-      t = top_merge(t, top_shfl_xor(t, 32));
-      if (hh == 0 && tokr < j_max) part[(size_t)(ti * 2 + wm) * a.ldc + tokr] = TopPartial{t.m, t.m2, t.s, t.idx};
-    }
+          for (int v = 0; v < 16; ++v) sum += __builtin_amdgcn_exp2f(__builtin_fmaf(acc[i][j][v], c, -mc));
+        Top t;
+        t.m = m * a.scale;
+        t.m2 = m2 * a.scale;
+        t.s = sum;
+        t.idx = (m == -INFINITY) ? 0x7fffffff
+                                 : i0 + wm * 128 + (code >> 4) * 32 + 8 * ((code & 15) >> 2) + 4 * hh + (code & 3);
+        t = top_merge(t, top_shfl_xor(t, 32));
+        const int tokr = j0 + wn * (BN / 2) + j * 32 + l32;
+        if (hh == 0 && tokr < j_max) part[(size_t)(ti * 2 + wm) * a.ldc + tokr] = TopPartial{t.m, t.m2, t.s, t.idx};
+      }
+    };
+    if (i0 + BM <= i_max) reduce_columns(std::false_type{}); else reduce_columns(std::true_type{});
     return;
   }
 

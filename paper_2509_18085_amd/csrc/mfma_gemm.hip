@@ -102,46 +102,64 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   const int kt0 = (int)(((long long)KT_all * kz) / a.ksplit);
   const int KT = (int)(((long long)KT_all * (kz + 1)) / a.ksplit) - kt0;
 
-  // ---- per-lane global sources.  A wave-load covers 8 rows; lane -> (row, swizzled 16-byte chunk)
-  const bf16_t* xsrc[LX];
-  const bf16_t* ysrc[LY];
+  // ---- global sources.  A wave-load covers 8 rows; lane -> (row, swizzled 16-byte chunk).  Addresses are a
+  // wavefront-uniform base (scalar registers) plus a 32-bit per-lane byte offset that never changes: the
+  // loads take the scalar-base form and the K loop needs no vector arithmetic for them.
+  const char* xbase;
+  const char* ybase[LY];
+  unsigned xoff[LX], yoff[LY];
   {
     const bf16_t* X = (EPI == EPI_LMHEAD) ? (const bf16_t*)a.W[0] : (const bf16_t*)a.A;
     const int ldx = (EPI == EPI_LMHEAD) ? ldw : a.lda;
+    xbase = reinterpret_cast<const char*>(X + (size_t)kt0 * BKK);
 #pragma unroll
     for (int q = 0; q < LX; ++q) {
       const int row = 8 * (wave * LX + q) + (lane >> 3);
       const int chunk = (lane & 7) ^ ((row >> 1) & 7);
       const int gi = min(i0 + row, i_max - 1);
-      xsrc[q] = X + (size_t)gi * ldx + (size_t)kt0 * BKK + chunk * 8;
+      xoff[q] = (unsigned)gi * (unsigned)(ldx * 2) + chunk * 16;
     }
 #pragma unroll
     for (int q = 0; q < LY; ++q) {
-      const int row = 8 * (wave * LY + q) + (lane >> 3);
+      const int row0 = 8 * (wave * LY + q);            // first row of the wave-load: uniform
+      const int row = row0 + (lane >> 3);
       const int chunk = (lane & 7) ^ ((row >> 1) & 7);
-      const bf16_t* p;
+      const bf16_t* base;
+      int r;                                            // row inside the matrix `base` points to
       if (EPI == EPI_LMHEAD) {
-        p = (const bf16_t*)a.A + (size_t)min(j0 + row, j_max - 1) * a.lda;
-      } else if (EPI == EPI_SWIGLU) {
-        // rows of every 32-row MFMA tile: 16 gate rows then the 16 up rows of the same features
-        const int f = tj * (BN / 2) + (row >> 5) * 16 + (row & 15);
-        p = ((row & 16) ? (const bf16_t*)a.W[1] : (const bf16_t*)a.W[0]) + (size_t)f * ldw;
+        base = (const bf16_t*)a.A;
+        r = min(j0 + row, j_max - 1);
+        yoff[q] = (unsigned)r * (unsigned)(a.lda * 2) + chunk * 16;
       } else {
-        const int n = j0 + row;   // column of the fused [seg0 | seg1 | seg2] output; 8-row groups never straddle
-        if (n < a.Nseg[0]) p = (const bf16_t*)a.W[0] + (size_t)n * ldw;
-        else if (n < a.Nseg[0] + a.Nseg[1]) p = (const bf16_t*)a.W[1] + (size_t)(n - a.Nseg[0]) * ldw;
-        else p = (const bf16_t*)a.W[2] + (size_t)(n - a.Nseg[0] - a.Nseg[1]) * ldw;
+        if (EPI == EPI_SWIGLU) {
+          // rows of every 32-row MFMA tile: 16 gate rows then the 16 up rows of the same features
+          base = (row0 & 16) ? (const bf16_t*)a.W[1] : (const bf16_t*)a.W[0];
+          r = tj * (BN / 2) + (row >> 5) * 16 + (row & 15);
+        } else {
+          const int n0 = j0 + row0;   // column of the fused [seg0 | seg1 | seg2] output; 8-row groups never straddle
+          int seg0;
+          if (n0 < a.Nseg[0]) { base = (const bf16_t*)a.W[0]; seg0 = 0; }
+          else if (n0 < a.Nseg[0] + a.Nseg[1]) { base = (const bf16_t*)a.W[1]; seg0 = a.Nseg[0]; }
+          else { base = (const bf16_t*)a.W[2]; seg0 = a.Nseg[0] + a.Nseg[1]; }
+          r = j0 + row - seg0;
+        }
+        yoff[q] = (unsigned)r * (unsigned)(ldw * 2) + chunk * 16;
       }
-      ysrc[q] = p + (size_t)kt0 * BKK + chunk * 8;
+      ybase[q] = reinterpret_cast<const char*>(base + (size_t)kt0 * BKK);
     }
   }
+  // 16 bytes per lane, global (scalar base + 32-bit lane offset) -> LDS (M0 = destination of lane 0).  Written
+  // out because the compiler only emits the 64-bit-lane-address form, which costs a 64-bit vector add per load.
+  auto dma16 = [](const char* ubase, unsigned lane_off, const bf16_t* lds_dst) {
+    const unsigned m0v = (unsigned)(size_t)(lds_ptr_t)lds_dst;
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                 :: "s"(m0v), "v"(lane_off), "s"(ubase) : "memory");
+  };
   auto load_x = [&](int q, int t) {
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(xsrc[q] + (size_t)t * BKK),
-                                     (lds_ptr_t)(Xs + (t % SX) * XSTAGE + (wave * LX + q) * 512), 16, 0, 0);
+    dma16(xbase + (size_t)t * (BKK * 2), xoff[q], Xs + (t % SX) * XSTAGE + (wave * LX + q) * 512);
   };
   auto load_y = [&](int q, int t) {
-    __builtin_amdgcn_global_load_lds((glb_ptr_t)(ysrc[q] + (size_t)t * BKK),
-                                     (lds_ptr_t)(Ys + (t % SY) * YSTAGE + (wave * LY + q) * 512), 16, 0, 0);
+    dma16(ybase[q] + (size_t)t * (BKK * 2), yoff[q], Ys + (t % SY) * YSTAGE + (wave * LY + q) * 512);
   };
   constexpr int LS = XDEEP ? LY : LX, LD = XDEEP ? LX : LY;   // wave-loads of the shallow / deep operand
   auto load_sh = [&](int q, int t) { if (XDEEP) load_y(q, t); else load_x(q, t); };
@@ -463,6 +481,10 @@ int mfma_ksplit(int N, int K) {
 
 bool mfma_gemm_supported(int epi, const GemmArgs& a) {
   if (a.K % BKK != 0 || a.K < BKK || a.M < 1) return false;
+  // per-lane byte offsets inside an operand are 32-bit
+  const size_t lim = (size_t)1 << 32;
+  const size_t ldw = a.ldw ? a.ldw : a.K;
+  if ((size_t)a.M * a.lda * 2 >= lim || (size_t)a.N * ldw * 2 >= lim) return false;
   if (epi == EPI_SWIGLU) return a.N % 32 == 0;
   if (epi == EPI_LMHEAD) return a.N >= 1;
   if (a.N % 64 != 0) return false;

@@ -25,6 +25,10 @@ What the paper fixes and where:
   * acceptance walk over children of the last accepted node               Alg. 1 step 5, Eqs. (4)-(6)
   * the accepted draft's own distribution (same forward pass) yields the next state
                                                                           App. A, case 2
+  * draft blocks = current block + tokens c_ij named by draft formulas {(i, j)}, i = token
+    position rank, j = vocabulary rank                                    Sec. 4.4.2, 4.4.3
+  * pruning score: geometric means of token probabilities, of the children's local scores,
+    and of the two                                                        Sec. 4.4.4
 
 Readings taken where the paper is silent (architecture details are not in the paper at
 all; the shapes come from the workload configurations):
@@ -39,7 +43,10 @@ all; the shapes come from the workload configurations):
 Pins (tests/test_oracle_pins.py): closed forms, rotary invariances, agreement of the
 cached formulation with a dense-mask single-sequence formulation (two independent
 formulations of Sec. 4.3), torch's CPU scaled-dot-product attention, brute-force
-enumeration of all walks on small graphs, and the losslessness theorem on a tiny model.
+enumeration of all walks on small graphs, the losslessness theorem on a tiny model; for
+drafting and pruning a hand-worked example, an independent loop implementation on exact
+fractions, the graph conditions of Eqs. (4)-(6), and the link to Next(X, p): the formula
+"ranks 1..s, vocabulary rank 1" reproduces the threshold rule's next state and is accepted.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -374,3 +381,120 @@ def decode_block(model: Dict, block0: np.ndarray, *, drafter: Optional[Drafter] 
         info = r
         traj.append(state.copy())
     return state, traj, nfe, depths, saved
+
+
+# ----------------------------------------------------------------------------------------
+# drafting from the current distribution and pruning of the draft graph (Sec. 4.4)
+# ----------------------------------------------------------------------------------------
+
+def head_topk(hidden: np.ndarray, final_norm: np.ndarray, w_vocab: np.ndarray, k: int, *,
+              rms_eps: float, logit_scale: float = 1.0, operand_dtype: str = "f64"
+              ) -> Tuple[np.ndarray, np.ndarray]:
+    """Drafting source (Sec. 4.4.2): for every position of one block, the k most likely
+    tokens of the current distribution and their probabilities, most likely first
+    (the vocabulary sort that defines the vocabulary rank j; ties go to the lowest token id).
+
+    hidden [B,d] -> (tokens [B,k] int32, probs [B,k] float64).
+    """
+    h = rms_norm(np.asarray(hidden, F64), final_norm, rms_eps)
+    if operand_dtype == "bf16":
+        h = round_to_bf16(h)
+    logits = logit_scale * (h @ np.asarray(w_vocab, F64).T)
+    p = softmax_rows(logits)
+    B, V = p.shape
+    tok = np.zeros((B, k), np.int32)
+    pr = np.zeros((B, k), F64)
+    for b in range(B):
+        order = sorted(range(V), key=lambda v: (-logits[b, v], v))[:k]
+        tok[b] = order
+        pr[b] = p[b, order]
+    return tok, pr
+
+
+def position_order(state: np.ndarray, mask_id: int, conf: np.ndarray) -> List[int]:
+    """Token position sort (Sec. 4.4.2, first relation): the still-masked positions of the
+    block, most confident first.  position_order(...)[i-1] is the position whose token
+    position rank is i.  Reading: only masked positions are candidates for unmasking; equal
+    confidences go to the lower position."""
+    masked = [b for b in range(len(state)) if int(state[b]) == mask_id]
+    return sorted(masked, key=lambda b: (-float(conf[b]), b))
+
+
+def geometric_mean(values: Sequence[float]) -> float:
+    """GM(v_1..v_k) = (prod v)^(1/k) (Sec. 4.4.4)."""
+    v = [float(x) for x in values]
+    assert len(v) > 0
+    if min(v) <= 0.0:
+        return 0.0
+    return float(np.exp(np.mean(np.log(np.asarray(v, F64)))))
+
+
+def draft_and_prune(state: np.ndarray, mask_id: int, topk_tokens: np.ndarray, topk_probs: np.ndarray,
+                    formulas: Sequence[Sequence[Tuple[int, int]]], edges: np.ndarray, d_star: int) -> Dict:
+    """Build the draft blocks of a draft graph from the current distribution and prune the
+    graph to a budget (Sec. 4.4.2 and 4.4.4).
+
+    state        [B]    the current block X_k(t) (mask_id where masked)
+    topk_tokens  [B,K]  c_{.j}: the K most likely tokens per position, most likely first
+    topk_probs   [B,K]  their probabilities (column 0 = the confidence max(p_b))
+    formulas     D draft formulas, formula m = set of (i, j), 1-based: i = token position rank,
+                 j = vocabulary rank.  Node m (1..D) of the graph is the block obtained by
+                 unmasking c_ij at the position of rank i for every (i, j) of formula m;
+                 node 0 is the current block (empty formula).
+    edges        [E,2]  (parent, child) over nodes 0..D
+    d_star       number of draft nodes to keep
+
+    Readings (the paper does not say): a formula that names a position rank beyond the number
+    of masked positions, a vocabulary rank beyond K, or the same position twice cannot be
+    built and is dropped; children(q) for the child score are the buildable children of q in
+    `edges`; a node without buildable children scores its local score alone; the D* best
+    scores are kept, equal scores in favour of the lower node index; the root is always kept;
+    edges whose two ends are kept survive.
+
+    Returns dict: drafts [D+1,B] (row 0 = state, unbuildable rows = state), buildable [D+1] bool,
+    local [D+1], child [D+1] (nan where there is none), score [D+1], kept (ascending node
+    indices, root first), states [len(kept),B], edges [E',2] renumbered to positions in kept.
+    """
+    state = np.asarray(state, np.int32)
+    B = state.size
+    K = int(np.asarray(topk_tokens).shape[1])
+    D = len(formulas)
+    order = position_order(state, mask_id, np.asarray(topk_probs, F64)[:, 0])
+    drafts = np.tile(state, (D + 1, 1))
+    buildable = np.zeros(D + 1, bool)
+    buildable[0] = True
+    local = np.full(D + 1, np.nan, F64)
+    for m, formula in enumerate(formulas, start=1):
+        pairs = list(formula)
+        ranks = [i for i, _ in pairs]
+        ok = len(pairs) > 0 and len(set(ranks)) == len(ranks) and all(
+            1 <= i <= len(order) and 1 <= j <= K for i, j in pairs)
+        if not ok:
+            continue
+        probs = []
+        for i, j in pairs:
+            b = order[i - 1]
+            drafts[m, b] = int(topk_tokens[b, j - 1])
+            probs.append(float(topk_probs[b, j - 1]))
+        buildable[m] = True
+        local[m] = geometric_mean(probs)                                   # localScore
+    edges = np.asarray(edges, np.int64).reshape(-1, 2)
+    child = np.full(D + 1, np.nan, F64)
+    score = np.full(D + 1, np.nan, F64)
+    for m in range(1, D + 1):
+        if not buildable[m]:
+            continue
+        kids = sorted({int(c) for a, c in edges if int(a) == m and 1 <= int(c) <= D and buildable[int(c)]})
+        if kids:
+            child[m] = geometric_mean([local[c] for c in kids])           # childScore
+            score[m] = geometric_mean([local[m], child[m]])               # score
+        else:
+            score[m] = local[m]
+    cand = [m for m in range(1, D + 1) if buildable[m]]
+    best = sorted(cand, key=lambda m: (-score[m], m))[:max(0, int(d_star))]
+    kept = [0] + sorted(best)
+    pos = {m: r for r, m in enumerate(kept)}
+    new_edges = [(pos[int(a)], pos[int(c)]) for a, c in edges if int(a) in pos and int(c) in pos]
+    return {"order": order, "drafts": drafts, "buildable": buildable, "local": local, "child": child,
+            "score": score, "kept": np.asarray(kept, np.int32), "states": drafts[kept],
+            "edges": np.asarray(new_edges, np.int32).reshape(-1, 2)}

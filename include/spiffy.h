@@ -154,6 +154,35 @@ int spiffy_graph_accept(const int32_t *graph_edges, int32_t E, const int32_t *dr
                         const int32_t *target_states, int32_t G, int32_t B, int32_t root,
                         spiffy_accept_result *result, int32_t *accepted_state, void *stream);
 
+/* Drafting and pruning for the NEXT step (Sec. 4.4.2 drafting source, 4.4.3 draft formulas, 4.4.4 pruning),
+ * one launch, no host synchronisation.  All pointers are device memory.
+ *   state [B] int32: the current block X_k(t); positions equal to mask_id are masked.
+ *   topk_tokens [B,K] int32, topk_probs [B,K] float: per position the K most likely tokens of the current
+ *     distribution and their probabilities, most likely first (column 0 = the confidence); only rows of
+ *     masked positions are read.  With K = 1 these are the argmax / conf rows that spiffy_decode_head wrote
+ *     for the accepted node.
+ *   formula_offsets [D+1], formula_pairs [nnz,2] int32: draft formula m (1..D) is the set of pairs
+ *     (i, j), 1-based, i = token position rank (masked positions sorted by confidence, most confident
+ *     first, ties to the lower position), j = vocabulary rank; pairs formula_offsets[m-1] ..
+ *     formula_offsets[m]-1.  Node 0 of the graph is the current block (empty formula).
+ *   edges [E,2] int32 (parent, child) over nodes 0..D;  0 <= D <= SPIFFY_MAX_G-1, 1 <= B <= 4096,
+ *     1 <= K <= 16, 0 <= d_star.
+ * Outputs: drafts [D+1,B] (row m = the current block with c_ij unmasked at the position of rank i for every
+ * pair of formula m; a formula that names a rank beyond the masked positions, a vocabulary rank beyond K or
+ * one position twice, or whose offsets are not increasing within [0,nnz], cannot be built: its row is the
+ * current block and buildable[m] = 0); local [D+1], score [D+1] float (geometric means of Sec. 4.4.4 over the
+ * buildable children in `edges`; no children: the local score; NaN for node 0 and unbuildable nodes);
+ * kept [d_star+1]: node 0 and the d_star best-scoring buildable nodes (equal scores to the lower index), in
+ * ascending node order; states_out [d_star+1,B]: their blocks in that order; edges_out [E,2]: the edges whose
+ * two ends are kept, original order, renumbered to positions in `kept`; counts [2]: number of kept nodes and
+ * of surviving edges.  states_out / edges_out / counts are the block_tokens / graph_edges of the next
+ * spiffy_verify_step. */
+int spiffy_draft_prune(const int32_t *state, int32_t B, int32_t mask_id, const int32_t *topk_tokens,
+                       const float *topk_probs, int32_t K, const int32_t *formula_offsets,
+                       const int32_t *formula_pairs, int32_t D, int32_t nnz, const int32_t *edges, int32_t E,
+                       int32_t d_star, int32_t *drafts, uint8_t *buildable, float *local, float *score,
+                       int32_t *kept, int32_t *states_out, int32_t *edges_out, int32_t *counts, void *stream);
+
 /* The whole step on one stream with no host synchronisation: embed, n_layers x verify_layer,
  * decode_head, graph_accept.  layers / prefix are HOST arrays of n_layers structs.
  * hidden_out [G,B,d] receives the last layer's output (may be NULL: kept in the workspace). */

@@ -388,6 +388,26 @@ int spiffy_graph_accept(const int32_t* graph_edges, int32_t E, const int32_t* dr
                                  (hipStream_t)stream));
 }
 
+int spiffy_draft_prune(const int32_t* state, int32_t B, int32_t mask_id, const int32_t* topk_tokens,
+                       const float* topk_probs, int32_t K, const int32_t* formula_offsets,
+                       const int32_t* formula_pairs, int32_t D, int32_t nnz, const int32_t* edges, int32_t E,
+                       int32_t d_star, int32_t* drafts, uint8_t* buildable, float* local, float* score,
+                       int32_t* kept, int32_t* states_out, int32_t* edges_out, int32_t* counts, void* stream) {
+  if (!state || !topk_tokens || !topk_probs || !formula_offsets || !drafts || !buildable || !local || !score ||
+      !kept || !states_out || !counts)
+    return SPIFFY_EINVAL;
+  if ((nnz > 0 && !formula_pairs) || (E > 0 && (!edges || !edges_out))) return SPIFFY_EINVAL;
+  if (B < 1 || B > 4096 || K < 1 || K > 16 || D < 0 || D > SPIFFY_MAX_G - 1 || nnz < 0 || E < 0 || d_star < 0)
+    return SPIFFY_ESHAPE;
+  DraftPruneArgs a;
+  a.state = state; a.topk_tokens = topk_tokens; a.topk_probs = topk_probs;
+  a.formula_offsets = formula_offsets; a.formula_pairs = formula_pairs; a.edges = edges;
+  a.drafts = drafts; a.buildable = buildable; a.local = local; a.score = score; a.kept = kept;
+  a.states_out = states_out; a.edges_out = edges_out; a.counts = counts;
+  a.B = B; a.K = K; a.D = D; a.nnz = nnz; a.E = E; a.d_star = d_star; a.mask_id = mask_id;
+  return dev(launch_draft_prune(a, (hipStream_t)stream));
+}
+
 int spiffy_verify_step(const spiffy_model_cfg* cfg, int32_t n_layers, const spiffy_layer_weights* layers,
                        const spiffy_prefix_kv* prefix, const void* w_embed, const void* final_norm,
                        const void* w_vocab, const int32_t* block_tokens, int32_t G, int32_t B, int32_t pos0,

@@ -43,6 +43,26 @@ hipError_t launch_head_finalize(const TopPartial* row_top, const int32_t* row_id
                                 float threshold, int force_one, int32_t* argmax, float* conf,
                                 uint8_t* unmask, float* margin, int32_t* target, hipStream_t st);
 
+// drafting + pruning (one wavefront); all pointers device memory
+struct DraftPruneArgs {
+  const int32_t* state;            // [B]
+  const int32_t* topk_tokens;      // [B][K]
+  const float* topk_probs;         // [B][K], column 0 = confidence
+  const int32_t* formula_offsets;  // [D+1]
+  const int32_t* formula_pairs;    // [nnz][2]: (i, j), 1-based
+  const int32_t* edges;            // [E][2] over nodes 0..D
+  int32_t* drafts;                 // [D+1][B]
+  uint8_t* buildable;              // [D+1]
+  float* local;                    // [D+1]
+  float* score;                    // [D+1]
+  int32_t* kept;                   // [d_star+1]
+  int32_t* states_out;             // [d_star+1][B]
+  int32_t* edges_out;              // [E][2]
+  int32_t* counts;                 // [2]: kept nodes, surviving edges
+  int B, K, D, nnz, E, d_star, mask_id;
+};
+hipError_t launch_draft_prune(const DraftPruneArgs& a, hipStream_t st);
+
 hipError_t launch_graph_accept(const int32_t* edges, int E, const int32_t* draft, const int32_t* target,
                                int G, int B, int root, spiffy_accept_result* res, int32_t* state,
                                hipStream_t st);

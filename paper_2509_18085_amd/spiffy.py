@@ -21,7 +21,8 @@ SPIFFY_BF16, SPIFFY_F32 = 0, 1
 MAX_G = 64
 
 EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "spiffy_embed",
-           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_verify_step"]
+           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune",
+           "spiffy_verify_step"]
 GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
 
@@ -76,6 +77,9 @@ def _load() -> C.CDLL:
     lib.spiffy_gemm.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     lib.spiffy_graph_accept.restype = C.c_int
     lib.spiffy_graph_accept.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.spiffy_draft_prune.restype = C.c_int
+    lib.spiffy_draft_prune.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, vp,
+                                       vp, vp, vp, vp, vp]
     lib.spiffy_verify_step.restype = C.c_int
     lib.spiffy_verify_step.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp,
                                        i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
@@ -225,6 +229,34 @@ def graph_accept(graph_edges: torch.Tensor, draft_states: torch.Tensor, target_s
     _check(lib.spiffy_graph_accept(_ptr(graph_edges) if E else None, E, _ptr(draft_states), _ptr(target_states),
                                    G, B, root, _ptr(res), _ptr(state), _stream(stream)), "spiffy_graph_accept")
     return res, state
+
+
+def draft_prune(state: torch.Tensor, mask_id: int, topk_tokens: torch.Tensor, topk_probs: torch.Tensor,
+                formula_offsets: torch.Tensor, formula_pairs: torch.Tensor, edges: Optional[torch.Tensor],
+                d_star: int, stream=None) -> Dict[str, torch.Tensor]:
+    """Draft blocks from formulas and the pruned graph for the next step; every tensor on the device.
+    Returns drafts [D+1,B], buildable [D+1], local, score [D+1], kept [d_star+1], states [d_star+1,B],
+    edges [E,2], counts [2] (kept nodes, surviving edges)."""
+    dev = state.device
+    B = int(state.numel())
+    K = int(topk_tokens.shape[1])
+    D = int(formula_offsets.numel()) - 1
+    nnz = int(formula_pairs.shape[0]) if formula_pairs is not None else 0
+    E = int(edges.shape[0]) if edges is not None else 0
+    out = dict(drafts=torch.empty((D + 1, B), dtype=torch.int32, device=dev),
+               buildable=torch.empty(D + 1, dtype=torch.uint8, device=dev),
+               local=torch.empty(D + 1, dtype=torch.float32, device=dev),
+               score=torch.empty(D + 1, dtype=torch.float32, device=dev),
+               kept=torch.full((d_star + 1,), -1, dtype=torch.int32, device=dev),
+               states=torch.empty((d_star + 1, B), dtype=torch.int32, device=dev),
+               edges=torch.empty((max(E, 1), 2), dtype=torch.int32, device=dev),
+               counts=torch.empty(2, dtype=torch.int32, device=dev))
+    _check(lib.spiffy_draft_prune(_ptr(state), B, mask_id, _ptr(topk_tokens), _ptr(topk_probs), K,
+                                  _ptr(formula_offsets), _ptr(formula_pairs) if nnz else None, D, nnz,
+                                  _ptr(edges) if E else None, E, d_star, _ptr(out["drafts"]), _ptr(out["buildable"]),
+                                  _ptr(out["local"]), _ptr(out["score"]), _ptr(out["kept"]), _ptr(out["states"]),
+                                  _ptr(out["edges"]), _ptr(out["counts"]), _stream(stream)), "spiffy_draft_prune")
+    return out
 
 
 class StepPlan:

@@ -128,6 +128,32 @@ def test_graph_accept_argument_errors():
     assert call(G=0) == sp.SPIFFY_EINVAL
 
 
+def test_draft_prune_argument_errors():
+    def call(**k):
+        return sp.lib.spiffy_draft_prune(
+            k.get("state", DUMMY), k.get("B", 32), 99, k.get("tok", DUMMY), DUMMY, k.get("K", 2),
+            k.get("off", DUMMY), k.get("pairs", DUMMY), k.get("D", 5), k.get("nnz", 9), k.get("edges", DUMMY),
+            k.get("E", 4), k.get("d_star", 3), k.get("drafts", DUMMY), DUMMY, DUMMY, DUMMY, DUMMY, DUMMY,
+            k.get("eout", DUMMY), k.get("counts", DUMMY), None)
+    assert call(state=None) == sp.SPIFFY_EINVAL
+    assert call(tok=None) == sp.SPIFFY_EINVAL
+    assert call(off=None) == sp.SPIFFY_EINVAL
+    assert call(pairs=None) == sp.SPIFFY_EINVAL
+    assert call(edges=None) == sp.SPIFFY_EINVAL
+    assert call(eout=None) == sp.SPIFFY_EINVAL
+    assert call(drafts=None) == sp.SPIFFY_EINVAL
+    assert call(counts=None) == sp.SPIFFY_EINVAL
+    assert call(B=0) == sp.SPIFFY_ESHAPE
+    assert call(B=4097) == sp.SPIFFY_ESHAPE
+    assert call(K=0) == sp.SPIFFY_ESHAPE
+    assert call(K=17) == sp.SPIFFY_ESHAPE
+    assert call(D=64) == sp.SPIFFY_ESHAPE
+    assert call(D=-1) == sp.SPIFFY_ESHAPE
+    assert call(nnz=-1) == sp.SPIFFY_ESHAPE
+    assert call(E=-1) == sp.SPIFFY_ESHAPE
+    assert call(d_star=-1) == sp.SPIFFY_ESHAPE
+
+
 def test_verify_step_argument_errors():
     cfg = _cfg("c3")
     w, p = _layer_structs()

@@ -430,3 +430,167 @@ def test_small_block_duplicates_are_bit_identical(sp):
         for key in ("argmax", "unmask", "target_states"):
             assert torch.equal(out[key][:n], out[key][k * n:(k + 1) * n]), (k, key)
         assert torch.equal(out["conf"][:n], out["conf"][k * n:(k + 1) * n])
+
+
+# ------------------------------------------------------------------ drafting and pruning (Sec. 4.4)
+
+def _draft_case(rng, B, K, V, D, tie_grid):
+    mask_id = V
+    state = np.array([mask_id if rng.random() < 0.6 else int(rng.integers(0, V)) for _ in range(B)], np.int32)
+    tok = np.stack([rng.choice(V, size=K, replace=False) for _ in range(B)]).astype(np.int32)
+    if tie_grid:      # a coarse grid: equal confidences and equal scores do occur, and are exact in float32
+        prob = np.sort(rng.integers(1, 9, size=(B, K)) / 16.0, axis=1)[:, ::-1].astype(np.float32)
+    else:
+        prob = np.sort(rng.uniform(0.01, 1.0, size=(B, K)), axis=1)[:, ::-1].astype(np.float32)
+    n_masked = int((state == mask_id).sum())
+    formulas = []
+    for _ in range(D):
+        k = int(rng.integers(1, 5))
+        hi = max(1, n_masked + 1)
+        ranks = rng.choice(np.arange(1, hi + 1), size=min(k, hi), replace=False)
+        f = [(int(i), int(rng.integers(1, K + 2))) for i in ranks]
+        if rng.random() < 0.1 and len(f) > 1:
+            f[1] = (f[0][0], f[1][1])                       # the same position twice
+        formulas.append(f)
+    sets = [set()] + [set(f) for f in formulas]
+    edges = [(a, c) for a in range(D + 1) for c in range(1, D + 1) if a != c and sets[a] < sets[c]]
+    edges += edges[:2]                                      # repeated edges count once
+    return state, mask_id, tok, prob, formulas, np.array(edges, np.int32).reshape(-1, 2)
+
+
+def _run_draft_prune(sp, state, mask_id, tok, prob, formulas, edges, d_star):
+    off = np.cumsum([0] + [len(f) for f in formulas]).astype(np.int32)
+    pairs = np.array([p for f in formulas for p in f], np.int32).reshape(-1, 2)
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    out = sp.draft_prune(t(state), mask_id, t(tok), t(prob), t(off), t(pairs) if len(pairs) else None,
+                         t(edges) if len(edges) else None, d_star)
+    torch.cuda.synchronize()
+    return {k: v.cpu().numpy() for k, v in out.items()}
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_draft_prune_parity(sp, seed):
+    """Draft blocks, buildability and the kept sub-graph bit-exact; scores to float32 rounding.  The
+    decision 'which d_star nodes are kept' is compared where the oracle's scores around the cut are
+    separated by more than float32 rounding of the geometric means (equal scores are exact on the tie
+    grid and go to the lower node on both sides)."""
+    rng = np.random.default_rng(900 + seed)
+    B = int(rng.choice([4, 32, 33, 200]))
+    K = int(rng.integers(1, 5))
+    D = int(rng.choice([0, 1, 7, 23, 63]))
+    state, mask_id, tok, prob, formulas, edges = _draft_case(rng, B, K, 1000, D, tie_grid=seed % 2 == 0)
+    d_star = int(rng.integers(0, D + 2))
+    got = _run_draft_prune(sp, state, mask_id, tok, prob, formulas, edges, d_star)
+    ref = O().draft_and_prune(state, mask_id, tok, prob.astype(np.float64), formulas, edges, d_star)
+    np.testing.assert_array_equal(got["drafts"], ref["drafts"])
+    np.testing.assert_array_equal(got["buildable"].astype(bool), ref["buildable"])
+    for name in ("local", "score"):
+        g, r = got[name].astype(np.float64), ref[name]
+        assert (np.isnan(g) == np.isnan(r)).all(), name
+        ok = ~np.isnan(r)
+        np.testing.assert_allclose(g[ok], r[ok], rtol=2e-6, atol=1e-12, err_msg=name)
+    sc = np.sort(ref["score"][1:][ref["buildable"][1:]])[::-1]
+    n_keep = min(d_star, len(sc))
+    clear_cut = True
+    if 0 < n_keep < len(sc):
+        a, b = sc[n_keep - 1], sc[n_keep]
+        clear_cut = a == b or (a - b) > 1e-5 * a
+    # scores that are equal in exact arithmetic must also be equal in float32 for the index rule to agree
+    uniq = np.unique(sc)
+    exact_ties_ok = all((b - a) > 1e-5 * b for a, b in zip(uniq, uniq[1:])) or seed % 2 == 0
+    assert int(got["counts"][0]) == 1 + n_keep
+    if clear_cut and exact_ties_ok:
+        np.testing.assert_array_equal(got["kept"][:1 + n_keep], ref["kept"])
+        np.testing.assert_array_equal(got["states"][:1 + n_keep], ref["states"])
+        assert int(got["counts"][1]) == len(ref["edges"])
+        np.testing.assert_array_equal(got["edges"][:len(ref["edges"])], ref["edges"])
+
+
+def test_draft_prune_golden_and_edge_cases(sp):
+    import json, os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "draft_prune_case.json")))
+    formulas = [[tuple(p) for p in f] for f in g["formulas"]]
+    got = _run_draft_prune(sp, np.array(g["state"], np.int32), g["mask_id"], np.array(g["topk_tokens"], np.int32),
+                           np.array(g["topk_probs"], np.float32), formulas, np.array(g["edges"], np.int32), g["d_star"])
+    e = g["expected"]
+    np.testing.assert_array_equal(got["drafts"], np.array(e["drafts"]))
+    assert got["kept"][:int(got["counts"][0])].tolist() == e["kept"]
+    assert got["edges"][:int(got["counts"][1])].tolist() == e["edges"]
+    for name in ("local", "score"):
+        for a, b in zip(got[name], e[name]):
+            assert (b is None and np.isnan(a)) or abs(a - b) < 1e-6
+    # nothing masked: no formula can be built, only the root is kept, no edge survives
+    st = np.arange(8, dtype=np.int32)
+    got = _run_draft_prune(sp, st, 99, np.zeros((8, 1), np.int32), np.ones((8, 1), np.float32),
+                           [[(1, 1)], [(1, 1), (2, 1)]], np.array([[0, 1], [1, 2]], np.int32), 2)
+    assert got["buildable"].tolist() == [1, 0, 0] and got["counts"].tolist() == [1, 0]
+    np.testing.assert_array_equal(got["drafts"], np.tile(st, (3, 1)))
+    # no formulas at all, no edges
+    got = _run_draft_prune(sp, np.full(5, 7, np.int32), 7, np.zeros((5, 2), np.int32),
+                           np.full((5, 2), 0.5, np.float32), [], np.zeros((0, 2), np.int32), 3)
+    assert got["counts"].tolist() == [1, 0] and got["kept"][0] == 0
+    # offsets that do not increase: that formula is not built, the others are
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+    out = sp.draft_prune(t(np.full(4, 9, np.int32)), 9, t(np.arange(4, dtype=np.int32).reshape(4, 1)),
+                         t(np.array([[.9], [.8], [.7], [.6]], np.float32)), t(np.array([0, 1, 1, 2], np.int32)),
+                         t(np.array([[1, 1], [2, 1]], np.int32)), None, 3)
+    torch.cuda.synchronize()
+    assert out["buildable"].cpu().tolist() == [1, 1, 0, 1]
+    assert out["drafts"].cpu().tolist() == [[9, 9, 9, 9], [0, 9, 9, 9], [9, 9, 9, 9], [9, 1, 9, 9]]
+
+
+def test_draft_prune_feeds_the_next_step(sp):
+    """Closed loop on the device: verify -> draft from the accepted node's top-1 rows -> verify again.
+    With formulas 'the s most confident positions' one of the drafts is the target of the accepted
+    state (threshold rule, Sec. 3.1) and the walk accepts it at depth >= 1, as the oracle does."""
+    cfg = synth.CONFIGS["c1"]
+    seed = synth.DEFAULT_SEED
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
+    prefix = [synth.prefix_kv(cfg, l, seed) for l in range(cfg.L)]
+    hw = synth.head_weights(cfg, seed)
+    we = synth.embed_weights(cfg, seed)
+    scfg = sp.cfg_from_synth(cfg)
+    scale = 40.0
+    plan1 = sp.StepPlan(scfg, [sp.layer_weights(dev_weights(w)) for w in layers],
+                        [sp.prefix_kv(k.to(DEV), v.to(DEV)) for k, v in prefix], we.to(DEV),
+                        hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), 1, cfg.B, cfg.P, 0.5,
+                        logit_scale=scale, device=DEV)
+    state0 = np.full((1, cfg.B), cfg.mask_id, np.int32)
+    state0[0, 1] = 5
+    out1 = plan1.run(torch.from_numpy(state0).to(DEV), None)
+    torch.cuda.synchronize()
+    new_state = out1["accepted_state"].clone()
+    # formulas: the s most confident masked positions, s = 1..B, chained by inclusion
+    formulas = [[(i, 1) for i in range(1, n + 1)] for n in range(1, cfg.B + 1)]
+    off = torch.tensor(np.cumsum([0] + [len(f) for f in formulas]).astype(np.int32), device=DEV)
+    pairs = torch.tensor(np.array([p for f in formulas for p in f], np.int32), device=DEV)
+    edges = torch.tensor(np.array([[a, c] for a in range(cfg.B + 1) for c in range(a + 1, cfg.B + 1)], np.int32),
+                         device=DEV)
+    d_star = 3
+    dp = sp.draft_prune(new_state, cfg.mask_id, out1["argmax"][0].reshape(cfg.B, 1).contiguous(),
+                        out1["conf"][0].reshape(cfg.B, 1).contiguous(), off, pairs, edges, d_star)
+    torch.cuda.synchronize()
+    n_kept, n_edges = [int(x) for x in dp["counts"].cpu()]
+    assert n_kept == 1 + min(d_star, int((new_state == cfg.mask_id).sum()))
+    plan2 = sp.StepPlan(scfg, [sp.layer_weights(dev_weights(w)) for w in layers],
+                        [sp.prefix_kv(k.to(DEV), v.to(DEV)) for k, v in prefix], we.to(DEV),
+                        hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), n_kept, cfg.B, cfg.P, 0.5,
+                        logit_scale=scale, device=DEV)
+    out2 = plan2.run(dp["states"][:n_kept].contiguous(), dp["edges"][:n_edges].contiguous())
+    torch.cuda.synchronize()
+    # oracle on the same two steps
+    m = dict(layers=[np_weights(w) for w in layers], prefix=[(to_np(k), to_np(v)) for k, v in prefix],
+             w_embed=to_np(we), final_norm=to_np(hw["final_norm"]), w_vocab=to_np(hw["w_vocab"]))
+    kw = dict(n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P, mask_id=cfg.mask_id,
+              threshold=0.5, rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, logit_scale=scale, force_one=True)
+    r1 = O().verify_step(m["layers"], m["prefix"], m["w_embed"], m["final_norm"], m["w_vocab"], state0,
+                         np.zeros((0, 2), np.int32), **kw)
+    np.testing.assert_array_equal(new_state.cpu().numpy(), r1["accepted_state"])
+    rdp = O().draft_and_prune(r1["accepted_state"], cfg.mask_id, r1["argmax"][0].reshape(-1, 1),
+                              r1["conf"][0].reshape(-1, 1).astype(np.float64), formulas, edges.cpu().numpy(), d_star)
+    np.testing.assert_array_equal(dp["states"][:n_kept].cpu().numpy(), rdp["states"])
+    r2 = O().verify_step(m["layers"], m["prefix"], m["w_embed"], m["final_norm"], m["w_vocab"], rdp["states"],
+                         rdp["edges"], **kw)
+    res = out2["result"].cpu().tolist()
+    assert res[0] == r2["node"] and res[1] == r2["depth"]
+    np.testing.assert_array_equal(out2["accepted_state"].cpu().numpy(), r2["accepted_state"])

@@ -157,9 +157,43 @@ def main():
         "setup_s": t_setup,
     }
 
+    line["next_step_drafting"] = drafting_leg(sp, cfg, plan, d_states, dev)
+
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, layers, prefix, hw, states, edges)
     print(json.dumps(line))
+
+
+def drafting_leg(sp, cfg, plan, d_states, dev, iters=50):
+    """Not part of the timed step: latency of building and pruning the next step's draft graph on the
+    device (spiffy_draft_prune) from the accepted node's top-1 rows, G-1 formulas 'the s most confident
+    positions' pruned to (G-1)/2."""
+    import numpy as np
+    import torch
+    D = cfg.G - 1
+    formulas = [[(i, 1) for i in range(1, (n % cfg.B) + 2)] for n in range(D)]
+    off = torch.tensor(np.cumsum([0] + [len(f) for f in formulas]).astype(np.int32), device=dev)
+    pairs = torch.tensor(np.array([p for f in formulas for p in f], np.int32).reshape(-1, 2), device=dev)
+    sets = [set()] + [set(f) for f in formulas]
+    e = [(a, c) for a in range(D + 1) for c in range(1, D + 1) if a != c and sets[a] < sets[c]]
+    edges = torch.tensor(np.array(e, np.int32).reshape(-1, 2), device=dev) if e else None
+    node = int(plan.out["result"][0].item())
+    state = plan.out["accepted_state"]
+    tok = plan.out["argmax"][node].reshape(cfg.B, 1).contiguous()
+    prob = plan.out["conf"][node].reshape(cfg.B, 1).contiguous()
+    d_star = max(1, D // 2)
+    for _ in range(3):
+        out = sp.draft_prune(state, cfg.mask_id, tok, prob, off, pairs, edges, d_star)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        out = sp.draft_prune(state, cfg.mask_id, tok, prob, off, pairs, edges, d_star)
+    e1.record()
+    torch.cuda.synchronize()
+    return {"draft_prune_us": e0.elapsed_time(e1) * 1e3 / iters, "formulas": D, "d_star": d_star,
+            "edges_in": len(e), "kept_nodes": int(out["counts"][0].item()), "edges_out": int(out["counts"][1].item()),
+            "note": "includes the binding's output allocations; one 64-lane kernel launch"}
 
 
 def stored_traffic(config):

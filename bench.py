@@ -191,7 +191,20 @@ def drafting_leg(sp, cfg, plan, d_states, dev, iters=50):
         out = sp.draft_prune(state, cfg.mask_id, tok, prob, off, pairs, edges, d_star)
     e1.record()
     torch.cuda.synchronize()
-    return {"draft_prune_us": e0.elapsed_time(e1) * 1e3 / iters, "formulas": D, "d_star": d_star,
+    draft_us = e0.elapsed_time(e1) * 1e3 / iters
+    # drafting source with vocabulary ranks up to 3: top-3 rows of the accepted node from what the head left
+    scfg = plan.cfg
+    for _ in range(3):
+        sp.head_topk(scfg, plan.w_vocab, d_states, 3, LOGIT_SCALE, plan.workspace, result=plan.out["result"],
+                     after_step=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(iters):
+        sp.head_topk(scfg, plan.w_vocab, d_states, 3, LOGIT_SCALE, plan.workspace, result=plan.out["result"],
+                     after_step=True)
+    e1.record()
+    torch.cuda.synchronize()
+    return {"draft_prune_us": draft_us, "head_top3_us": e0.elapsed_time(e1) * 1e3 / iters, "formulas": D, "d_star": d_star,
             "edges_in": len(e), "kept_nodes": int(out["counts"][0].item()), "edges_out": int(out["counts"][1].item()),
             "note": "includes the binding's output allocations; one 64-lane kernel launch"}
 

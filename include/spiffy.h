@@ -50,6 +50,7 @@ enum { SPIFFY_BF16 = 0, SPIFFY_F32 = 1 };
 /* Limits checked by the host: G <= SPIFFY_MAX_G for the walk (one node per lane of a 64-wide
  * wavefront, 64-bit child masks); rows G*B <= SPIFFY_MAX_ROWS. */
 #define SPIFFY_MAX_G 64
+#define SPIFFY_MAX_TOPK 8   /* vocabulary ranks per position that spiffy_head_topk can return */
 #define SPIFFY_MAX_ROWS 16384
 
 typedef struct {
@@ -153,6 +154,22 @@ int spiffy_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W0, 
 int spiffy_graph_accept(const int32_t *graph_edges, int32_t E, const int32_t *draft_states,
                         const int32_t *target_states, int32_t G, int32_t B, int32_t root,
                         spiffy_accept_result *result, int32_t *accepted_state, void *stream);
+
+/* Drafting source (Sec. 4.4.2, vocabulary sort): the K most likely tokens and their probabilities at every
+ * masked position of one node's block, most likely first (equal logits to the lower token id), from the
+ * distribution the preceding head pass computed for that node.  Must follow, on the same stream, a
+ * spiffy_decode_head (after_step = 0) or spiffy_verify_step (after_step = 1) call with the same cfg, G, B,
+ * block_tokens, logit_scale, w_vocab and workspace: it reads what that call left in the workspace (the
+ * gathered normalised rows and the per-row / per-vocabulary-chunk summaries) and recomputes only the logits
+ * of the K best 128-token chunks of every row.  The node is result->node read on the device (result may be
+ * NULL: then `node`, 0 <= node < G).  1 <= K <= SPIFFY_MAX_TOPK.
+ * Outputs (device): topk_tokens [B,K] int32, topk_probs [B,K] float.  Column 0 is exactly the argmax / conf
+ * of that node's rows.  Positions that are not masked get their own token and probability 0; ranks that do
+ * not exist (K > vocab) get token -1 and probability 0.  These are the inputs of spiffy_draft_prune. */
+int spiffy_head_topk(const spiffy_model_cfg *cfg, const void *w_vocab, const int32_t *block_tokens, int32_t G,
+                     int32_t B, const spiffy_accept_result *result, int32_t node, int32_t K, float logit_scale,
+                     int32_t after_step, int32_t *topk_tokens, float *topk_probs, void *workspace,
+                     size_t workspace_bytes, void *stream);
 
 /* Drafting and pruning for the NEXT step (Sec. 4.4.2 drafting source, 4.4.3 draft formulas, 4.4.4 pruning),
  * one launch, no host synchronisation.  All pointers are device memory.

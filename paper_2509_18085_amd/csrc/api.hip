@@ -93,6 +93,8 @@ struct HeadWs {
   int32_t *row_idx, *count;
   void* nf;
   TopPartial *part, *part2, *row_top;
+  float* cand_val;       // top-K refinement candidates [B][SPIFFY_MAX_TOPK][SPIFFY_MAX_TOPK]
+  int32_t* cand_idx;
   int m_cap, n_part;
   size_t bytes;
 };
@@ -108,6 +110,8 @@ HeadWs carve_head(const spiffy_model_cfg* c, int G, int B, void* base) {
   w.part = (TopPartial*)cv.take(sizeof(TopPartial) * (size_t)w.n_part * w.m_cap);
   w.part2 = (TopPartial*)cv.take(sizeof(TopPartial) * (size_t)kLmheadCombineSlices * w.m_cap);
   w.row_top = (TopPartial*)cv.take(sizeof(TopPartial) * w.m_cap);
+  w.cand_val = (float*)cv.take(sizeof(float) * (size_t)B * SPIFFY_MAX_TOPK * SPIFFY_MAX_TOPK);
+  w.cand_idx = (int32_t*)cv.take(sizeof(int32_t) * (size_t)B * SPIFFY_MAX_TOPK * SPIFFY_MAX_TOPK);
   w.bytes = cv.off;
   return w;
 }
@@ -386,6 +390,38 @@ int spiffy_graph_accept(const int32_t* graph_edges, int32_t E, const int32_t* dr
   if (rc) return rc;
   return dev(launch_graph_accept(graph_edges, E, draft_states, target_states, G, B, root, result, accepted_state,
                                  (hipStream_t)stream));
+}
+
+int spiffy_head_topk(const spiffy_model_cfg* cfg, const void* w_vocab, const int32_t* block_tokens, int32_t G,
+                     int32_t B, const spiffy_accept_result* result, int32_t node, int32_t K, float logit_scale,
+                     int32_t after_step, int32_t* topk_tokens, float* topk_probs, void* workspace,
+                     size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(G, B))) return rc;
+  if (!w_vocab || !block_tokens || !topk_tokens || !topk_probs || !workspace) return SPIFFY_EINVAL;
+  if (!(logit_scale > 0.f) || !std::isfinite(logit_scale)) return SPIFFY_EINVAL;
+  if (!result && (node < 0 || node >= G)) return SPIFFY_EINVAL;
+  if (K < 1 || K > SPIFFY_MAX_TOPK) return SPIFFY_ESHAPE;
+  if (cfg->dtype == SPIFFY_BF16 && cfg->d % 8 != 0) return SPIFFY_ESHAPE;
+  if (!aligned16(w_vocab)) return SPIFFY_EALIGN;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPIFFY_EALIGN;
+  void* head_base = workspace;
+  if (after_step) {
+    // the step's workspace: hidden states, next states, then the scratch the head pass ran in (P does not move it)
+    const StepWs sw = carve_step(cfg, G, B, 0, workspace);
+    if (workspace_bytes < (size_t)((char*)sw.rest - (char*)workspace) + carve_head(cfg, G, B, nullptr).bytes)
+      return SPIFFY_EWORKSPACE;
+    head_base = sw.rest;
+  } else if (workspace_bytes < carve_head(cfg, G, B, nullptr).bytes) {
+    return SPIFFY_EWORKSPACE;
+  }
+  const HeadWs ws = carve_head(cfg, G, B, head_base);
+  HeadTopkArgs a;
+  a.dtype = cfg->dtype; a.nf = ws.nf; a.w_vocab = w_vocab; a.d = cfg->d; a.V = cfg->vocab; a.scale = logit_scale;
+  a.part = ws.part; a.n_part = ws.n_part; a.m_cap = ws.m_cap; a.row_top = ws.row_top; a.row_idx = ws.row_idx;
+  a.count = ws.count; a.tokens = block_tokens; a.result = result; a.node = node; a.G = G; a.B = B; a.K = K;
+  a.cand_val = ws.cand_val; a.cand_idx = ws.cand_idx; a.out_tokens = topk_tokens; a.out_probs = topk_probs;
+  return dev(launch_head_topk(a, (hipStream_t)stream));
 }
 
 int spiffy_draft_prune(const int32_t* state, int32_t B, int32_t mask_id, const int32_t* topk_tokens,

@@ -43,6 +43,28 @@ hipError_t launch_head_finalize(const TopPartial* row_top, const int32_t* row_id
                                 float threshold, int force_one, int32_t* argmax, float* conf,
                                 uint8_t* unmask, float* margin, int32_t* target, hipStream_t st);
 
+// top-K tokens of the accepted node's rows from what the head pass left behind; all pointers device memory
+struct HeadTopkArgs {
+  int dtype;
+  const void* nf;                 // gathered normalised rows [count][d]
+  const void* w_vocab;            // [V][d]
+  int d, V;
+  float scale;
+  const TopPartial* part;         // [n_part][m_cap] per-128-token summaries (MFMA head), or unused
+  int n_part, m_cap;
+  const TopPartial* row_top;      // [count] merged summaries
+  const int32_t* row_idx;         // [count] flattened (g,b) of every compacted row, ascending
+  const int32_t* count;
+  const int32_t* tokens;          // [G*B] block tokens
+  const spiffy_accept_result* result;   // node read on the device; NULL: use `node`
+  int node, G, B, K;
+  float* cand_val;                // [B][SPIFFY_MAX_TOPK][SPIFFY_MAX_TOPK]
+  int32_t* cand_idx;
+  int32_t* out_tokens;            // [B][K]
+  float* out_probs;               // [B][K]
+};
+hipError_t launch_head_topk(const HeadTopkArgs& a, hipStream_t st);
+
 // drafting + pruning (one wavefront); all pointers device memory
 struct DraftPruneArgs {
   const int32_t* state;            // [B]

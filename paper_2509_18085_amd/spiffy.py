@@ -21,7 +21,7 @@ SPIFFY_BF16, SPIFFY_F32 = 0, 1
 MAX_G = 64
 
 EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "spiffy_embed",
-           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune",
+           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk",
            "spiffy_verify_step"]
 GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
@@ -77,6 +77,8 @@ def _load() -> C.CDLL:
     lib.spiffy_gemm.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     lib.spiffy_graph_accept.restype = C.c_int
     lib.spiffy_graph_accept.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.spiffy_head_topk.restype = C.c_int
+    lib.spiffy_head_topk.argtypes = [cfgp, vp, vp, i32, i32, vp, i32, i32, f32, i32, vp, vp, vp, sz, vp]
     lib.spiffy_draft_prune.restype = C.c_int
     lib.spiffy_draft_prune.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, vp,
                                        vp, vp, vp, vp, vp]
@@ -229,6 +231,23 @@ def graph_accept(graph_edges: torch.Tensor, draft_states: torch.Tensor, target_s
     _check(lib.spiffy_graph_accept(_ptr(graph_edges) if E else None, E, _ptr(draft_states), _ptr(target_states),
                                    G, B, root, _ptr(res), _ptr(state), _stream(stream)), "spiffy_graph_accept")
     return res, state
+
+
+def head_topk(cfg: ModelCfg, w_vocab: torch.Tensor, block_tokens: torch.Tensor, K: int, logit_scale: float,
+              workspace: torch.Tensor, *, result: Optional[torch.Tensor] = None, node: int = 0,
+              after_step: bool = False, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Top-K tokens / probabilities per position of one node, from what the preceding decode_head
+    (after_step=False) or verify_step (after_step=True) call left in `workspace`.  `result` = the device
+    accept result (node read on the device) or None to use `node`."""
+    G, B = block_tokens.shape
+    tok = torch.empty((B, K), dtype=torch.int32, device=block_tokens.device)
+    prob = torch.empty((B, K), dtype=torch.float32, device=block_tokens.device)
+    wp, wn = _ws(workspace)
+    _check(lib.spiffy_head_topk(C.byref(cfg), _ptr(w_vocab), _ptr(block_tokens), G, B,
+                                _ptr(result) if result is not None else None, node, K, logit_scale,
+                                1 if after_step else 0, _ptr(tok), _ptr(prob), wp, wn, _stream(stream)),
+           "spiffy_head_topk")
+    return tok, prob
 
 
 def draft_prune(state: torch.Tensor, mask_id: int, topk_tokens: torch.Tensor, topk_probs: torch.Tensor,

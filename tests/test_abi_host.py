@@ -128,6 +128,29 @@ def test_graph_accept_argument_errors():
     assert call(G=0) == sp.SPIFFY_EINVAL
 
 
+def test_head_topk_argument_errors():
+    cfg = sp.cfg_from_synth(synth.CONFIGS["c2"])
+    big = 1 << 40
+    def call(**k):
+        return sp.lib.spiffy_head_topk(
+            C.byref(k.get("cfg", cfg)), k.get("wv", DUMMY), k.get("tok", DUMMY), k.get("G", 4), 32,
+            k.get("res", DUMMY), k.get("node", 0), k.get("K", 2), k.get("scale", 1.0), k.get("after", 0),
+            k.get("ot", DUMMY), DUMMY, k.get("ws", 0x100000), k.get("wsb", big), None)
+    assert call(wv=None) == sp.SPIFFY_EINVAL
+    assert call(tok=None) == sp.SPIFFY_EINVAL
+    assert call(ot=None) == sp.SPIFFY_EINVAL
+    assert call(ws=None) == sp.SPIFFY_EINVAL
+    assert call(scale=0.0) == sp.SPIFFY_EINVAL
+    assert call(res=None, node=4) == sp.SPIFFY_EINVAL
+    assert call(res=None, node=-1) == sp.SPIFFY_EINVAL
+    assert call(K=0) == sp.SPIFFY_ESHAPE
+    assert call(K=9) == sp.SPIFFY_ESHAPE
+    assert call(wv=DUMMY + 2) == sp.SPIFFY_EALIGN
+    assert call(ws=0x100010) == sp.SPIFFY_EALIGN
+    assert call(wsb=1024) == sp.SPIFFY_EWORKSPACE
+    assert call(wsb=1024, after=1) == sp.SPIFFY_EWORKSPACE
+
+
 def test_draft_prune_argument_errors():
     def call(**k):
         return sp.lib.spiffy_draft_prune(

@@ -594,3 +594,122 @@ def test_draft_prune_feeds_the_next_step(sp):
     res = out2["result"].cpu().tolist()
     assert res[0] == r2["node"] and res[1] == r2["depth"]
     np.testing.assert_array_equal(out2["accepted_state"].cpu().numpy(), r2["accepted_state"])
+
+
+# ------------------------------------------------------------------ drafting source: top-K per position
+
+def check_head_topk(sp, cfg, states, hidden, hw, logit_scale, K, nodes):
+    """spiffy_head_topk after spiffy_decode_head against oracle.head_topk.  Column 0 must be exactly the
+    argmax / conf of the head pass; rank j tokens are compared where the oracle's logit gaps to the
+    neighbouring ranks exceed the tie margin (the ranking is an integer decided by floats)."""
+    scfg = sp.cfg_from_synth(cfg)
+    G = states.shape[0]
+    ws = sp.alloc_workspace(scfg, G, cfg.B, 0, DEV)
+    wv = hw["w_vocab"].to(DEV)
+    d_states = torch.from_numpy(states).to(DEV)
+    out = sp.decode_head(scfg, hidden.to(DEV), hw["final_norm"].to(DEV), wv, d_states, 0.9, ws,
+                         logit_scale=logit_scale, force_one=True)
+    tie = 1e-3 * max(1.0, logit_scale)
+    n_cmp = 0
+    for node in nodes:
+        tok, prob = sp.head_topk(scfg, wv, d_states, K, logit_scale, ws, node=node)
+        torch.cuda.synchronize()
+        tok, prob = tok.cpu().numpy(), prob.cpu().numpy()
+        kk = min(K + 1, cfg.V)
+        rt, rp = O().head_topk(to_np(hidden)[node], to_np(hw["final_norm"]), to_np(hw["w_vocab"]), kk,
+                               rms_eps=cfg.rms_eps, logit_scale=logit_scale,
+                               operand_dtype="bf16" if cfg.dtype == "bf16" else "f64")
+        amax, conf = out["argmax"][node].cpu().numpy(), out["conf"][node].cpu().numpy()
+        for b in range(cfg.B):
+            if states[node, b] != cfg.mask_id:
+                assert (tok[b] == states[node, b]).all() and (prob[b] == 0).all()
+                continue
+            assert tok[b, 0] == amax[b] and prob[b, 0] == conf[b]
+            logp = np.log(np.maximum(rp[b], 1e-300))
+            gaps = logp[:-1] - logp[1:]                       # logit gap between rank j and j+1
+            for j in range(min(K, cfg.V)):
+                clear = (j == 0 or gaps[j - 1] > tie) and (j >= len(gaps) or gaps[j] > tie)
+                if clear:
+                    assert tok[b, j] == rt[b, j], (node, b, j, tok[b], rt[b])
+                    assert abs(prob[b, j] - rp[b, j]) <= (1e-4 if cfg.dtype == "f32" else 2e-2) * rp[b, j] + 1e-30
+                    n_cmp += 1
+            assert (np.diff(prob[b][tok[b] >= 0]) <= 1e-7).all()
+            assert len(set(tok[b][tok[b] >= 0].tolist())) == int((tok[b] >= 0).sum())
+            if K > cfg.V:
+                assert (tok[b, cfg.V:] == -1).all() and (prob[b, cfg.V:] == 0).all()
+    assert n_cmp > 0
+    return n_cmp
+
+
+def test_head_topk_config1_fp32(sp):
+    cfg = synth.CONFIGS["c1"]
+    st, _ = synth.draft_graph("c1", cfg)
+    for K, scale in ((1, 1.0), (3, 15.0), (8, 40.0)):
+        check_head_topk(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), scale, K, range(cfg.G))
+
+
+def test_head_topk_generic_bf16_small_vocab(sp):
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=96, V=5, B=9, G=3)
+    st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.3, 0.9, 4)
+    st[1, :] = cfg.mask_id
+    check_head_topk(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 3.0, 8, range(cfg.G))
+
+
+@pytest.mark.parametrize("V,K", [(1280, 2), (1000, 4), (300, 8), (126464, 3)])
+def test_head_topk_mfma_refinement(sp, V, K):
+    """MFMA head: the K best tokens come from recomputing the K best 128-token chunks of every row (ragged
+    last chunk, K larger than the number of chunks, the full LLaDA vocabulary)."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=256, V=V, B=8 if V > 100000 else 32, G=3)
+    assert sp.uses_mfma(sp.cfg_from_synth(cfg), cfg.B) in (0, 1)
+    st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.2, 0.9, 11)
+    st[2, :] = cfg.mask_id
+    check_head_topk(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 6.0, K, (0, 2))
+
+
+def test_head_topk_after_step_with_device_result(sp):
+    """After spiffy_verify_step, node taken from the device-side accept result; K = 2 formulas feed
+    spiffy_draft_prune and the pruned graph is what the oracle builds from the same distribution."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=1280, P=100, B=32, G=4)
+    seed = 5
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
+    prefix = [synth.prefix_kv(cfg, l, seed) for l in range(cfg.L)]
+    hw = synth.head_weights(cfg, seed)
+    we = synth.embed_weights(cfg, seed)
+    scfg = sp.cfg_from_synth(cfg)
+    scale = 12.0
+    plan = sp.StepPlan(scfg, [sp.layer_weights(dev_weights(w)) for w in layers],
+                       [sp.prefix_kv(k.to(DEV), v.to(DEV)) for k, v in prefix], we.to(DEV),
+                       hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), cfg.G, cfg.B, cfg.P, 0.9,
+                       logit_scale=scale, device=DEV)
+    states = synth.random_states(cfg.G, cfg.B, cfg.V, 0.3, 0.8, 3)
+    d_states = torch.from_numpy(states).to(DEV)
+    out = plan.run(d_states, None)
+    K = 2
+    tok, prob = sp.head_topk(scfg, plan.w_vocab, d_states, K, scale, plan.workspace, result=out["result"],
+                             after_step=True)
+    torch.cuda.synchronize()
+    node = int(out["result"][0].item())
+    assert node == 0                       # no edges: the root is accepted
+    hidden = out["hidden"][node].float().cpu().numpy().astype(np.float64)
+    rt, rp = O().head_topk(hidden, to_np(hw["final_norm"]), to_np(hw["w_vocab"]), K + 1, rms_eps=cfg.rms_eps,
+                           logit_scale=scale, operand_dtype="bf16")
+    tie = 1e-3 * scale
+    m = states[node] == cfg.mask_id
+    logp = np.log(rp)
+    clear = m & (logp[:, 0] - logp[:, 1] > tie) & (logp[:, 1] - logp[:, 2] > tie)
+    assert clear.sum() >= 4
+    np.testing.assert_array_equal(tok.cpu().numpy()[clear], rt[clear][:, :K])
+    np.testing.assert_allclose(prob.cpu().numpy()[clear], rp[clear][:, :K], rtol=2e-2)
+    # the drafting kernel takes these rows as they are
+    new_state = out["accepted_state"]
+    formulas = [[(1, 1)], [(1, 2)], [(1, 1), (2, 1)], [(1, 1), (2, 2)]]
+    off = torch.tensor(np.cumsum([0] + [len(f) for f in formulas]).astype(np.int32), device=DEV)
+    pairs = torch.tensor(np.array([p for f in formulas for p in f], np.int32), device=DEV)
+    edges = torch.tensor(np.array([[0, 1], [0, 2], [1, 3], [1, 4]], np.int32), device=DEV)
+    dp = sp.draft_prune(new_state, cfg.mask_id, tok, prob, off, pairs, edges, 3)
+    torch.cuda.synchronize()
+    ref = O().draft_and_prune(new_state.cpu().numpy(), cfg.mask_id, tok.cpu().numpy(),
+                              prob.cpu().numpy().astype(np.float64), formulas, edges.cpu().numpy(), 3)
+    np.testing.assert_array_equal(dp["drafts"].cpu().numpy(), ref["drafts"])
+    n_kept = int(dp["counts"][0].item())
+    np.testing.assert_array_equal(dp["kept"][:n_kept].cpu().numpy(), ref["kept"])

@@ -713,3 +713,19 @@ def test_head_topk_after_step_with_device_result(sp):
     np.testing.assert_array_equal(dp["drafts"].cpu().numpy(), ref["drafts"])
     n_kept = int(dp["counts"][0].item())
     np.testing.assert_array_equal(dp["kept"][:n_kept].cpu().numpy(), ref["kept"])
+
+
+def test_layer_and_head_at_the_row_limit(sp):
+    """G = SPIFFY_MAX_G states of 256 tokens = SPIFFY_MAX_ROWS rows (64 row tiles, blocks that span eight
+    32-row query groups), narrow model so the oracle finishes in seconds."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=256, Hq=2, Hkv=1, hd=128, F=256, V=640, P=70, B=256, G=64)
+    assert cfg.G * cfg.B == 16384
+    check_layer(sp, cfg)
+    st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.05, 0.3, 9)
+    check_head(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 0.9, 6.0)
+
+
+def test_single_token_blocks(sp):
+    """B = 1: every state is one token that attends to the prefix and to itself."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=256, Hq=2, Hkv=2, hd=128, F=256, V=640, P=150, B=1, G=37)
+    check_layer(sp, cfg)

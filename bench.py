@@ -158,6 +158,7 @@ def main():
     }
 
     line["next_step_drafting"] = drafting_leg(sp, cfg, plan, d_states, dev)
+    line["decode_loop"] = decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev)
 
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, layers, prefix, hw, states, edges)
@@ -207,6 +208,50 @@ def drafting_leg(sp, cfg, plan, d_states, dev, iters=50):
     return {"draft_prune_us": draft_us, "head_top3_us": e0.elapsed_time(e1) * 1e3 / iters, "formulas": D, "d_star": d_star,
             "edges_in": len(e), "kept_nodes": int(out["counts"][0].item()), "edges_out": int(out["counts"][1].item()),
             "note": "includes the binding's output allocations; one 64-lane kernel launch"}
+
+
+def decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev, max_steps=8):
+    """Not part of the timed step: the host loop of speculative block decoding (Alg. 1) on the same model:
+    verify -> top-K -> draft/prune -> verify for up to max_steps forward passes of one all-MASK block, with
+    G-1 formulas 'the s most confident positions', all kept; then the cache extension for one block."""
+    import time
+    import torch
+    from paper_2509_18085_amd import decode
+    cap = cfg.P + 2 * cfg.B
+    ck, cv = [], []
+    for k, v in prefix:
+        kk = torch.zeros((cfg.Hkv, cap, cfg.hd), dtype=k.dtype, device=dev)
+        vv = torch.zeros_like(kk)
+        kk[:, :cfg.P] = k
+        vv[:, :cfg.P] = v
+        ck.append(kk)
+        cv.append(vv)
+    D = cfg.G - 1
+    graph = decode.DraftGraph([[(i, 1) for i in range(1, (n % cfg.B) + 2)] for n in range(D)], device=dev)
+    dec = decode.BlockDecoder(sp.cfg_from_synth(cfg), layers, ck, cv, cfg.P, w_embed, hw["final_norm"], hw["w_vocab"],
+                              cfg.B, cfg.threshold, logit_scale=LOGIT_SCALE, graph=graph, d_star=D, device=dev)
+    block0 = torch.full((cfg.B,), cfg.mask_id, dtype=torch.int32, device=dev)
+    dec.decode_block(block0, max_steps=2)                       # warm-up
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    r = dec.decode_block(block0, max_steps=max_steps)
+    torch.cuda.synchronize()
+    loop_ms = (time.perf_counter() - t0) * 1e3
+    block = torch.randint(0, cfg.V - 1, (cfg.B,), dtype=torch.int32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    dec.plan.commit_block(block)                                # warm-up; rewrites the same cache rows
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(3):
+        dec.plan.commit_block(block)
+    e1.record()
+    torch.cuda.synchronize()
+    return {"forward_passes": r["nfe"], "loop_ms": loop_ms, "ms_per_forward_pass": loop_ms / max(1, r["nfe"]),
+            "accepted_depths": r["depths"], "states_verified": r["n_states"], "tokens_unmasked": int((r["final"] != cfg.mask_id).sum().item()),
+            "commit_block_ms": e0.elapsed_time(e1) / 3,
+            "note": "first pass has one state; later passes one state per formula that the remaining MASK positions "
+                    "can still build; includes top-K, drafting, pruning and the host reads of the accept result; "
+                    "random weights, so drafts built from the previous distribution are not expected to be accepted"}
 
 
 def stored_traffic(config):

@@ -81,6 +81,8 @@ typedef struct {
 typedef struct {
   const void *k, *v;
   int32_t P;
+  int32_t capacity; /* rows allocated per KV head (the stride between heads); 0 means P.  A cache that
+                     * spiffy_commit_block extends is allocated with capacity > P. */
 } spiffy_prefix_kv;
 
 /* Result of the walk: accepted node id, number of accepted drafts (depth), decode steps covered
@@ -212,6 +214,17 @@ int spiffy_verify_step(const spiffy_model_cfg *cfg, int32_t n_layers,
                        float *conf, uint8_t *unmask, float *top2_margin, int32_t *target_states,
                        spiffy_accept_result *result, int32_t *accepted_state, void *workspace,
                        size_t workspace_bytes, void *stream);
+
+/* Prefix-cache extension when a block is complete (prefix caching, Sec. 3.1: the keys and values of everything
+ * before the block being decoded stay fixed).  One forward pass of the finished block (B tokens, no MASK
+ * expected but not checked) through the n_layers layers; in every layer the block's keys (rotated at positions
+ * pos0 .. pos0+B-1) and values are written to rows P .. P+B-1 of every KV head of that layer's cache, where
+ * P = prefix[l].P.  prefix[l].k / .v must have capacity >= P + B rows per head; the structs themselves are not
+ * modified: the caller adds B to every P before the next block.  layers / prefix are HOST arrays.  Workspace as
+ * for spiffy_verify_step with G = 1. */
+int spiffy_commit_block(const spiffy_model_cfg *cfg, int32_t n_layers, const spiffy_layer_weights *layers,
+                        const spiffy_prefix_kv *prefix, const void *w_embed, const int32_t *block_tokens,
+                        int32_t B, int32_t pos0, void *workspace, size_t workspace_bytes, void *stream);
 
 #ifdef __cplusplus
 }

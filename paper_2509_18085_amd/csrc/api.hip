@@ -145,6 +145,7 @@ int check_layer_args(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w,
   if (!w->wq || !w->wk || !w->wv || !w->wo || !w->w_gate || !w->w_up || !w->w_down || !w->norm1 || !w->norm2)
     return SPIFFY_EINVAL;
   if (prefix->P < 0 || (prefix->P > 0 && (!prefix->k || !prefix->v))) return SPIFFY_EINVAL;
+  if (prefix->capacity != 0 && prefix->capacity < prefix->P) return SPIFFY_EINVAL;
   const void* ptrs[] = {w->wq, w->wk, w->wv, w->wo, w->w_gate, w->w_up, w->w_down, w->norm1, w->norm2,
                         w->bq, w->bk, w->bv, prefix->k, prefix->v};
   for (const void* p : ptrs)
@@ -161,6 +162,7 @@ struct LayerChain {
   const void* next_norm1 = nullptr;
   bool rope_ready = false;
   bool normed_out = false;   // set when ws.n holds the next layer's normalised input on return
+  bool append_kv = false;    // write the (rotated) K and V rows of state 0 into the cache at rows P .. P+B-1
 };
 
 int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const spiffy_prefix_kv* prefix,
@@ -189,7 +191,13 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   AttnArgs a;
   a.qkv = ws.qkv; a.prefix_k = prefix->k; a.prefix_v = prefix->v; a.out = ws.attn; a.partial = ws.attn_partial;
   a.G = G; a.B = B; a.Hq = cfg->n_q_heads; a.Hkv = cfg->n_kv_heads; a.hd = cfg->head_dim; a.P = prefix->P;
+  a.ldp = prefix->capacity;
   a.pos0 = pos0; a.rope_base = cfg->rope_base; a.rope_ready = chain && chain->rope_ready;
+  if (chain && chain->append_kv &&
+      (rc = dev(launch_kv_append(dt, ws.qkv, a.Hq, a.Hkv, a.hd, B, pos0, cfg->rope_base,
+                                 const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P,
+                                 prefix->capacity ? prefix->capacity : prefix->P, st))))
+    return rc;
   if ((rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st)))) return rc;
 
   // output projection + residual (+ RMSNorm-2 fused into the split-K reduction when K is sliced)
@@ -485,6 +493,38 @@ int spiffy_verify_step(const spiffy_model_cfg* cfg, int32_t n_layers, const spif
                      argmax, conf, unmask, top2_margin, tgt, ws.rest, st)))
     return rc;
   return dev(launch_graph_accept(graph_edges, E, block_tokens, tgt, G, B, root, result, accepted_state, st));
+}
+
+int spiffy_commit_block(const spiffy_model_cfg* cfg, int32_t n_layers, const spiffy_layer_weights* layers,
+                        const spiffy_prefix_kv* prefix, const void* w_embed, const int32_t* block_tokens, int32_t B,
+                        int32_t pos0, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(1, B))) return rc;
+  if (n_layers < 1 || !layers || !prefix || !w_embed || !block_tokens || !workspace || pos0 < 0)
+    return SPIFFY_EINVAL;
+  if (!aligned16(w_embed)) return SPIFFY_EALIGN;
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPIFFY_EALIGN;
+  int P_max = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if ((rc = check_layer_args(cfg, &layers[l], &prefix[l], 1, B))) return rc;
+    if (!prefix[l].k || !prefix[l].v) return SPIFFY_EINVAL;
+    const int cap = prefix[l].capacity ? prefix[l].capacity : prefix[l].P;
+    if ((int64_t)prefix[l].P + B > cap) return SPIFFY_ESHAPE;      // no room for the block's rows
+    if (prefix[l].P > P_max) P_max = prefix[l].P;
+  }
+  const StepWs ws = carve_step(cfg, 1, B, P_max, workspace);
+  if (workspace_bytes < ws.bytes) return SPIFFY_EWORKSPACE;
+  hipStream_t st = (hipStream_t)stream;
+  if ((rc = dev(launch_embed(cfg->dtype, w_embed, block_tokens, B, cfg->d, cfg->vocab, ws.hidden, st)))) return rc;
+  LayerChain chain;
+  chain.append_kv = true;
+  for (int l = 0; l < n_layers; ++l) {
+    chain.normed_in = chain.normed_out;
+    chain.next_norm1 = (l + 1 < n_layers) ? layers[l + 1].norm1 : nullptr;
+    if ((rc = run_layer(cfg, &layers[l], &prefix[l], ws.hidden, 1, B, pos0, ws.hidden, ws.rest, st, &chain))) return rc;
+    chain.rope_ready = true;
+  }
+  return SPIFFY_OK;
 }
 
 #pragma GCC visibility pop

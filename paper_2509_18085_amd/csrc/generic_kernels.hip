@@ -199,7 +199,7 @@ hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs& a, hipStream_
 template <typename T>
 __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__ qkv, const T* __restrict__ pk,
                                                            const T* __restrict__ pv, T* __restrict__ out, int G,
-                                                           int B, int Hq, int Hkv, int hd, int P, int pos0,
+                                                           int B, int Hq, int Hkv, int hd, int P, int ldp, int pos0,
                                                            float rope_base) {
   extern __shared__ float smem[];
   __shared__ float red[4];
@@ -236,7 +236,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
   for (int j = threadIdx.x; j < T_all; j += 256) {
     float dot = 0.f;
     if (j < P) {
-      const T* kr = pk + ((size_t)kvh * P + j) * hd;
+      const T* kr = pk + ((size_t)kvh * ldp + j) * hd;
       for (int i = 0; i < hd; ++i) dot = fmaf(qs[i], to_f32(kr[i]), dot);
     } else {
       const int bb = j - P;
@@ -267,7 +267,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
     const int j0 = c * per, j1 = min(T_all, j0 + per);
     float o = 0.f;
     for (int j = j0; j < j1; ++j) {
-      const float v = (j < P) ? to_f32(pv[((size_t)kvh * P + j) * hd + t])
+      const float v = (j < P) ? to_f32(pv[((size_t)kvh * ldp + j) * hd + t])
                               : to_f32(qkv[(size_t)(g * B + (j - P)) * ld + (Hq + Hkv + kvh) * hd + t]);
       o = fmaf(sc[j], v, o);
     }
@@ -295,14 +295,14 @@ hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attn_generic_kernel<float><<<grid, 256, smem, st>>>((const float*)a.qkv, (const float*)a.prefix_k,
                                                         (const float*)a.prefix_v, (float*)a.out, a.G, a.B, a.Hq,
-                                                        a.Hkv, a.hd, a.P, a.pos0, a.rope_base);
+                                                        a.Hkv, a.hd, a.P, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base);
   } else {
     hipError_t e = hipFuncSetAttribute((const void*)attn_generic_kernel<bf16_t>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attn_generic_kernel<bf16_t><<<grid, 256, smem, st>>>((const bf16_t*)a.qkv, (const bf16_t*)a.prefix_k,
                                                          (const bf16_t*)a.prefix_v, (bf16_t*)a.out, a.G, a.B, a.Hq,
-                                                         a.Hkv, a.hd, a.P, a.pos0, a.rope_base);
+                                                         a.Hkv, a.hd, a.P, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base);
   }
   return hipGetLastError();
 }
@@ -338,6 +338,45 @@ __global__ __launch_bounds__(256) void compact_rows_kernel(const int32_t* __rest
 hipError_t launch_compact_rows(const int32_t* tok, const uint8_t* mask, int mask_id, int M, int32_t* row_idx,
                                int32_t* count, hipStream_t st) {
   compact_rows_kernel<<<1, 256, 0, st>>>(tok, mask, mask_id, M, row_idx, count);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// prefix-cache extension: one thread per (token b, kv head, frequency f)
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void kv_append_kernel(const T* __restrict__ qkv, int Hq, int Hkv, int hd, int B,
+                                                        int pos0, float base, T* __restrict__ ck, T* __restrict__ cv,
+                                                        int P, int ldp) {
+  const int half = hd / 2;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= B * Hkv * half) return;
+  const int f = i % half, kvh = (i / half) % Hkv, b = i / (half * Hkv);
+  const int ld = (Hq + 2 * Hkv) * hd;
+  const T* kr = qkv + (size_t)b * ld + (Hq + kvh) * hd;
+  const T* vr = qkv + (size_t)b * ld + (Hq + Hkv + kvh) * hd;
+  // same table values as the attention kernels use: angle in double, cos / sin rounded to float
+  const double inv_freq = pow((double)base, -2.0 * (double)f / (double)hd);
+  const double ang = (double)(pos0 + b) * inv_freq;
+  const float c = (float)cos(ang), s = (float)sin(ang);
+  const float x1 = to_f32(kr[f]), x2 = to_f32(kr[f + half]);
+  T* kd = ck + ((size_t)kvh * ldp + P + b) * hd;
+  T* vd = cv + ((size_t)kvh * ldp + P + b) * hd;
+  kd[f] = from_f32<T>(x1 * c - x2 * s);
+  kd[f + half] = from_f32<T>(x2 * c + x1 * s);
+  vd[f] = vr[f];
+  vd[f + half] = vr[f + half];
+}
+
+hipError_t launch_kv_append(int dtype, const void* qkv, int Hq, int Hkv, int hd, int B, int pos0, float rope_base,
+                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st) {
+  const int n = B * Hkv * (hd / 2);
+  if (dtype == SPIFFY_F32)
+    kv_append_kernel<float><<<cdiv(n, 256), 256, 0, st>>>((const float*)qkv, Hq, Hkv, hd, B, pos0, rope_base,
+                                                          (float*)cache_k, (float*)cache_v, P, ldp);
+  else
+    kv_append_kernel<bf16_t><<<cdiv(n, 256), 256, 0, st>>>((const bf16_t*)qkv, Hq, Hkv, hd, B, pos0, rope_base,
+                                                           (bf16_t*)cache_k, (bf16_t*)cache_v, P, ldp);
   return hipGetLastError();
 }
 

@@ -21,10 +21,16 @@ struct AttnArgs {
   void* out;             // [M, Hq*hd]
   void* partial;         // MFMA path: split partials (fp32)
   int G, B, Hq, Hkv, hd, P, pos0;
+  int ldp;               // rows allocated per KV head in prefix_k / prefix_v (0 = P)
   float rope_base;
   int rope_ready;        // MFMA path: the rotary table at the start of `partial` is already filled
 };
 hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t st);
+// Prefix-cache extension (Sec. 3.1): the K rows (rotated at positions pos0 .. pos0+B-1) and V rows of the
+// first B rows of the fused qkv activations go to rows P .. P+B-1 of every KV head of the cache
+// ([Hkv][ldp][hd]).  Must run before the attention of the same layer reads the cache only up to row P.
+hipError_t launch_kv_append(int dtype, const void* qkv, int Hq, int Hkv, int hd, int B, int pos0, float rope_base,
+                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st);
 
 // masked-row list: row_idx[0..count) = flattened (g,b) with mask set, ascending; *count.
 hipError_t launch_compact_rows(const int32_t* tokens, const uint8_t* mask, int mask_id, int M,

@@ -259,7 +259,7 @@ struct AttnKArgs {
   bf16_t* out;
   float* opart;         // [nS][M][Hq][128]
   float* mlpart;        // [nS][M][Hq][2]
-  int M, B, Hq, Hkv, P, ld, nQ, nS;
+  int M, B, Hq, Hkv, P, ldp, ld, nQ, nS;   // ldp = rows allocated per KV head of the prefix
 };
 
 // the lane's 8 MFMA operand fragments of LDS tile row `row` (K layout): hd = 16*kk + 8*hh + e
@@ -317,8 +317,8 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
   const int kbeg = sp * SPLIT_KEYS;
   const int kend = min(a.P, kbeg + SPLIT_KEYS);
   const int n_tiles = kend > kbeg ? (kend - kbeg + KTILE - 1) / KTILE : 0;
-  const bf16_t* pk = a.pk + (size_t)kvh * a.P * HD;
-  const bf16_t* pv = a.pv + (size_t)kvh * a.P * HD;
+  const bf16_t* pk = a.pk + (size_t)kvh * a.ldp * HD;
+  const bf16_t* pv = a.pv + (size_t)kvh * a.ldp * HD;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
   // LDS-DMA of N_ROWS rows of 256 bytes (rows row0 .. clamped to row_max of a matrix with row stride `ld`
   // elements, starting at `src`) into an LDS tile; wavefront `wave` brings N_ROWS/8 consecutive rows:
@@ -593,7 +593,7 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   k.out = (bf16_t*)a.out;
   k.opart = opart;
   k.mlpart = mlpart;
-  k.M = M; k.B = a.B; k.Hq = a.Hq; k.Hkv = a.Hkv; k.P = a.P;
+  k.M = M; k.B = a.B; k.Hq = a.Hq; k.Hkv = a.Hkv; k.P = a.P; k.ldp = a.ldp ? a.ldp : a.P;
   k.ld = (a.Hq + 2 * a.Hkv) * HD;
   k.nQ = cdiv(M, QTILE);
   k.nS = nS;

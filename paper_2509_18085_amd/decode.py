@@ -1,0 +1,117 @@
+"""Host loop of speculative block decoding (Alg. 1) on top of the C-ABI entry points.
+
+One iteration = one forward pass: spiffy_verify_step over the current block and its drafts, then, while
+MASK tokens remain, the next step's draft graph on the device (spiffy_head_topk + spiffy_draft_prune).
+When a block is complete its keys / values are appended to the prefix cache (spiffy_commit_block,
+prefix caching of Sec. 3.1) and the next block starts.  Per forward pass the host reads back 4 + B + 2
+integers (accept result, accepted block, sizes of the pruned graph); everything else stays on the device.
+Only argument marshalling and the loop live here: every step of the path runs in the library's kernels.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+from . import spiffy as sp
+
+
+class DraftGraph:
+    """D draft formulas {(i, j)} (1-based: token position rank, vocabulary rank; Sec. 4.4.3) and the edges
+    (parent, child) over nodes 0..D, node 0 = the current block.  Edges default to formula inclusion."""
+
+    def __init__(self, formulas: Sequence[Sequence[Tuple[int, int]]], edges: Optional[np.ndarray] = None,
+                 device="cuda"):
+        self.formulas = [list(map(tuple, f)) for f in formulas]
+        self.D = len(self.formulas)
+        self.K = max([j for f in self.formulas for _, j in f], default=1)
+        if edges is None:
+            sets = [set()] + [set(f) for f in self.formulas]
+            edges = np.array([(a, c) for a in range(self.D + 1) for c in range(1, self.D + 1)
+                              if a != c and sets[a] < sets[c]], np.int32).reshape(-1, 2)
+        self.edges_np = np.asarray(edges, np.int32).reshape(-1, 2)
+        off = np.cumsum([0] + [len(f) for f in self.formulas]).astype(np.int32)
+        pairs = np.array([p for f in self.formulas for p in f], np.int32).reshape(-1, 2)
+        self.offsets = torch.from_numpy(off).to(device)
+        self.pairs = torch.from_numpy(pairs).to(device) if len(pairs) else None
+        self.edges = torch.from_numpy(self.edges_np).to(device) if len(self.edges_np) else None
+
+
+class BlockDecoder:
+    """Decodes blocks of B tokens one after the other against a growing prefix cache.
+
+    layers: per layer dict of device weight tensors; cache_k / cache_v: per layer device tensors
+    [Hkv, capacity, hd] whose first P0 rows hold the context; graph: DraftGraph or None (vanilla decoding,
+    one state per forward pass); d_star: draft nodes kept per step.
+    """
+
+    def __init__(self, cfg: sp.ModelCfg, layers: Sequence[Dict[str, torch.Tensor]], cache_k: Sequence[torch.Tensor],
+                 cache_v: Sequence[torch.Tensor], P0: int, w_embed: torch.Tensor, final_norm: torch.Tensor,
+                 w_vocab: torch.Tensor, B: int, threshold: float, logit_scale: float = 1.0, force_one: bool = True,
+                 graph: Optional[DraftGraph] = None, d_star: int = 0, device="cuda"):
+        self.cfg, self.B, self.graph, self.device = cfg, B, graph, device
+        self.d_star = d_star if graph is not None else 0
+        self.logit_scale = logit_scale
+        self.P = P0
+        self.capacity = int(cache_k[0].shape[1])
+        prefix = [sp.prefix_kv(k, v, P0) for k, v in zip(cache_k, cache_v)]
+        self.plan = sp.StepPlan(cfg, [sp.layer_weights(w) for w in layers], prefix, w_embed, final_norm, w_vocab,
+                                1 + self.d_star, B, P0, threshold, logit_scale=logit_scale, force_one=force_one,
+                                device=device)
+        # the workspace must also fit the longest prefix the cache can hold
+        self.plan.workspace = sp.alloc_workspace(cfg, 1 + self.d_star, B, self.capacity, device)
+
+    def decode_block(self, block0: torch.Tensor, max_steps: int = 4096) -> Dict:
+        """block0 [B] int32 on the device.  Returns the final block (device), the number of forward passes,
+        the accepted depth and the number of states verified in every pass, and the block after every pass
+        (host copies)."""
+        mask_id = self.cfg.mask_id
+        state = block0.to(torch.int32).reshape(1, self.B).contiguous()
+        states, edges = state, None
+        nfe, depths, n_states, traj = 0, [], [], [state[0].cpu().numpy().copy()]
+        while nfe < max_steps:
+            cur = states[0].cpu().numpy()
+            if not (cur == mask_id).any():
+                break
+            out = self.plan.run(states.contiguous(), edges)
+            nfe += 1
+            n_states.append(int(states.shape[0]))
+            res = out["result"].cpu().tolist()
+            depths.append(int(res[1]))
+            new_state = out["accepted_state"].clone()
+            new_np = new_state.cpu().numpy()
+            traj.append(new_np.copy())
+            if not (new_np == mask_id).any() or self.graph is None or self.d_star == 0:
+                states, edges = new_state.reshape(1, self.B), None
+                continue
+            tok, prob = sp.head_topk(self.cfg, self.plan.w_vocab, states.contiguous(), self.graph.K, self.logit_scale,
+                                     self.plan.workspace, result=out["result"], after_step=True)
+            dp = sp.draft_prune(new_state, mask_id, tok, prob, self.graph.offsets, self.graph.pairs, self.graph.edges,
+                                self.d_star)
+            n_kept, n_edges = [int(x) for x in dp["counts"].cpu().tolist()]
+            states = dp["states"][:n_kept]
+            edges = dp["edges"][:n_edges].contiguous() if n_edges else None
+        return dict(final=states[0].clone(), nfe=nfe, depths=depths, n_states=n_states, trajectory=traj)
+
+    def commit(self, block: torch.Tensor) -> None:
+        """Append the finished block to the cache; the next block sits right after it."""
+        if self.P + self.B > self.capacity:
+            raise sp.SpiffyError(sp.SPIFFY_ESHAPE, "BlockDecoder.commit: cache is full")
+        self.plan.commit_block(block.to(torch.int32).contiguous())
+        self.P += self.B
+        self.plan.set_prefix_len(self.P)
+
+    def generate(self, n_blocks: int) -> Dict:
+        """Decode n_blocks all-MASK blocks in sequence.  Returns tokens [n_blocks*B] (host), forward passes
+        and accepted depths per block."""
+        out_tokens: List[np.ndarray] = []
+        nfe, depths = [], []
+        for _ in range(n_blocks):
+            block0 = torch.full((self.B,), self.cfg.mask_id, dtype=torch.int32, device=self.device)
+            r = self.decode_block(block0)
+            out_tokens.append(r["final"].cpu().numpy())
+            nfe.append(r["nfe"])
+            depths.append(r["depths"])
+            self.commit(r["final"])
+        return dict(tokens=np.concatenate(out_tokens), nfe=nfe, depths=depths)

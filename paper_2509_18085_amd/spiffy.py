@@ -21,7 +21,7 @@ SPIFFY_BF16, SPIFFY_F32 = 0, 1
 MAX_G = 64
 
 EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "spiffy_embed",
-           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk",
+           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk", "spiffy_commit_block",
            "spiffy_verify_step"]
 GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
@@ -39,7 +39,7 @@ class LayerWeights(C.Structure):
 
 
 class PrefixKV(C.Structure):
-    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("P", C.c_int32)]
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("P", C.c_int32), ("capacity", C.c_int32)]
 
 
 class AcceptResult(C.Structure):
@@ -77,6 +77,9 @@ def _load() -> C.CDLL:
     lib.spiffy_gemm.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     lib.spiffy_graph_accept.restype = C.c_int
     lib.spiffy_graph_accept.argtypes = [vp, i32, vp, vp, i32, i32, i32, vp, vp, vp]
+    lib.spiffy_commit_block.restype = C.c_int
+    lib.spiffy_commit_block.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, i32, i32,
+                                        vp, sz, vp]
     lib.spiffy_head_topk.restype = C.c_int
     lib.spiffy_head_topk.argtypes = [cfgp, vp, vp, i32, i32, vp, i32, i32, f32, i32, vp, vp, vp, sz, vp]
     lib.spiffy_draft_prune.restype = C.c_int
@@ -135,9 +138,12 @@ def layer_weights(w: Dict[str, torch.Tensor]) -> LayerWeights:
     return lw
 
 
-def prefix_kv(k: Optional[torch.Tensor], v: Optional[torch.Tensor]) -> PrefixKV:
-    P = 0 if k is None else int(k.shape[1])
-    p = PrefixKV(_ptr(k) if P else None, _ptr(v) if P else None, P)
+def prefix_kv(k: Optional[torch.Tensor], v: Optional[torch.Tensor], P: Optional[int] = None) -> PrefixKV:
+    """k, v [Hkv, rows, hd].  P = rows in use (default: all of them); rows beyond P are room for
+    commit_block to extend the cache."""
+    rows = 0 if k is None else int(k.shape[1])
+    P = rows if P is None else int(P)
+    p = PrefixKV(_ptr(k) if rows else None, _ptr(v) if rows else None, P, rows if rows != P else 0)
     p._keep = (k, v)
     return p
 
@@ -286,7 +292,7 @@ class StepPlan:
                  w_embed: torch.Tensor, final_norm: torch.Tensor, w_vocab: torch.Tensor, G: int, B: int,
                  pos0: int, threshold: float, logit_scale: float = 1.0, force_one: bool = True,
                  root: int = 0, device="cuda"):
-        self.cfg, self.G, self.B, self.pos0 = cfg, G, B, pos0
+        self.cfg, self.G, self.G_cap, self.B, self.pos0 = cfg, G, G, B, pos0
         self.threshold, self.logit_scale, self.force_one, self.root = threshold, logit_scale, int(force_one), root
         self.n_layers = len(layers)
         self._layers = (LayerWeights * max(1, self.n_layers))(*layers)
@@ -305,8 +311,26 @@ class StepPlan:
                         result=torch.empty(4, dtype=torch.int32, device=device),
                         accepted_state=torch.empty(B, dtype=torch.int32, device=device))
 
+    def set_prefix_len(self, P: int, pos0: Optional[int] = None) -> None:
+        """After commit_block: the caches hold P rows per head; the block now sits at pos0 (default P)."""
+        for l in range(self.n_layers):
+            self._prefix[l].P = P
+        self.pos0 = P if pos0 is None else pos0
+
+    def commit_block(self, block_tokens: torch.Tensor, stream=None) -> None:
+        """Append the finished block's keys / values to every layer's cache (rows P .. P+B-1)."""
+        wp, wn = _ws(self.workspace)
+        _check(lib.spiffy_commit_block(C.byref(self.cfg), self.n_layers, self._layers, self._prefix,
+                                       _ptr(self.w_embed), _ptr(block_tokens), self.B, self.pos0, wp, wn,
+                                       _stream(stream)), "spiffy_commit_block")
+
     def run(self, block_tokens: torch.Tensor, graph_edges: Optional[torch.Tensor], stream=None) -> Dict[str, torch.Tensor]:
+        """block_tokens [G,B] with G <= the plan's capacity; rows 0..G-1 of the outputs are written."""
         o = self.out
+        G = int(block_tokens.shape[0])
+        if G > self.G_cap:
+            raise SpiffyError(SPIFFY_ESHAPE, "StepPlan.run: more states than the plan was sized for")
+        self.G = G
         E = int(graph_edges.shape[0]) if graph_edges is not None else 0
         wp, wn = _ws(self.workspace)
         _check(lib.spiffy_verify_step(

@@ -194,6 +194,30 @@ def test_verify_step_argument_errors():
     assert call(G=100) == sp.SPIFFY_ESHAPE                      # walk supports at most 64 nodes
 
 
+def test_commit_block_argument_errors():
+    cfg = _cfg("c3")
+    w, _ = _layer_structs()
+    layers = (sp.LayerWeights * 1)(w)
+    def call(**k):
+        prefix = (sp.PrefixKV * 1)(sp.PrefixKV(k.get("pk", DUMMY), DUMMY, k.get("P", 64), k.get("cap", 128)))
+        return sp.lib.spiffy_commit_block(
+            C.byref(cfg), k.get("L", 1), layers, prefix, k.get("we", DUMMY), k.get("tok", DUMMY), k.get("B", 32),
+            k.get("pos0", 64), k.get("ws", 0x100000), k.get("wsb", 16), None)
+    assert call() == sp.SPIFFY_EWORKSPACE                       # every argument check passed
+    assert call(cap=95) == sp.SPIFFY_ESHAPE                     # 64 + 32 rows do not fit
+    assert call(cap=0) == sp.SPIFFY_ESHAPE                      # capacity 0 means P: no room at all
+    assert call(cap=32) == sp.SPIFFY_EINVAL                     # capacity below P
+    assert call(pk=None) == sp.SPIFFY_EINVAL                    # a cache to append to is required
+    assert call(L=0) == sp.SPIFFY_EINVAL
+    assert call(we=None) == sp.SPIFFY_EINVAL
+    assert call(tok=None) == sp.SPIFFY_EINVAL
+    assert call(ws=None) == sp.SPIFFY_EINVAL
+    assert call(pos0=-1) == sp.SPIFFY_EINVAL
+    assert call(B=0) == sp.SPIFFY_EINVAL
+    assert call(B=5000) == sp.SPIFFY_ESHAPE
+    assert call(ws=0x100010) == sp.SPIFFY_EALIGN
+
+
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     import importlib
     monkeypatch.setattr(sp, "LIB_PATH", str(tmp_path / "nope.so"))

@@ -729,3 +729,120 @@ def test_single_token_blocks(sp):
     """B = 1: every state is one token that attends to the prefix and to itself."""
     cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=256, Hq=2, Hkv=2, hd=128, F=256, V=640, P=150, B=1, G=37)
     check_layer(sp, cfg)
+
+
+# ------------------------------------------------------------------ prefix-cache extension and the decode loop
+
+def _oracle_commit(m, kw, block, P):
+    """Oracle side of spiffy_commit_block: forward of the finished block, its rotated K and V appended."""
+    h = O().embed(m["w_embed"], block[None, :])
+    new_prefix = []
+    for w, (pk, pv) in zip(m["layers"], m["prefix"]):
+        h, ks, vs = O().verify_layer(w, pk, pv, h, n_q_heads=kw["n_q_heads"], n_kv_heads=kw["n_kv_heads"],
+                                     head_dim=kw["head_dim"], pos0=P, rms_eps=kw["rms_eps"],
+                                     rope_base=kw["rope_base"], return_kv=True)
+        new_prefix.append((np.concatenate([pk, ks[0]], axis=1), np.concatenate([pv, vs[0]], axis=1)))
+    return new_prefix
+
+
+def _decoder_setup(sp, cfg, seed, n_blocks, threshold, scale, graph, d_star):
+    from paper_2509_18085_amd import decode
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
+    prefix = [synth.prefix_kv(cfg, l, seed) for l in range(cfg.L)]
+    hw = synth.head_weights(cfg, seed)
+    we = synth.embed_weights(cfg, seed)
+    cap = cfg.P + n_blocks * cfg.B
+    ck, cv = [], []
+    for k, v in prefix:
+        kk = torch.zeros((cfg.Hkv, cap, cfg.hd), dtype=k.dtype, device=DEV)
+        vv = torch.zeros_like(kk)
+        kk[:, :cfg.P] = k.to(DEV)
+        vv[:, :cfg.P] = v.to(DEV)
+        ck.append(kk)
+        cv.append(vv)
+    dec = decode.BlockDecoder(sp.cfg_from_synth(cfg), [dev_weights(w) for w in layers], ck, cv, cfg.P, we.to(DEV),
+                              hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), cfg.B, threshold, logit_scale=scale,
+                              graph=graph, d_star=d_star, device=DEV)
+    m = dict(layers=[np_weights(w) for w in layers], prefix=[(to_np(k), to_np(v)) for k, v in prefix],
+             w_embed=to_np(we), final_norm=to_np(hw["final_norm"]), w_vocab=to_np(hw["w_vocab"]))
+    kw = dict(n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P, mask_id=cfg.mask_id,
+              threshold=threshold, rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, logit_scale=scale, force_one=True)
+    return dec, ck, cv, m, kw
+
+
+@pytest.mark.parametrize("key", ["c1", "bf16_mfma"])
+def test_commit_block_appends_the_blocks_keys_and_values(sp, key):
+    cfg = synth.CONFIGS["c1"] if key == "c1" else synth.CONFIGS["c1"].scaled(
+        dtype="bf16", L=2, d=256, Hq=4, Hkv=2, hd=128, F=320, V=640, P=70, B=32, G=1)
+    dec, ck, cv, m, kw = _decoder_setup(sp, cfg, 3, 2, 0.9, 1.0, None, 0)
+    before_k = [k.clone() for k in ck]
+    block = np.random.default_rng(1).integers(0, cfg.V, size=cfg.B).astype(np.int32)
+    dec.commit(torch.from_numpy(block).to(DEV))
+    torch.cuda.synchronize()
+    ref = _oracle_commit(m, kw, block, cfg.P)
+    t = tol(cfg)
+    for l in range(cfg.L):
+        gk, gv = to_np(ck[l]), to_np(cv[l])
+        np.testing.assert_array_equal(gk[:, :cfg.P], to_np(before_k[l])[:, :cfg.P])          # context untouched
+        assert (gk[:, cfg.P + cfg.B:] == 0).all() and (gv[:, cfg.P + cfg.B:] == 0).all()       # nothing beyond the block
+        for got, want in ((gk, ref[l][0]), (gv, ref[l][1])):
+            e_max, _ = rel_err(got[:, cfg.P:cfg.P + cfg.B], want[:, cfg.P:])
+            assert e_max < t, (l, e_max)
+    assert dec.P == cfg.P + cfg.B
+
+
+def test_decode_two_blocks_matches_the_oracle_loop(sp):
+    """Configuration 1 (fp32): the device loop verify -> top-K -> draft/prune -> verify, with the cache extended
+    between blocks, produces the oracle's tokens, forward-pass counts and accepted depths; and the same tokens as
+    vanilla decoding on the device (losslessness, App. A) with NFE_vanilla - NFE = accepted drafts that still
+    had a MASK."""
+    from paper_2509_18085_amd import decode
+    cfg = synth.CONFIGS["c1"]
+    scale, tau, d_star = 12.0, 0.5, 3
+    formulas = [[(i, 1) for i in range(1, n + 1)] for n in range(1, 5)] + [[(1, 2)], [(1, 1), (2, 2)]]
+    graph = decode.DraftGraph(formulas, device=DEV)
+    dec, _, _, m, kw = _decoder_setup(sp, cfg, synth.DEFAULT_SEED, 2, tau, scale, graph, d_star)
+    got = dec.generate(2)
+    vdec, _, _, _, _ = _decoder_setup(sp, cfg, synth.DEFAULT_SEED, 2, tau, scale, None, 0)
+    van = vdec.generate(2)
+    np.testing.assert_array_equal(got["tokens"], van["tokens"])
+    assert all(n <= v for n, v in zip(got["nfe"], van["nfe"])) and sum(got["nfe"]) < sum(van["nfe"])
+
+    # the oracle's loop with the same drafter
+    def drafter(state, info):
+        if not info:
+            return np.zeros((0, state.size), np.int32), np.zeros((0, 2), np.int32)
+        t, p = O().head_topk(info["hidden"][info["node"]], m["final_norm"], m["w_vocab"], graph.K,
+                             rms_eps=kw["rms_eps"], logit_scale=scale)
+        out = O().draft_and_prune(state, cfg.mask_id, t, p, formulas, graph.edges_np, d_star)
+        return out["states"][1:], out["edges"]
+
+    tokens, nfes, depths = [], [], []
+    P = cfg.P
+    for _ in range(2):
+        model = dict(m, kw=dict(kw, pos0=P))
+        block0 = np.full(cfg.B, cfg.mask_id, np.int32)
+        final, traj, nfe, dps, _ = O().decode_block(model, block0, drafter=drafter)
+        tokens.append(final)
+        nfes.append(nfe)
+        depths.append(dps)
+        m["prefix"] = _oracle_commit(m, model["kw"], final, P)
+        P += cfg.B
+    np.testing.assert_array_equal(got["tokens"], np.concatenate(tokens))
+    assert got["nfe"] == nfes and got["depths"] == depths
+
+
+def test_decode_is_lossless_on_the_mfma_path(sp):
+    """bf16 MFMA kernels: a row's arithmetic does not depend on the states verified with it, so speculative
+    decoding reproduces vanilla decoding token for token over several blocks, in fewer forward passes."""
+    from paper_2509_18085_amd import decode
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=1280, P=100, B=32, G=1)
+    formulas = [[(i, 1) for i in range(1, n + 1)] for n in (1, 2, 3, 4, 6, 8, 12, 16)] + [[(1, 2)], [(1, 1), (2, 2)]]
+    graph = decode.DraftGraph(formulas, device=DEV)
+    dec, _, _, _, _ = _decoder_setup(sp, cfg, 11, 3, 0.7, 16.0, graph, 5)
+    vdec, _, _, _, _ = _decoder_setup(sp, cfg, 11, 3, 0.7, 16.0, None, 0)
+    got, van = dec.generate(3), vdec.generate(3)
+    np.testing.assert_array_equal(got["tokens"], van["tokens"])
+    assert not (got["tokens"] == cfg.mask_id).any()
+    assert sum(got["nfe"]) < sum(van["nfe"])
+    assert sum(sum(d) for d in got["depths"]) >= sum(van["nfe"]) - sum(got["nfe"])

@@ -18,6 +18,7 @@ What the paper fixes and where:
     the block it drafts for; attention inside a block is bidirectional    Fig. 4 caption
   * keys/values of everything before the block are cached and fixed       Sec. 3.1 (prefix caching)
   * exactness holds with fixed context KV / blockwise-causal context      Sec. 4.3, App. A.2
+  * dual cache: the fixed context also holds the tokens after the block   Sec. 4.3, App. A.2
   * Next(X, p): per-position top-1 probability and token, unmask the chosen positions
                                                                           Alg. 1 steps 1-4, App. A
   * threshold rule: unmask every masked position whose top-1 probability exceeds tau
@@ -46,7 +47,10 @@ formulations of Sec. 4.3), torch's CPU scaled-dot-product attention, brute-force
 enumeration of all walks on small graphs, the losslessness theorem on a tiny model; for
 drafting and pruning a hand-worked example, an independent loop implementation on exact
 fractions, the graph conditions of Eqs. (4)-(6), and the link to Next(X, p): the formula
-"ranks 1..s, vocabulary rank 1" reproduces the threshold rule's next state and is accepted.
+"ranks 1..s, vocabulary rank 1" reproduces the threshold rule's next state and is accepted;
+for the dual cache (tests/test_oracle_suffix_pins.py) the mean-of-values closed form over
+P + B + S rows, torch's attention, the block rows of a full bidirectional one-layer forward,
+the dense-mask formulation with the suffix in the context, and a scalar brute force.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -113,7 +117,8 @@ def _w(d: Dict, k: str) -> Optional[np.ndarray]:
 def verify_layer(w: Dict[str, np.ndarray], prefix_k: np.ndarray, prefix_v: np.ndarray,
                  hidden_in: np.ndarray, *, n_q_heads: int, n_kv_heads: int, head_dim: int,
                  pos0: int, rms_eps: float = 1e-5, rope_base: float = 10000.0,
-                 return_kv: bool = False):
+                 return_kv: bool = False, suffix_k: Optional[np.ndarray] = None,
+                 suffix_v: Optional[np.ndarray] = None):
     """hidden_in [G,B,d] -> hidden_out [G,B,d].
 
     Each g is processed on its own (that independence is the attention mask of Fig. 4):
@@ -121,6 +126,11 @@ def verify_layer(w: Dict[str, np.ndarray], prefix_k: np.ndarray, prefix_v: np.nd
     block, bidirectionally.  prefix_k / prefix_v are [Hkv, P, hd]; prefix_k is already
     rotated at positions 0..P-1.  The block sits at positions pos0..pos0+B-1 for every g
     (Sec. 4.3, "appropriate positional embeddings").
+
+    suffix_k / suffix_v [Hkv, S, hd] (dual cache, Sec. 4.3 / App. A.2): fixed keys / values of
+    the S true-sequence tokens after the block, suffix_k already rotated at positions
+    pos0+B .. pos0+B+S-1.  Every block, true or draft, attends to them as it attends to the
+    prefix (Fig. 4 caption: all blocks of the true sequence except the one drafted for).
     """
     x_all = np.asarray(hidden_in, F64)
     G, B, d = x_all.shape
@@ -133,6 +143,10 @@ def verify_layer(w: Dict[str, np.ndarray], prefix_k: np.ndarray, prefix_v: np.nd
     pos = pos0 + np.arange(B)
     out = np.empty_like(x_all)
     ks, vs = [], []
+    if suffix_k is None:
+        sk, sv = np.zeros((Hkv, 0, hd), F64), np.zeros((Hkv, 0, hd), F64)
+    else:
+        sk, sv = np.asarray(suffix_k, F64), np.asarray(suffix_v, F64)
     for g in range(G):
         x = x_all[g]                                            # [B, d]
         n = rms_norm(x, w["norm1"], rms_eps)
@@ -151,9 +165,9 @@ def verify_layer(w: Dict[str, np.ndarray], prefix_k: np.ndarray, prefix_v: np.nd
         o = np.empty((B, Hq, hd), F64)
         for h in range(Hq):
             kvh = h // rep
-            keys = np.concatenate([pk[kvh], k[kvh]], axis=0)    # [P+B, hd]
-            vals = np.concatenate([pv[kvh], v[kvh]], axis=0)
-            s = (q[h] @ keys.T) / np.sqrt(float(hd))            # [B, P+B]
+            keys = np.concatenate([pk[kvh], k[kvh], sk[kvh]], axis=0)    # [P+B+S, hd]
+            vals = np.concatenate([pv[kvh], v[kvh], sv[kvh]], axis=0)
+            s = (q[h] @ keys.T) / np.sqrt(float(hd))            # [B, P+B+S]
             p = softmax_rows(s)
             o[:, h, :] = p @ vals
         h1 = x + o.reshape(B, Hq * hd) @ wo.T
@@ -265,11 +279,14 @@ def graph_accept(edges: np.ndarray, draft_states: np.ndarray, target_states: np.
 def verify_step(layers: Sequence[Dict], prefix: Sequence[Tuple[np.ndarray, np.ndarray]],
                 w_embed, final_norm, w_vocab, block_tokens, edges, *, n_q_heads, n_kv_heads,
                 head_dim, pos0, mask_id, threshold, rms_eps=1e-5, rope_base=10000.0,
-                logit_scale=1.0, force_one=True, root=0):
+                logit_scale=1.0, force_one=True, root=0, suffix=None):
+    """suffix: None, or per layer (suffix_k, suffix_v) of the dual cache."""
     h = embed(w_embed, block_tokens)
-    for w, (pk, pv) in zip(layers, prefix):
+    for l, (w, (pk, pv)) in enumerate(zip(layers, prefix)):
+        sk, sv = suffix[l] if suffix is not None else (None, None)
         h = verify_layer(w, pk, pv, h, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
-                         head_dim=head_dim, pos0=pos0, rms_eps=rms_eps, rope_base=rope_base)
+                         head_dim=head_dim, pos0=pos0, rms_eps=rms_eps, rope_base=rope_base,
+                         suffix_k=sk, suffix_v=sv)
     amax, conf, unmask, margin, target = decode_head(
         h, final_norm, w_vocab, block_tokens, mask_id, threshold, rms_eps=rms_eps,
         logit_scale=logit_scale, force_one=force_one)
@@ -323,19 +340,23 @@ def masked_forward(layers: Sequence[Dict], x: np.ndarray, positions: np.ndarray,
     return hs, Ks, Vs
 
 
-def verification_mask(P: int, B: int, G: int) -> Tuple[np.ndarray, np.ndarray]:
+def verification_mask(P: int, B: int, G: int, S: int = 0) -> Tuple[np.ndarray, np.ndarray]:
     """Dense mask and position ids of the single-sequence formulation
-    [prefix ; block_0 ; ... ; block_{G-1}] (Fig. 4 caption, with fixed prefix KV):
-    prefix rows see the prefix only; the rows of block g see the prefix and block g.
-    Every block reuses positions P..P+B-1."""
-    T = P + G * B
+    [prefix ; block_0 ; ... ; block_{G-1} ; suffix] (Fig. 4 caption, with fixed context KV):
+    context rows (prefix and the S suffix tokens after the block) see the context only; the
+    rows of block g see the context and block g.  Every block reuses positions P..P+B-1;
+    the suffix sits at P+B..P+B+S-1."""
+    T = P + G * B + S
+    ctx = np.zeros(T, bool)
+    ctx[:P] = True
+    ctx[P + G * B:] = True
     allow = np.zeros((T, T), bool)
-    allow[:P, :P] = True
+    allow[np.ix_(ctx, ctx)] = True
     for g in range(G):
         r = slice(P + g * B, P + (g + 1) * B)
-        allow[r, :P] = True
+        allow[r, ctx] = True
         allow[r, r] = True
-    pos = np.concatenate([np.arange(P)] + [P + np.arange(B)] * G)
+    pos = np.concatenate([np.arange(P)] + [P + np.arange(B)] * G + [P + B + np.arange(S)])
     return allow, pos
 
 

@@ -72,7 +72,7 @@ CONFIGS: Dict[str, Config] = {
 # tensor ids used to derive independent streams from one seed
 _TID = dict(wq=1, wk=2, wv=3, wo=4, w_gate=5, w_up=6, w_down=7, norm1=8, norm2=9,
             prefix_k=10, prefix_v=11, w_embed=12, w_vocab=13, final_norm=14, hidden=15,
-            bq=16, bk=17, bv=18)
+            bq=16, bk=17, bv=18, suffix_k=19, suffix_v=20)
 
 
 def _gen(seed: int, tid: int, layer: int, device) -> torch.Generator:
@@ -115,6 +115,16 @@ def prefix_kv(cfg: Config, layer: int, seed: int = DEFAULT_SEED, device="cpu",
     dt = cfg.torch_dtype()
     k = _normal((cfg.Hkv, P, cfg.hd), 1.0, 0.0, seed, _TID["prefix_k"], layer, device, dt)
     v = _normal((cfg.Hkv, P, cfg.hd), 1.0, 0.0, seed, _TID["prefix_v"], layer, device, dt)
+    return k, v
+
+
+def suffix_kv(cfg: Config, layer: int, S: int, seed: int = DEFAULT_SEED, device="cpu"
+              ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Cached K and V of the S tokens after the block (dual cache), each [Hkv, S, hd], N(0,1); K counts as
+    already rotated."""
+    dt = cfg.torch_dtype()
+    k = _normal((cfg.Hkv, S, cfg.hd), 1.0, 0.0, seed, _TID["suffix_k"], layer, device, dt)
+    v = _normal((cfg.Hkv, S, cfg.hd), 1.0, 0.0, seed, _TID["suffix_v"], layer, device, dt)
     return k, v
 
 

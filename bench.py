@@ -36,6 +36,8 @@ def main():
     ap.add_argument("--config", default="c3")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=5)
+    ap.add_argument("--step-only", action="store_true",
+                    help="skip the legs outside the timed step (drafting, decode loop, dual cache): for profiles")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run plain device copies of 1 GiB (calibration of the FETCH_SIZE/WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -157,8 +159,10 @@ def main():
         "setup_s": t_setup,
     }
 
-    line["next_step_drafting"] = drafting_leg(sp, cfg, plan, d_states, dev)
-    line["decode_loop"] = decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev)
+    if not args.step_only:
+        line["next_step_drafting"] = drafting_leg(sp, cfg, plan, d_states, dev)
+        line["decode_loop"] = decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev)
+        line["dual_cache_step"] = dual_cache_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, dev, seed)
 
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, layers, prefix, hw, states, edges)
@@ -252,6 +256,34 @@ def decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev, max_steps=8):
             "note": "first pass has one state; later passes one state per formula that the remaining MASK positions "
                     "can still build; includes top-K, drafting, pruning and the host reads of the accept result; "
                     "random weights, so drafts built from the previous distribution are not expected to be accepted"}
+
+
+def dual_cache_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, dev, seed, S=224, steps=5):
+    """Not part of the timed step: the same step with a dual cache (Sec. 4.3 / App. A.2), S fixed keys /
+    values of the tokens after the block in every layer (S = 224: a 256-token generation, first block)."""
+    import time
+    import torch
+    from paper_2509_18085_amd import synth
+    cap = cfg.P + cfg.B + S
+    pf = []
+    for l, (k, v) in enumerate(prefix):
+        sk, sv = synth.suffix_kv(cfg, l, S, seed, device=dev)
+        kk = torch.zeros((cfg.Hkv, cap, cfg.hd), dtype=k.dtype, device=dev)
+        vv = torch.zeros_like(kk)
+        kk[:, :cfg.P], vv[:, :cfg.P] = k, v
+        kk[:, cfg.P + cfg.B:], vv[:, cfg.P + cfg.B:] = sk, sv
+        pf.append(sp.prefix_kv(kk, vv, cfg.P, S))
+    plan = sp.StepPlan(sp.cfg_from_synth(cfg), [sp.layer_weights(w) for w in layers], pf, w_embed, hw["final_norm"],
+                       hw["w_vocab"], cfg.G, cfg.B, cfg.P, cfg.threshold, logit_scale=LOGIT_SCALE, device=dev)
+    for _ in range(2):
+        plan.run(d_states, d_edges)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        plan.run(d_states, d_edges)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    return {"suffix_rows": S, "ms_per_step": ms, "states_per_s": cfg.G / (ms * 1e-3)}
 
 
 def stored_traffic(config):

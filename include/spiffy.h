@@ -76,13 +76,18 @@ typedef struct {
   const void *bq, *bk, *bv;
 } spiffy_layer_weights;
 
-/* Cached context of one layer (prefix caching, Sec. 3.1): k and v are each [Hkv, P, hd];
- * k is already rotated at positions 0..P-1.  P may be 0 (then k, v may be NULL). */
+/* Cached context of one layer (prefix caching, Sec. 3.1; dual cache, Sec. 4.3 / App. A.2): k and v are each
+ * [Hkv, capacity, hd] and row j holds sequence position j; k rows are already rotated at their positions.
+ * Rows 0 .. P-1 are the prefix.  P may be 0 (then, with S = 0, k and v may be NULL).  With S > 0 rows
+ * P+B .. P+B+S-1 hold the S tokens after the block (B = the block size of the call): every block, true or
+ * draft, attends to prefix, itself and suffix (Fig. 4).  Rows P .. P+B-1, the slot of the block being decoded,
+ * are never read; spiffy_commit_block writes them. */
 typedef struct {
   const void *k, *v;
   int32_t P;
   int32_t capacity; /* rows allocated per KV head (the stride between heads); 0 means P.  A cache that
-                     * spiffy_commit_block extends is allocated with capacity > P. */
+                     * spiffy_commit_block extends, or that holds a suffix, has capacity >= P + B + S. */
+  int32_t S;        /* suffix rows; 0 = prefix cache only */
 } spiffy_prefix_kv;
 
 /* Result of the walk: accepted node id, number of accepted drafts (depth), decode steps covered
@@ -98,7 +103,8 @@ const char *spiffy_status_str(int status);
 int spiffy_uses_mfma(const spiffy_model_cfg *cfg, int32_t B);
 
 /* Bytes of caller-provided scratch needed by verify_layer / decode_head / verify_step for up to
- * G states of B tokens and a prefix of up to P_max.  0 on invalid arguments. */
+ * G states of B tokens and up to P_max cached rows per layer (prefix and suffix together, P + S).
+ * 0 on invalid arguments. */
 size_t spiffy_workspace_bytes(const spiffy_model_cfg *cfg, int32_t G, int32_t B, int32_t P_max);
 
 /* Token embedding of the G states: hidden_out[g,b,:] = w_embed[block_tokens[g,b],:]; masked

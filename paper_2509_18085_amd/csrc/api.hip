@@ -146,11 +146,13 @@ int check_layer_args(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w,
     return SPIFFY_EINVAL;
   if (prefix->P < 0 || (prefix->P > 0 && (!prefix->k || !prefix->v))) return SPIFFY_EINVAL;
   if (prefix->capacity != 0 && prefix->capacity < prefix->P) return SPIFFY_EINVAL;
+  if (prefix->S < 0 || (prefix->S > 0 && (!prefix->k || !prefix->v))) return SPIFFY_EINVAL;
+  if (prefix->S > 0 && (int64_t)prefix->P + B + prefix->S > prefix->capacity) return SPIFFY_ESHAPE;  // suffix rows sit after the block's slot
   const void* ptrs[] = {w->wq, w->wk, w->wv, w->wo, w->w_gate, w->w_up, w->w_down, w->norm1, w->norm2,
                         w->bq, w->bk, w->bv, prefix->k, prefix->v};
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return SPIFFY_EALIGN;
-  if (!layer_mfma(cfg) && generic_attn_smem(cfg, B, prefix->P) > kMaxGenericSmem) return SPIFFY_ESHAPE;
+  if (!layer_mfma(cfg) && generic_attn_smem(cfg, B, prefix->P + prefix->S) > kMaxGenericSmem) return SPIFFY_ESHAPE;
   return SPIFFY_OK;
 }
 
@@ -171,7 +173,7 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   const int M = G * B, d = cfg->d, dt = cfg->dtype;
   const int qd = cfg->n_q_heads * cfg->head_dim, kvd = cfg->n_kv_heads * cfg->head_dim;
   const bool mf = layer_mfma(cfg);
-  const LayerWs ws = carve_layer(cfg, G, B, prefix->P, workspace);
+  const LayerWs ws = carve_layer(cfg, G, B, prefix->P + prefix->S, workspace);
   int rc;
   if (chain) chain->normed_out = false;
   if (!(chain && chain->normed_in) &&
@@ -192,6 +194,7 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   a.qkv = ws.qkv; a.prefix_k = prefix->k; a.prefix_v = prefix->v; a.out = ws.attn; a.partial = ws.attn_partial;
   a.G = G; a.B = B; a.Hq = cfg->n_q_heads; a.Hkv = cfg->n_kv_heads; a.hd = cfg->head_dim; a.P = prefix->P;
   a.ldp = prefix->capacity;
+  a.S = prefix->S;
   a.pos0 = pos0; a.rope_base = cfg->rope_base; a.rope_ready = chain && chain->rope_ready;
   if (chain && chain->append_kv &&
       (rc = dev(launch_kv_append(dt, ws.qkv, a.Hq, a.Hkv, a.hd, B, pos0, cfg->rope_base,
@@ -339,7 +342,7 @@ int spiffy_verify_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights*
   if ((rc = check_layer_args(cfg, w, prefix, G, B))) return rc;
   if (!aligned16(hidden_in) || !aligned16(hidden_out) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
     return SPIFFY_EALIGN;
-  if (workspace_bytes < carve_layer(cfg, G, B, prefix->P, nullptr).bytes) return SPIFFY_EWORKSPACE;
+  if (workspace_bytes < carve_layer(cfg, G, B, prefix->P + prefix->S, nullptr).bytes) return SPIFFY_EWORKSPACE;
   return run_layer(cfg, w, prefix, hidden_in, G, B, pos0, hidden_out, workspace, (hipStream_t)stream);
 }
 
@@ -468,7 +471,7 @@ int spiffy_verify_step(const spiffy_model_cfg* cfg, int32_t n_layers, const spif
   int P_max = 0;
   for (int l = 0; l < n_layers; ++l) {
     if ((rc = check_layer_args(cfg, &layers[l], &prefix[l], G, B))) return rc;
-    if (prefix[l].P > P_max) P_max = prefix[l].P;
+    if (prefix[l].P + prefix[l].S > P_max) P_max = prefix[l].P + prefix[l].S;
   }
   if ((rc = check_head_args(cfg, workspace, final_norm, w_vocab, block_tokens, threshold, logit_scale, argmax, conf,
                             unmask)))
@@ -510,7 +513,7 @@ int spiffy_commit_block(const spiffy_model_cfg* cfg, int32_t n_layers, const spi
     if (!prefix[l].k || !prefix[l].v) return SPIFFY_EINVAL;
     const int cap = prefix[l].capacity ? prefix[l].capacity : prefix[l].P;
     if ((int64_t)prefix[l].P + B > cap) return SPIFFY_ESHAPE;      // no room for the block's rows
-    if (prefix[l].P > P_max) P_max = prefix[l].P;
+    if (prefix[l].P + prefix[l].S > P_max) P_max = prefix[l].P + prefix[l].S;
   }
   const StepWs ws = carve_step(cfg, 1, B, P_max, workspace);
   if (workspace_bytes < ws.bytes) return SPIFFY_EWORKSPACE;

@@ -194,27 +194,29 @@ hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs& a, hipStream_
 
 // ---------------------------------------------------------------------------------------------
 // generic attention: one workgroup per (state g, position b, query head h)
-// keys = [P cached keys ; the B keys of state g], bidirectional inside the block (Fig. 4)
+// keys = [P cached keys ; the B keys of state g ; S cached keys of the tokens after the block (dual cache)],
+// bidirectional inside the block (Fig. 4); cache row j holds sequence position j, so rows P .. P+B-1 of the
+// cache (the slot of the block itself) are never read
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__ qkv, const T* __restrict__ pk,
                                                            const T* __restrict__ pv, T* __restrict__ out, int G,
-                                                           int B, int Hq, int Hkv, int hd, int P, int ldp, int pos0,
-                                                           float rope_base) {
+                                                           int B, int Hq, int Hkv, int hd, int P, int S, int ldp,
+                                                           int pos0, float rope_base) {
   extern __shared__ float smem[];
   __shared__ float red[4];
   const int half = hd >> 1;
   float* qs = smem;              // [hd] rotated query
   float* cs = qs + hd;           // [B][half] cos
   float* sn = cs + B * half;     // [B][half] sin
-  float* sc = sn + B * half;     // [P+B] scores
-  float* acc = sc + (P + B);     // [nchunk][hd]
+  float* sc = sn + B * half;     // [P+B+S] scores
+  float* acc = sc + (P + B + S); // [nchunk][hd]
   const int h = blockIdx.x % Hq;
   const int m = blockIdx.x / Hq;       // flattened (g,b)
   const int g = m / B, b = m % B;
   const int kvh = h / (Hq / Hkv);
   const int ld = (Hq + 2 * Hkv) * hd;
-  const int T_all = P + B;
+  const int T_all = P + B + S;
   for (int i = threadIdx.x; i < B * half; i += 256) {
     const int bb = i / half, f = i % half;
     const double inv_freq = pow((double)rope_base, -2.0 * (double)f / (double)hd);
@@ -235,7 +237,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
   float mx = -INFINITY;
   for (int j = threadIdx.x; j < T_all; j += 256) {
     float dot = 0.f;
-    if (j < P) {
+    if (j < P || j >= P + B) {
       const T* kr = pk + ((size_t)kvh * ldp + j) * hd;
       for (int i = 0; i < hd; ++i) dot = fmaf(qs[i], to_f32(kr[i]), dot);
     } else {
@@ -267,7 +269,7 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
     const int j0 = c * per, j1 = min(T_all, j0 + per);
     float o = 0.f;
     for (int j = j0; j < j1; ++j) {
-      const float v = (j < P) ? to_f32(pv[((size_t)kvh * ldp + j) * hd + t])
+      const float v = (j < P || j >= P + B) ? to_f32(pv[((size_t)kvh * ldp + j) * hd + t])
                               : to_f32(qkv[(size_t)(g * B + (j - P)) * ld + (Hq + Hkv + kvh) * hd + t]);
       o = fmaf(sc[j], v, o);
     }
@@ -281,13 +283,13 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
   }
 }
 
-size_t attn_generic_smem(int B, int hd, int P) {
+size_t attn_generic_smem(int B, int hd, int P) {   // P = cached keys, prefix and suffix together
   const int nchunk = 256 / hd > 0 ? 256 / hd : 1;
   return sizeof(float) * ((size_t)hd + (size_t)B * hd + (size_t)(P + B) + (size_t)nchunk * hd);
 }
 
 hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t st) {
-  const size_t smem = attn_generic_smem(a.B, a.hd, a.P);
+  const size_t smem = attn_generic_smem(a.B, a.hd, a.P + a.S);
   const int grid = a.G * a.B * a.Hq;
   if (dtype == SPIFFY_F32) {
     hipError_t e = hipFuncSetAttribute((const void*)attn_generic_kernel<float>,
@@ -295,14 +297,14 @@ hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attn_generic_kernel<float><<<grid, 256, smem, st>>>((const float*)a.qkv, (const float*)a.prefix_k,
                                                         (const float*)a.prefix_v, (float*)a.out, a.G, a.B, a.Hq,
-                                                        a.Hkv, a.hd, a.P, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base);
+                                                        a.Hkv, a.hd, a.P, a.S, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base);
   } else {
     hipError_t e = hipFuncSetAttribute((const void*)attn_generic_kernel<bf16_t>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attn_generic_kernel<bf16_t><<<grid, 256, smem, st>>>((const bf16_t*)a.qkv, (const bf16_t*)a.prefix_k,
                                                          (const bf16_t*)a.prefix_v, (bf16_t*)a.out, a.G, a.B, a.Hq,
-                                                         a.Hkv, a.hd, a.P, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base);
+                                                         a.Hkv, a.hd, a.P, a.S, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base);
   }
   return hipGetLastError();
 }

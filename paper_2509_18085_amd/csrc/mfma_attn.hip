@@ -259,7 +259,8 @@ struct AttnKArgs {
   bf16_t* out;
   float* opart;         // [nS][M][Hq][128]
   float* mlpart;        // [nS][M][Hq][2]
-  int M, B, Hq, Hkv, P, ldp, ld, nQ, nS;   // ldp = rows allocated per KV head of the prefix
+  int M, B, Hq, Hkv, P, S, ldp, ld, nQ, nS;   // ldp = rows allocated per KV head of the cache; S = suffix rows
+  int split;                                   // cached rows per split: the P + S rows shared out evenly, whole tiles
 };
 
 // the lane's 8 MFMA operand fragments of LDS tile row `row` (K layout): hd = 16*kk + 8*hh + e
@@ -288,6 +289,8 @@ __device__ __forceinline__ void rotate_frags(bf16x8 (&f)[8], const float2* __res
   }
 }
 
+// DUAL: the cache also holds rows of the tokens after the block (a.S > 0)
+template <bool DUAL>
 __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
@@ -314,9 +317,13 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) w.o[n][v] = 0.f;
 
-  const int kbeg = sp * SPLIT_KEYS;
-  const int kend = min(a.P, kbeg + SPLIT_KEYS);
-  const int n_tiles = kend > kbeg ? (kend - kbeg + KTILE - 1) / KTILE : 0;
+  // The cached keys form one axis of P + S rows: the prefix (cache rows 0 .. P-1), then the tokens after the
+  // block (dual cache: cache rows P+B .. P+B+S-1).  Split `sp` owns a.split consecutive rows of that axis
+  // and streams its prefix part, then its suffix part; [kbeg, kend) are cache rows of the part in progress.
+  const int v0 = sp * a.split, v1 = min(a.P + a.S, v0 + a.split);
+  int kbeg = min(v0, a.P);
+  int kend = min(v1, a.P);
+  int n_tiles = kend > kbeg ? (kend - kbeg + KTILE - 1) / KTILE : 0;
   const bf16_t* pk = a.pk + (size_t)kvh * a.ldp * HD;
   const bf16_t* pv = a.pv + (size_t)kvh * a.ldp * HD;
   const int wave_u = __builtin_amdgcn_readfirstlane(wave);
@@ -410,7 +417,16 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
   }
   __syncthreads();   // Q and own-block stages are free again
 
-  // ---- prefix keys of this split: LDS-DMA ring, up to NSTAGE-1 tiles ahead -------------------------
+  // ---- cached keys of this split: LDS-DMA ring, up to NSTAGE-1 tiles ahead --------------------------
+#pragma nounroll
+  for (int part = 0; part < (DUAL ? 2 : 1); ++part) {
+  if (part == 1) {
+    kbeg = max(v0, a.P) + a.B;
+    kend = max(v1, a.P) + a.B;
+    n_tiles = kend > kbeg ? (kend - kbeg + KTILE - 1) / KTILE : 0;
+    if (n_tiles > 0) issue_tile(0);      // the ring is drained: every stage is free
+  }
+  if (n_tiles == 0) continue;
   if (1 < n_tiles) issue_tile(1);
   if (2 < n_tiles) issue_tile(2);
   // full tiles run through the software pipeline (scores of tile t+1 under the softmax of tile t); a ragged
@@ -457,6 +473,7 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
     process_tile<true>(w, ks, ks + TILE_ELEMS, st, lane, [nvalid](int key) { return key < nvalid; });
   }
   __syncthreads();   // all tiles consumed, no DMA in flight: the ring can be reused
+  }
 
   // ---- merge the two key halves of each wavefront pair through LDS ------------------------------
   {
@@ -553,7 +570,7 @@ bool mfma_attn_supported(const AttnArgs& a) {
   return a.hd == HD && a.Hq % a.Hkv == 0 && a.B >= 1 && a.G >= 1;
 }
 
-// rope table + split partials
+// rope table + split partials; P = cached keys, prefix and suffix together
 size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P) {
   const size_t M = (size_t)G * B;
   size_t bytes = align_up(sizeof(float2) * (size_t)B * (hd / 2), 256);
@@ -568,13 +585,16 @@ size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P) {
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_prefix_mfma_kernel,
+    hipError_t e = hipFuncSetAttribute((const void*)attn_prefix_mfma_kernel<false>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnSmem);
+    if (e != hipSuccess) return e;
+    e = hipFuncSetAttribute((const void*)attn_prefix_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)kAttnSmem);
     if (e != hipSuccess) return e;
     attr_done = true;
   }
   const int M = a.G * a.B;
-  const int nS = n_splits(a.P);
+  const int nS = n_splits(a.P + a.S);
   unsigned char* ws = reinterpret_cast<unsigned char*>(a.partial);
   float2* rope = reinterpret_cast<float2*>(ws);
   ws += align_up(sizeof(float2) * (size_t)a.B * (HD / 2), 256);
@@ -593,11 +613,13 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   k.out = (bf16_t*)a.out;
   k.opart = opart;
   k.mlpart = mlpart;
-  k.M = M; k.B = a.B; k.Hq = a.Hq; k.Hkv = a.Hkv; k.P = a.P; k.ldp = a.ldp ? a.ldp : a.P;
+  k.M = M; k.B = a.B; k.Hq = a.Hq; k.Hkv = a.Hkv; k.P = a.P; k.S = a.S; k.ldp = a.ldp ? a.ldp : a.P;
   k.ld = (a.Hq + 2 * a.Hkv) * HD;
   k.nQ = cdiv(M, QTILE);
   k.nS = nS;
-  attn_prefix_mfma_kernel<<<k.nQ * nS * a.Hq, NT, kAttnSmem, st>>>(k);
+  k.split = (int)align_up(cdiv(a.P + a.S, nS), KTILE);      // at most SPLIT_KEYS; a function of P + S only
+  if (a.S > 0) attn_prefix_mfma_kernel<true><<<k.nQ * nS * a.Hq, NT, kAttnSmem, st>>>(k);
+  else attn_prefix_mfma_kernel<false><<<k.nQ * nS * a.Hq, NT, kAttnSmem, st>>>(k);
   if (nS > 1) attn_combine_kernel<<<M * a.Hq, 128, 0, st>>>(opart, mlpart, (bf16_t*)a.out, M, a.Hq, nS);
   return hipGetLastError();
 }

@@ -43,19 +43,20 @@ class BlockDecoder:
 
     layers: per layer dict of device weight tensors; cache_k / cache_v: per layer device tensors
     [Hkv, capacity, hd] whose first P0 rows hold the context; graph: DraftGraph or None (vanilla decoding,
-    one state per forward pass); d_star: draft nodes kept per step.
+    one state per forward pass); d_star: draft nodes kept per step.  S0 > 0: dual cache, rows P0+B .. P0+B+S0-1
+    hold fixed keys / values of the tokens after the first block; every committed block takes B rows off it.
     """
 
     def __init__(self, cfg: sp.ModelCfg, layers: Sequence[Dict[str, torch.Tensor]], cache_k: Sequence[torch.Tensor],
                  cache_v: Sequence[torch.Tensor], P0: int, w_embed: torch.Tensor, final_norm: torch.Tensor,
                  w_vocab: torch.Tensor, B: int, threshold: float, logit_scale: float = 1.0, force_one: bool = True,
-                 graph: Optional[DraftGraph] = None, d_star: int = 0, device="cuda"):
+                 graph: Optional[DraftGraph] = None, d_star: int = 0, device="cuda", S0: int = 0):
         self.cfg, self.B, self.graph, self.device = cfg, B, graph, device
         self.d_star = d_star if graph is not None else 0
         self.logit_scale = logit_scale
-        self.P = P0
+        self.P, self.S = P0, S0
         self.capacity = int(cache_k[0].shape[1])
-        prefix = [sp.prefix_kv(k, v, P0) for k, v in zip(cache_k, cache_v)]
+        prefix = [sp.prefix_kv(k, v, P0, S0) for k, v in zip(cache_k, cache_v)]
         self.plan = sp.StepPlan(cfg, [sp.layer_weights(w) for w in layers], prefix, w_embed, final_norm, w_vocab,
                                 1 + self.d_star, B, P0, threshold, logit_scale=logit_scale, force_one=force_one,
                                 device=device)
@@ -100,7 +101,8 @@ class BlockDecoder:
             raise sp.SpiffyError(sp.SPIFFY_ESHAPE, "BlockDecoder.commit: cache is full")
         self.plan.commit_block(block.to(torch.int32).contiguous())
         self.P += self.B
-        self.plan.set_prefix_len(self.P)
+        self.S = max(0, self.S - self.B)
+        self.plan.set_prefix_len(self.P, S=self.S)
 
     def generate(self, n_blocks: int) -> Dict:
         """Decode n_blocks all-MASK blocks in sequence.  Returns tokens [n_blocks*B] (host), forward passes

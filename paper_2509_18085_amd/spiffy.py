@@ -39,7 +39,7 @@ class LayerWeights(C.Structure):
 
 
 class PrefixKV(C.Structure):
-    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("P", C.c_int32), ("capacity", C.c_int32)]
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("P", C.c_int32), ("capacity", C.c_int32), ("S", C.c_int32)]
 
 
 class AcceptResult(C.Structure):
@@ -138,12 +138,13 @@ def layer_weights(w: Dict[str, torch.Tensor]) -> LayerWeights:
     return lw
 
 
-def prefix_kv(k: Optional[torch.Tensor], v: Optional[torch.Tensor], P: Optional[int] = None) -> PrefixKV:
-    """k, v [Hkv, rows, hd].  P = rows in use (default: all of them); rows beyond P are room for
-    commit_block to extend the cache."""
+def prefix_kv(k: Optional[torch.Tensor], v: Optional[torch.Tensor], P: Optional[int] = None, S: int = 0) -> PrefixKV:
+    """k, v [Hkv, rows, hd], row j = sequence position j.  P = prefix rows in use (default: all of them); rows
+    beyond P are room for commit_block to extend the cache; S = rows of the tokens after the block (dual
+    cache), which sit at rows P+B .. P+B+S-1."""
     rows = 0 if k is None else int(k.shape[1])
     P = rows if P is None else int(P)
-    p = PrefixKV(_ptr(k) if rows else None, _ptr(v) if rows else None, P, rows if rows != P else 0)
+    p = PrefixKV(_ptr(k) if rows else None, _ptr(v) if rows else None, P, rows if rows != P else 0, int(S))
     p._keep = (k, v)
     return p
 
@@ -299,7 +300,7 @@ class StepPlan:
         self._prefix = (PrefixKV * max(1, self.n_layers))(*prefix)
         self._keep = (list(layers), list(prefix), w_embed, final_norm, w_vocab)
         self.w_embed, self.final_norm, self.w_vocab = w_embed, final_norm, w_vocab
-        P_max = max([p.P for p in prefix], default=0)
+        P_max = max([p.P + p.S for p in prefix], default=0)
         self.workspace = alloc_workspace(cfg, G, B, P_max, device)
         dt = _tdtype(cfg)
         self.out = dict(hidden=torch.empty((G, B, cfg.d), dtype=dt, device=device),
@@ -311,10 +312,13 @@ class StepPlan:
                         result=torch.empty(4, dtype=torch.int32, device=device),
                         accepted_state=torch.empty(B, dtype=torch.int32, device=device))
 
-    def set_prefix_len(self, P: int, pos0: Optional[int] = None) -> None:
-        """After commit_block: the caches hold P rows per head; the block now sits at pos0 (default P)."""
+    def set_prefix_len(self, P: int, pos0: Optional[int] = None, S: Optional[int] = None) -> None:
+        """After commit_block: the caches hold P prefix rows per head (and S suffix rows, if given); the block
+        now sits at pos0 (default P)."""
         for l in range(self.n_layers):
             self._prefix[l].P = P
+            if S is not None:
+                self._prefix[l].S = S
         self.pos0 = P if pos0 is None else pos0
 
     def commit_block(self, block_tokens: torch.Tensor, stream=None) -> None:

@@ -846,3 +846,130 @@ def test_decode_is_lossless_on_the_mfma_path(sp):
     assert not (got["tokens"] == cfg.mask_id).any()
     assert sum(got["nfe"]) < sum(van["nfe"])
     assert sum(sum(d) for d in got["depths"]) >= sum(van["nfe"]) - sum(got["nfe"])
+
+
+# ------------------------------------------------------------------ dual cache: fixed K/V of the tokens after the block
+
+def _full_cache(cfg, S, seed, layer=0, extra=0):
+    """[Hkv, P+B+S+extra, hd] caches: prefix rows, the block's slot (filled with a large value that must never
+    be read), suffix rows."""
+    pk, pv = synth.prefix_kv(cfg, layer, seed)
+    sk, sv = synth.suffix_kv(cfg, layer, S, seed)
+    cap = cfg.P + cfg.B + S + extra
+    ck = torch.full((cfg.Hkv, cap, cfg.hd), 1e4, dtype=pk.dtype)
+    cv = torch.full((cfg.Hkv, cap, cfg.hd), 1e4, dtype=pk.dtype)
+    ck[:, :cfg.P], cv[:, :cfg.P] = pk, pv
+    ck[:, cfg.P + cfg.B:cfg.P + cfg.B + S], cv[:, cfg.P + cfg.B:cfg.P + cfg.B + S] = sk, sv
+    return ck, cv, pk, pv, sk, sv
+
+
+def check_layer_dual(sp, cfg, S, seed=5, bias=False):
+    w = synth.layer_weights(cfg, 0, seed, bias=bias)
+    ck, cv, pk, pv, sk, sv = _full_cache(cfg, S, seed, extra=3)
+    x = synth.hidden_states(cfg, seed)
+    scfg = sp.cfg_from_synth(cfg)
+    ws = sp.alloc_workspace(scfg, cfg.G, cfg.B, cfg.P + S, DEV)
+    pf = sp.prefix_kv(ck.to(DEV), cv.to(DEV), cfg.P, S)
+    got = sp.verify_layer(scfg, sp.layer_weights(dev_weights(w)), pf, x.to(DEV), cfg.P, ws)
+    torch.cuda.synchronize()
+    ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), to_np(x), suffix_k=to_np(sk), suffix_v=to_np(sv),
+                           **oracle_kw(cfg))
+    e_max, e_norm = rel_err(to_np(got.cpu()), ref)
+    print("dual-cache layer %s P=%d S=%d: max-rel %.3e  normwise %.3e" % (cfg.name, cfg.P, S, e_max, e_norm))
+    assert e_max < tol(cfg), (cfg, S, e_max, e_norm)
+    return got
+
+
+def test_layer_dual_cache_generic(sp):
+    check_layer_dual(sp, synth.CONFIGS["c1"], 24, bias=True)
+    check_layer_dual(sp, synth.CONFIGS["c1"].scaled(P=0), 5)
+    check_layer_dual(sp, synth.CONFIGS["c1"].scaled(dtype="bf16", P=37, B=5, G=3), 11)
+
+
+@pytest.mark.parametrize("P,S", [(100, 70), (0, 64), (64, 1), (1024, 224), (2000, 300), (2048, 2049), (4200, 224)])
+def test_layer_dual_cache_mfma(sp, P, S):
+    """Suffix parts of one and of several key splits, ragged tails in both parts, a split whose rows come from
+    both parts (2000 + 300), an empty prefix."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=256, Hq=2, Hkv=1, hd=128, F=256, P=P, B=32, G=5)
+    assert sp.uses_mfma(sp.cfg_from_synth(cfg), cfg.B) == 1
+    check_layer_dual(sp, cfg, S)
+
+
+def test_dual_cache_rows_are_context_wherever_they_sit(sp):
+    """MFMA path: a suffix of S rows gives the output of a prefix cache that holds the same rows (keys are
+    already rotated), to rounding of the different summation order; S = 0 is bit-identical to no suffix."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=256, Hq=2, Hkv=2, hd=128, F=256, P=192, B=32, G=4)
+    S = 128
+    a = check_layer_dual(sp, cfg, S)
+    w = synth.layer_weights(cfg, 0, 5)
+    _, _, pk, pv, sk, sv = _full_cache(cfg, S, 5)
+    x = synth.hidden_states(cfg, 5)
+    b = run_layer(sp, cfg.scaled(P=cfg.P + S), w, torch.cat([pk, sk], 1), torch.cat([pv, sv], 1), x, pos0=cfg.P)
+    e_max, _ = rel_err(to_np(a.cpu()), to_np(b))
+    assert e_max < 2e-2
+    c = run_layer(sp, cfg, w, pk, pv, x)
+    scfg = sp.cfg_from_synth(cfg)
+    ws = sp.alloc_workspace(scfg, cfg.G, cfg.B, cfg.P, DEV)
+    pad = torch.zeros((cfg.Hkv, cfg.P + 40, cfg.hd), dtype=pk.dtype)
+    pad[:, :cfg.P] = pk
+    padv = pad.clone()
+    padv[:, :cfg.P] = pv
+    d = sp.verify_layer(scfg, sp.layer_weights(dev_weights(w)), sp.prefix_kv(pad.to(DEV), padv.to(DEV), cfg.P, 0),
+                        x.to(DEV), cfg.P, ws)
+    assert torch.equal(d.cpu(), c)
+
+
+@pytest.mark.parametrize("key", ["c1", "bf16_mfma"])
+def test_step_and_commit_with_dual_cache(sp, key):
+    """Whole step with suffix rows against the oracle; then the block is committed into its slot between prefix
+    and suffix, and the appended rows match the oracle's keys / values of a block that attended to both."""
+    cfg = synth.CONFIGS["c1"] if key == "c1" else synth.CONFIGS["c1"].scaled(
+        dtype="bf16", L=2, d=256, Hq=4, Hkv=2, hd=128, F=320, V=640, P=70, B=32, G=4)
+    S, seed, scale = 2 * cfg.B, 9, 8.0
+    scfg = sp.cfg_from_synth(cfg)
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
+    caches = [_full_cache(cfg, S, seed, layer=l) for l in range(cfg.L)]
+    hw, we = synth.head_weights(cfg, seed), synth.embed_weights(cfg, seed)
+    states, edges = synth.draft_graph("c1", cfg.scaled(G=4), seed)
+    dk = [c[0].to(DEV) for c in caches]
+    dv = [c[1].to(DEV) for c in caches]
+    plan = sp.StepPlan(scfg, [sp.layer_weights(dev_weights(w)) for w in layers],
+                       [sp.prefix_kv(k, v, cfg.P, S) for k, v in zip(dk, dv)], we.to(DEV), hw["final_norm"].to(DEV),
+                       hw["w_vocab"].to(DEV), len(states), cfg.B, cfg.P, 0.5, logit_scale=scale, device=DEV)
+    out = plan.run(torch.from_numpy(states).to(DEV), torch.from_numpy(np.ascontiguousarray(edges)).to(DEV))
+    torch.cuda.synchronize()
+    m = dict(layers=[np_weights(w) for w in layers], prefix=[(to_np(c[2]), to_np(c[3])) for c in caches],
+             suffix=[(to_np(c[4]), to_np(c[5])) for c in caches])
+    ref = O().verify_step(m["layers"], m["prefix"], to_np(we), to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states, edges,
+                          n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P, mask_id=cfg.mask_id,
+                          threshold=0.5, rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, logit_scale=scale,
+                          suffix=m["suffix"])
+    e_max, _ = rel_err(to_np(out["hidden"].cpu()), ref["hidden"])
+    assert e_max < (1e-4 if cfg.dtype == "f32" else 4e-2), e_max         # bf16: two chained layers
+    masked = states == cfg.mask_id
+    if cfg.dtype == "f32":
+        safe = masked & (ref["margin"] > 1e-3 * max(1.0, scale))
+        np.testing.assert_array_equal(out["argmax"].cpu().numpy()[safe], ref["argmax"][safe])
+    else:       # decisions from the step's own hidden states, operands of the same precision on both sides
+        amax, _, _, margin, _ = O().decode_head(to_np(out["hidden"].cpu()), to_np(hw["final_norm"]), to_np(hw["w_vocab"]),
+                                                states, cfg.mask_id, 0.5, rms_eps=cfg.rms_eps, logit_scale=scale,
+                                                operand_dtype="bf16")
+        safe = masked & (margin > 1e-3 * max(1.0, scale))
+        np.testing.assert_array_equal(out["argmax"].cpu().numpy()[safe], amax[safe])
+    tgt = out["target_states"].cpu().numpy()
+    walk = O().graph_accept(edges, states, tgt, 0)
+    assert tuple(out["result"].cpu().tolist()[:3]) == walk[:3]
+    # commit a finished block into its slot
+    block = np.random.default_rng(2).integers(0, cfg.V - 1, size=cfg.B).astype(np.int32)
+    plan.commit_block(torch.from_numpy(block).to(DEV))
+    torch.cuda.synchronize()
+    h = O().embed(to_np(we), block[None, :])
+    for l in range(cfg.L):
+        h, ks, vs = O().verify_layer(m["layers"][l], m["prefix"][l][0], m["prefix"][l][1], h, suffix_k=m["suffix"][l][0],
+                                     suffix_v=m["suffix"][l][1], return_kv=True, **oracle_kw(cfg))
+        gk, gv = to_np(dk[l].cpu()), to_np(dv[l].cpu())
+        for got, want in ((gk, ks[0]), (gv, vs[0])):
+            e_max, _ = rel_err(got[:, cfg.P:cfg.P + cfg.B], want)
+            assert e_max < tol(cfg), (l, e_max)
+        np.testing.assert_array_equal(gk[:, cfg.P + cfg.B:], to_np(caches[l][0])[:, cfg.P + cfg.B:])   # suffix untouched
+        np.testing.assert_array_equal(gk[:, :cfg.P], to_np(caches[l][0])[:, :cfg.P])

@@ -973,3 +973,62 @@ def test_step_and_commit_with_dual_cache(sp, key):
             assert e_max < tol(cfg), (l, e_max)
         np.testing.assert_array_equal(gk[:, cfg.P + cfg.B:], to_np(caches[l][0])[:, cfg.P + cfg.B:])   # suffix untouched
         np.testing.assert_array_equal(gk[:, :cfg.P], to_np(caches[l][0])[:, :cfg.P])
+
+
+def test_decode_with_dual_cache_matches_the_oracle_loop(sp):
+    """Configuration 1 (fp32), two blocks with 2B suffix rows after the first: device loop = oracle loop
+    (tokens, forward passes, depths); each committed block takes B rows off the suffix."""
+    from paper_2509_18085_amd import decode
+    cfg = synth.CONFIGS["c1"]
+    scale, tau, d_star, seed, S0 = 12.0, 0.5, 3, synth.DEFAULT_SEED, 2 * cfg.B
+    formulas = [[(i, 1) for i in range(1, n + 1)] for n in range(1, 5)] + [[(1, 2)], [(1, 1), (2, 2)]]
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
+    caches = [_full_cache(cfg, S0, seed, layer=l) for l in range(cfg.L)]
+    hw, we = synth.head_weights(cfg, seed), synth.embed_weights(cfg, seed)
+
+    def run(graph, d):
+        ck = [c[0].clone().to(DEV) for c in caches]
+        cv = [c[1].clone().to(DEV) for c in caches]
+        dec = decode.BlockDecoder(sp.cfg_from_synth(cfg), [dev_weights(w) for w in layers], ck, cv, cfg.P, we.to(DEV),
+                                  hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), cfg.B, tau, logit_scale=scale,
+                                  graph=graph, d_star=d, device=DEV, S0=S0)
+        return dec.generate(2)
+
+    graph = decode.DraftGraph(formulas, device=DEV)
+    got, van = run(graph, d_star), run(None, 0)
+    np.testing.assert_array_equal(got["tokens"], van["tokens"])
+    assert sum(got["nfe"]) < sum(van["nfe"])
+
+    lw = [np_weights(w) for w in layers]
+    full_k = [to_np(c[0]) for c in caches]
+    full_v = [to_np(c[1]) for c in caches]
+    w_np = dict(w_embed=to_np(we), final_norm=to_np(hw["final_norm"]), w_vocab=to_np(hw["w_vocab"]))
+
+    def drafter(state, info):
+        if not info:
+            return np.zeros((0, state.size), np.int32), np.zeros((0, 2), np.int32)
+        t, p = O().head_topk(info["hidden"][info["node"]], w_np["final_norm"], w_np["w_vocab"], graph.K,
+                             rms_eps=cfg.rms_eps, logit_scale=scale)
+        out = O().draft_and_prune(state, cfg.mask_id, t, p, formulas, graph.edges_np, d_star)
+        return out["states"][1:], out["edges"]
+
+    tokens, nfes, depths = [], [], []
+    P, S = cfg.P, S0
+    for _ in range(2):
+        prefix = [(k[:, :P], v[:, :P]) for k, v in zip(full_k, full_v)]
+        suffix = [(k[:, P + cfg.B:P + cfg.B + S], v[:, P + cfg.B:P + cfg.B + S]) for k, v in zip(full_k, full_v)]
+        kw = dict(n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=P, mask_id=cfg.mask_id, threshold=tau,
+                  rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, logit_scale=scale, force_one=True, suffix=suffix)
+        model = dict(layers=lw, prefix=prefix, kw=kw, **w_np)
+        final, _, nfe, dps, _ = O().decode_block(model, np.full(cfg.B, cfg.mask_id, np.int32), drafter=drafter)
+        tokens.append(final)
+        nfes.append(nfe)
+        depths.append(dps)
+        h = O().embed(w_np["w_embed"], final[None, :])
+        for l in range(cfg.L):
+            h, ks, vs = O().verify_layer(lw[l], prefix[l][0], prefix[l][1], h, suffix_k=suffix[l][0], suffix_v=suffix[l][1],
+                                         return_kv=True, **oracle_kw(cfg, P))
+            full_k[l][:, P:P + cfg.B], full_v[l][:, P:P + cfg.B] = ks[0], vs[0]
+        P, S = P + cfg.B, S - cfg.B
+    np.testing.assert_array_equal(got["tokens"], np.concatenate(tokens))
+    assert got["nfe"] == nfes and got["depths"] == depths

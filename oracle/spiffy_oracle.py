@@ -30,6 +30,9 @@ What the paper fixes and where:
     position rank, j = vocabulary rank                                    Sec. 4.4.2, 4.4.3
   * pruning score: geometric means of token probabilities, of the children's local scores,
     and of the two                                                        Sec. 4.4.4
+  * calibration, optimal subgraph: among all size-D node sets of the candidate graph in which
+    every node is of level 1 or 2 or has a parent in the set, the one with the largest total
+    count                                                                 Alg. 2 part 3, App. D.1
 
 Readings taken where the paper is silent (architecture details are not in the paper at
 all; the shapes come from the workload configurations):
@@ -50,7 +53,10 @@ fractions, the graph conditions of Eqs. (4)-(6), and the link to Next(X, p): the
 "ranks 1..s, vocabulary rank 1" reproduces the threshold rule's next state and is accepted;
 for the dual cache (tests/test_oracle_suffix_pins.py) the mean-of-values closed form over
 P + B + S rows, torch's attention, the block rows of a full bidirectional one-layer forward,
-the dense-mask formulation with the suffix in the context, and a scalar brute force.
+the dense-mask formulation with the suffix in the context, and a scalar brute force; for the
+subgraph search (tests/test_oracle_subgraph_pins.py) a hand-worked example, the paper's
+breadth-first growth from the root levels as a second formulation, and closed forms for the
+number of connected sets and the optimum on structured graphs.
 No function here is "parity unpinned".
 """
 from __future__ import annotations
@@ -519,3 +525,40 @@ def draft_and_prune(state: np.ndarray, mask_id: int, topk_tokens: np.ndarray, to
     return {"order": order, "drafts": drafts, "buildable": buildable, "local": local, "child": child,
             "score": score, "kept": np.asarray(kept, np.int32), "states": drafts[kept],
             "edges": np.asarray(new_edges, np.int32).reshape(-1, 2)}
+
+
+# ----------------------------------------------------------------------------------------
+# offline calibration, part 3: optimal connected subgraph (Alg. 2; App. D.1)
+# ----------------------------------------------------------------------------------------
+
+def subgraph_is_connected(nodes: Sequence[int], level: Sequence[int], parents: Sequence[set]) -> bool:
+    """App. D.1: a node is connected to the set g if its level is 1 or 2 or one of its parents
+    is in g; g is connected if every one of its nodes is."""
+    g = set(nodes)
+    return all(level[q] in (1, 2) or (parents[q] & g) for q in g)
+
+
+def subgraph_search(count: Sequence[int], level: Sequence[int], edges: np.ndarray, D: int) -> Dict:
+    """G* = argmax over connected node sets Q of size D of sum_{q in Q} count(q) (App. D.1).
+
+    count[q], level[q] (1-based level k of node q_kv) for the N nodes of the candidate graph;
+    edges [E,2] rows (p, q): p is a parent of q (rows with an end outside 0..N-1 are ignored).
+    Every size-D subset is tried.  Equal sums go to the subset whose bit mask
+    sum_q 2^q is smallest.  Returns best_nodes (ascending; empty if no connected set of size D
+    exists), best_mask, best_sum (0 if none), n_connected (the size of G')."""
+    import itertools
+    N = len(count)
+    parents = [set() for _ in range(N)]
+    for p, q in np.asarray(edges, np.int64).reshape(-1, 2):
+        if 0 <= p < N and 0 <= q < N:
+            parents[q].add(int(p))
+    best, best_mask, best_sum, n_conn = (), 0, 0, 0
+    for nodes in itertools.combinations(range(N), D):
+        if not subgraph_is_connected(nodes, level, parents):
+            continue
+        n_conn += 1
+        total = sum(int(count[q]) for q in nodes)
+        mask = sum(1 << q for q in nodes)
+        if n_conn == 1 or total > best_sum or (total == best_sum and mask < best_mask):
+            best, best_mask, best_sum = nodes, mask, total
+    return dict(best_nodes=list(best), best_mask=best_mask, best_sum=best_sum, n_connected=n_conn)

@@ -316,3 +316,45 @@ def draft_graph(cfg_key: str, cfg: Config, seed: int = DEFAULT_SEED):
         st, e, _ = subset_lattice(cfg.B, cfg.V, copies, seed)
         return st, e
     raise KeyError(cfg_key)
+
+
+def candidate_graph(n_levels: int, width: int = 3, seed: int = DEFAULT_SEED, extend_prob: float = 0.75,
+                    top_count: int = 4000, stream: int = 500):
+    """Synthetic candidate graph of the shape Alg. 2 part 2 produces: n_levels levels of `width` nodes, every
+    node a set of (token position rank, vocabulary rank) pairs.  A node of level k > 1 extends a random node of
+    level k-1 by one to three pairs with probability extend_prob (so chains of subsets exist, as frequent
+    unmasking sequences give), else it is a fresh set of k..k+2 pairs; edges are all (p, q) with p a strict
+    subset of q; counts fall off with the level (frequent short sequences, rare long ones) with noise.
+    Returns (count [N] int64, level [N] int32 1-based, edges [E,2] int32 (parent, child), formulas)."""
+    r = _rng(seed, stream)
+    formulas: List[frozenset] = []
+    level: List[int] = []
+
+    def fresh_pair(have):
+        while True:
+            p = (int(r.integers(1, 9)), int(1 + (r.random() < 0.2) + (r.random() < 0.05)))
+            if all(p[0] != q[0] for q in have):
+                return p
+
+    for k in range(1, n_levels + 1):
+        made = []
+        while len(made) < width:
+            prev = [f for f, l in zip(formulas, level) if l == k - 1]
+            if prev and r.random() < extend_prob:
+                f = set(prev[int(r.integers(0, len(prev)))])
+                n_add = int(r.integers(1, 4))
+            else:
+                f, n_add = set(), int(r.integers(k, k + 3))
+            for _ in range(n_add):
+                if len({q[0] for q in f}) >= 8:
+                    break
+                f.add(fresh_pair(f))
+            f = frozenset(f)
+            if f and f not in formulas and f not in made:
+                made.append(f)
+        formulas += made
+        level += [k] * width
+    N = len(formulas)
+    edges = np.array([(p, q) for p in range(N) for q in range(N) if formulas[p] < formulas[q]], np.int32).reshape(-1, 2)
+    count = np.array([max(1, int(top_count / l ** 1.3 * r.uniform(0.3, 1.0))) for l in level], np.int64)
+    return count, np.array(level, np.int32), edges, [sorted(f) for f in formulas]

@@ -163,6 +163,7 @@ def main():
         line["next_step_drafting"] = drafting_leg(sp, cfg, plan, d_states, dev)
         line["decode_loop"] = decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev)
         line["dual_cache_step"] = dual_cache_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, dev, seed)
+        line["calibration_subgraph_search"] = subgraph_leg(sp, dev, seed)
 
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, layers, prefix, hw, states, edges)
@@ -284,6 +285,35 @@ def dual_cache_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, dev,
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
     return {"suffix_rows": S, "ms_per_step": ms, "states_per_s": cfg.G / (ms * 1e-3)}
+
+
+def subgraph_leg(sp, dev, seed, n_levels=15, D=10, iters=3):
+    """Not part of the timed step: the optimal-subgraph search of the offline calibration (Alg. 2 part 3) on a
+    synthetic candidate graph of n_levels x 3 nodes; every C(N, D) node set is tried."""
+    import math
+    import torch
+    from paper_2509_18085_amd import synth
+    count, level, edges, _ = synth.candidate_graph(n_levels, seed=seed)
+    N = len(count)
+    c, l, e = (torch.from_numpy(x).to(dev) for x in (count, level, edges))
+    out = sp.subgraph_search(c, l, e, D)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        out = sp.subgraph_search(c, l, e, D, workspace=out["_workspace"])
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / iters
+    sets = math.comb(N, D)
+    # per tried set: one 64-bit add, two 64-bit ANDs, one OR, one zero test, one 64-bit compare = 10 32-bit
+    # integer lane operations; peak = 256 CUs x 64 lanes x 2.4 GHz
+    ops, peak = 10.0 * sets, 256 * 64 * 2.4e9
+    return {"nodes": N, "edges": int(len(edges)), "D": D, "sets_tried": sets, "ms": ms, "sets_per_s": sets / (ms * 1e-3),
+            "connected_sets": int(out["n_connected"].item()), "best_sum": int(out["best_sum"].item()),
+            "roofline": {"kernel": "sg_search_kernel", "bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12,
+                         "peak": peak / 1e12, "unit": "Top/s (int32 lane operations)",
+                         "frac": ops / (ms * 1e-3) / peak, "traffic": None}}
 
 
 def stored_traffic(config):

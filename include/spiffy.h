@@ -232,6 +232,22 @@ int spiffy_commit_block(const spiffy_model_cfg *cfg, int32_t n_layers, const spi
                         const spiffy_prefix_kv *prefix, const void *w_embed, const int32_t *block_tokens,
                         int32_t B, int32_t pos0, void *workspace, size_t workspace_bytes, void *stream);
 
+/* Offline calibration, part 3 (Alg. 2; App. D.1): the optimal subgraph of the candidate graph.  The graph has
+ * N <= 64 nodes (draft formulas q_kv); count [N] is each node's frequency, level [N] its 1-based level k, edges
+ * [E,2] rows (p, q): p is a parent of q (rows with an end outside 0..N-1 are ignored).  A node is connected to a
+ * set if its level is 1 or 2 or one of its parents is in the set; G' is every set of D nodes all of which are
+ * connected to it; the result is the set of G' with the largest summed count, equal sums going to the smaller
+ * bit mask sum_q 2^q.  Every one of the C(N, D) sets is tried; more than SPIFFY_SUBGRAPH_MAX_SETS is refused
+ * (SPIFFY_ESHAPE).  Outputs: *best_mask, *best_sum, *n_connected = |G'|, nodes_out [D] (optional) the chosen
+ * nodes ascending.  When G' is empty (also D > N): mask 0, sum 0, nodes -1.  |count| must stay below 2^56 so the
+ * sums cannot wrap.  All arrays and outputs are device memory; workspace (256-byte aligned) of
+ * spiffy_subgraph_search_workspace_bytes() bytes.  Enqueues three kernels; no host synchronisation. */
+#define SPIFFY_SUBGRAPH_MAX_SETS (1ull << 40)
+size_t spiffy_subgraph_search_workspace_bytes(void);
+int spiffy_subgraph_search(const int64_t *count, const int32_t *level, int32_t N, const int32_t *edges, int32_t E,
+                           int32_t D, uint64_t *best_mask, int64_t *best_sum, uint64_t *n_connected,
+                           int32_t *nodes_out, void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

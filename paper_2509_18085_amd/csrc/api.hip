@@ -530,5 +530,33 @@ int spiffy_commit_block(const spiffy_model_cfg* cfg, int32_t n_layers, const spi
   return SPIFFY_OK;
 }
 
+size_t spiffy_subgraph_search_workspace_bytes(void) { return subgraph_search_workspace_bytes(); }
+
+int spiffy_subgraph_search(const int64_t* count, const int32_t* level, int32_t N, const int32_t* edges, int32_t E,
+                           int32_t D, uint64_t* best_mask, int64_t* best_sum, uint64_t* n_connected,
+                           int32_t* nodes_out, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!count || !level || !best_mask || !best_sum || !n_connected || !workspace || (E > 0 && !edges))
+    return SPIFFY_EINVAL;
+  if (N < 1 || N > 64 || D < 1 || D > 64 || E < 0) return SPIFFY_ESHAPE;
+  // C(N, D) sets are tried one by one: refuse what would run for minutes
+  unsigned long long total = 1;
+  if (D > N) {
+    total = 0;
+  } else {
+    const int k = D < N - D ? D : N - D;
+    for (int i = 1; i <= k; ++i) {
+      total = total * (unsigned long long)(N - k + i) / (unsigned long long)i;     // exact: a product of i consecutive integers
+      if (total > SPIFFY_SUBGRAPH_MAX_SETS) return SPIFFY_ESHAPE;
+    }
+  }
+  if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPIFFY_EALIGN;
+  if (workspace_bytes < subgraph_search_workspace_bytes()) return SPIFFY_EWORKSPACE;
+  SubgraphArgs a;
+  a.count = count; a.level = level; a.edges = edges; a.N = N; a.E = E; a.D = D; a.total_sets = total;
+  a.best_mask = best_mask; a.best_sum = best_sum; a.n_connected = n_connected; a.nodes_out = nodes_out;
+  a.workspace = workspace;
+  return dev(launch_subgraph_search(a, (hipStream_t)stream));
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

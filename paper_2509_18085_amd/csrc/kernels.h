@@ -108,4 +108,20 @@ bool mfma_attn_supported(const AttnArgs& a);
 size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P);
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st);
 
+// Calibration, part 3 (Alg. 2; App. D.1): best connected node set of size D.  All pointers device memory.
+struct SubgraphArgs {
+  const int64_t* count;          // [N]
+  const int32_t* level;          // [N], 1-based
+  const int32_t* edges;          // [E][2] (parent, child)
+  int N, E, D;
+  unsigned long long total_sets; // C(N, D), for the launch size
+  uint64_t* best_mask;
+  int64_t* best_sum;
+  uint64_t* n_connected;
+  int32_t* nodes_out;            // [D] or NULL
+  void* workspace;
+};
+size_t subgraph_search_workspace_bytes();
+hipError_t launch_subgraph_search(const SubgraphArgs& a, hipStream_t st);
+
 }  // namespace spiffy

@@ -22,7 +22,7 @@ MAX_G = 64
 
 EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "spiffy_embed",
            "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk", "spiffy_commit_block",
-           "spiffy_verify_step"]
+           "spiffy_subgraph_search_workspace_bytes", "spiffy_subgraph_search", "spiffy_verify_step"]
 GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
 
@@ -85,6 +85,10 @@ def _load() -> C.CDLL:
     lib.spiffy_draft_prune.restype = C.c_int
     lib.spiffy_draft_prune.argtypes = [vp, i32, i32, vp, vp, i32, vp, vp, i32, i32, vp, i32, i32, vp, vp, vp, vp,
                                        vp, vp, vp, vp, vp]
+    lib.spiffy_subgraph_search_workspace_bytes.restype = C.c_size_t
+    lib.spiffy_subgraph_search_workspace_bytes.argtypes = []
+    lib.spiffy_subgraph_search.restype = C.c_int
+    lib.spiffy_subgraph_search.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.spiffy_verify_step.restype = C.c_int
     lib.spiffy_verify_step.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp,
                                        i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
@@ -282,6 +286,27 @@ def draft_prune(state: torch.Tensor, mask_id: int, topk_tokens: torch.Tensor, to
                                   _ptr(edges) if E else None, E, d_star, _ptr(out["drafts"]), _ptr(out["buildable"]),
                                   _ptr(out["local"]), _ptr(out["score"]), _ptr(out["kept"]), _ptr(out["states"]),
                                   _ptr(out["edges"]), _ptr(out["counts"]), _stream(stream)), "spiffy_draft_prune")
+    return out
+
+
+def subgraph_search(count: torch.Tensor, level: torch.Tensor, edges: Optional[torch.Tensor], D: int,
+                    workspace: Optional[torch.Tensor] = None, stream=None) -> Dict[str, torch.Tensor]:
+    """Best connected node set of size D of a candidate graph (calibration, part 3).  count [N] int64, level [N]
+    int32, edges [E,2] int32 (parent, child), all on the device.  Returns device tensors best_mask [1] (int64
+    holding the 64-bit mask), best_sum [1], n_connected [1], nodes [D]."""
+    dev = count.device
+    N = int(count.numel())
+    E = int(edges.shape[0]) if edges is not None else 0
+    if workspace is None:
+        workspace = torch.empty(int(lib.spiffy_subgraph_search_workspace_bytes()) + 256, dtype=torch.uint8, device=dev)
+    wp, wn = _ws(workspace)
+    out = dict(best_mask=torch.empty(1, dtype=torch.int64, device=dev), best_sum=torch.empty(1, dtype=torch.int64, device=dev),
+               n_connected=torch.empty(1, dtype=torch.int64, device=dev),
+               nodes=torch.empty(max(1, min(D, 64)), dtype=torch.int32, device=dev))
+    _check(lib.spiffy_subgraph_search(_ptr(count), _ptr(level), N, _ptr(edges) if E else None, E, D, _ptr(out["best_mask"]),
+                                      _ptr(out["best_sum"]), _ptr(out["n_connected"]), _ptr(out["nodes"]), wp, wn,
+                                      _stream(stream)), "spiffy_subgraph_search")
+    out["_workspace"] = workspace
     return out
 
 

@@ -218,6 +218,35 @@ def test_commit_block_argument_errors():
     assert call(ws=0x100010) == sp.SPIFFY_EALIGN
 
 
+def test_subgraph_search_argument_errors():
+    assert sp.lib.spiffy_subgraph_search_workspace_bytes() > 0
+    def call(**k):
+        return sp.lib.spiffy_subgraph_search(
+            k.get("count", DUMMY), k.get("level", DUMMY), k.get("N", 30), k.get("edges", DUMMY), k.get("E", 5),
+            k.get("D", 5), k.get("mask", DUMMY), k.get("sum", DUMMY), k.get("n", DUMMY), None, k.get("ws", 0x100000),
+            k.get("wsb", 16), None)
+    assert call() == sp.SPIFFY_EWORKSPACE                       # every argument check passed
+    assert call(count=None) == sp.SPIFFY_EINVAL
+    assert call(level=None) == sp.SPIFFY_EINVAL
+    assert call(edges=None) == sp.SPIFFY_EINVAL
+    assert call(edges=None, E=0) == sp.SPIFFY_EWORKSPACE
+    assert call(mask=None) == sp.SPIFFY_EINVAL
+    assert call(sum=None) == sp.SPIFFY_EINVAL
+    assert call(n=None) == sp.SPIFFY_EINVAL
+    assert call(ws=None) == sp.SPIFFY_EINVAL
+    assert call(N=0) == sp.SPIFFY_ESHAPE
+    assert call(N=65) == sp.SPIFFY_ESHAPE
+    assert call(D=0) == sp.SPIFFY_ESHAPE
+    assert call(D=65) == sp.SPIFFY_ESHAPE
+    assert call(E=-1) == sp.SPIFFY_ESHAPE
+    assert call(N=64, D=32) == sp.SPIFFY_ESHAPE                 # 1.8e18 sets: refused
+    assert call(N=64, D=12) == sp.SPIFFY_ESHAPE                 # 3.3e12 > 2^40
+    assert call(N=64, D=11) == sp.SPIFFY_EWORKSPACE             # 7.4e11 sets: accepted
+    assert call(N=64, D=64) == sp.SPIFFY_EWORKSPACE
+    assert call(N=3, D=9) == sp.SPIFFY_EWORKSPACE               # more than there are nodes: an empty answer, not an error
+    assert call(ws=0x100010) == sp.SPIFFY_EALIGN
+
+
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     import importlib
     monkeypatch.setattr(sp, "LIB_PATH", str(tmp_path / "nope.so"))

@@ -1032,3 +1032,98 @@ def test_decode_with_dual_cache_matches_the_oracle_loop(sp):
         P, S = P + cfg.B, S - cfg.B
     np.testing.assert_array_equal(got["tokens"], np.concatenate(tokens))
     assert got["nfe"] == nfes and got["depths"] == depths
+
+
+# ------------------------------------------------------------------ calibration: optimal connected subgraph
+
+def _run_subgraph(sp, count, level, edges, D):
+    e = np.asarray(edges, np.int32).reshape(-1, 2)
+    out = sp.subgraph_search(torch.tensor(np.asarray(count), dtype=torch.int64, device=DEV),
+                             torch.tensor(np.asarray(level), dtype=torch.int32, device=DEV),
+                             torch.from_numpy(np.ascontiguousarray(e)).to(DEV) if len(e) else None, D)
+    torch.cuda.synchronize()
+    mask = int(out["best_mask"].cpu().numpy().view(np.uint64)[0])
+    return dict(best_mask=mask, best_sum=int(out["best_sum"].item()), n_connected=int(out["n_connected"].item()),
+                best_nodes=[q for q in out["nodes"].cpu().tolist()[:D] if q >= 0])
+
+
+def test_subgraph_search_golden(sp):
+    import json, os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "subgraph_case.json")))
+    for c in g["cases"]:
+        r = _run_subgraph(sp, g["count"], g["level"], g["edges"], c["D"])
+        assert r["n_connected"] == len(c["sets"]), c
+        assert (r["best_nodes"], r["best_sum"], r["best_mask"]) == (c["best_nodes"], c["best_sum"], c["best_mask"]), c
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_subgraph_search_parity(sp, seed):
+    """Every output bit-exact against the oracle's enumeration: graphs below and above the 12 tabulated low
+    nodes, every D that keeps the oracle within seconds, equal counts (the tie rule decides)."""
+    n_levels = [2, 3, 4, 5, 6, 7, 8, 4][seed]
+    count, level, edges, _ = synth.candidate_graph(n_levels, seed=100 + seed)
+    if seed % 3 == 2:
+        count = (count // 500 + 1).astype(np.int64)          # many equal sums
+    if seed == 7:
+        edges = np.concatenate([edges, [[-1, 2], [3, 99], [5, 5]]]).astype(np.int32)   # ignored rows, a self-loop
+    N = len(count)
+    import math
+    for D in range(1, N + 2):
+        if math.comb(N, min(D, N)) > 800000:
+            continue
+        ref = O().subgraph_search(count, level, edges, D)
+        got = _run_subgraph(sp, count, level, edges, D)
+        assert got == ref, (seed, N, D, got, ref)
+
+
+def test_subgraph_search_closed_forms_at_size(sp):
+    """Sizes the oracle cannot enumerate: results the structure fixes.  (1) all nodes root-level: every set is
+    connected, the optimum is the D largest counts; (2) the D largest counts form a chain from a root, planted
+    in a random candidate graph: that chain is the optimum; (3) a star: C(m, D-1) sets."""
+    import math
+    r = np.random.default_rng(4)
+    N, D = 40, 8                                              # 7.7e7 sets
+    count = r.integers(1, 10 ** 6, N).astype(np.int64)
+    got = _run_subgraph(sp, count, np.ones(N, np.int32) + (np.arange(N) % 2), np.zeros((0, 2), np.int32), D)
+    top = sorted(np.argsort(-count, kind="stable")[:D].tolist())
+    assert got["n_connected"] == math.comb(N, D) and got["best_nodes"] == top and got["best_sum"] == int(count[top].sum())
+
+    count, level, edges, _ = synth.candidate_graph(15, seed=8)       # 45 nodes
+    N, D = len(count), 10                                            # 3.2e9 sets
+    chain = [1] + list(r.permutation(np.arange(6, N))[:D - 1])       # node 1 is of level 1
+    count = count.copy()
+    count[chain] = 10 ** 6 + np.arange(D)
+    edges = np.concatenate([edges, [[a, b] for a, b in zip(chain[:-1], chain[1:])]]).astype(np.int32)
+    got = _run_subgraph(sp, count, level, edges, D)
+    assert got["best_nodes"] == sorted(int(c) for c in chain) and got["best_sum"] == int(count[chain].sum())
+    assert 0 < got["n_connected"] < math.comb(N, D)
+    # relabelling the nodes changes neither the optimum value nor the number of connected sets
+    perm = r.permutation(N)
+    inv = np.argsort(perm)
+    got_p = _run_subgraph(sp, count[perm], level[perm], inv[edges], D)
+    assert got_p["best_sum"] == got["best_sum"] and got_p["n_connected"] == got["n_connected"]
+    assert sorted(int(perm[q]) for q in got_p["best_nodes"]) == got["best_nodes"]
+
+    m, D = 50, 6                                              # star: root 0 and 50 leaves of level 3
+    count = np.concatenate([[1], r.integers(1, 1000, m)]).astype(np.int64)
+    got = _run_subgraph(sp, count, np.array([2] + [3] * m, np.int32), np.array([[0, q] for q in range(1, m + 1)], np.int32), D)
+    leaves = sorted((np.argsort(-count[1:], kind="stable")[:D - 1] + 1).tolist())
+    assert got["n_connected"] == math.comb(m, D - 1) and got["best_sum"] == 1 + int(count[leaves].sum())
+
+
+def test_subgraph_search_edge_cases(sp):
+    one = _run_subgraph(sp, [7], [1], [], 1)
+    assert one == dict(best_mask=1, best_sum=7, n_connected=1, best_nodes=[0])
+    none = _run_subgraph(sp, [7], [3], [], 1)                 # a single node that is not root-level
+    assert none == dict(best_mask=0, best_sum=0, n_connected=0, best_nodes=[])
+    too_many = _run_subgraph(sp, [1, 2, 3], [1, 1, 1], [], 4)
+    assert too_many == dict(best_mask=0, best_sum=0, n_connected=0, best_nodes=[])
+    # 64 nodes, the highest bit in use; negative counts are sums like any other
+    count = -np.arange(1, 65, dtype=np.int64)
+    ref = O().subgraph_search(count, np.ones(64, np.int32), np.zeros((0, 2), int), 2)
+    got = _run_subgraph(sp, count, np.ones(64, np.int32), [], 2)
+    assert got == ref and got["best_nodes"] == [0, 1]
+    level = np.array([3] * 63 + [1], np.int32)                # only node 63 is a root, everyone its child
+    edges = np.array([[63, q] for q in range(63)], np.int32)
+    got = _run_subgraph(sp, np.arange(64, dtype=np.int64), level, edges, 3)
+    assert got["best_nodes"] == [61, 62, 63] and got["n_connected"] == 63 * 62 // 2 and got["best_mask"] == 7 << 61

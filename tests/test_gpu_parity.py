@@ -224,6 +224,44 @@ def test_layer_shapes_of_configs_3_4_5_reduced_rows(sp):
     check_layer(sp, synth.CONFIGS["c5"].scaled(G=40, P=2500))
 
 
+@pytest.mark.parametrize("key", ["c3", "c4", "c5"])
+def test_layer_full_size_in_the_bench_launch_configuration(sp, key):
+    """Configurations 3-5 at their full sizes (all G states, so the tile widths, K splits and key splits are the
+    ones the benchmark times); the oracle computes sampled states, which it can do one by one because a state's
+    rows depend on no other state."""
+    cfg = synth.CONFIGS[key]
+    w = synth.layer_weights(cfg, 0)
+    pk, pv = synth.prefix_kv(cfg, 0)
+    x = synth.hidden_states(cfg)
+    got = run_layer(sp, cfg, w, pk, pv, x)
+    sample = sorted({0, cfg.G // 2 - 1, cfg.G - 1})
+    ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), to_np(x[sample]), **oracle_kw(cfg))
+    e_max, e_norm = rel_err(to_np(got[sample]), ref)
+    print("full-size layer %s, states %s: max-rel %.3e  normwise %.3e" % (cfg.name, sample, e_max, e_norm))
+    assert e_max < tol(cfg), (key, e_max, e_norm)
+    assert torch.isfinite(got.float()).all()
+
+
+def test_step_two_layers_at_config3_size(sp):
+    """The chained whole-step path at configuration 3's full row count, prefix length and widths (two layers to
+    keep the oracle in seconds): hidden states of sampled states, and the walk on the step's own next states."""
+    cfg = synth.CONFIGS["c3"].scaled(L=2, V=2048)
+    plan, layers, prefix, hw, w_embed, states, edges = build_step(sp, cfg, "c3", synth.DEFAULT_SEED, 8.0)
+    out = plan.run(torch.from_numpy(states).to(DEV), torch.from_numpy(edges).to(DEV))
+    torch.cuda.synchronize()
+    sample = [0, 13, cfg.G - 1]
+    h = O().embed(to_np(w_embed), states[sample])
+    for w, (pk, pv) in zip(layers, prefix):
+        h = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), h, **oracle_kw(cfg))
+    e_max, e_norm = rel_err(to_np(out["hidden"][sample].cpu()), h)
+    print("two chained layers at config 3 size: max-rel %.3e  normwise %.3e" % (e_max, e_norm))
+    # the second layer adds its own rounding to the first layer's error carried through it: 3 x the one-layer bound
+    assert e_max < 6e-2 and e_norm < 1.2e-2, (e_max, e_norm)
+    ref = O().graph_accept(edges, states, out["target_states"].cpu().numpy(), 0)
+    assert tuple(out["result"].cpu().tolist()[:3]) == ref[:3]
+    assert out["accepted_state"].cpu().tolist() == ref[3].tolist()
+
+
 # ------------------------------------------------------------------ head parity
 
 def run_head(sp, cfg, hidden, hw, states, threshold, logit_scale, force_one):

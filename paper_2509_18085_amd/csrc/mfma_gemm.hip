@@ -5,6 +5,8 @@
 //   * one workgroup per CU: 256 x BN output tile (BN = 192 or 128), 4 wavefronts in a 2x2 grid, each
 //     wavefront owns 128 x BN/2 (accumulators in AGPRs).  The L2 delivers about 32 B/clk to a CU, so
 //     a tile needs >= 64..128 flop per loaded byte; 128x128 tiles are bound by that, 256x192 is not.
+//     With few rows (one to eight states) the projections only stream weights: the same kernel with
+//     128- or 64-row tiles does half or a quarter of the matrix work per tile and covers more CUs.
 //   * K advances in steps of 64 so every row segment is one full 128-byte line; operands go
 //     global -> LDS directly (LDS-DMA loads, no register staging), rows XOR-swizzled so the
 //     16-byte fragment reads are conflict-free.
@@ -47,12 +49,18 @@ __device__ __forceinline__ void wait_vmcnt() {   // vmcnt <= N; lgkmcnt / expcnt
 }
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
-template <int EPI, int BN, int SD>
+template <int EPI, int BN, int SD, int BMT = 256>
 __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int tiles_i, int tiles_j) {
+  constexpr int BM = BMT;                         // rows of the output tile: 256, or 128 / 64 when there are few rows
   // which operand is the weight matrix (deep ring): Y for the projections, X for the LM head
   constexpr bool XDEEP = (EPI == EPI_LMHEAD);
-  constexpr int SX = XDEEP ? SD : 2, SY = XDEEP ? 2 : SD;
-  constexpr int TM = 4, TN = BN / 64;
+  // UNI (64-row tiles, a weight-streaming problem): both operands ride rings of SD stages and every load runs
+  // SD tiles ahead, so SD-2 whole tiles stay in flight across a barrier.  Otherwise the activation operand has
+  // two stages and is loaded two tiles ahead; its loads sit behind the weight loads in the in-order counter,
+  // so only the newest weight tile can stay in flight.
+  constexpr bool UNI = (BMT == 64) && !XDEEP;
+  constexpr int SX = XDEEP ? SD : (UNI ? SD : 2), SY = XDEEP ? 2 : SD;
+  constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int LX = BM / 32, LY = BN / 32;       // 1-KB wave-loads (8 rows x 128 B) per wavefront per K-tile
   constexpr int NL = LX + LY;
   constexpr int XSTAGE = BM * BKK, YSTAGE = BN * BKK;
@@ -166,8 +174,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   auto load_dp = [&](int q, int t) { if (XDEEP) load_x(q, t); else load_y(q, t); };
   // load `idx` of group g (the loads issued after barrier g): shallow operand of tile g+2 first, then
   // the deep operand of tile g+SD
+  constexpr int SH_AHEAD = UNI ? SD : 2;
   auto group_load = [&](int idx, int g, bool checked = true) {
-    if (idx < LS) { if (!checked || g + 2 < KT) load_sh(idx, g + 2); }
+    if (idx < LS) { if (!checked || g + SH_AHEAD < KT) load_sh(idx, g + SH_AHEAD); }
     else { if (!checked || g + SD < KT) load_dp(idx - LS, g + SD); }
   };
 
@@ -193,12 +202,16 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     if (t < KT) {
 #pragma unroll
       for (int q = 0; q < LD; ++q) load_dp(q, t);
+      if (UNI) {
+#pragma unroll
+        for (int q = 0; q < LS; ++q) load_sh(q, t);
+      }
     }
 #pragma unroll
   for (int idx = 0; idx < NL / 4; ++idx) group_load(idx, -1);
 
   const int sw_r = (l32 >> 1) & 7;
-  const int xrow = (wm * 128 + l32) * BKK;
+  const int xrow = (wm * (BM / 2) + l32) * BKK;
   const int yrow = (wn * (BN / 2) + l32) * BKK;
   bf16x8 fx[2][TM], fy[2][TN];
   auto ldfrag = [&](int buf, const bf16_t* xs, const bf16_t* ys, int kk, int r) {
@@ -206,7 +219,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     if (r < TM) fx[buf][r] = *reinterpret_cast<const bf16x8*>(xs + xrow + r * 32 * BKK + slot);
     else fy[buf][r - TM] = *reinterpret_cast<const bf16x8*>(ys + yrow + (r - TM) * 32 * BKK + slot);
   };
-  if (short_k) wait_vmcnt<0>(); else wait_vmcnt<(SD - 2) * LD + NL / 4>();   // tile 0 is in LDS
+  // loads younger than tile 0's: the whole tiles 1 .. SD-2 (UNI) or their weight halves, and the start of group -1
+  constexpr int W_FIRST = (SD - 2) * (UNI ? NL : LD) + NL / 4;
+  constexpr int W_STEADY = UNI ? (SD - 2) * NL : LD;
+  static_assert(W_FIRST <= 63 && W_STEADY <= 63, "vmcnt is a 6-bit counter");
+  if (short_k) wait_vmcnt<0>(); else wait_vmcnt<W_FIRST>();   // tile 0 is in LDS
   __builtin_amdgcn_s_barrier();
 #pragma unroll
   for (int r = 0; r < NF; ++r) ldfrag(0, Xs, Ys, 0, r);
@@ -214,6 +231,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   // fragment reads of the next K step issued after MFMA m of the current one: [frag_lo(m), frag_lo(m+1)).
   // One per MFMA from the second on when there are enough MFMAs, else spread over all but the last.
   auto frag_lo = [](int m) {
+    if (NMF == 1) return m < 1 ? 0 : NF;
     if (NF <= NMF - 1) return m < 1 ? 0 : (m - 1 < NF ? m - 1 : NF);
     return m < NMF - 1 ? (m * NF) / (NMF - 1) : NF;
   };
@@ -239,7 +257,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     }
     // barrier kt: tile kt+1 is in LDS for every wavefront (only the deep-operand loads of group kt-1
     // may still fly), and no wavefront reads the stages of tile kt after this point
-    if (STEADY || (!short_k && kt + SD - 1 < KT)) wait_vmcnt<LD>(); else wait_vmcnt<0>();
+    if (STEADY || (!short_k && kt + SD - 1 < KT)) wait_vmcnt<W_STEADY>(); else wait_vmcnt<0>();
     wait_lgkm0();
     __builtin_amdgcn_s_barrier();
     const bf16_t* xs1 = Xs + ((kt + 1) % SX) * XSTAGE;
@@ -284,7 +302,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
           for (int v = 0; v < 16; ++v) {
             float l = acc[i][j][v];
             if (CHECKED) {
-              const int idx = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+              const int idx = i0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
               if (idx >= i_max) l = -INFINITY;
               acc[i][j][v] = l;
             }
@@ -304,7 +322,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
         t.m2 = m2 * a.scale;
         t.s = sum;
         t.idx = (m == -INFINITY) ? 0x7fffffff
-                                 : i0 + wm * 128 + (code >> 4) * 32 + 8 * ((code & 15) >> 2) + 4 * hh + (code & 3);
+                                 : i0 + wm * (BM / 2) + (code >> 4) * 32 + 8 * ((code & 15) >> 2) + 4 * hh + (code & 3);
         t = top_merge(t, top_shfl_xor(t, 32));
         const int tokr = j0 + wn * (BN / 2) + j * 32 + l32;
         if (hh == 0 && tokr < j_max) part[(size_t)(ti * 2 + wm) * a.ldc + tokr] = TopPartial{t.m, t.m2, t.s, t.idx};
@@ -320,7 +338,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+        const int r = i0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
         if (r >= i_max) continue;
 #pragma unroll
         for (int j = 0; j < TN; ++j) P[(size_t)r * a.ldc + j0 + wn * (BN / 2) + j * 32 + l32] = acc[i][j][v];
@@ -341,7 +359,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the gate lane's row
+        const int r = i0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the gate lane's row
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           float a0 = acc[i][j][v], a1 = acc[i][j][v + 1];
@@ -385,7 +403,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-        const int r = i0 + wm * 128 + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the even lane's row
+        const int r = i0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the even lane's row
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           float a0 = acc[i][j][v] + bv[j], a1 = acc[i][j][v + 1] + bv[j];
@@ -411,21 +429,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   if (i0 + BM <= i_max) store_all(std::false_type{}); else store_all(std::true_type{});
 }
 
-template <int EPI, int BN, int SD>
+template <int EPI, int BN, int SD, int BMT>
 constexpr size_t smem_bytes() {
-  return sizeof(bf16_t) * (size_t)(EPI == EPI_LMHEAD ? SD * BM + 2 * BN : 2 * BM + SD * BN) * BKK;
+  return sizeof(bf16_t) * (size_t)(EPI == EPI_LMHEAD ? SD * BMT + 2 * BN : (BMT == 64 ? SD : 2) * BMT + SD * BN) * BKK;
 }
 
-template <int EPI, int BN, int SD>
+template <int EPI, int BN, int SD, int BMT = 256>
 hipError_t launch_t(const GemmArgs& a, int tiles_i, int tiles_j, hipStream_t st) {
   static bool attr_done = false;
   if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI, BN, SD>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<EPI, BN, SD>());
+    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI, BN, SD, BMT>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<EPI, BN, SD, BMT>());
     if (e != hipSuccess) return e;
     attr_done = true;
   }
-  gemm_bf16_mfma_kernel<EPI, BN, SD><<<tiles_i * tiles_j * a.ksplit, 256, smem_bytes<EPI, BN, SD>(), st>>>(a, tiles_i, tiles_j);
+  gemm_bf16_mfma_kernel<EPI, BN, SD, BMT><<<tiles_i * tiles_j * a.ksplit, 256, smem_bytes<EPI, BN, SD, BMT>(), st>>>(a, tiles_i, tiles_j);
   return hipGetLastError();
 }
 
@@ -498,46 +516,66 @@ bool mfma_gemm_supported(int epi, const GemmArgs& a) {
 
 int mfma_lmhead_partials_per_row(int V) { return cdiv(V, BM) * 2; }
 
-// Column-tile width: a pure scheduling choice (it never changes the K order of any output element).
-// Estimated cost = rounds over the 256 CUs x width / efficiency of that width.
-static int choose_bn(int m_tiles, int n_cols, int unit, int ksplit, bool allow192) {
+// Tile shape: a pure scheduling choice (it never changes the K order of any output element, so a row's result
+// is bit-identical whatever shape runs it).  Estimated cost = rounds over the 256 CUs x time of one K-tile of
+// one workgroup, the larger of its matrix-pipe time (32 cycles per 32x32x16 MFMA, 4 K steps, a penalty for
+// narrow tiles) and the time to bring its operands in (about 40 bytes per clock per CU).  With few rows
+// (one or a few states) the projections are weight-streaming problems: 64- and 128-row tiles spend a quarter
+// or half of the matrix work of a 256-row tile on them and cover more CUs.
+struct TileShape { int bm, bn; };
+static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow192) {
+  const int heights[3] = {256, 128, 64};
   const int widths[3] = {192, 128, 64};
   const float eff[3] = {1.0f, 0.85f, 0.55f};
-  int best = 0;
+  TileShape best = {256, 0};
   float best_cost = 1e30f;
-  for (int i = 0; i < 3; ++i) {
-    const int cols = widths[i] / unit;          // output columns (or SwiGLU features) per tile
-    if ((i == 0 && !allow192) || n_cols % cols != 0) continue;
-    const int tiles = m_tiles * (n_cols / cols) * ksplit;
-    const float cost = (float)cdiv(tiles, 256) * widths[i] / eff[i];
-    if (cost < best_cost) { best_cost = cost; best = widths[i]; }
-  }
+  for (int h = 0; h < 3; ++h)
+    for (int i = 0; i < 3; ++i) {
+      const int bm = heights[h], bn = widths[i];
+      const int cols = bn / unit;                 // output columns (or SwiGLU features) per tile
+      if ((bn == 192 && (!allow192 || bm == 64)) || (bn == 64 && bm != 256) || n_cols % cols != 0) continue;
+      const int tiles = cdiv(M, bm) * (n_cols / cols) * ksplit;
+      const float mfma = (float)(bm / 64) * (float)(bn / 64) * 128.0f / eff[i];
+      const float load = (float)(bm + bn) * 3.2f;
+      const float cost = (float)cdiv(tiles, 256) * (mfma > load ? mfma : load);
+      if (cost < best_cost) { best_cost = cost; best = {bm, bn}; }
+    }
   return best;
+}
+
+template <int EPI>
+static hipError_t launch_shape(const GemmArgs& a, TileShape t, int unit, hipStream_t st) {
+  const int mt = cdiv(a.M, t.bm), nt = a.N / (t.bn / unit);
+  constexpr bool W192 = EPI != EPI_PARTIAL;       // the split-K projections never take the 192-wide tile
+  if (t.bm == 256) {
+    if constexpr (W192) if (t.bn == 192) return launch_t<EPI, 192, 3>(a, mt, nt, st);
+    if (t.bn == 128) return launch_t<EPI, 128, 4>(a, mt, nt, st);
+    return launch_t<EPI, 64, 4>(a, mt, nt, st);
+  }
+  // few rows: the weight ring is as deep as the LDS allows (bytes in flight are what sets the streaming rate)
+  if (t.bm == 128) {
+    if constexpr (W192) if (t.bn == 192) return launch_t<EPI, 192, 4, 128>(a, mt, nt, st);
+    return launch_t<EPI, 128, 6, 128>(a, mt, nt, st);
+  }
+  return launch_t<EPI, 128, 6, 64>(a, mt, nt, st);
 }
 
 hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
   GemmArgs a = a0;
   if (a.ksplit < 1) a.ksplit = 1;
-  const int mt = cdiv(a.M, BM);
   switch (epi) {
-    case EPI_STORE: {
-      const int bn = choose_bn(mt, a.N, 1, 1, true);
-      if (bn == 192) return launch_t<EPI_STORE, 192, 3>(a, mt, a.N / 192, st);
-      if (bn == 128) return launch_t<EPI_STORE, 128, 4>(a, mt, a.N / 128, st);
-      return launch_t<EPI_STORE, 64, 4>(a, mt, a.N / 64, st);
-    }
-    case EPI_RESID:
-      if (choose_bn(mt, a.N, 1, 1, false) == 64) return launch_t<EPI_RESID, 64, 4>(a, mt, a.N / 64, st);
+    case EPI_STORE:
+      return launch_shape<EPI_STORE>(a, choose_tile(a.M, a.N, 1, 1, true), 1, st);
+    case EPI_RESID: {
+      const int mt = cdiv(a.M, BM);
+      TileShape t = choose_tile(a.M, a.N, 1, 1, false);
+      if (t.bm == 256 && t.bn == 64) return launch_t<EPI_RESID, 64, 4>(a, mt, a.N / 64, st);
       return launch_t<EPI_RESID, 128, 4>(a, mt, a.N / 128, st);
-    case EPI_PARTIAL:
-      if (choose_bn(mt, a.N, 1, a.ksplit, false) == 64) return launch_t<EPI_PARTIAL, 64, 4>(a, mt, a.N / 64, st);
-      return launch_t<EPI_PARTIAL, 128, 4>(a, mt, a.N / 128, st);
-    case EPI_SWIGLU: {
-      const int bn = choose_bn(mt, a.N, 2, 1, true);   // a tile of width w holds w/2 features
-      if (bn == 192) return launch_t<EPI_SWIGLU, 192, 3>(a, mt, a.N / 96, st);
-      if (bn == 128) return launch_t<EPI_SWIGLU, 128, 4>(a, mt, a.N / 64, st);
-      return launch_t<EPI_SWIGLU, 64, 4>(a, mt, a.N / 32, st);
     }
+    case EPI_PARTIAL:
+      return launch_shape<EPI_PARTIAL>(a, choose_tile(a.M, a.N, 1, a.ksplit, false), 1, st);
+    case EPI_SWIGLU:
+      return launch_shape<EPI_SWIGLU>(a, choose_tile(a.M, a.N, 2, 1, true), 2, st);   // a tile of width w holds w/2 features
     case EPI_LMHEAD:
       return launch_t<EPI_LMHEAD, 192, 3>(a, cdiv(a.N, BM), cdiv(a.M, 192), st);
     default:

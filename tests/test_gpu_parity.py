@@ -211,6 +211,22 @@ def test_layer_mfma_batch_invariance_and_duplicates(sp):
     assert torch.equal(shuffled, full[perm])
 
 
+def test_layer_rows_are_bit_identical_across_tile_heights(sp):
+    """1, 4, 8 and 32 states run the projections on 64-, 128- and 256-row tiles (weight streaming with few rows):
+    the tile shape is scheduling only, every state's rows come out bit-identical."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=1024, Hq=8, Hkv=8, hd=128, F=3072, P=200, B=32, G=32, V=1280)
+    w = synth.layer_weights(cfg, 0)
+    pk, pv = synth.prefix_kv(cfg, 0)
+    x = synth.hidden_states(cfg)
+    full = run_layer(sp, cfg, w, pk, pv, x)
+    for lo, n in ((5, 1), (8, 4), (16, 8), (0, 16)):
+        part = run_layer(sp, cfg, w, pk, pv, x[lo:lo + n].contiguous())
+        assert torch.equal(part, full[lo:lo + n]), (lo, n)
+    ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), to_np(x[5:6]), **oracle_kw(cfg))
+    e_max, _ = rel_err(to_np(full[5:6]), ref)
+    assert e_max < tol(cfg), e_max
+
+
 def test_layer_config2_full_size(sp):
     """One LLaDA-8B-shaped layer at the full configuration-2 size, all 512 rows against the oracle."""
     check_layer(sp, synth.CONFIGS["c2"])

@@ -533,7 +533,7 @@ static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow
     for (int i = 0; i < 3; ++i) {
       const int bm = heights[h], bn = widths[i];
       const int cols = bn / unit;                 // output columns (or SwiGLU features) per tile
-      if ((bn == 192 && (!allow192 || bm == 64)) || (bn == 64 && bm != 256) || n_cols % cols != 0) continue;
+      if ((bn == 192 && (!allow192 || bm == 64)) || (bn == 64 && bm == 128) || n_cols % cols != 0) continue;
       const int tiles = cdiv(M, bm) * (n_cols / cols) * ksplit;
       const float mfma = (float)(bm / 64) * (float)(bn / 64) * 128.0f / eff[i];
       const float load = (float)(bm + bn) * 3.2f;
@@ -557,6 +557,7 @@ static hipError_t launch_shape(const GemmArgs& a, TileShape t, int unit, hipStre
     if constexpr (W192) if (t.bn == 192) return launch_t<EPI, 192, 4, 128>(a, mt, nt, st);
     return launch_t<EPI, 128, 6, 128>(a, mt, nt, st);
   }
+  if (t.bn == 64) return launch_t<EPI, 64, 8, 64>(a, mt, nt, st);
   return launch_t<EPI, 128, 6, 64>(a, mt, nt, st);
 }
 

@@ -338,7 +338,7 @@ def cpu_baseline(cfg, layers, prefix, hw, states, edges):
     from oracle import spiffy_oracle as O
 
     f64 = lambda t: t.detach().cpu().double().numpy()
-    n_layers = min(cfg.L, 4)
+    n_layers = min(cfg.L, 10)          # about 10 s of host work at the headline configuration
     rng = np.random.default_rng(0)
     x = rng.standard_normal((cfg.G, cfg.B, cfg.d))
     t_layers = 0.0

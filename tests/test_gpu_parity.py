@@ -1181,3 +1181,16 @@ def test_subgraph_search_edge_cases(sp):
     edges = np.array([[63, q] for q in range(63)], np.int32)
     got = _run_subgraph(sp, np.arange(64, dtype=np.int64), level, edges, 3)
     assert got["best_nodes"] == [61, 62, 63] and got["n_connected"] == 63 * 62 // 2 and got["best_mask"] == 7 << 61
+
+
+@pytest.mark.parametrize("scale", [1 << 29, 1 << 30, 1 << 41])
+def test_subgraph_search_large_counts_take_the_64_bit_path(sp, scale):
+    """Counts whose magnitudes add up to 2^30 or more are summed in 64 bits; below that in 32 bits: both against
+    the oracle, with negative counts and sums beyond 2^44."""
+    count, level, edges, _ = synth.candidate_graph(6, seed=300)
+    r = np.random.default_rng(scale % 1000)
+    big = (r.integers(-8, 9, len(count)) * (scale // 8)).astype(np.int64) + count
+    for D in (1, 4, 9):
+        ref = O().subgraph_search(big, level, edges, D)
+        got = _run_subgraph(sp, big, level, edges, D)
+        assert got == ref, (scale, D, got, ref)

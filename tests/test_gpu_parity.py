@@ -1194,3 +1194,32 @@ def test_subgraph_search_large_counts_take_the_64_bit_path(sp, scale):
         ref = O().subgraph_search(big, level, edges, D)
         got = _run_subgraph(sp, big, level, edges, D)
         assert got == ref, (scale, D, got, ref)
+
+
+# ------------------------------------------------------------------ the step inside a HIP graph
+
+def test_step_replays_from_a_captured_graph(sp):
+    """The whole step allocates nothing, never synchronises and records no memset: captured once into a HIP graph
+    it replays with new inputs written into the same buffers, bit-identical to the eager call each time (eager
+    work and synchronisations between the replays)."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=1280, P=100, B=32, G=6)
+    plan, layers, prefix, hw, w_embed, states, edges = build_step(sp, cfg, "c1_literal", 7, 20.0)
+    d_states = torch.from_numpy(states).to(DEV)
+    d_edges = torch.from_numpy(np.ascontiguousarray(edges)).to(DEV)
+    plan.run(d_states, d_edges)                      # first call outside the capture: one-time kernel attributes
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        plan.run(d_states, d_edges)
+    keys = ("hidden", "argmax", "conf", "unmask", "target_states", "result", "accepted_state")
+    for trial in range(4):
+        new_states = synth.random_states(cfg.G, cfg.B, cfg.V, 0.3, 0.7, 50 + trial)
+        d_states.copy_(torch.from_numpy(new_states).to(DEV))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = {k: plan.out[k].clone() for k in keys}
+        plan.run(d_states, d_edges)                  # eager, same buffers
+        torch.cuda.synchronize()
+        for k in keys:
+            assert torch.equal(got[k], plan.out[k]), (trial, k)
+        assert not torch.equal(got["hidden"], torch.zeros_like(got["hidden"]))

@@ -49,16 +49,19 @@ __device__ __forceinline__ void wait_vmcnt() {   // vmcnt <= N; lgkmcnt / expcnt
 }
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
+// 64-row tiles, and 128-row tiles up to 128 columns wide, are weight-streaming shapes: both operand rings SD deep
+constexpr bool uniform_rings(int epi, int bn, int bmt) { return epi != EPI_LMHEAD && (bmt == 64 || (bmt == 128 && bn <= 128)); }
+
 template <int EPI, int BN, int SD, int BMT = 256>
 __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int tiles_i, int tiles_j) {
   constexpr int BM = BMT;                         // rows of the output tile: 256, or 128 / 64 when there are few rows
   // which operand is the weight matrix (deep ring): Y for the projections, X for the LM head
   constexpr bool XDEEP = (EPI == EPI_LMHEAD);
-  // UNI (64-row tiles, a weight-streaming problem): both operands ride rings of SD stages and every load runs
+  // UNI (64-row and narrow 128-row tiles, weight-streaming problems): both operands ride rings of SD stages and every load runs
   // SD tiles ahead, so SD-2 whole tiles stay in flight across a barrier.  Otherwise the activation operand has
   // two stages and is loaded two tiles ahead; its loads sit behind the weight loads in the in-order counter,
   // so only the newest weight tile can stay in flight.
-  constexpr bool UNI = (BMT == 64) && !XDEEP;
+  constexpr bool UNI = uniform_rings(EPI, BN, BMT);
   constexpr int SX = XDEEP ? SD : (UNI ? SD : 2), SY = XDEEP ? 2 : SD;
   constexpr int TM = BM / 64, TN = BN / 64;
   constexpr int LX = BM / 32, LY = BN / 32;       // 1-KB wave-loads (8 rows x 128 B) per wavefront per K-tile
@@ -431,7 +434,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 
 template <int EPI, int BN, int SD, int BMT>
 constexpr size_t smem_bytes() {
-  return sizeof(bf16_t) * (size_t)(EPI == EPI_LMHEAD ? SD * BMT + 2 * BN : (BMT == 64 ? SD : 2) * BMT + SD * BN) * BKK;
+  return sizeof(bf16_t) * (size_t)(EPI == EPI_LMHEAD ? SD * BMT + 2 * BN : (uniform_rings(EPI, BN, BMT) ? SD : 2) * BMT + SD * BN) * BKK;
 }
 
 template <int EPI, int BN, int SD, int BMT = 256>
@@ -555,7 +558,7 @@ static hipError_t launch_shape(const GemmArgs& a, TileShape t, int unit, hipStre
   // few rows: the weight ring is as deep as the LDS allows (bytes in flight are what sets the streaming rate)
   if (t.bm == 128) {
     if constexpr (W192) if (t.bn == 192) return launch_t<EPI, 192, 4, 128>(a, mt, nt, st);
-    return launch_t<EPI, 128, 6, 128>(a, mt, nt, st);
+    return launch_t<EPI, 128, 4, 128>(a, mt, nt, st);
   }
   if (t.bn == 64) return launch_t<EPI, 64, 8, 64>(a, mt, nt, st);
   return launch_t<EPI, 128, 6, 64>(a, mt, nt, st);

@@ -185,41 +185,54 @@ __global__ __launch_bounds__(kThreads) void sg_prepare_kernel(const long long* _
     ws->mid_cov[idx] = cov;
     ws->mid_bits[idx] = (unsigned short)v;
   }
-  // size pairs; the 64-bit divisions are done here once instead of by every thread of the search
-  if (tid == 0) {
-    const int nT = N - h - hm;
-    int n = 0;
-    for (int a = 0; a <= h; ++a)
-      for (int b = 0; b <= hm; ++b) {
-        const int kT = D - a - b;
-        if (kT < 0 || kT > nT) continue;
-        SgGroup g;
-        g.nM = (unsigned int)s_binom[hm * kBinomN + b];
-        g.npair = s_binom[nT * kBinomN + kT] * g.nM;
-        g.per = (g.npair + n_threads - 1) / n_threads;
-        g.kT = kT;
-        g.m0 = s_moff[b];
-        // A group with fewer pairs than threads gives each of its lanes one pair and all nE low entries, a lump
-        // that unbalances the wavefronts: cut it into runs of at least 128 entries, each a group of its own
-        // (same pairs, own starting thread), as many as it takes to give every thread about one unit.
-        const int nE = (int)s_binom[h * kBinomN + a];
-        int runs = 1;
-        if (g.npair < n_threads) {
-          const unsigned long long fill = n_threads / g.npair;
-          runs = (nE + 127) / 128;
-          if ((unsigned long long)runs > fill) runs = (int)fill;
-          if (runs > kMaxGroups - 200 - n) runs = kMaxGroups - 200 - n;       // keep room for the groups to come
-          if (runs < 1) runs = 1;
-        }
-        for (int c = 0; c < runs; ++c) {
-          const int lo = (int)((long long)nE * c / runs), hi = (int)((long long)nE * (c + 1) / runs);
-          g.e0 = s_off[a] + lo;
-          g.nE = hi - lo;
-          g.start = ((unsigned long long)n * 64ull * 1543ull) % n_threads;
-          ws->groups[n++] = g;
-        }
+  // Size pairs; the 64-bit divisions are done here once instead of by every thread of the search.  Thread
+  // a*(hm+1)+b owns pair (a, b).  A pair with fewer (top, middle) pairs than threads gives each of its lanes
+  // one pair and all its low entries, a lump that unbalances the wavefronts: it is cut into runs of at least
+  // 128 low entries (at most 8: the low table's largest group has 924), each a group of its own with the same
+  // pairs and its own starting thread, as many as it takes to give every thread about one unit.
+  __shared__ int s_runs[(kLow + 1) * (kMid + 1)], s_first[(kLow + 1) * (kMid + 1) + 1];
+  const int nT = N - h - hm;
+  const int n_ab = (h + 1) * (hm + 1);
+  SgGroup g;
+  int runs = 0, nE = 0, ga = 0;
+  if (tid < n_ab) {
+    ga = tid / (hm + 1);
+    const int gb = tid % (hm + 1);
+    const int kT = D - ga - gb;
+    if (kT >= 0 && kT <= nT) {
+      g.nM = (unsigned int)s_binom[hm * kBinomN + gb];
+      g.npair = s_binom[nT * kBinomN + kT] * g.nM;
+      g.per = (g.npair + n_threads - 1) / n_threads;
+      g.kT = kT;
+      g.m0 = s_moff[gb];
+      nE = (int)s_binom[h * kBinomN + ga];
+      runs = 1;
+      if (g.npair < n_threads) {
+        const unsigned long long fill = n_threads / g.npair;
+        runs = (nE + 127) / 128;
+        if ((unsigned long long)runs > fill) runs = (int)fill;
+        if (runs < 1) runs = 1;
       }
+    }
+    s_runs[tid] = runs;
+  }
+  __syncthreads();
+  if (tid == 0) {
+    int n = 0;
+    for (int i = 0; i < n_ab; ++i) {
+      s_first[i] = n;
+      n += s_runs[i];
+    }
     ws->n_groups = n;
+  }
+  __syncthreads();
+  for (int c = 0; c < runs; ++c) {
+    const int lo = (int)((long long)nE * c / runs), hi = (int)((long long)nE * (c + 1) / runs);
+    const int n = s_first[tid] + c;
+    g.e0 = s_off[ga] + lo;
+    g.nE = hi - lo;
+    g.start = ((unsigned long long)n * 64ull * 1543ull) % n_threads;
+    ws->groups[n] = g;
   }
 }
 

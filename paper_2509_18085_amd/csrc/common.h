@@ -3,6 +3,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/spiffy.h"
 
 namespace spiffy {
@@ -105,6 +107,19 @@ __device__ __forceinline__ int xcd_contiguous(int id, int total) {
 }
 
 inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// Raise a kernel's dynamic LDS limit once per device: `done` holds one bit per device id.  Safe from several host
+// threads (setting the attribute twice is harmless).
+inline hipError_t allow_dynamic_lds(const void* kernel, int bytes, std::atomic<unsigned long long>& done) {
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  const unsigned long long bit = 1ull << (dev & 63);
+  if (done.load(std::memory_order_acquire) & bit) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess) done.fetch_or(bit, std::memory_order_release);
+  return e;
+}
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace spiffy

@@ -583,16 +583,11 @@ size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P) {
 }
 
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)attn_prefix_mfma_kernel<false>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)kAttnSmem);
-    if (e != hipSuccess) return e;
-    e = hipFuncSetAttribute((const void*)attn_prefix_mfma_kernel<true>, hipFuncAttributeMaxDynamicSharedMemorySize,
-                            (int)kAttnSmem);
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static std::atomic<unsigned long long> lds_ok[2];
+  hipError_t e = allow_dynamic_lds((const void*)attn_prefix_mfma_kernel<false>, (int)kAttnSmem, lds_ok[0]);
+  if (e != hipSuccess) return e;
+  e = allow_dynamic_lds((const void*)attn_prefix_mfma_kernel<true>, (int)kAttnSmem, lds_ok[1]);
+  if (e != hipSuccess) return e;
   const int M = a.G * a.B;
   const int nS = n_splits(a.P + a.S);
   unsigned char* ws = reinterpret_cast<unsigned char*>(a.partial);

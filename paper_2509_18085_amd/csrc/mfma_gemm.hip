@@ -439,13 +439,10 @@ constexpr size_t smem_bytes() {
 
 template <int EPI, int BN, int SD, int BMT = 256>
 hipError_t launch_t(const GemmArgs& a, int tiles_i, int tiles_j, hipStream_t st) {
-  static bool attr_done = false;
-  if (!attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)gemm_bf16_mfma_kernel<EPI, BN, SD, BMT>,
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_bytes<EPI, BN, SD, BMT>());
-    if (e != hipSuccess) return e;
-    attr_done = true;
-  }
+  static std::atomic<unsigned long long> lds_ok{0};
+  const hipError_t e = allow_dynamic_lds((const void*)gemm_bf16_mfma_kernel<EPI, BN, SD, BMT>,
+                                         (int)smem_bytes<EPI, BN, SD, BMT>(), lds_ok);
+  if (e != hipSuccess) return e;
   gemm_bf16_mfma_kernel<EPI, BN, SD, BMT><<<tiles_i * tiles_j * a.ksplit, 256, smem_bytes<EPI, BN, SD, BMT>(), st>>>(a, tiles_i, tiles_j);
   return hipGetLastError();
 }

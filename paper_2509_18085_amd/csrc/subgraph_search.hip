@@ -492,15 +492,17 @@ size_t subgraph_search_workspace_bytes() {
 }
 
 hipError_t launch_subgraph_search(const SubgraphArgs& a, hipStream_t st) {
-  static int n_cu = 0;
+  // compute units of the current device (asked once per device id; the answer decides only how the work is cut)
+  static std::atomic<int> cu_of_device[64];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  int n_cu = cu_of_device[dev & 63].load(std::memory_order_acquire);
   if (n_cu == 0) {
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
+    e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
     if (e != hipSuccess) return e;
-    hipDeviceProp_t prop;
-    e = hipGetDeviceProperties(&prop, dev);
-    if (e != hipSuccess) return e;
-    n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    if (n_cu <= 0) n_cu = 256;
+    cu_of_device[dev & 63].store(n_cu, std::memory_order_release);
   }
   // two workgroups of 16 wavefronts per compute unit, fewer when there is little to share out
   int blocks = 2 * n_cu < subgraph_search_max_blocks() ? 2 * n_cu : subgraph_search_max_blocks();

@@ -47,6 +47,9 @@ def main():
 
     import numpy as np
     import torch
+    if not os.path.exists(os.path.join(ROOT, "paper_2509_18085_amd", "libspiffy.so")):
+        from paper_2509_18085_amd import build as _build      # nothing built yet: build; otherwise load what is there
+        _build.build()
     from paper_2509_18085_amd import spiffy as sp, synth
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"

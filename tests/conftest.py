@@ -10,3 +10,12 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def pytest_sessionstart(session):
+    """The tests load the library that is built; only when there is none do they build it (the binding itself
+    never does: it fails loudly)."""
+    lib = os.path.join(ROOT, "paper_2509_18085_amd", "libspiffy.so")
+    if not os.path.exists(lib):
+        from paper_2509_18085_amd import build
+        build.build()

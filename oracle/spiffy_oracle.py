@@ -19,6 +19,9 @@ What the paper fixes and where:
   * keys/values of everything before the block are cached and fixed       Sec. 3.1 (prefix caching)
   * exactness holds with fixed context KV / blockwise-causal context      Sec. 4.3, App. A.2
   * dual cache: the fixed context also holds the tokens after the block   Sec. 4.3, App. A.2
+  * full-sequence models with a prefix cache only: the true sequence (block ; suffix) is
+    recomputed in the call and attends to itself; a draft block attends to the context, to
+    itself and to the true suffix, not to the block it drafts for           Sec. 4.3, Fig. 4, App. A.2
   * Next(X, p): per-position top-1 probability and token, unmask the chosen positions
                                                                           Alg. 1 steps 1-4, App. A
   * threshold rule: unmask every masked position whose top-1 probability exceeds tau
@@ -54,6 +57,8 @@ fractions, the graph conditions of Eqs. (4)-(6), and the link to Next(X, p): the
 for the dual cache (tests/test_oracle_suffix_pins.py) the mean-of-values closed form over
 P + B + S rows, torch's attention, the block rows of a full bidirectional one-layer forward,
 the dense-mask formulation with the suffix in the context, and a scalar brute force; for the
+full-sequence step (tests/test_oracle_fullseq_pins.py) the dense-mask single-sequence
+formulation, the reduction to a plain cached forward for one state, and draft isolation; for the
 subgraph search (tests/test_oracle_subgraph_pins.py) a hand-worked example, the paper's
 breadth-first growth from the root levels as a second formulation, and closed forms for the
 number of connected sets and the optimum on structured graphs.
@@ -562,3 +567,95 @@ def subgraph_search(count: Sequence[int], level: Sequence[int], edges: np.ndarra
         if n_conn == 1 or total > best_sum or (total == best_sum and mask < best_mask):
             best, best_mask, best_sum = nodes, mask, total
     return dict(best_nodes=list(best), best_mask=best_mask, best_sum=best_sum, n_connected=n_conn)
+
+
+# ----------------------------------------------------------------------------------------
+# full-sequence models with a prefix cache only (Sec. 4.3, Fig. 4, App. A.2)
+# ----------------------------------------------------------------------------------------
+
+def _attend(q, keys, vals, head_dim):
+    s = (q @ keys.T) / np.sqrt(float(head_dim))
+    return softmax_rows(s) @ vals
+
+
+def verify_layer_fullseq(w: Dict[str, np.ndarray], prefix_k: np.ndarray, prefix_v: np.ndarray,
+                         hidden_blocks: np.ndarray, hidden_suffix: np.ndarray, *, n_q_heads: int,
+                         n_kv_heads: int, head_dim: int, pos0: int, rms_eps: float = 1e-5,
+                         rope_base: float = 10000.0):
+    """One layer of the verification call of a full-sequence bidirectional model that caches only
+    the prefix: hidden_blocks [G,B,d] (block 0 = the true block, the others drafts) and
+    hidden_suffix [S,d] (the true tokens after the block) -> (out_blocks, out_suffix).
+
+    Fig. 4: the true sequence keeps attending to itself, so the rows of block 0 and of the suffix
+    see the cached prefix, block 0 and the suffix; the rows of a draft block see the prefix, their
+    own block and the true suffix (all true blocks except the one drafted for).  Block rows sit at
+    positions pos0..pos0+B-1 for every g, suffix rows at pos0+B..pos0+B+S-1."""
+    xb = np.asarray(hidden_blocks, F64)
+    xs = np.asarray(hidden_suffix, F64)
+    G, B, d = xb.shape
+    S = xs.shape[0]
+    Hq, Hkv, hd = n_q_heads, n_kv_heads, head_dim
+    rep = Hq // Hkv
+    pk, pv = np.asarray(prefix_k, F64), np.asarray(prefix_v, F64)
+
+    def qkv(x, pos):
+        n = rms_norm(x, w["norm1"], rms_eps)
+        q, k, v = n @ _w(w, "wq").T, n @ _w(w, "wk").T, n @ _w(w, "wv").T
+        if _w(w, "bq") is not None:
+            q = q + _w(w, "bq")
+        if _w(w, "bk") is not None:
+            k = k + _w(w, "bk")
+        if _w(w, "bv") is not None:
+            v = v + _w(w, "bv")
+        T = x.shape[0]
+        q = rope(q.reshape(T, Hq, hd).transpose(1, 0, 2), pos, rope_base)
+        k = rope(k.reshape(T, Hkv, hd).transpose(1, 0, 2), pos, rope_base)
+        return q, k, v.reshape(T, Hkv, hd).transpose(1, 0, 2)
+
+    def rest(x, o):
+        h1 = x + o @ _w(w, "wo").T
+        n2 = rms_norm(h1, w["norm2"], rms_eps)
+        return h1 + (silu(n2 @ _w(w, "w_gate").T) * (n2 @ _w(w, "w_up").T)) @ _w(w, "w_down").T
+
+    pos_b = pos0 + np.arange(B)
+    pos_s = pos0 + B + np.arange(S)
+    qs, ks, vs = qkv(xs, pos_s)                                  # the true suffix
+    blocks = [qkv(xb[g], pos_b) for g in range(G)]
+    out_b = np.empty_like(xb)
+    for g in range(G):
+        qg, kg, vg = blocks[g]
+        o = np.empty((B, Hq, hd), F64)
+        for h in range(Hq):
+            c = h // rep
+            keys = np.concatenate([pk[c], kg[c], ks[c]], axis=0)
+            vals = np.concatenate([pv[c], vg[c], vs[c]], axis=0)
+            o[:, h, :] = _attend(qg[h], keys, vals, hd)
+        out_b[g] = rest(xb[g], o.reshape(B, Hq * hd))
+    _, k0, v0 = blocks[0]                                        # the true block
+    o = np.empty((S, Hq, hd), F64)
+    for h in range(Hq):
+        c = h // rep
+        keys = np.concatenate([pk[c], k0[c], ks[c]], axis=0)
+        vals = np.concatenate([pv[c], v0[c], vs[c]], axis=0)
+        o[:, h, :] = _attend(qs[h], keys, vals, hd)
+    out_s = rest(xs, o.reshape(S, Hq * hd)) if S else xs.copy()
+    return out_b, out_s
+
+
+def verify_step_fullseq(layers: Sequence[Dict], prefix: Sequence[Tuple[np.ndarray, np.ndarray]],
+                        w_embed, final_norm, w_vocab, block_tokens, suffix_tokens, edges, *,
+                        n_q_heads, n_kv_heads, head_dim, pos0, mask_id, threshold, rms_eps=1e-5,
+                        rope_base=10000.0, logit_scale=1.0, force_one=True, root=0):
+    """The whole step for a full-sequence model: embed, the layers above, the head on the G blocks
+    (the suffix is only context), the walk."""
+    hb = embed(w_embed, block_tokens)
+    hs = embed(w_embed, np.asarray(suffix_tokens).reshape(-1))
+    for w, (pk, pv) in zip(layers, prefix):
+        hb, hs = verify_layer_fullseq(w, pk, pv, hb, hs, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads,
+                                      head_dim=head_dim, pos0=pos0, rms_eps=rms_eps, rope_base=rope_base)
+    amax, conf, unmask, margin, target = decode_head(
+        hb, final_norm, w_vocab, block_tokens, mask_id, threshold, rms_eps=rms_eps,
+        logit_scale=logit_scale, force_one=force_one)
+    node, depth, n_steps, state = graph_accept(edges, block_tokens, target, root)
+    return dict(hidden=hb, hidden_suffix=hs, argmax=amax, conf=conf, unmask=unmask, margin=margin,
+                target_states=target, node=node, depth=depth, n_steps=n_steps, accepted_state=state)

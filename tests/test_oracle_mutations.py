@@ -8,6 +8,7 @@ import types
 import pytest
 
 import test_oracle_drafting_pins as drafting
+import test_oracle_fullseq_pins as fullseq
 import test_oracle_pins as pins
 import test_oracle_subgraph_pins as subgraph
 import test_oracle_suffix_pins as suffix
@@ -25,7 +26,7 @@ def build(src):
 def run(mod, checks, monkeypatch):
     """Run the pins against `mod`; returns the names of those that failed."""
     failed = []
-    for m in (pins, drafting, subgraph, suffix):
+    for m in (pins, drafting, subgraph, suffix, fullseq):
         monkeypatch.setattr(m, "O", mod)
     for fn, kwargs in checks:
         try:
@@ -105,6 +106,14 @@ CASES = [
      [P(drafting.test_worked_example)]),
     ("drafts: vocabulary rank off by one", "drafts[m, b] = int(topk_tokens[b, j - 1])", "drafts[m, b] = int(topk_tokens[b, min(j, K - 1)])",
      [P(drafting.test_worked_example)]),
+    ("full sequence: drafts see the true block instead of themselves", "keys = np.concatenate([pk[c], kg[c], ks[c]], axis=0)",
+     "keys = np.concatenate([pk[c], blocks[0][1][c], ks[c]], axis=0)", [P(fullseq.test_dense_mask_formulation_through_all_layers)]),
+    ("full sequence: suffix at the block's positions", "pos_s = pos0 + B + np.arange(S)", "pos_s = pos0 + np.arange(S)",
+     [P(fullseq.test_dense_mask_formulation_through_all_layers)]),
+    ("full sequence: the suffix sees a draft instead of the true block", "    _, k0, v0 = blocks[0]  ", "    _, k0, v0 = blocks[-1]  ",
+     [P(fullseq.test_dense_mask_formulation_through_all_layers)]),
+    ("full sequence: the suffix is not updated", "out_s = rest(xs, o.reshape(S, Hq * hd)) if S else xs.copy()", "out_s = xs.copy()",
+     [P(fullseq.test_one_state_is_a_plain_cached_forward_over_block_and_suffix)]),
     ("subgraph: only level 1 is a root", "return all(level[q] in (1, 2) or (parents[q] & g) for q in g)", "return all(level[q] in (1,) or (parents[q] & g) for q in g)",
      [P(subgraph.test_hand_worked_example)]),
     ("subgraph: edges reversed", "            parents[q].add(int(p))\n    best, best_mask", "            parents[p].add(int(q))\n    best, best_mask",

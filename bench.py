@@ -166,6 +166,7 @@ def main():
         line["next_step_drafting"] = drafting_leg(sp, cfg, plan, d_states, dev)
         line["decode_loop"] = decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev)
         line["dual_cache_step"] = dual_cache_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, dev, seed)
+        line["full_sequence_step"] = full_sequence_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, dev)
         line["calibration_subgraph_search"] = subgraph_leg(sp, dev, seed)
 
     if not args.no_cpu_baseline:
@@ -317,6 +318,33 @@ def subgraph_leg(sp, dev, seed, n_levels=15, D=10, iters=3):
             "roofline": {"kernel": "sg_search_kernel", "bound": "alu", "achieved": ops / (ms * 1e-3) / 1e12,
                          "peak": peak / 1e12, "unit": "Top/s (int32 lane operations)",
                          "frac": ops / (ms * 1e-3) / peak, "traffic": None}}
+
+
+def full_sequence_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, dev, S=224, steps=5):
+    """Not part of the timed step: the step of a full-sequence model that caches only the prefix (Sec. 4.3, Fig. 4):
+    the S true tokens after the block are recomputed in the call (S more rows through every layer) and every
+    draft attends to their fresh keys / values."""
+    import time
+    import torch
+    cap = cfg.P + cfg.B + S
+    pf = []
+    for k, v in prefix:
+        kk = torch.zeros((cfg.Hkv, cap, cfg.hd), dtype=k.dtype, device=dev)
+        vv = torch.zeros_like(kk)
+        kk[:, :cfg.P], vv[:, :cfg.P] = k, v
+        pf.append(sp.prefix_kv(kk, vv, cfg.P))
+    plan = sp.SeqStepPlan(sp.cfg_from_synth(cfg), [sp.layer_weights(w) for w in layers], pf, w_embed, hw["final_norm"],
+                          hw["w_vocab"], cfg.G, cfg.B, S, cfg.P, cfg.threshold, logit_scale=LOGIT_SCALE, device=dev)
+    suffix = torch.full((S,), cfg.mask_id, dtype=torch.int32, device=dev)
+    for _ in range(2):
+        plan.run(d_states, suffix, d_edges)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        plan.run(d_states, suffix, d_edges)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    return {"suffix_rows": S, "rows_per_layer": cfg.G * cfg.B + S, "ms_per_step": ms, "states_per_s": cfg.G / (ms * 1e-3)}
 
 
 def stored_traffic(config):

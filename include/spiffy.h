@@ -221,6 +221,27 @@ int spiffy_verify_step(const spiffy_model_cfg *cfg, int32_t n_layers,
                        spiffy_accept_result *result, int32_t *accepted_state, void *workspace,
                        size_t workspace_bytes, void *stream);
 
+/* The whole step for a full-sequence bidirectional model that caches only the prefix (Sec. 4.3, Fig. 4, App. A.2):
+ * the true sequence after the prefix, i.e. the true block (state 0) and the S tokens after it (suffix_tokens [S],
+ * device memory), is recomputed in the call and attends to itself; every draft block attends to the prefix, to
+ * itself and to the true suffix, never to the block it drafts for.  In every layer the rotated keys and the values
+ * of the true block and of the suffix are WRITTEN to rows P .. P+B+S-1 of that layer's cache (prefix[l].k / .v must
+ * have capacity >= P + B + S; prefix[l].S must be 0: the suffix is computed here, not cached), from where the
+ * blocks read the suffix and the suffix rows read the whole true sequence.  The suffix sits at positions
+ * pos0+B .. pos0+B+S-1.  Head and walk run on the G blocks only.  hidden_out [G*B + S, d] (block rows, then
+ * suffix rows; may be NULL).  Workspace from spiffy_workspace_bytes_seq.  S <= SPIFFY_MAX_SUFFIX; S = 0 is
+ * spiffy_verify_step.  Other arguments and errors as for spiffy_verify_step. */
+#define SPIFFY_MAX_SUFFIX 4096
+size_t spiffy_workspace_bytes_seq(const spiffy_model_cfg *cfg, int32_t G, int32_t B, int32_t S, int32_t P_max);
+int spiffy_verify_step_seq(const spiffy_model_cfg *cfg, int32_t n_layers, const spiffy_layer_weights *layers,
+                           const spiffy_prefix_kv *prefix, const void *w_embed, const void *final_norm,
+                           const void *w_vocab, const int32_t *block_tokens, const int32_t *suffix_tokens,
+                           int32_t G, int32_t B, int32_t S, int32_t pos0, const int32_t *graph_edges, int32_t E,
+                           int32_t root, float threshold, float logit_scale, int32_t force_one, void *hidden_out,
+                           int32_t *argmax, float *conf, uint8_t *unmask, float *top2_margin,
+                           int32_t *target_states, spiffy_accept_result *result, int32_t *accepted_state,
+                           void *workspace, size_t workspace_bytes, void *stream);
+
 /* Prefix-cache extension when a block is complete (prefix caching, Sec. 3.1: the keys and values of everything
  * before the block being decoded stay fixed).  One forward pass of the finished block (B tokens, no MASK
  * expected but not checked) through the n_layers layers; in every layer the block's keys (rotated at positions

@@ -70,11 +70,13 @@ struct Carve {
 };
 
 struct LayerWs {
-  void *n, *qkv, *attn, *h, *act, *attn_partial, *splitk;
+  void *n, *qkv, *attn, *h, *act, *attn_partial, *attn_partial_seq, *splitk;
   size_t bytes;
 };
-LayerWs carve_layer(const spiffy_model_cfg* c, int G, int B, int P, void* base) {
-  const size_t M = (size_t)G * B, es = esize(c->dtype);
+// P = cached rows (prefix and suffix together).  S_seq > 0: full-sequence step, S_seq true suffix rows ride along
+// after the G*B block rows and have an attention scratch of their own (queries over the P + B + S_seq cache rows).
+LayerWs carve_layer(const spiffy_model_cfg* c, int G, int B, int P, void* base, int S_seq = 0) {
+  const size_t M = (size_t)G * B + S_seq, es = esize(c->dtype);
   const size_t qkv_cols = (size_t)(c->n_q_heads + 2 * c->n_kv_heads) * c->head_dim;
   Carve cv(base);
   LayerWs w;
@@ -83,7 +85,8 @@ LayerWs carve_layer(const spiffy_model_cfg* c, int G, int B, int P, void* base) 
   w.attn = cv.take(M * (size_t)c->n_q_heads * c->head_dim * es);
   w.h = cv.take(M * c->d * es);
   w.act = cv.take(M * c->ffn * es);
-  w.attn_partial = cv.take(layer_mfma(c) ? mfma_attn_partial_bytes(G, B, c->n_q_heads, c->head_dim, P) : 0);
+  w.attn_partial = cv.take(layer_mfma(c) ? mfma_attn_partial_bytes(G, B, c->n_q_heads, c->head_dim, P + S_seq) : 0);
+  w.attn_partial_seq = cv.take(layer_mfma(c) && S_seq ? mfma_attn_partial_bytes(1, S_seq, c->n_q_heads, c->head_dim, P + B + S_seq) : 0);
   w.splitk = cv.take(layer_mfma(c) ? sizeof(float) * 4 * M * c->d : 0);   // up to 4 K slices of [M,d] fp32
   w.bytes = cv.off;
   return w;
@@ -124,13 +127,13 @@ struct StepWs {
   void* rest;
   size_t rest_bytes, bytes;
 };
-StepWs carve_step(const spiffy_model_cfg* c, int G, int B, int P, void* base) {
+StepWs carve_step(const spiffy_model_cfg* c, int G, int B, int P, void* base, int S_seq = 0) {
   const size_t M = (size_t)G * B;
   Carve cv(base);
   StepWs w;
-  w.hidden = cv.take(M * c->d * esize(c->dtype));
+  w.hidden = cv.take((M + S_seq) * c->d * esize(c->dtype));
   w.target = (int32_t*)cv.take(sizeof(int32_t) * M);
-  const size_t lb = carve_layer(c, G, B, P, nullptr).bytes, hb = carve_head(c, G, B, nullptr).bytes;
+  const size_t lb = carve_layer(c, G, B, P, nullptr, S_seq).bytes, hb = carve_head(c, G, B, nullptr).bytes;
   w.rest_bytes = lb > hb ? lb : hb;
   w.rest = cv.take(w.rest_bytes);
   w.bytes = cv.off;
@@ -165,16 +168,44 @@ struct LayerChain {
   bool rope_ready = false;
   bool normed_out = false;   // set when ws.n holds the next layer's normalised input on return
   bool append_kv = false;    // write the (rotated) K and V rows of state 0 into the cache at rows P .. P+B-1
+  int seq_S = 0;             // full-sequence step: this many true suffix rows follow the G*B block rows
+  bool rope_ready_seq = false;
 };
+
+// The same product as two launches over the row ranges [0, rows_a) and [rows_a, rows_a + rows_b): each range gets the
+// tile shape that suits its height (a ragged total would otherwise pay a whole extra round of the tall tiles).
+// Rows are independent and the K order of an element does not depend on the shape, so nothing else changes.
+hipError_t launch_gemm_mfma_rows(int epi, GemmArgs g, int rows_a, int rows_b, int dtype, hipStream_t st) {
+  const size_t es = esize(dtype), ces = epi == EPI_PARTIAL ? sizeof(float) : es;
+  g.Mz = rows_a + rows_b;
+  GemmArgs a = g;
+  a.M = rows_a;
+  hipError_t e = launch_gemm_mfma(epi, a, st);
+  if (e != hipSuccess || rows_b == 0) return e;
+  GemmArgs b = g;
+  b.M = rows_b;
+  b.A = reinterpret_cast<const char*>(g.A) + (size_t)rows_a * g.lda * es;
+  b.C = reinterpret_cast<char*>(g.C) + (size_t)rows_a * g.ldc * ces;
+  if (g.R) b.R = reinterpret_cast<const char*>(g.R) + (size_t)rows_a * g.ldc * es;
+  return launch_gemm_mfma(epi, b, st);
+}
 
 int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const spiffy_prefix_kv* prefix,
               const void* hidden_in, int G, int B, int pos0, void* hidden_out, void* workspace, hipStream_t st,
               LayerChain* chain = nullptr) {
-  const int M = G * B, d = cfg->d, dt = cfg->dtype;
+  // S_seq > 0 (full-sequence step): rows G*B .. G*B+S_seq-1 of every activation matrix are the true suffix.  It is
+  // recomputed like the blocks; its fresh keys / values, and those of the true block (state 0), go to the cache
+  // rows behind the prefix, where the blocks find the suffix (as in the dual-cache layout) and the suffix rows
+  // find the whole true sequence.
+  const int S_seq = chain ? chain->seq_S : 0;
+  const int M = G * B + S_seq, d = cfg->d, dt = cfg->dtype;
   const int qd = cfg->n_q_heads * cfg->head_dim, kvd = cfg->n_kv_heads * cfg->head_dim;
   const bool mf = layer_mfma(cfg);
-  const LayerWs ws = carve_layer(cfg, G, B, prefix->P + prefix->S, workspace);
+  const LayerWs ws = carve_layer(cfg, G, B, prefix->P + prefix->S, workspace, S_seq);
   int rc;
+  auto mfma_rows = [&](int epi, const GemmArgs& ga) {
+    return S_seq ? launch_gemm_mfma_rows(epi, ga, G * B, S_seq, dt, st) : launch_gemm_mfma(epi, ga, st);
+  };
   if (chain) chain->normed_out = false;
   if (!(chain && chain->normed_in) &&
       (rc = dev(launch_rmsnorm(dt, hidden_in, w->norm1, cfg->rms_eps, M, d, nullptr, nullptr, ws.n, st))))
@@ -188,20 +219,38 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   g.Nseg[0] = qd; g.Nseg[1] = kvd; g.Nseg[2] = kvd;
   g.N = qd + 2 * kvd; g.C = ws.qkv; g.ldc = g.N; g.scale = 1.f;
   const bool mf_qkv = mf && mfma_gemm_supported(EPI_STORE, g);
-  if ((rc = dev(mf_qkv ? launch_gemm_mfma(EPI_STORE, g, st) : launch_gemm_generic(dt, EPI_STORE, g, st)))) return rc;
+  if ((rc = dev(mf_qkv ? mfma_rows(EPI_STORE, g) : launch_gemm_generic(dt, EPI_STORE, g, st)))) return rc;
 
   AttnArgs a;
   a.qkv = ws.qkv; a.prefix_k = prefix->k; a.prefix_v = prefix->v; a.out = ws.attn; a.partial = ws.attn_partial;
   a.G = G; a.B = B; a.Hq = cfg->n_q_heads; a.Hkv = cfg->n_kv_heads; a.hd = cfg->head_dim; a.P = prefix->P;
   a.ldp = prefix->capacity;
-  a.S = prefix->S;
+  a.S = S_seq ? S_seq : prefix->S;
+  a.own = 1;
   a.pos0 = pos0; a.rope_base = cfg->rope_base; a.rope_ready = chain && chain->rope_ready;
-  if (chain && chain->append_kv &&
+  const int ldp = prefix->capacity ? prefix->capacity : prefix->P;
+  if (chain && (chain->append_kv || S_seq) &&
       (rc = dev(launch_kv_append(dt, ws.qkv, a.Hq, a.Hkv, a.hd, B, pos0, cfg->rope_base,
-                                 const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P,
-                                 prefix->capacity ? prefix->capacity : prefix->P, st))))
+                                 const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st))))
     return rc;
+  if (S_seq) {
+    const size_t es = esize(dt);
+    const char* qkv_seq = reinterpret_cast<const char*>(ws.qkv) + (size_t)G * B * g.N * es;
+    if ((rc = dev(launch_kv_append(dt, qkv_seq, a.Hq, a.Hkv, a.hd, S_seq, pos0 + B, cfg->rope_base,
+                                   const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P + B, ldp, st))))
+      return rc;
+  }
   if ((rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st)))) return rc;
+  if (S_seq) {      // the suffix rows: queries at positions pos0+B .., keys = cache rows 0 .. P+B+S_seq-1, no block of their own
+    const size_t es = esize(dt);
+    AttnArgs b = a;
+    b.qkv = reinterpret_cast<const char*>(ws.qkv) + (size_t)G * B * g.N * es;
+    b.out = reinterpret_cast<char*>(ws.attn) + (size_t)G * B * qd * es;
+    b.partial = ws.attn_partial_seq;
+    b.G = 1; b.B = S_seq; b.P = prefix->P + B + S_seq; b.S = 0; b.own = 0;
+    b.pos0 = pos0 + B; b.rope_ready = chain->rope_ready_seq;
+    if ((rc = dev(mf && mfma_attn_supported(b) ? launch_attn_mfma(b, st) : launch_attn_generic(dt, b, st)))) return rc;
+  }
 
   // output projection + residual (+ RMSNorm-2 fused into the split-K reduction when K is sliced)
   std::memset(&g, 0, sizeof(g));
@@ -212,12 +261,12 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
     const int ks = mfma_ksplit(d, qd);
     if (ks > 1) {
       g.C = ws.splitk; g.ksplit = ks;
-      if ((rc = dev(launch_gemm_mfma(EPI_PARTIAL, g, st)))) return rc;
+      if ((rc = dev(mfma_rows(EPI_PARTIAL, g)))) return rc;
       if ((rc = dev(launch_splitk_reduce((const float*)ws.splitk, ks, hidden_in, ws.h, w->norm2, cfg->rms_eps, ws.n, M,
                                          d, st))))
         return rc;
       normed = true;
-    } else if ((rc = dev(launch_gemm_mfma(EPI_RESID, g, st)))) return rc;
+    } else if ((rc = dev(mfma_rows(EPI_RESID, g)))) return rc;
   } else if ((rc = dev(launch_gemm_generic(dt, EPI_RESID, g, st)))) return rc;
 
   if (!normed && (rc = dev(launch_rmsnorm(dt, ws.h, w->norm2, cfg->rms_eps, M, d, nullptr, nullptr, ws.n, st))))
@@ -226,7 +275,7 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   std::memset(&g, 0, sizeof(g));
   g.A = ws.n; g.lda = d; g.M = M; g.K = d; g.W[0] = w->w_gate; g.W[1] = w->w_up; g.N = cfg->ffn;
   g.C = ws.act; g.ldc = cfg->ffn; g.scale = 1.f;
-  if ((rc = dev(mf && mfma_gemm_supported(EPI_SWIGLU, g) ? launch_gemm_mfma(EPI_SWIGLU, g, st)
+  if ((rc = dev(mf && mfma_gemm_supported(EPI_SWIGLU, g) ? mfma_rows(EPI_SWIGLU, g)
                                                           : launch_gemm_generic(dt, EPI_SWIGLU, g, st))))
     return rc;
 
@@ -237,13 +286,13 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
     const int ks = mfma_ksplit(d, cfg->ffn);
     if (ks > 1) {
       g.C = ws.splitk; g.ksplit = ks;
-      if ((rc = dev(launch_gemm_mfma(EPI_PARTIAL, g, st)))) return rc;
+      if ((rc = dev(mfma_rows(EPI_PARTIAL, g)))) return rc;
       const void* ng = chain ? chain->next_norm1 : nullptr;
       if (chain && ng) chain->normed_out = true;
       return dev(launch_splitk_reduce((const float*)ws.splitk, ks, ws.h, hidden_out, ng, cfg->rms_eps,
                                       ng ? ws.n : nullptr, M, d, st));
     }
-    return dev(launch_gemm_mfma(EPI_RESID, g, st));
+    return dev(mfma_rows(EPI_RESID, g));
   }
   return dev(launch_gemm_generic(dt, EPI_RESID, g, st));
 }
@@ -491,6 +540,68 @@ int spiffy_verify_step(const spiffy_model_cfg* cfg, int32_t n_layers, const spif
     chain.next_norm1 = (l + 1 < n_layers) ? layers[l + 1].norm1 : nullptr;
     if ((rc = run_layer(cfg, &layers[l], &prefix[l], hid, G, B, pos0, hid, ws.rest, st, &chain))) return rc;
     chain.rope_ready = true;      // same pos0 / B / base for every layer: the table is computed once
+  }
+  if ((rc = run_head(cfg, hid, final_norm, w_vocab, block_tokens, nullptr, G, B, threshold, logit_scale, force_one,
+                     argmax, conf, unmask, top2_margin, tgt, ws.rest, st)))
+    return rc;
+  return dev(launch_graph_accept(graph_edges, E, block_tokens, tgt, G, B, root, result, accepted_state, st));
+}
+
+size_t spiffy_workspace_bytes_seq(const spiffy_model_cfg* cfg, int32_t G, int32_t B, int32_t S, int32_t P_max) {
+  if (check_cfg(cfg) || check_gb(G, B) || P_max < 0 || S < 0 || S > SPIFFY_MAX_SUFFIX) return 0;
+  return carve_step(cfg, G, B, P_max, nullptr, S).bytes;
+}
+
+int spiffy_verify_step_seq(const spiffy_model_cfg* cfg, int32_t n_layers, const spiffy_layer_weights* layers,
+                           const spiffy_prefix_kv* prefix, const void* w_embed, const void* final_norm,
+                           const void* w_vocab, const int32_t* block_tokens, const int32_t* suffix_tokens, int32_t G,
+                           int32_t B, int32_t S, int32_t pos0, const int32_t* graph_edges, int32_t E, int32_t root,
+                           float threshold, float logit_scale, int32_t force_one, void* hidden_out, int32_t* argmax,
+                           float* conf, uint8_t* unmask, float* top2_margin, int32_t* target_states,
+                           spiffy_accept_result* result, int32_t* accepted_state, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(G, B))) return rc;
+  if (n_layers < 1 || !layers || !prefix || !w_embed || !workspace || pos0 < 0 || S < 0 || (S > 0 && !suffix_tokens))
+    return SPIFFY_EINVAL;
+  if (S > SPIFFY_MAX_SUFFIX) return SPIFFY_ESHAPE;
+  if (!aligned16(w_embed) || (hidden_out && !aligned16(hidden_out)) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SPIFFY_EALIGN;
+  int P_max = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if ((rc = check_layer_args(cfg, &layers[l], &prefix[l], G, B))) return rc;
+    if (prefix[l].S != 0) return SPIFFY_EINVAL;                       // the suffix is computed here, not cached
+    if (S > 0) {
+      if (!prefix[l].k || !prefix[l].v) return SPIFFY_EINVAL;         // rows behind the prefix are written
+      if ((int64_t)prefix[l].P + B + S > prefix[l].capacity) return SPIFFY_ESHAPE;
+      if (!layer_mfma(cfg) && generic_attn_smem(cfg, S, prefix[l].P + B + S) > kMaxGenericSmem) return SPIFFY_ESHAPE;
+    }
+    if (prefix[l].P > P_max) P_max = prefix[l].P;
+  }
+  if ((rc = check_head_args(cfg, workspace, final_norm, w_vocab, block_tokens, threshold, logit_scale, argmax, conf,
+                            unmask)))
+    return rc;
+  const int32_t* tgt_probe = target_states ? target_states : reinterpret_cast<const int32_t*>(workspace);
+  if ((rc = check_accept_args(graph_edges, E, block_tokens, tgt_probe, G, B, root, result))) return rc;
+  const StepWs ws = carve_step(cfg, G, B, P_max, workspace, S);
+  if (workspace_bytes < ws.bytes) return SPIFFY_EWORKSPACE;
+
+  hipStream_t st = (hipStream_t)stream;
+  void* hid = hidden_out ? hidden_out : ws.hidden;
+  int32_t* tgt = target_states ? target_states : ws.target;
+  if ((rc = dev(launch_embed(cfg->dtype, w_embed, block_tokens, G * B, cfg->d, cfg->vocab, hid, st)))) return rc;
+  if (S > 0) {
+    void* hid_seq = reinterpret_cast<char*>(hid) + (size_t)G * B * cfg->d * esize(cfg->dtype);
+    if ((rc = dev(launch_embed(cfg->dtype, w_embed, suffix_tokens, S, cfg->d, cfg->vocab, hid_seq, st)))) return rc;
+  }
+  LayerChain chain;
+  chain.seq_S = S;
+  for (int l = 0; l < n_layers; ++l) {
+    chain.normed_in = chain.normed_out;
+    chain.next_norm1 = (l + 1 < n_layers) ? layers[l + 1].norm1 : nullptr;
+    if ((rc = run_layer(cfg, &layers[l], &prefix[l], hid, G, B, pos0, hid, ws.rest, st, &chain))) return rc;
+    chain.rope_ready = true;
+    chain.rope_ready_seq = true;
   }
   if ((rc = run_head(cfg, hid, final_norm, w_vocab, block_tokens, nullptr, G, B, threshold, logit_scale, force_one,
                      argmax, conf, unmask, top2_margin, tgt, ws.rest, st)))

@@ -95,7 +95,8 @@ struct GemmArgs {
   int lda, ldc;
   int ldw;              // row stride of the weight segments in elements (0 = K, i.e. dense rows)
   float scale;          // LMHEAD: logit scale
-  int ksplit;           // PARTIAL: number of K slices (C = fp32 [ksplit][M][N]); otherwise 1
+  int ksplit;           // PARTIAL: number of K slices (C = fp32 [ksplit][Mz][N]); otherwise 1
+  int Mz;               // PARTIAL: rows per K slice of C when only some of them are computed by this launch (0 = M)
 };
 
 // Workgroup ids are handed to the 8 XCDs round-robin (id % 8).  Map id -> logical index so that every

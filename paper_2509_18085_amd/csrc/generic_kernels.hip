@@ -202,7 +202,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__ qkv, const T* __restrict__ pk,
                                                            const T* __restrict__ pv, T* __restrict__ out, int G,
                                                            int B, int Hq, int Hkv, int hd, int P, int S, int ldp,
-                                                           int pos0, float rope_base) {
+                                                           int pos0, float rope_base, int own) {
   extern __shared__ float smem[];
   __shared__ float red[4];
   const int half = hd >> 1;
@@ -216,7 +216,8 @@ __global__ __launch_bounds__(256) void attn_generic_kernel(const T* __restrict__
   const int g = m / B, b = m % B;
   const int kvh = h / (Hq / Hkv);
   const int ld = (Hq + 2 * Hkv) * hd;
-  const int T_all = P + B + S;
+  // own == 0 (queries that are not a block of their own: the true suffix): cache rows 0 .. P-1 only
+  const int T_all = own ? P + B + S : P;
   for (int i = threadIdx.x; i < B * half; i += 256) {
     const int bb = i / half, f = i % half;
     const double inv_freq = pow((double)rope_base, -2.0 * (double)f / (double)hd);
@@ -297,14 +298,14 @@ hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t st) {
     if (e != hipSuccess) return e;
     attn_generic_kernel<float><<<grid, 256, smem, st>>>((const float*)a.qkv, (const float*)a.prefix_k,
                                                         (const float*)a.prefix_v, (float*)a.out, a.G, a.B, a.Hq,
-                                                        a.Hkv, a.hd, a.P, a.S, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base);
+                                                        a.Hkv, a.hd, a.P, a.S, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base, a.own);
   } else {
     hipError_t e = hipFuncSetAttribute((const void*)attn_generic_kernel<bf16_t>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
     attn_generic_kernel<bf16_t><<<grid, 256, smem, st>>>((const bf16_t*)a.qkv, (const bf16_t*)a.prefix_k,
                                                          (const bf16_t*)a.prefix_v, (bf16_t*)a.out, a.G, a.B, a.Hq,
-                                                         a.Hkv, a.hd, a.P, a.S, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base);
+                                                         a.Hkv, a.hd, a.P, a.S, a.ldp ? a.ldp : a.P, a.pos0, a.rope_base, a.own);
   }
   return hipGetLastError();
 }

@@ -23,6 +23,7 @@ struct AttnArgs {
   int G, B, Hq, Hkv, hd, P, pos0;
   int ldp;               // rows allocated per KV head in prefix_k / prefix_v (0 = P)
   int S;                 // dual cache: rows P+B .. P+B+S-1 of the same arrays hold the tokens after the block
+  int own;               // 1: every state also attends to its own B rows (keys / values from qkv); 0: cache rows only
   float rope_base;
   int rope_ready;        // MFMA path: the rotary table at the start of `partial` is already filled
 };

@@ -260,6 +260,7 @@ struct AttnKArgs {
   float* opart;         // [nS][M][Hq][128]
   float* mlpart;        // [nS][M][Hq][2]
   int M, B, Hq, Hkv, P, S, ldp, ld, nQ, nS;   // ldp = rows allocated per KV head of the cache; S = suffix rows
+  int own;                                     // 0: no own-block keys (queries that only read the cache)
   int split;                                   // cached rows per split: the P + S rows shared out evenly, whole tiles
 };
 
@@ -350,7 +351,7 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
     issue_rows(R64{}, std::true_type{}, stage + TILE_ELEMS, pv, kbeg + t * KTILE, kend - 1, HD);
   };
   // own-block rows c0 .. c0+127 (K and V columns of the fused activations) into stages 1 and 2
-  const bool has_own = sp == a.nS - 1;
+  const bool has_own = a.own && sp == a.nS - 1;
   const int own_lo = (m0 / a.B) * a.B;
   const int own_hi = min(a.M, ((min(m0 + QTILE, a.M) - 1) / a.B + 1) * a.B);
   auto issue_own = [&](int c0) {
@@ -609,6 +610,7 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   k.opart = opart;
   k.mlpart = mlpart;
   k.M = M; k.B = a.B; k.Hq = a.Hq; k.Hkv = a.Hkv; k.P = a.P; k.S = a.S; k.ldp = a.ldp ? a.ldp : a.P;
+  k.own = a.own;
   k.ld = (a.Hq + 2 * a.Hkv) * HD;
   k.nQ = cdiv(M, QTILE);
   k.nS = nS;

@@ -336,7 +336,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   }
 
   if (EPI == EPI_PARTIAL) {
-    float* P = reinterpret_cast<float*>(a.C) + (size_t)kz * a.M * a.ldc;
+    float* P = reinterpret_cast<float*>(a.C) + (size_t)kz * (a.Mz ? a.Mz : a.M) * a.ldc;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll

@@ -22,7 +22,8 @@ MAX_G = 64
 
 EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "spiffy_embed",
            "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk", "spiffy_commit_block",
-           "spiffy_subgraph_search_workspace_bytes", "spiffy_subgraph_search", "spiffy_verify_step"]
+           "spiffy_subgraph_search_workspace_bytes", "spiffy_subgraph_search", "spiffy_verify_step",
+           "spiffy_workspace_bytes_seq", "spiffy_verify_step_seq"]
 GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
 
@@ -89,6 +90,12 @@ def _load() -> C.CDLL:
     lib.spiffy_subgraph_search_workspace_bytes.argtypes = []
     lib.spiffy_subgraph_search.restype = C.c_int
     lib.spiffy_subgraph_search.argtypes = [vp, vp, i32, vp, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.spiffy_workspace_bytes_seq.restype = sz
+    lib.spiffy_workspace_bytes_seq.argtypes = [cfgp, i32, i32, i32, i32]
+    lib.spiffy_verify_step_seq.restype = C.c_int
+    lib.spiffy_verify_step_seq.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp, vp,
+                                           i32, i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
+                                           vp, vp, sz, vp]
     lib.spiffy_verify_step.restype = C.c_int
     lib.spiffy_verify_step.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp,
                                        i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
@@ -368,4 +375,41 @@ class StepPlan:
             self.root, self.threshold, self.logit_scale, self.force_one, _ptr(o["hidden"]), _ptr(o["argmax"]),
             _ptr(o["conf"]), _ptr(o["unmask"]), _ptr(o["margin"]), _ptr(o["target_states"]), _ptr(o["result"]),
             _ptr(o["accepted_state"]), wp, wn, _stream(stream)), "spiffy_verify_step")
+        return o
+
+
+class SeqStepPlan(StepPlan):
+    """spiffy_verify_step_seq with pre-marshalled arguments: the step of a full-sequence model that caches only
+    the prefix.  S true tokens after the block ride along; the caches need capacity >= P + B + S (rows behind
+    the prefix are rewritten by every call)."""
+
+    def __init__(self, cfg: ModelCfg, layers: Sequence[LayerWeights], prefix: Sequence[PrefixKV], w_embed: torch.Tensor,
+                 final_norm: torch.Tensor, w_vocab: torch.Tensor, G: int, B: int, S: int, pos0: int, threshold: float,
+                 logit_scale: float = 1.0, force_one: bool = True, root: int = 0, device="cuda"):
+        super().__init__(cfg, layers, prefix, w_embed, final_norm, w_vocab, G, B, pos0, threshold, logit_scale=logit_scale,
+                         force_one=force_one, root=root, device=device)
+        self.S = S
+        P_max = max([p.P for p in prefix], default=0)
+        n = int(lib.spiffy_workspace_bytes_seq(C.byref(cfg), G, B, S, P_max))
+        if n == 0:
+            raise SpiffyError(SPIFFY_EINVAL, "spiffy_workspace_bytes_seq")
+        self.workspace = torch.empty(n + 256, dtype=torch.uint8, device=device)
+        self.out["hidden"] = torch.empty((G * B + S, cfg.d), dtype=_tdtype(cfg), device=device)
+
+    def run(self, block_tokens: torch.Tensor, suffix_tokens: torch.Tensor, graph_edges: Optional[torch.Tensor],
+            stream=None) -> Dict[str, torch.Tensor]:
+        """block_tokens [G,B], suffix_tokens [S].  out["hidden"] holds the G*B block rows, then the S suffix rows."""
+        o = self.out
+        G = int(block_tokens.shape[0])
+        if G != self.G_cap or int(suffix_tokens.numel()) != self.S:
+            raise SpiffyError(SPIFFY_ESHAPE, "SeqStepPlan.run: shapes differ from the plan's")
+        E = int(graph_edges.shape[0]) if graph_edges is not None else 0
+        wp, wn = _ws(self.workspace)
+        _check(lib.spiffy_verify_step_seq(
+            C.byref(self.cfg), self.n_layers, self._layers, self._prefix, _ptr(self.w_embed), _ptr(self.final_norm),
+            _ptr(self.w_vocab), _ptr(block_tokens), _ptr(suffix_tokens) if self.S else None, G, self.B, self.S, self.pos0,
+            _ptr(graph_edges) if E else None, E, self.root, self.threshold, self.logit_scale, self.force_one,
+            _ptr(o["hidden"]), _ptr(o["argmax"]), _ptr(o["conf"]), _ptr(o["unmask"]), _ptr(o["margin"]),
+            _ptr(o["target_states"]), _ptr(o["result"]), _ptr(o["accepted_state"]), wp, wn, _stream(stream)),
+            "spiffy_verify_step_seq")
         return o

@@ -247,6 +247,30 @@ def test_subgraph_search_argument_errors():
     assert call(ws=0x100010) == sp.SPIFFY_EALIGN
 
 
+def test_verify_step_seq_argument_errors():
+    cfg = _cfg("c3")
+    w, _ = _layer_structs()
+    layers = (sp.LayerWeights * 1)(w)
+    def call(**k):
+        prefix = (sp.PrefixKV * 1)(sp.PrefixKV(k.get("pk", DUMMY), DUMMY, 64, k.get("cap", 1024), k.get("pS", 0)))
+        return sp.lib.spiffy_verify_step_seq(
+            C.byref(cfg), k.get("L", 1), layers, prefix, DUMMY, DUMMY, DUMMY, DUMMY, k.get("suf", DUMMY), k.get("G", 4), 32,
+            k.get("S", 224), 64, DUMMY, 2, 0, 0.9, 1.0, 1, None, DUMMY, DUMMY, DUMMY, None, None, DUMMY, None,
+            0x100000, k.get("wsb", 16), None)
+    assert call() == sp.SPIFFY_EWORKSPACE                       # every argument check passed
+    assert call(S=0, suf=None) == sp.SPIFFY_EWORKSPACE          # no suffix: the plain step
+    assert call(suf=None) == sp.SPIFFY_EINVAL
+    assert call(S=-1) == sp.SPIFFY_EINVAL
+    assert call(S=5000) == sp.SPIFFY_ESHAPE
+    assert call(cap=64 + 32 + 223) == sp.SPIFFY_ESHAPE          # no room behind the prefix for block and suffix
+    assert call(pS=8) == sp.SPIFFY_EINVAL                       # a cached suffix and a computed one exclude each other
+    assert call(pk=None) == sp.SPIFFY_EINVAL
+    assert call(L=0) == sp.SPIFFY_EINVAL
+    assert sp.lib.spiffy_workspace_bytes_seq(C.byref(cfg), 4, 32, 224, 64) > sp.lib.spiffy_workspace_bytes(C.byref(cfg), 4, 32, 64)
+    assert sp.lib.spiffy_workspace_bytes_seq(C.byref(cfg), 4, 32, 0, 64) == sp.lib.spiffy_workspace_bytes(C.byref(cfg), 4, 32, 64)
+    assert sp.lib.spiffy_workspace_bytes_seq(C.byref(cfg), 4, 32, 5000, 64) == 0
+
+
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     import importlib
     monkeypatch.setattr(sp, "LIB_PATH", str(tmp_path / "nope.so"))

@@ -1223,3 +1223,82 @@ def test_step_replays_from_a_captured_graph(sp):
         for k in keys:
             assert torch.equal(got[k], plan.out[k]), (trial, k)
         assert not torch.equal(got["hidden"], torch.zeros_like(got["hidden"]))
+
+
+# ------------------------------------------------------------------ full-sequence step: the true suffix recomputed in the call
+
+def _seq_setup(sp, cfg, S, seed, scale, tau):
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
+    prefix = [synth.prefix_kv(cfg, l, seed) for l in range(cfg.L)]
+    hw, we = synth.head_weights(cfg, seed), synth.embed_weights(cfg, seed)
+    states, edges = synth.draft_graph("c1", cfg.scaled(G=4), seed)
+    suffix = np.full(S, cfg.mask_id, np.int32)
+    suffix[::5] = 3                                           # a suffix that is not one repeated row
+    caches = []
+    for k, v in prefix:
+        ck = torch.full((cfg.Hkv, cfg.P + cfg.B + S + 2, cfg.hd), 1e4, dtype=k.dtype)
+        cv = torch.full_like(ck, 1e4)
+        ck[:, :cfg.P], cv[:, :cfg.P] = k, v
+        caches.append((ck.to(DEV), cv.to(DEV)))
+    plan = sp.SeqStepPlan(sp.cfg_from_synth(cfg), [sp.layer_weights(dev_weights(w)) for w in layers],
+                          [sp.prefix_kv(k, v, cfg.P) for k, v in caches], we.to(DEV), hw["final_norm"].to(DEV),
+                          hw["w_vocab"].to(DEV), len(states), cfg.B, S, cfg.P, tau, logit_scale=scale, device=DEV)
+    return plan, layers, prefix, hw, we, states, edges, suffix, caches
+
+
+@pytest.mark.parametrize("key,S", [("c1", 16), ("c1", 0), ("bf16_generic", 7), ("bf16_mfma", 96), ("bf16_mfma", 1), ("bf16_mfma_long", 224)])
+def test_step_full_sequence(sp, key, S):
+    """Hidden states of blocks and suffix, decisions and the walk against the oracle; fp32 end to end, bf16 stage-wise.
+    The cache rows behind the prefix are filled with 1e4 before the call: a read of a stale row would show."""
+    if key == "c1":
+        cfg = synth.CONFIGS["c1"]
+    elif key == "bf16_generic":
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", P=37, B=5)
+    elif key == "bf16_mfma":
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=4, Hkv=2, hd=128, F=320, V=640, P=70, B=32)
+    else:
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=640, P=1900, B=32)
+    scale, tau = 8.0, 0.5
+    plan, layers, prefix, hw, we, states, edges, suffix, caches = _seq_setup(sp, cfg, S, 9, scale, tau)
+    out = plan.run(torch.from_numpy(states).to(DEV), torch.from_numpy(suffix).to(DEV),
+                   torch.from_numpy(np.ascontiguousarray(edges)).to(DEV))
+    torch.cuda.synchronize()
+    G = len(states)
+    ref = O().verify_step_fullseq([np_weights(w) for w in layers], [(to_np(k), to_np(v)) for k, v in prefix], to_np(we),
+                                  to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states, suffix, edges, n_q_heads=cfg.Hq,
+                                  n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P, mask_id=cfg.mask_id, threshold=tau,
+                                  rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, logit_scale=scale)
+    hid = to_np(out["hidden"].cpu())
+    bound = 1e-4 if cfg.dtype == "f32" else (2e-2 if cfg.L == 1 else 4e-2)
+    e_b, _ = rel_err(hid[:G * cfg.B].reshape(G, cfg.B, cfg.d), ref["hidden"])
+    assert e_b < bound, e_b
+    if S:
+        e_s, _ = rel_err(hid[G * cfg.B:], ref["hidden_suffix"])
+        assert e_s < bound, e_s
+    masked = states == cfg.mask_id
+    if cfg.dtype == "f32":
+        safe = masked & (ref["margin"] > 1e-3 * scale)
+        np.testing.assert_array_equal(out["argmax"].cpu().numpy()[safe], ref["argmax"][safe])
+    tgt = out["target_states"].cpu().numpy()
+    walk = O().graph_accept(edges, states, tgt, 0)
+    assert tuple(out["result"].cpu().tolist()[:3]) == walk[:3]
+    # the cache: prefix untouched, the slot of the block and the suffix rows rewritten, nothing beyond
+    for (ck, cv), (k, v) in zip(caches, prefix):
+        assert torch.equal(ck[:, :cfg.P].cpu(), k) and torch.equal(cv[:, :cfg.P].cpu(), v)
+        assert (ck[:, cfg.P + cfg.B + S:].cpu() == 1e4).all()
+        if S:
+            assert (ck[:, cfg.P:cfg.P + cfg.B + S].float().abs().cpu() < 1e3).all()
+
+
+def test_step_full_sequence_without_suffix_is_the_step(sp):
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=4, Hkv=2, hd=128, F=320, V=640, P=70, B=32)
+    plan, layers, prefix, hw, we, states, edges, suffix, caches = _seq_setup(sp, cfg, 0, 9, 8.0, 0.5)
+    d_states, d_edges = torch.from_numpy(states).to(DEV), torch.from_numpy(np.ascontiguousarray(edges)).to(DEV)
+    a = {k: v.clone() for k, v in plan.run(d_states, torch.zeros(0, dtype=torch.int32, device=DEV), d_edges).items()}
+    base = sp.StepPlan(plan.cfg, plan._keep[0], [sp.prefix_kv(k.to(DEV), v.to(DEV)) for k, v in prefix], we.to(DEV),
+                       hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), len(states), cfg.B, cfg.P, 0.5, logit_scale=8.0,
+                       device=DEV)
+    b = base.run(d_states, d_edges)
+    torch.cuda.synchronize()
+    for k in ("hidden", "argmax", "conf", "unmask", "target_states", "result", "accepted_state"):
+        assert torch.equal(a[k].reshape(b[k].shape), b[k]), k

@@ -105,15 +105,16 @@ class BlockDecoder:
         self.plan.set_prefix_len(self.P, S=self.S)
 
     def generate(self, n_blocks: int) -> Dict:
-        """Decode n_blocks all-MASK blocks in sequence.  Returns tokens [n_blocks*B] (host), forward passes
-        and accepted depths per block."""
+        """Decode n_blocks all-MASK blocks in sequence.  Returns tokens [n_blocks*B] (host), forward passes,
+        accepted depths and states verified per pass, per block."""
         out_tokens: List[np.ndarray] = []
-        nfe, depths = [], []
+        nfe, depths, n_states = [], [], []
         for _ in range(n_blocks):
             block0 = torch.full((self.B,), self.cfg.mask_id, dtype=torch.int32, device=self.device)
             r = self.decode_block(block0)
             out_tokens.append(r["final"].cpu().numpy())
             nfe.append(r["nfe"])
             depths.append(r["depths"])
+            n_states.append(r["n_states"])
             self.commit(r["final"])
-        return dict(tokens=np.concatenate(out_tokens), nfe=nfe, depths=depths)
+        return dict(tokens=np.concatenate(out_tokens), nfe=nfe, depths=depths, n_states=n_states)

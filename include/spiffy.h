@@ -166,8 +166,10 @@ int spiffy_graph_accept(const int32_t *graph_edges, int32_t E, const int32_t *dr
 /* Drafting source (Sec. 4.4.2, vocabulary sort): the K most likely tokens and their probabilities at every
  * masked position of one node's block, most likely first (equal logits to the lower token id), from the
  * distribution the preceding head pass computed for that node.  Must follow, on the same stream, a
- * spiffy_decode_head (after_step = 0) or spiffy_verify_step (after_step = 1) call with the same cfg, G, B,
- * block_tokens, logit_scale, w_vocab and workspace: it reads what that call left in the workspace (the
+ * spiffy_decode_head, spiffy_verify_step or spiffy_verify_step_seq call with the same cfg, G, B,
+ * block_tokens, logit_scale, w_vocab and workspace (after_step says which kind, 0 = decode_head; every step
+ * keeps the head's scratch at the start of its workspace, so the flag does not change where it is looked
+ * for): it reads what that call left in the workspace (the
  * gathered normalised rows and the per-row / per-vocabulary-chunk summaries) and recomputes only the logits
  * of the K best 128-token chunks of every row.  The node is result->node read on the device (result may be
  * NULL: then `node`, 0 <= node < G).  1 <= K <= SPIFFY_MAX_TOPK.

@@ -383,6 +383,8 @@ def decode_block(model: Dict, block0: np.ndarray, *, drafter: Optional[Drafter] 
     """Decode one block to completion.  ``model`` holds layers, prefix, w_embed,
     final_norm, w_vocab and the keyword settings of ``verify_step``.
 
+    With a "suffix_tokens" entry the forward is that of a full-sequence model (the tokens after the
+    block are recomputed in every pass).
     drafter=None: vanilla loop, one forward per state (G=1, no edges).
     drafter(state, info): returns (draft_states [D,B], edges [E,2] over nodes 0..D with
     node 0 = the true state) to be verified together with the true state.
@@ -403,8 +405,12 @@ def decode_block(model: Dict, block0: np.ndarray, *, drafter: Optional[Drafter] 
         else:
             dr, edges = drafter(state, info)
             states = np.concatenate([state[None, :], np.asarray(dr, np.int32).reshape(-1, state.size)])
-        r = verify_step(model["layers"], model["prefix"], model["w_embed"], model["final_norm"],
-                        model["w_vocab"], states, edges, **kw)
+        if "suffix_tokens" in model:      # full-sequence model with a prefix cache only (Sec. 4.3)
+            r = verify_step_fullseq(model["layers"], model["prefix"], model["w_embed"], model["final_norm"],
+                                    model["w_vocab"], states, model["suffix_tokens"], edges, **kw)
+        else:
+            r = verify_step(model["layers"], model["prefix"], model["w_embed"], model["final_norm"],
+                            model["w_vocab"], states, edges, **kw)
         nfe += 1
         depths.append(r["depth"])
         vacuous = r["depth"] > 0 and not (states[r["node"]] == kw["mask_id"]).any()
@@ -581,7 +587,7 @@ def _attend(q, keys, vals, head_dim):
 def verify_layer_fullseq(w: Dict[str, np.ndarray], prefix_k: np.ndarray, prefix_v: np.ndarray,
                          hidden_blocks: np.ndarray, hidden_suffix: np.ndarray, *, n_q_heads: int,
                          n_kv_heads: int, head_dim: int, pos0: int, rms_eps: float = 1e-5,
-                         rope_base: float = 10000.0):
+                         rope_base: float = 10000.0, return_kv: bool = False):
     """One layer of the verification call of a full-sequence bidirectional model that caches only
     the prefix: hidden_blocks [G,B,d] (block 0 = the true block, the others drafts) and
     hidden_suffix [S,d] (the true tokens after the block) -> (out_blocks, out_suffix).
@@ -639,6 +645,8 @@ def verify_layer_fullseq(w: Dict[str, np.ndarray], prefix_k: np.ndarray, prefix_
         vals = np.concatenate([pv[c], v0[c], vs[c]], axis=0)
         o[:, h, :] = _attend(qs[h], keys, vals, hd)
     out_s = rest(xs, o.reshape(S, Hq * hd)) if S else xs.copy()
+    if return_kv:                                                # rotated keys and values of the true block
+        return out_b, out_s, k0, v0
     return out_b, out_s
 
 

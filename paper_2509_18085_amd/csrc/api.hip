@@ -131,11 +131,13 @@ StepWs carve_step(const spiffy_model_cfg* c, int G, int B, int P, void* base, in
   const size_t M = (size_t)G * B;
   Carve cv(base);
   StepWs w;
-  w.hidden = cv.take((M + S_seq) * c->d * esize(c->dtype));
-  w.target = (int32_t*)cv.take(sizeof(int32_t) * M);
+  // the layer / head scratch comes first, so that the head's leftovers sit at the start of the workspace whatever
+  // G, B, P and S_seq were (spiffy_head_topk finds them there after a step)
   const size_t lb = carve_layer(c, G, B, P, nullptr, S_seq).bytes, hb = carve_head(c, G, B, nullptr).bytes;
   w.rest_bytes = lb > hb ? lb : hb;
   w.rest = cv.take(w.rest_bytes);
+  w.hidden = cv.take((M + S_seq) * c->d * esize(c->dtype));
+  w.target = (int32_t*)cv.take(sizeof(int32_t) * M);
   w.bytes = cv.off;
   return w;
 }
@@ -465,16 +467,11 @@ int spiffy_head_topk(const spiffy_model_cfg* cfg, const void* w_vocab, const int
   if (cfg->dtype == SPIFFY_BF16 && cfg->d % 8 != 0) return SPIFFY_ESHAPE;
   if (!aligned16(w_vocab)) return SPIFFY_EALIGN;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPIFFY_EALIGN;
+  // a step keeps its layer / head scratch at the start of its workspace, so the head's leftovers are found at the
+  // same place after spiffy_decode_head and after a whole step
+  (void)after_step;
   void* head_base = workspace;
-  if (after_step) {
-    // the step's workspace: hidden states, next states, then the scratch the head pass ran in (P does not move it)
-    const StepWs sw = carve_step(cfg, G, B, 0, workspace);
-    if (workspace_bytes < (size_t)((char*)sw.rest - (char*)workspace) + carve_head(cfg, G, B, nullptr).bytes)
-      return SPIFFY_EWORKSPACE;
-    head_base = sw.rest;
-  } else if (workspace_bytes < carve_head(cfg, G, B, nullptr).bytes) {
-    return SPIFFY_EWORKSPACE;
-  }
+  if (workspace_bytes < carve_head(cfg, G, B, nullptr).bytes) return SPIFFY_EWORKSPACE;
   const HeadWs ws = carve_head(cfg, G, B, head_base);
   HeadTopkArgs a;
   a.dtype = cfg->dtype; a.nf = ws.nf; a.w_vocab = w_vocab; a.d = cfg->d; a.V = cfg->vocab; a.scale = logit_scale;

@@ -45,23 +45,40 @@ class BlockDecoder:
     [Hkv, capacity, hd] whose first P0 rows hold the context; graph: DraftGraph or None (vanilla decoding,
     one state per forward pass); d_star: draft nodes kept per step.  S0 > 0: dual cache, rows P0+B .. P0+B+S0-1
     hold fixed keys / values of the tokens after the first block; every committed block takes B rows off it.
+    seq_S0 > 0 (instead of S0): full-sequence model with a prefix cache only: seq_S0 MASK tokens after the first
+    block are recomputed in every pass (spiffy_verify_step_seq); a finished block is committed by one more such
+    pass on its final tokens, which leaves its keys / values in its slot of the cache.
     """
 
     def __init__(self, cfg: sp.ModelCfg, layers: Sequence[Dict[str, torch.Tensor]], cache_k: Sequence[torch.Tensor],
                  cache_v: Sequence[torch.Tensor], P0: int, w_embed: torch.Tensor, final_norm: torch.Tensor,
                  w_vocab: torch.Tensor, B: int, threshold: float, logit_scale: float = 1.0, force_one: bool = True,
-                 graph: Optional[DraftGraph] = None, d_star: int = 0, device="cuda", S0: int = 0):
+                 graph: Optional[DraftGraph] = None, d_star: int = 0, device="cuda", S0: int = 0, seq_S0: int = 0):
         self.cfg, self.B, self.graph, self.device = cfg, B, graph, device
         self.d_star = d_star if graph is not None else 0
         self.logit_scale = logit_scale
         self.P, self.S = P0, S0
         self.capacity = int(cache_k[0].shape[1])
         prefix = [sp.prefix_kv(k, v, P0, S0) for k, v in zip(cache_k, cache_v)]
-        self.plan = sp.StepPlan(cfg, [sp.layer_weights(w) for w in layers], prefix, w_embed, final_norm, w_vocab,
-                                1 + self.d_star, B, P0, threshold, logit_scale=logit_scale, force_one=force_one,
-                                device=device)
-        # the workspace must also fit the longest prefix the cache can hold
-        self.plan.workspace = sp.alloc_workspace(cfg, 1 + self.d_star, B, self.capacity, device)
+        self.seq_S = seq_S0
+        if seq_S0:
+            if S0:
+                raise sp.SpiffyError(sp.SPIFFY_EINVAL, "BlockDecoder: a cached suffix and a recomputed one exclude each other")
+            self.plan = sp.SeqStepPlan(cfg, [sp.layer_weights(w) for w in layers], prefix, w_embed, final_norm, w_vocab,
+                                       1 + self.d_star, B, seq_S0, P0, threshold, logit_scale=logit_scale,
+                                       force_one=force_one, device=device)
+            self.suffix = torch.full((seq_S0,), cfg.mask_id, dtype=torch.int32, device=device)
+        else:
+            self.plan = sp.StepPlan(cfg, [sp.layer_weights(w) for w in layers], prefix, w_embed, final_norm, w_vocab,
+                                    1 + self.d_star, B, P0, threshold, logit_scale=logit_scale, force_one=force_one,
+                                    device=device)
+            # the workspace must also fit the longest prefix the cache can hold
+            self.plan.workspace = sp.alloc_workspace(cfg, 1 + self.d_star, B, self.capacity, device)
+
+    def _step(self, states, edges):
+        if isinstance(self.plan, sp.SeqStepPlan):
+            return self.plan.run(states, self.suffix[:self.seq_S], edges)
+        return self.plan.run(states, edges)
 
     def decode_block(self, block0: torch.Tensor, max_steps: int = 4096) -> Dict:
         """block0 [B] int32 on the device.  Returns the final block (device), the number of forward passes,
@@ -75,7 +92,7 @@ class BlockDecoder:
             cur = states[0].cpu().numpy()
             if not (cur == mask_id).any():
                 break
-            out = self.plan.run(states.contiguous(), edges)
+            out = self._step(states.contiguous(), edges)
             nfe += 1
             n_states.append(int(states.shape[0]))
             res = out["result"].cpu().tolist()
@@ -99,6 +116,17 @@ class BlockDecoder:
         """Append the finished block to the cache; the next block sits right after it."""
         if self.P + self.B > self.capacity:
             raise sp.SpiffyError(sp.SPIFFY_ESHAPE, "BlockDecoder.commit: cache is full")
+        if isinstance(self.plan, sp.SeqStepPlan):
+            if self.seq_S:
+                # one pass on the finished block: every pass with a suffix writes the true block's keys / values
+                # (which depend on the suffix) into its slot
+                self._step(block.to(torch.int32).reshape(1, self.B).contiguous(), None)
+            else:
+                self.plan.commit_block(block.to(torch.int32).contiguous())
+            self.P += self.B
+            self.seq_S = max(0, self.seq_S - self.B)
+            self.plan.set_prefix_len(self.P)
+            return
         self.plan.commit_block(block.to(torch.int32).contiguous())
         self.P += self.B
         self.S = max(0, self.S - self.B)

@@ -388,8 +388,8 @@ class SeqStepPlan(StepPlan):
                  logit_scale: float = 1.0, force_one: bool = True, root: int = 0, device="cuda"):
         super().__init__(cfg, layers, prefix, w_embed, final_norm, w_vocab, G, B, pos0, threshold, logit_scale=logit_scale,
                          force_one=force_one, root=root, device=device)
-        self.S = S
-        P_max = max([p.P for p in prefix], default=0)
+        self.S = self.S_cap = S
+        P_max = max([p.capacity or p.P for p in prefix], default=0)      # room for a prefix that grows by committed blocks
         n = int(lib.spiffy_workspace_bytes_seq(C.byref(cfg), G, B, S, P_max))
         if n == 0:
             raise SpiffyError(SPIFFY_EINVAL, "spiffy_workspace_bytes_seq")
@@ -398,11 +398,14 @@ class SeqStepPlan(StepPlan):
 
     def run(self, block_tokens: torch.Tensor, suffix_tokens: torch.Tensor, graph_edges: Optional[torch.Tensor],
             stream=None) -> Dict[str, torch.Tensor]:
-        """block_tokens [G,B], suffix_tokens [S].  out["hidden"] holds the G*B block rows, then the S suffix rows."""
+        """block_tokens [G,B] and suffix_tokens [S], both within the plan's capacity.  out["hidden"] holds the G*B
+        block rows, then the S suffix rows."""
         o = self.out
         G = int(block_tokens.shape[0])
-        if G != self.G_cap or int(suffix_tokens.numel()) != self.S:
-            raise SpiffyError(SPIFFY_ESHAPE, "SeqStepPlan.run: shapes differ from the plan's")
+        S = int(suffix_tokens.numel()) if suffix_tokens is not None else 0
+        if G > self.G_cap or S > self.S_cap:
+            raise SpiffyError(SPIFFY_ESHAPE, "SeqStepPlan.run: more states or suffix rows than the plan was sized for")
+        self.G, self.S = G, S
         E = int(graph_edges.shape[0]) if graph_edges is not None else 0
         wp, wn = _ws(self.workspace)
         _check(lib.spiffy_verify_step_seq(

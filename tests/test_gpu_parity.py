@@ -1302,3 +1302,73 @@ def test_step_full_sequence_without_suffix_is_the_step(sp):
     torch.cuda.synchronize()
     for k in ("hidden", "argmax", "conf", "unmask", "target_states", "result", "accepted_state"):
         assert torch.equal(a[k].reshape(b[k].shape), b[k]), k
+
+
+def test_decode_full_sequence_matches_the_oracle_loop(sp):
+    """Configuration 1 (fp32), three blocks, the first with 2B MASK tokens behind it that every pass recomputes:
+    device loop = oracle loop (tokens, forward passes, depths), and the same tokens as vanilla decoding.  A
+    finished block's keys / values come from one more pass on its final tokens, with the suffix still behind it."""
+    from paper_2509_18085_amd import decode
+    cfg = synth.CONFIGS["c1"]
+    scale, tau, d_star, seed, S0, n_blocks = 12.0, 0.5, 3, synth.DEFAULT_SEED, 2 * cfg.B, 3
+    formulas = [[(i, 1) for i in range(1, n + 1)] for n in range(1, 5)] + [[(1, 2)], [(1, 1), (2, 2)]]
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
+    prefix = [synth.prefix_kv(cfg, l, seed) for l in range(cfg.L)]
+    hw, we = synth.head_weights(cfg, seed), synth.embed_weights(cfg, seed)
+
+    def run(graph, d):
+        ck, cv = [], []
+        for k, v in prefix:
+            kk = torch.full((cfg.Hkv, cfg.P + n_blocks * cfg.B, cfg.hd), 1e4, dtype=k.dtype)
+            vv = torch.full_like(kk, 1e4)
+            kk[:, :cfg.P], vv[:, :cfg.P] = k, v
+            ck.append(kk.to(DEV))
+            cv.append(vv.to(DEV))
+        dec = decode.BlockDecoder(sp.cfg_from_synth(cfg), [dev_weights(w) for w in layers], ck, cv, cfg.P, we.to(DEV),
+                                  hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), cfg.B, tau, logit_scale=scale,
+                                  graph=graph, d_star=d, device=DEV, seq_S0=S0)
+        return dec.generate(n_blocks), ck, cv
+
+    graph = decode.DraftGraph(formulas, device=DEV)
+    (got, ck, cv), (van, _, _) = run(graph, d_star), run(None, 0)
+    np.testing.assert_array_equal(got["tokens"], van["tokens"])
+    assert sum(got["nfe"]) < sum(van["nfe"])
+
+    lw = [np_weights(w) for w in layers]
+    w_np = dict(w_embed=to_np(we), final_norm=to_np(hw["final_norm"]), w_vocab=to_np(hw["w_vocab"]))
+    pre = [(to_np(k), to_np(v)) for k, v in prefix]
+
+    def drafter(state, info):
+        if not info:
+            return np.zeros((0, state.size), np.int32), np.zeros((0, 2), np.int32)
+        t, p = O().head_topk(info["hidden"][info["node"]], w_np["final_norm"], w_np["w_vocab"], graph.K,
+                             rms_eps=cfg.rms_eps, logit_scale=scale)
+        out = O().draft_and_prune(state, cfg.mask_id, t, p, formulas, graph.edges_np, d_star)
+        return out["states"][1:], out["edges"]
+
+    tokens, nfes, depths = [], [], []
+    P, S = cfg.P, S0
+    for _ in range(n_blocks):
+        kw = dict(n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=P, mask_id=cfg.mask_id, threshold=tau,
+                  rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, logit_scale=scale, force_one=True)
+        suffix = np.full(S, cfg.mask_id, np.int32)
+        model = dict(layers=lw, prefix=pre, kw=kw, suffix_tokens=suffix, **w_np)
+        final, _, nfe, dps, _ = O().decode_block(model, np.full(cfg.B, cfg.mask_id, np.int32), drafter=drafter)
+        tokens.append(final)
+        nfes.append(nfe)
+        depths.append(dps)
+        hb, hs = O().embed(w_np["w_embed"], final[None, :]), O().embed(w_np["w_embed"], suffix)
+        new_pre = []
+        for l in range(cfg.L):
+            hb, hs, k0, v0 = O().verify_layer_fullseq(lw[l], pre[l][0], pre[l][1], hb, hs, return_kv=True,
+                                                      **oracle_kw(cfg, P))
+            new_pre.append((np.concatenate([pre[l][0], k0], axis=1), np.concatenate([pre[l][1], v0], axis=1)))
+        pre = new_pre
+        P, S = P + cfg.B, max(0, S - cfg.B)
+    np.testing.assert_array_equal(got["tokens"], np.concatenate(tokens))
+    assert got["nfe"] == nfes and got["depths"] == depths
+    # the caches now hold the oracle's prefix: context and the three committed blocks
+    for l in range(cfg.L):
+        for got_c, want in ((ck[l], pre[l][0]), (cv[l], pre[l][1])):
+            e_max, _ = rel_err(to_np(got_c.cpu()), want)
+            assert e_max < 1e-4, (l, e_max)

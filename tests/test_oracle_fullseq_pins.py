@@ -46,11 +46,14 @@ def test_dense_mask_formulation_through_all_layers():
     _, Kp, Vp = O.masked_forward(layers, w_embed[prefix_tok], np.arange(cfg.P), np.ones((cfg.P, cfg.P), bool), **kw)
     allow, pos = fig4_mask(cfg.P, cfg.B, cfg.G, S)
     x = w_embed[np.concatenate([prefix_tok, states.reshape(-1), suffix_tok])]
-    hs, _, _ = O.masked_forward(layers, x, pos, allow, **kw)
+    hs, Kd, Vd = O.masked_forward(layers, x, pos, allow, **kw)
     hb, hsuf = O.embed(w_embed, states), O.embed(w_embed, suffix_tok)
     for l, w in enumerate(layers):
-        hb, hsuf = O.verify_layer_fullseq(w, Kp[l], Vp[l], hb, hsuf, pos0=cfg.P, **kw)
+        hb, hsuf, k0, v0 = O.verify_layer_fullseq(w, Kp[l], Vp[l], hb, hsuf, pos0=cfg.P, return_kv=True, **kw)
         ref = hs[l + 1]
+        # the keys / values handed back for the cache are those of the true block in the dense forward
+        np.testing.assert_allclose(k0, Kd[l][:, cfg.P:cfg.P + cfg.B], rtol=1e-10, atol=1e-12)
+        np.testing.assert_allclose(v0, Vd[l][:, cfg.P:cfg.P + cfg.B], rtol=1e-10, atol=1e-12)
         np.testing.assert_allclose(hb, ref[cfg.P:cfg.P + cfg.G * cfg.B].reshape(cfg.G, cfg.B, cfg.d), rtol=1e-10, atol=1e-12)
         np.testing.assert_allclose(hsuf, ref[cfg.P + cfg.G * cfg.B:], rtol=1e-10, atol=1e-12)
     # the mask matters where it should: a draft that sees the true block, or a suffix that sees a draft, differs
@@ -116,3 +119,37 @@ def test_step_head_and_walk_run_on_the_blocks_only():
                          rms_eps=cfg.rms_eps, logit_scale=30.0)
     np.testing.assert_array_equal(r["target_states"], head[4])
     assert (r["node"], r["depth"]) == O.graph_accept(edges, states, head[4], 0)[:2]
+
+
+def test_decode_loop_of_a_full_sequence_model():
+    """The block loop with a recomputed suffix: without a suffix it is the cached loop; with one, every pass is
+    verify_step_fullseq on the current state, and the result does not depend on drafts (App. A)."""
+    cfg, layers, w_embed, prefix_tok, states, suffix_tok = _setup(G=1, B=4)
+    r = np.random.default_rng(2)
+    kw = dict(_kw(cfg), pos0=cfg.P, mask_id=cfg.mask_id, threshold=0.95, logit_scale=2.0, force_one=True)
+    _, Kp, Vp = O.masked_forward(layers, w_embed[prefix_tok], np.arange(cfg.P), np.ones((cfg.P, cfg.P), bool), **_kw(cfg))
+    model = dict(layers=layers, prefix=list(zip(Kp, Vp)), w_embed=w_embed, final_norm=np.ones(cfg.d),
+                 w_vocab=r.standard_normal((cfg.V, cfg.d)) / np.sqrt(cfg.d), kw=kw)
+    block0 = np.full(cfg.B, cfg.mask_id, np.int32)
+    plain = O.decode_block(model, block0)
+    empty = O.decode_block(dict(model, suffix_tokens=suffix_tok[:0]), block0)
+    np.testing.assert_array_equal(plain[0], empty[0])
+    assert plain[2] == empty[2]
+    seq_model = dict(model, suffix_tokens=suffix_tok)
+    van = O.decode_block(seq_model, block0)
+    # every state of the trajectory is one full-sequence step from the one before
+    for a, b in zip(van[1][:-1], van[1][1:]):
+        step = O.verify_step_fullseq(layers, model["prefix"], w_embed, model["final_norm"], model["w_vocab"], a[None],
+                                     suffix_tok, np.zeros((0, 2), np.int32), **kw)
+        np.testing.assert_array_equal(step["accepted_state"], b)
+
+    def drafter(state, info):                      # the right next state (a chain of two) and a wrong one
+        nxt = O.verify_step_fullseq(layers, model["prefix"], w_embed, model["final_norm"], model["w_vocab"], state[None],
+                                    suffix_tok, np.zeros((0, 2), np.int32), **kw)["accepted_state"]
+        wrong = state.copy()
+        wrong[np.flatnonzero(state == cfg.mask_id)[:1]] = 1
+        return np.stack([nxt, wrong]), np.array([[0, 1], [0, 2]], np.int32)
+
+    spec = O.decode_block(seq_model, block0, drafter=drafter)
+    np.testing.assert_array_equal(spec[0], van[0])
+    assert spec[2] < van[2]

@@ -309,6 +309,9 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
   const int m0 = qt * QTILE;
   const int m0w = m0 + qw * 32;
   const int qrow = min(m0w + l32, a.M - 1);
+  // A wavefront pair whose 32 query rows all lie beyond M (one or two states in a 128-row tile) takes part in the
+  // transfers and barriers only: the pairs that do have rows then keep their SIMDs to themselves.
+  const bool active = __builtin_amdgcn_readfirstlane(m0w) < a.M;
 
   WaveState w;
   w.m_run = -INFINITY;
@@ -392,7 +395,7 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
         wait_vmcnt<0>();
         __builtin_amdgcn_s_barrier();
       }
-      if (st == 0) {
+      if (st == 0 && active) {
 #pragma unroll
         for (int sub = 0; sub < 4; ++sub) {
           const int k_lo = c0 + sub * 32;
@@ -439,7 +442,7 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
     if (n_tiles >= 3) wait_vmcnt<2 * DMA_PER_TILE>(); else if (n_tiles == 2) wait_vmcnt<DMA_PER_TILE>(); else wait_vmcnt<0>();
     __builtin_amdgcn_s_barrier();
     f32x16 sa, sb;
-    scores(w, sa, smem, st, lane);
+    if (active) scores(w, sa, smem, st, lane);
     // step t: tile t+1 has landed (tile t+2 may be in flight) and every wavefront is done with step t-1,
     // i.e. with K of tile t and V of tile t-1, whose stage the next prefetch overwrites
     auto sync_and_prefetch = [&](int t) {
@@ -452,18 +455,18 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
     int t = 0;
     for (; t + 2 < n_pipe; t += 2) {     // two steps per trip: the score registers swap roles
       sync_and_prefetch(t);
-      pipe_step<true>(w, sa, sb, k_of(t + 1), v_of(t), st, lane);
+      if (active) pipe_step<true>(w, sa, sb, k_of(t + 1), v_of(t), st, lane);
       sync_and_prefetch(t + 1);
-      pipe_step<true>(w, sb, sa, k_of(t + 2), v_of(t + 1), st, lane);
+      if (active) pipe_step<true>(w, sb, sa, k_of(t + 2), v_of(t + 1), st, lane);
     }
     if (t + 1 < n_pipe) {
       sync_and_prefetch(t);
-      pipe_step<true>(w, sa, sb, k_of(t + 1), v_of(t), st, lane);
+      if (active) pipe_step<true>(w, sa, sb, k_of(t + 1), v_of(t), st, lane);
       sync_and_prefetch(t + 1);
-      pipe_step<false>(w, sb, sa, nullptr, v_of(t + 1), st, lane);
+      if (active) pipe_step<false>(w, sb, sa, nullptr, v_of(t + 1), st, lane);
     } else {
       sync_and_prefetch(t);
-      pipe_step<false>(w, sa, sb, nullptr, v_of(t), st, lane);
+      if (active) pipe_step<false>(w, sa, sb, nullptr, v_of(t), st, lane);
     }
   }
   if (ragged) {
@@ -471,7 +474,7 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
     __builtin_amdgcn_s_barrier();
     const bf16_t* ks = smem + ((n_tiles - 1) % NSTAGE) * STAGE_ELEMS;
     const int nvalid = kend - (kbeg + (n_tiles - 1) * KTILE);
-    process_tile<true>(w, ks, ks + TILE_ELEMS, st, lane, [nvalid](int key) { return key < nvalid; });
+    if (active) process_tile<true>(w, ks, ks + TILE_ELEMS, st, lane, [nvalid](int key) { return key < nvalid; });
   }
   __syncthreads();   // all tiles consumed, no DMA in flight: the ring can be reused
   }

@@ -50,11 +50,17 @@ __device__ __forceinline__ void wait_vmcnt() {   // vmcnt <= N; lgkmcnt / expcnt
 __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 // 64-row tiles, and 128-row tiles up to 128 columns wide, are weight-streaming shapes: both operand rings SD deep
-constexpr bool uniform_rings(int epi, int bn, int bmt) { return epi != EPI_LMHEAD && (bmt == 64 || (bmt == 128 && bn <= 128)); }
+constexpr bool uniform_rings(int epi, int bn, int bmt) { return epi != EPI_LMHEAD && (bmt <= 64 || (bmt == 128 && bn <= 128)); }
+// wavefronts of a workgroup: a 2 x 2 grid over the tile; a 32-row or 32-column tile has one wavefront along that side
+constexpr int waves_m(int bmt) { return bmt >= 64 ? 2 : 1; }
+constexpr int waves_n(int bn) { return bn >= 64 ? 2 : 1; }
 
 template <int EPI, int BN, int SD, int BMT = 256>
 __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int tiles_i, int tiles_j) {
-  constexpr int BM = BMT;                         // rows of the output tile: 256, or 128 / 64 when there are few rows
+  constexpr int BM = BMT;                         // rows of the output tile: 256, or 128 / 64 / 32 when there are few rows
+  constexpr int WM = waves_m(BMT), WN = waves_n(BN), NW = WM * WN;
+  constexpr int RW = BM / WM, CW = BN / WN;       // rows and columns of the tile that one wavefront owns
+  static_assert(EPI != EPI_LMHEAD || NW == 4, "the LM-head epilogue assumes the 2 x 2 wavefront grid");
   // which operand is the weight matrix (deep ring): Y for the projections, X for the LM head
   constexpr bool XDEEP = (EPI == EPI_LMHEAD);
   // UNI (64-row and narrow 128-row tiles, weight-streaming problems): both operands ride rings of SD stages and every load runs
@@ -63,8 +69,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   // so only the newest weight tile can stay in flight.
   constexpr bool UNI = uniform_rings(EPI, BN, BMT);
   constexpr int SX = XDEEP ? SD : (UNI ? SD : 2), SY = XDEEP ? 2 : SD;
-  constexpr int TM = BM / 64, TN = BN / 64;
-  constexpr int LX = BM / 32, LY = BN / 32;       // 1-KB wave-loads (8 rows x 128 B) per wavefront per K-tile
+  constexpr int TM = RW / 32, TN = CW / 32;
+  constexpr int LX = BM / (8 * NW), LY = BN / (8 * NW);   // 1-KB wave-loads (8 rows x 128 B) per wavefront per K-tile
   constexpr int NL = LX + LY;
   constexpr int XSTAGE = BM * BKK, YSTAGE = BN * BKK;
   constexpr int NMF = TM * TN, NF = TM + TN;
@@ -75,7 +81,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 
   // the wavefront id is uniform: keep it (and all LDS destination arithmetic) in scalar registers
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, hh = lane >> 5;
 
   int i_max, j_max, kz, ti, tj;
@@ -214,8 +220,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   for (int idx = 0; idx < NL / 4; ++idx) group_load(idx, -1);
 
   const int sw_r = (l32 >> 1) & 7;
-  const int xrow = (wm * (BM / 2) + l32) * BKK;
-  const int yrow = (wn * (BN / 2) + l32) * BKK;
+  const int xrow = (wm * RW + l32) * BKK;
+  const int yrow = (wn * CW + l32) * BKK;
   bf16x8 fx[2][TM], fy[2][TN];
   auto ldfrag = [&](int buf, const bf16_t* xs, const bf16_t* ys, int kk, int r) {
     const int slot = ((kk * 2 + hh) ^ sw_r) * 8;
@@ -254,7 +260,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 #pragma unroll
         for (int r = frag_lo(m); r < frag_lo(m + 1); ++r) ldfrag((kk + 1) & 1, xs, ys, kk + 1, r);
         const int slot = NMF + kk * NMF + m;      // position among the NSLOT MFMAs that follow barrier kt-1
-        if (((slot + 1) * NL) / NSLOT != (slot * NL) / NSLOT) group_load((slot * NL) / NSLOT, kt - 1, !STEADY);
+#pragma unroll
+        for (int idx = (slot * NL) / NSLOT; idx < ((slot + 1) * NL) / NSLOT; ++idx) group_load(idx, kt - 1, !STEADY);
         __builtin_amdgcn_sched_barrier(0);
       }
     }
@@ -272,7 +279,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
       acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[1][i], fy[1][j], acc[i][j], 0, 0, 0);
 #pragma unroll
       for (int r = frag_lo(m); r < frag_lo(m + 1); ++r) ldfrag(0, xs1, ys1, 0, r);
-      if (((m + 1) * NL) / NSLOT != (m * NL) / NSLOT) group_load((m * NL) / NSLOT, kt, !STEADY);
+#pragma unroll
+      for (int idx = (m * NL) / NSLOT; idx < ((m + 1) * NL) / NSLOT; ++idx) group_load(idx, kt, !STEADY);
       __builtin_amdgcn_sched_barrier(0);
     }
   };
@@ -284,8 +292,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   }
   for (; kt < KT; ++kt) k_tile(kt, std::false_type{});
 
-  // accumulator element (i,j,v) of this lane: row  = i0 + wm*128 + i*32 + 8*(v/4) + 4*hh + v%4
-  //                                           col  = wn*(BN/2) + j*32 + l32   (within the tile)
+  // accumulator element (i,j,v) of this lane: row  = i0 + wm*RW + i*32 + 8*(v/4) + 4*hh + v%4
+  //                                           col  = wn*CW + j*32 + l32   (within the tile)
   if (EPI == EPI_LMHEAD) {
     // Per token column: top value, its lowest vocabulary index, runner-up and sum of exponentials over the
     // lane's 64 vocabulary rows, on the unscaled accumulators (the scale is positive, so the order is the
@@ -305,7 +313,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
           for (int v = 0; v < 16; ++v) {
             float l = acc[i][j][v];
             if (CHECKED) {
-              const int idx = i0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+              const int idx = i0 + wm * RW + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
               if (idx >= i_max) l = -INFINITY;
               acc[i][j][v] = l;
             }
@@ -325,9 +333,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
         t.m2 = m2 * a.scale;
         t.s = sum;
         t.idx = (m == -INFINITY) ? 0x7fffffff
-                                 : i0 + wm * (BM / 2) + (code >> 4) * 32 + 8 * ((code & 15) >> 2) + 4 * hh + (code & 3);
+                                 : i0 + wm * RW + (code >> 4) * 32 + 8 * ((code & 15) >> 2) + 4 * hh + (code & 3);
         t = top_merge(t, top_shfl_xor(t, 32));
-        const int tokr = j0 + wn * (BN / 2) + j * 32 + l32;
+        const int tokr = j0 + wn * CW + j * 32 + l32;
         if (hh == 0 && tokr < j_max) part[(size_t)(ti * 2 + wm) * a.ldc + tokr] = TopPartial{t.m, t.m2, t.s, t.idx};
       }
     };
@@ -341,10 +349,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int r = i0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
+        const int r = i0 + wm * RW + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);
         if (r >= i_max) continue;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) P[(size_t)r * a.ldc + j0 + wn * (BN / 2) + j * 32 + l32] = acc[i][j][v];
+        for (int j = 0; j < TN; ++j) P[(size_t)r * a.ldc + j0 + wn * CW + j * 32 + l32] = acc[i][j][v];
       }
     return;
   }
@@ -362,7 +370,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-        const int r = i0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the gate lane's row
+        const int r = i0 + wm * RW + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the gate lane's row
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           float a0 = acc[i][j][v], a1 = acc[i][j][v + 1];
@@ -386,7 +394,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   float bv[TN];
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
-    const int n = j0 + wn * (BN / 2) + j * 32 + l32;
+    const int n = j0 + wn * CW + j * 32 + l32;
     bv[j] = 0.f;
     if (has_bias) {
       const bf16_t* bp = nullptr;
@@ -397,7 +405,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     }
   }
   // per-lane part of the address once; the row part below is the same for every lane of the half
-  const size_t lane_off = (size_t)odd * a.ldc + (j0 + wn * (BN / 2) + l32 - odd);
+  const size_t lane_off = (size_t)odd * a.ldc + (j0 + wn * CW + l32 - odd);
   bf16_t* Cl = C + lane_off;
   const bf16_t* Rl = R + lane_off;
   auto store_all = [&](auto checked_tag) {
@@ -406,7 +414,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     for (int i = 0; i < TM; ++i)
 #pragma unroll
       for (int v = 0; v < 16; v += 2) {
-        const int r = i0 + wm * (BM / 2) + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the even lane's row
+        const int r = i0 + wm * RW + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the even lane's row
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
           float a0 = acc[i][j][v] + bv[j], a1 = acc[i][j][v + 1] + bv[j];
@@ -443,7 +451,7 @@ hipError_t launch_t(const GemmArgs& a, int tiles_i, int tiles_j, hipStream_t st)
   const hipError_t e = allow_dynamic_lds((const void*)gemm_bf16_mfma_kernel<EPI, BN, SD, BMT>,
                                          (int)smem_bytes<EPI, BN, SD, BMT>(), lds_ok);
   if (e != hipSuccess) return e;
-  gemm_bf16_mfma_kernel<EPI, BN, SD, BMT><<<tiles_i * tiles_j * a.ksplit, 256, smem_bytes<EPI, BN, SD, BMT>(), st>>>(a, tiles_i, tiles_j);
+  gemm_bf16_mfma_kernel<EPI, BN, SD, BMT><<<tiles_i * tiles_j * a.ksplit, 64 * waves_m(BMT) * waves_n(BN), smem_bytes<EPI, BN, SD, BMT>(), st>>>(a, tiles_i, tiles_j);
   return hipGetLastError();
 }
 
@@ -523,17 +531,19 @@ int mfma_lmhead_partials_per_row(int V) { return cdiv(V, BM) * 2; }
 // (one or a few states) the projections are weight-streaming problems: 64- and 128-row tiles spend a quarter
 // or half of the matrix work of a 256-row tile on them and cover more CUs.
 struct TileShape { int bm, bn; };
-static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow192) {
-  const int heights[3] = {256, 128, 64};
-  const int widths[3] = {192, 128, 64};
-  const float eff[3] = {1.0f, 0.85f, 0.55f};
+static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow192, bool allow32 = false) {
+  const int heights[4] = {256, 128, 64, 32};
+  const int widths[4] = {192, 128, 64, 32};
+  const float eff[4] = {1.0f, 0.85f, 0.55f, 0.4f};
   TileShape best = {256, 0};
   float best_cost = 1e30f;
-  for (int h = 0; h < 3; ++h)
-    for (int i = 0; i < 3; ++i) {
+  for (int h = 0; h < 4; ++h)
+    for (int i = 0; i < 4; ++i) {
       const int bm = heights[h], bn = widths[i];
       const int cols = bn / unit;                 // output columns (or SwiGLU features) per tile
-      if ((bn == 192 && (!allow192 || bm == 64)) || (bn == 64 && bm == 128) || n_cols % cols != 0) continue;
+      if ((bn == 192 && (!allow192 || bm <= 64)) || (bn == 64 && bm == 128) || n_cols % cols != 0) continue;
+      // 32-wide tiles (one or two wavefronts per workgroup) exist for the split-K projections of one or two states
+      if ((bn == 32 || bm == 32) && !(allow32 && bn == 32 && bm <= 64)) continue;
       const int tiles = cdiv(M, bm) * (n_cols / cols) * ksplit;
       const float mfma = (float)(bm / 64) * (float)(bn / 64) * 128.0f / eff[i];
       const float load = (float)(bm + bn) * 3.2f;
@@ -557,6 +567,10 @@ static hipError_t launch_shape(const GemmArgs& a, TileShape t, int unit, hipStre
     if constexpr (W192) if (t.bn == 192) return launch_t<EPI, 192, 4, 128>(a, mt, nt, st);
     return launch_t<EPI, 128, 4, 128>(a, mt, nt, st);
   }
+  if constexpr (EPI == EPI_PARTIAL) {
+    if (t.bm == 32) return launch_t<EPI, 32, 9, 32>(a, mt, nt, st);
+    if (t.bn == 32) return launch_t<EPI, 32, 10, 64>(a, mt, nt, st);
+  }
   if (t.bn == 64) return launch_t<EPI, 64, 8, 64>(a, mt, nt, st);
   return launch_t<EPI, 128, 6, 64>(a, mt, nt, st);
 }
@@ -574,7 +588,7 @@ hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
       return launch_t<EPI_RESID, 128, 4>(a, mt, a.N / 128, st);
     }
     case EPI_PARTIAL:
-      return launch_shape<EPI_PARTIAL>(a, choose_tile(a.M, a.N, 1, a.ksplit, false), 1, st);
+      return launch_shape<EPI_PARTIAL>(a, choose_tile(a.M, a.N, 1, a.ksplit, false, true), 1, st);
     case EPI_SWIGLU:
       return launch_shape<EPI_SWIGLU>(a, choose_tile(a.M, a.N, 2, 1, true), 2, st);   // a tile of width w holds w/2 features
     case EPI_LMHEAD:

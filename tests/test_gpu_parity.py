@@ -212,14 +212,14 @@ def test_layer_mfma_batch_invariance_and_duplicates(sp):
 
 
 def test_layer_rows_are_bit_identical_across_tile_heights(sp):
-    """1, 4, 8 and 32 states run the projections on 64-, 128- and 256-row tiles (weight streaming with few rows):
+    """1 to 32 states run the projections on 32-, 64-, 128- and 256-row tiles (weight streaming with few rows):
     the tile shape is scheduling only, every state's rows come out bit-identical."""
     cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=1024, Hq=8, Hkv=8, hd=128, F=3072, P=200, B=32, G=32, V=1280)
     w = synth.layer_weights(cfg, 0)
     pk, pv = synth.prefix_kv(cfg, 0)
     x = synth.hidden_states(cfg)
     full = run_layer(sp, cfg, w, pk, pv, x)
-    for lo, n in ((5, 1), (8, 4), (16, 8), (0, 16)):
+    for lo, n in ((5, 1), (2, 2), (29, 3), (8, 4), (16, 8), (0, 16)):
         part = run_layer(sp, cfg, w, pk, pv, x[lo:lo + n].contiguous())
         assert torch.equal(part, full[lo:lo + n]), (lo, n)
     ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), to_np(x[5:6]), **oracle_kw(cfg))
@@ -465,6 +465,25 @@ def test_gemm_against_float64_matmul(sp, M, N, K, epi):
         ref = gg / (1.0 + np.exp(-gg)) * (a @ w1.T)
     torch.cuda.synchronize()
     e_max, e_norm = rel_err(to_np(got.cpu()), ref)
+    assert e_max < 1e-2 and e_norm < 4e-3, (e_max, e_norm)
+
+
+@pytest.mark.parametrize("N,K", [(4096, 4096), (4096, 12288), (1024, 2048)])
+def test_split_k_projection_rows_do_not_depend_on_the_row_count(sp, N, K):
+    """Output / down projection shapes: 32, 64, 96, 128 and 256 rows run on 32x32 (one wavefront), 64x32 (two),
+    64x64 and taller tiles; the K slices and the order inside a slice are the same, so the first rows come out
+    bit-identical, and they match the float64 product."""
+    g = torch.Generator().manual_seed(N + K)
+    A = (torch.randn((256, K), generator=g) * 0.5).to(torch.bfloat16).to(DEV)
+    W = (torch.randn((N, K), generator=g) * 0.03).to(torch.bfloat16).to(DEV)
+    R = torch.randn((256, N), generator=g).to(torch.bfloat16).to(DEV)
+    ws = torch.empty(4 * 256 * N * 4 + 256, dtype=torch.uint8, device=DEV)
+    full = sp.gemm(sp.GEMM_RESID, A, W, R=R, workspace=ws).clone()
+    for n in (32, 64, 96, 128, 17, 45):
+        part = sp.gemm(sp.GEMM_RESID, A[:n].contiguous(), W, R=R[:n].contiguous(), workspace=ws)
+        assert torch.equal(part, full[:n]), n
+    ref = to_np(R.cpu()) + to_np(A.cpu()) @ to_np(W.cpu()).T
+    e_max, e_norm = rel_err(to_np(full.cpu()), ref)
     assert e_max < 1e-2 and e_norm < 4e-3, (e_max, e_norm)
 
 

@@ -6,7 +6,9 @@
 //     wavefront owns 128 x BN/2 (accumulators in AGPRs).  The L2 delivers about 32 B/clk to a CU, so
 //     a tile needs >= 64..128 flop per loaded byte; 128x128 tiles are bound by that, 256x192 is not.
 //     With few rows (one to eight states) the projections only stream weights: the same kernel with
-//     128- or 64-row tiles does half or a quarter of the matrix work per tile and covers more CUs.
+//     128- or 64-row tiles does half or a quarter of the matrix work per tile and covers more CUs; the
+//     narrow split-K projections of one or two states take 32-column tiles with one wavefront along a
+//     32-wide side (64 x 32: two wavefronts, 32 x 32: one), so 256 workgroups stream instead of 128.
 //   * K advances in steps of 64 so every row segment is one full 128-byte line; operands go
 //     global -> LDS directly (LDS-DMA loads, no register staging), rows XOR-swizzled so the
 //     16-byte fragment reads are conflict-free.

@@ -269,6 +269,27 @@ def decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev, n_blocks=8):
         dec.plan.commit_block(block)
     e1.record()
     torch.cuda.synchronize()
+    # the first pass of a block, with the previous block's commit as a pass of its own and folded in
+    dec.P -= cfg.B
+    dec.plan.set_prefix_len(dec.P)
+    one = torch.full((1, cfg.B), cfg.mask_id, dtype=torch.int32, device=dev)
+
+    def separate():
+        dec.plan.commit_block(block)
+        dec.plan.set_prefix_len(dec.P + cfg.B)
+        dec.plan.run(one, None)
+        dec.plan.set_prefix_len(dec.P)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / 3
+
+    sep_ms, fused_ms = timed(separate), timed(lambda: dec.plan.run_commit(block, one, None))
     tokens = n_blocks * cfg.B
     return {"blocks": n_blocks, "tokens": tokens, "forward_passes": nfe, "states_verified": states, "ms": ms,
             "ms_per_forward_pass": ms / max(1, nfe), "tokens_per_s": tokens / (ms * 1e-3), "states_per_s": states / (ms * 1e-3),
@@ -277,7 +298,8 @@ def decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev, n_blocks=8):
                         "tokens_per_s": tokens / (v_ms * 1e-3)},
             "same_tokens_as_vanilla": bool((g["tokens"] == v["tokens"]).all()),
             "commit_block_ms": e0.elapsed_time(e1) / 3,
-            "note": "each time includes the 8 commits, top-K, drafting, pruning and the host reads of the accept result; "
+            "block_start_ms": {"commit_then_first_pass": sep_ms, "one_fused_pass": fused_ms},
+            "note": "each time includes the commits (folded into the next block's first pass, the last one a pass of its own), top-K, drafting, pruning and the host reads of the accept result; "
                     "a block's first pass has one state, later passes one state per formula that the remaining MASK "
                     "positions can still build; random weights: drafts built from the previous distribution are rarely "
                     "accepted, so the ratio of the two times is mostly the cost of verifying up to G-1 drafts per pass; "

@@ -166,7 +166,7 @@ int spiffy_graph_accept(const int32_t *graph_edges, int32_t E, const int32_t *dr
 /* Drafting source (Sec. 4.4.2, vocabulary sort): the K most likely tokens and their probabilities at every
  * masked position of one node's block, most likely first (equal logits to the lower token id), from the
  * distribution the preceding head pass computed for that node.  Must follow, on the same stream, a
- * spiffy_decode_head, spiffy_verify_step or spiffy_verify_step_seq call with the same cfg, G, B,
+ * spiffy_decode_head, spiffy_verify_step, spiffy_verify_step_seq or spiffy_verify_step_commit call with the same cfg, G, B,
  * block_tokens, logit_scale, w_vocab and workspace (after_step says which kind, 0 = decode_head; every step
  * keeps the head's scratch at the start of its workspace, so the flag does not change where it is looked
  * for): it reads what that call left in the workspace (the
@@ -254,6 +254,29 @@ int spiffy_verify_step_seq(const spiffy_model_cfg *cfg, int32_t n_layers, const 
 int spiffy_commit_block(const spiffy_model_cfg *cfg, int32_t n_layers, const spiffy_layer_weights *layers,
                         const spiffy_prefix_kv *prefix, const void *w_embed, const int32_t *block_tokens,
                         int32_t B, int32_t pos0, void *workspace, size_t workspace_bytes, void *stream);
+
+/* spiffy_commit_block of the block just finished and spiffy_verify_step of the first state(s) of the next block
+ * in ONE pass over the weights (with few states the step only streams weights, so two passes cost twice one;
+ * prefix caching, Sec. 3.1, and the step of Alg. 1).  prev_block_tokens [B] (device) is the finished block, at
+ * positions pos0-B .. pos0-1, with prefix[l].P rows in front of it; its keys / values are written to cache rows
+ * P .. P+B-1 of every layer (capacity >= P + B), exactly as spiffy_commit_block writes them.  block_tokens [G,B]
+ * are the states of the block at positions pos0 .. pos0+B-1: they attend to the P + B rows that are the prefix
+ * once the call has written them (and, with prefix[l].S > 0, to the S - B suffix rows behind their own slot, while
+ * the finished block attends to all S, as in the two separate calls).  Results: those of spiffy_commit_block
+ * followed by spiffy_verify_step with P + B (and S - B), bit for bit.  The structs are not modified: the caller
+ * adds B to every P (and takes B off every S) afterwards.  hidden_out [G*B + B, d] (the states' rows, then the
+ * finished block's; may be NULL).  pos0 >= B; (G + 1) * B <= SPIFFY_MAX_ROWS.  Workspace from
+ * spiffy_workspace_bytes_commit (P_max = the largest P + S).  Other arguments and errors as for
+ * spiffy_verify_step. */
+size_t spiffy_workspace_bytes_commit(const spiffy_model_cfg *cfg, int32_t G, int32_t B, int32_t P_max);
+int spiffy_verify_step_commit(const spiffy_model_cfg *cfg, int32_t n_layers, const spiffy_layer_weights *layers,
+                              const spiffy_prefix_kv *prefix, const void *w_embed, const void *final_norm,
+                              const void *w_vocab, const int32_t *prev_block_tokens, const int32_t *block_tokens,
+                              int32_t G, int32_t B, int32_t pos0, const int32_t *graph_edges, int32_t E,
+                              int32_t root, float threshold, float logit_scale, int32_t force_one, void *hidden_out,
+                              int32_t *argmax, float *conf, uint8_t *unmask, float *top2_margin,
+                              int32_t *target_states, spiffy_accept_result *result, int32_t *accepted_state,
+                              void *workspace, size_t workspace_bytes, void *stream);
 
 /* Offline calibration, part 3 (Alg. 2; App. D.1): the optimal subgraph of the candidate graph.  The graph has
  * N <= 64 nodes (draft formulas q_kv); count [N] is each node's frequency, level [N] its 1-based level k, edges

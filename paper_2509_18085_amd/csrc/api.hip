@@ -172,6 +172,10 @@ struct LayerChain {
   bool append_kv = false;    // write the (rotated) K and V rows of state 0 into the cache at rows P .. P+B-1
   int seq_S = 0;             // full-sequence step: this many true suffix rows follow the G*B block rows
   bool rope_ready_seq = false;
+  // commit-and-verify step (seq_S == B): the trailing B rows are the finished block BEFORE the one being decoded.
+  // prefix->P counts the rows in front of that finished block; its keys / values are written to cache rows
+  // P .. P+B-1 and the G states (positions pos0 = that block's + B) attend to P + B cached rows.
+  bool tail_is_prev_block = false;
 };
 
 // The same product as two launches over the row ranges [0, rows_a) and [rows_a, rows_a + rows_b): each range gets the
@@ -180,6 +184,12 @@ struct LayerChain {
 hipError_t launch_gemm_mfma_rows(int epi, GemmArgs g, int rows_a, int rows_b, int dtype, hipStream_t st) {
   const size_t es = esize(dtype), ces = epi == EPI_PARTIAL ? sizeof(float) : es;
   g.Mz = rows_a + rows_b;
+  // one launch when there are few rows in all (weight streaming sets the time: stream them once, not twice) or
+  // when the second range adds no 256-row tile
+  if (rows_a + rows_b <= 512 || cdiv(rows_a + rows_b, 256) == cdiv(rows_a, 256)) {
+    g.M = rows_a + rows_b;
+    return launch_gemm_mfma(epi, g, st);
+  }
   GemmArgs a = g;
   a.M = rows_a;
   hipError_t e = launch_gemm_mfma(epi, a, st);
@@ -200,6 +210,7 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   // rows behind the prefix, where the blocks find the suffix (as in the dual-cache layout) and the suffix rows
   // find the whole true sequence.
   const int S_seq = chain ? chain->seq_S : 0;
+  const bool prev = chain && chain->tail_is_prev_block;
   const int M = G * B + S_seq, d = cfg->d, dt = cfg->dtype;
   const int qd = cfg->n_q_heads * cfg->head_dim, kvd = cfg->n_kv_heads * cfg->head_dim;
   const bool mf = layer_mfma(cfg);
@@ -228,18 +239,23 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   a.G = G; a.B = B; a.Hq = cfg->n_q_heads; a.Hkv = cfg->n_kv_heads; a.hd = cfg->head_dim; a.P = prefix->P;
   a.ldp = prefix->capacity;
   a.S = S_seq ? S_seq : prefix->S;
+  if (prev) {                // the finished block has joined the prefix; a cached suffix loses the current block's slot
+    a.P = prefix->P + B;
+    a.S = prefix->S > B ? prefix->S - B : 0;
+  }
   a.own = 1;
   a.pos0 = pos0; a.rope_base = cfg->rope_base; a.rope_ready = chain && chain->rope_ready;
   const int ldp = prefix->capacity ? prefix->capacity : prefix->P;
-  if (chain && (chain->append_kv || S_seq) &&
+  if (chain && (chain->append_kv || (S_seq && !prev)) &&
       (rc = dev(launch_kv_append(dt, ws.qkv, a.Hq, a.Hkv, a.hd, B, pos0, cfg->rope_base,
                                  const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st))))
     return rc;
   if (S_seq) {
     const size_t es = esize(dt);
     const char* qkv_seq = reinterpret_cast<const char*>(ws.qkv) + (size_t)G * B * g.N * es;
-    if ((rc = dev(launch_kv_append(dt, qkv_seq, a.Hq, a.Hkv, a.hd, S_seq, pos0 + B, cfg->rope_base,
-                                   const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P + B, ldp, st))))
+    if ((rc = dev(launch_kv_append(dt, qkv_seq, a.Hq, a.Hkv, a.hd, S_seq, prev ? pos0 - B : pos0 + B, cfg->rope_base,
+                                   const_cast<void*>(prefix->k), const_cast<void*>(prefix->v),
+                                   prev ? prefix->P : prefix->P + B, ldp, st))))
       return rc;
   }
   if ((rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st)))) return rc;
@@ -251,6 +267,9 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
     b.partial = ws.attn_partial_seq;
     b.G = 1; b.B = S_seq; b.P = prefix->P + B + S_seq; b.S = 0; b.own = 0;
     b.pos0 = pos0 + B; b.rope_ready = chain->rope_ready_seq;
+    if (prev) {     // the finished block: one state at the positions before pos0, over the rows in front of it
+      b.P = prefix->P; b.S = prefix->S; b.own = 1; b.pos0 = pos0 - B;
+    }
     if ((rc = dev(mf && mfma_attn_supported(b) ? launch_attn_mfma(b, st) : launch_attn_generic(dt, b, st)))) return rc;
   }
 
@@ -593,6 +612,63 @@ int spiffy_verify_step_seq(const spiffy_model_cfg* cfg, int32_t n_layers, const 
   }
   LayerChain chain;
   chain.seq_S = S;
+  for (int l = 0; l < n_layers; ++l) {
+    chain.normed_in = chain.normed_out;
+    chain.next_norm1 = (l + 1 < n_layers) ? layers[l + 1].norm1 : nullptr;
+    if ((rc = run_layer(cfg, &layers[l], &prefix[l], hid, G, B, pos0, hid, ws.rest, st, &chain))) return rc;
+    chain.rope_ready = true;
+    chain.rope_ready_seq = true;
+  }
+  if ((rc = run_head(cfg, hid, final_norm, w_vocab, block_tokens, nullptr, G, B, threshold, logit_scale, force_one,
+                     argmax, conf, unmask, top2_margin, tgt, ws.rest, st)))
+    return rc;
+  return dev(launch_graph_accept(graph_edges, E, block_tokens, tgt, G, B, root, result, accepted_state, st));
+}
+
+size_t spiffy_workspace_bytes_commit(const spiffy_model_cfg* cfg, int32_t G, int32_t B, int32_t P_max) {
+  if (check_cfg(cfg) || check_gb(G, B) || check_gb(G + 1, B) || P_max < 0) return 0;
+  return carve_step(cfg, G, B, P_max, nullptr, B).bytes;
+}
+
+int spiffy_verify_step_commit(const spiffy_model_cfg* cfg, int32_t n_layers, const spiffy_layer_weights* layers,
+                              const spiffy_prefix_kv* prefix, const void* w_embed, const void* final_norm,
+                              const void* w_vocab, const int32_t* prev_block_tokens, const int32_t* block_tokens,
+                              int32_t G, int32_t B, int32_t pos0, const int32_t* graph_edges, int32_t E, int32_t root,
+                              float threshold, float logit_scale, int32_t force_one, void* hidden_out, int32_t* argmax,
+                              float* conf, uint8_t* unmask, float* top2_margin, int32_t* target_states,
+                              spiffy_accept_result* result, int32_t* accepted_state, void* workspace,
+                              size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(G, B)) || (rc = check_gb(G + 1, B))) return rc;
+  if (n_layers < 1 || !layers || !prefix || !w_embed || !workspace || !prev_block_tokens || pos0 < B) return SPIFFY_EINVAL;
+  if (!aligned16(w_embed) || (hidden_out && !aligned16(hidden_out)) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SPIFFY_EALIGN;
+  int P_max = 0;
+  for (int l = 0; l < n_layers; ++l) {
+    if ((rc = check_layer_args(cfg, &layers[l], &prefix[l], G, B))) return rc;
+    if (!prefix[l].k || !prefix[l].v) return SPIFFY_EINVAL;            // the finished block's rows are written
+    const int cap = prefix[l].capacity ? prefix[l].capacity : prefix[l].P;
+    if ((int64_t)prefix[l].P + B > cap) return SPIFFY_ESHAPE;
+    if (!layer_mfma(cfg) && generic_attn_smem(cfg, B, prefix[l].P + B + prefix[l].S) > kMaxGenericSmem) return SPIFFY_ESHAPE;
+    if (prefix[l].P + prefix[l].S > P_max) P_max = prefix[l].P + prefix[l].S;
+  }
+  if ((rc = check_head_args(cfg, workspace, final_norm, w_vocab, block_tokens, threshold, logit_scale, argmax, conf,
+                            unmask)))
+    return rc;
+  const int32_t* tgt_probe = target_states ? target_states : reinterpret_cast<const int32_t*>(workspace);
+  if ((rc = check_accept_args(graph_edges, E, block_tokens, tgt_probe, G, B, root, result))) return rc;
+  const StepWs ws = carve_step(cfg, G, B, P_max, workspace, B);
+  if (workspace_bytes < ws.bytes) return SPIFFY_EWORKSPACE;
+
+  hipStream_t st = (hipStream_t)stream;
+  void* hid = hidden_out ? hidden_out : ws.hidden;
+  int32_t* tgt = target_states ? target_states : ws.target;
+  void* hid_prev = reinterpret_cast<char*>(hid) + (size_t)G * B * cfg->d * esize(cfg->dtype);
+  if ((rc = dev(launch_embed(cfg->dtype, w_embed, block_tokens, G * B, cfg->d, cfg->vocab, hid, st)))) return rc;
+  if ((rc = dev(launch_embed(cfg->dtype, w_embed, prev_block_tokens, B, cfg->d, cfg->vocab, hid_prev, st)))) return rc;
+  LayerChain chain;
+  chain.seq_S = B;
+  chain.tail_is_prev_block = true;
   for (int l = 0; l < n_layers; ++l) {
     chain.normed_in = chain.normed_out;
     chain.next_norm1 = (l + 1 < n_layers) ? layers[l + 1].norm1 : nullptr;

@@ -61,6 +61,7 @@ class BlockDecoder:
         self.capacity = int(cache_k[0].shape[1])
         prefix = [sp.prefix_kv(k, v, P0, S0) for k, v in zip(cache_k, cache_v)]
         self.seq_S = seq_S0
+        self._pending = None
         if seq_S0:
             if S0:
                 raise sp.SpiffyError(sp.SPIFFY_EINVAL, "BlockDecoder: a cached suffix and a recomputed one exclude each other")
@@ -78,7 +79,25 @@ class BlockDecoder:
     def _step(self, states, edges):
         if isinstance(self.plan, sp.SeqStepPlan):
             return self.plan.run(states, self.suffix[:self.seq_S], edges)
+        if self._pending is not None:
+            # the block finished last is committed by the first pass of this one (one pass over the weights for both)
+            out = self.plan.run_commit(self._pending, states, edges)
+            self._pending = None
+            self._advance()
+            return out
         return self.plan.run(states, edges)
+
+    def _advance(self):
+        self.P += self.B
+        self.S = max(0, self.S - self.B)
+        self.plan.set_prefix_len(self.P, S=self.S)
+
+    def flush(self) -> None:
+        """Commit a block whose commit was deferred (no further block followed it)."""
+        if self._pending is not None:
+            self.plan.commit_block(self._pending)
+            self._pending = None
+            self._advance()
 
     def decode_block(self, block0: torch.Tensor, max_steps: int = 4096) -> Dict:
         """block0 [B] int32 on the device.  Returns the final block (device), the number of forward passes,
@@ -112,8 +131,11 @@ class BlockDecoder:
             edges = dp["edges"][:n_edges].contiguous() if n_edges else None
         return dict(final=states[0].clone(), nfe=nfe, depths=depths, n_states=n_states, trajectory=traj)
 
-    def commit(self, block: torch.Tensor) -> None:
-        """Append the finished block to the cache; the next block sits right after it."""
+    def commit(self, block: torch.Tensor, defer: bool = False) -> None:
+        """Append the finished block to the cache; the next block sits right after it.  defer=True (cached-prefix
+        models): the block's forward pass is folded into the first pass of the next block (spiffy_verify_step_commit,
+        same results); flush() commits it if no block follows."""
+        self.flush()
         if self.P + self.B > self.capacity:
             raise sp.SpiffyError(sp.SPIFFY_ESHAPE, "BlockDecoder.commit: cache is full")
         if isinstance(self.plan, sp.SeqStepPlan):
@@ -127,22 +149,23 @@ class BlockDecoder:
             self.seq_S = max(0, self.seq_S - self.B)
             self.plan.set_prefix_len(self.P)
             return
+        if defer and self.P + 2 * self.B <= self.capacity:
+            self._pending = block.to(torch.int32).contiguous()
+            return
         self.plan.commit_block(block.to(torch.int32).contiguous())
-        self.P += self.B
-        self.S = max(0, self.S - self.B)
-        self.plan.set_prefix_len(self.P, S=self.S)
+        self._advance()
 
     def generate(self, n_blocks: int) -> Dict:
         """Decode n_blocks all-MASK blocks in sequence.  Returns tokens [n_blocks*B] (host), forward passes,
         accepted depths and states verified per pass, per block."""
         out_tokens: List[np.ndarray] = []
         nfe, depths, n_states = [], [], []
-        for _ in range(n_blocks):
+        for i in range(n_blocks):
             block0 = torch.full((self.B,), self.cfg.mask_id, dtype=torch.int32, device=self.device)
             r = self.decode_block(block0)
             out_tokens.append(r["final"].cpu().numpy())
             nfe.append(r["nfe"])
             depths.append(r["depths"])
             n_states.append(r["n_states"])
-            self.commit(r["final"])
+            self.commit(r["final"], defer=i + 1 < n_blocks)
         return dict(tokens=np.concatenate(out_tokens), nfe=nfe, depths=depths, n_states=n_states)

@@ -23,7 +23,8 @@ MAX_G = 64
 EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "spiffy_embed",
            "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk", "spiffy_commit_block",
            "spiffy_subgraph_search_workspace_bytes", "spiffy_subgraph_search", "spiffy_verify_step",
-           "spiffy_workspace_bytes_seq", "spiffy_verify_step_seq"]
+           "spiffy_workspace_bytes_seq", "spiffy_verify_step_seq", "spiffy_workspace_bytes_commit",
+           "spiffy_verify_step_commit"]
 GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
 
@@ -96,6 +97,12 @@ def _load() -> C.CDLL:
     lib.spiffy_verify_step_seq.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp, vp,
                                            i32, i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
                                            vp, vp, sz, vp]
+    lib.spiffy_workspace_bytes_commit.restype = sz
+    lib.spiffy_workspace_bytes_commit.argtypes = [cfgp, i32, i32, i32]
+    lib.spiffy_verify_step_commit.restype = C.c_int
+    lib.spiffy_verify_step_commit.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp, vp,
+                                              i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
+                                              vp, vp, sz, vp]
     lib.spiffy_verify_step.restype = C.c_int
     lib.spiffy_verify_step.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp,
                                        i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
@@ -376,6 +383,39 @@ class StepPlan:
             _ptr(o["conf"]), _ptr(o["unmask"]), _ptr(o["margin"]), _ptr(o["target_states"]), _ptr(o["result"]),
             _ptr(o["accepted_state"]), wp, wn, _stream(stream)), "spiffy_verify_step")
         return o
+
+
+    def run_commit(self, prev_block: torch.Tensor, block_tokens: torch.Tensor, graph_edges: Optional[torch.Tensor],
+                   stream=None) -> Dict[str, torch.Tensor]:
+        """commit_block(prev_block) and run(block_tokens) in one pass over the weights (spiffy_verify_step_commit):
+        the plan's prefix length is the one BEFORE prev_block and its pos0 the position of prev_block; afterwards
+        the caller calls set_prefix_len(P + B).  Returns the step's outputs (hidden: the states' rows)."""
+        o = self.out
+        G = int(block_tokens.shape[0])
+        if G > self.G_cap:
+            raise SpiffyError(SPIFFY_ESHAPE, "StepPlan.run_commit: more states than the plan was sized for")
+        self.G = G
+        dev = block_tokens.device
+        if getattr(self, "_commit_ws", None) is None:
+            P_max = max([(p.capacity or p.P) for p in self._keep[1]], default=0)
+            n = int(lib.spiffy_workspace_bytes_commit(C.byref(self.cfg), self.G_cap, self.B, P_max))
+            if n == 0:
+                raise SpiffyError(SPIFFY_EINVAL, "spiffy_workspace_bytes_commit")
+            if self.workspace.numel() < n + 256:
+                self.workspace = torch.empty(n + 256, dtype=torch.uint8, device=dev)
+            self._commit_ws = True
+            self._commit_hidden = torch.empty(((self.G_cap + 1) * self.B, self.cfg.d), dtype=_tdtype(self.cfg), device=dev)
+        E = int(graph_edges.shape[0]) if graph_edges is not None else 0
+        wp, wn = _ws(self.workspace)
+        _check(lib.spiffy_verify_step_commit(
+            C.byref(self.cfg), self.n_layers, self._layers, self._prefix, _ptr(self.w_embed), _ptr(self.final_norm),
+            _ptr(self.w_vocab), _ptr(prev_block), _ptr(block_tokens), G, self.B, self.pos0 + self.B,
+            _ptr(graph_edges) if E else None, E, self.root, self.threshold, self.logit_scale, self.force_one,
+            _ptr(self._commit_hidden), _ptr(o["argmax"]), _ptr(o["conf"]), _ptr(o["unmask"]), _ptr(o["margin"]),
+            _ptr(o["target_states"]), _ptr(o["result"]), _ptr(o["accepted_state"]), wp, wn, _stream(stream)),
+            "spiffy_verify_step_commit")
+        return dict(o, hidden=self._commit_hidden[:G * self.B].view(G, self.B, self.cfg.d),
+                    hidden_prev=self._commit_hidden[G * self.B:(G + 1) * self.B])
 
 
 class SeqStepPlan(StepPlan):

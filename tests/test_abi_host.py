@@ -271,6 +271,30 @@ def test_verify_step_seq_argument_errors():
     assert sp.lib.spiffy_workspace_bytes_seq(C.byref(cfg), 4, 32, 5000, 64) == 0
 
 
+def test_verify_step_commit_argument_errors():
+    cfg = _cfg("c3")
+    w, _ = _layer_structs()
+    layers = (sp.LayerWeights * 1)(w)
+    def call(**k):
+        prefix = (sp.PrefixKV * 1)(sp.PrefixKV(k.get("pk", DUMMY), DUMMY, 64, k.get("cap", 1024), k.get("pS", 0)))
+        return sp.lib.spiffy_verify_step_commit(
+            C.byref(cfg), k.get("L", 1), layers, prefix, DUMMY, DUMMY, DUMMY, k.get("prev", DUMMY), DUMMY, k.get("G", 4), 32,
+            k.get("pos0", 96), DUMMY, 2, 0, 0.9, 1.0, 1, None, DUMMY, DUMMY, DUMMY, None, None, DUMMY, None,
+            0x100000, k.get("wsb", 16), None)
+    assert call() == sp.SPIFFY_EWORKSPACE                       # every argument check passed
+    assert call(pS=64) == sp.SPIFFY_EWORKSPACE                  # with a cached suffix behind the finished block
+    assert call(prev=None) == sp.SPIFFY_EINVAL
+    assert call(pos0=31) == sp.SPIFFY_EINVAL                    # no room for the finished block in front of pos0
+    assert call(cap=64 + 31) == sp.SPIFFY_ESHAPE                # no room for the finished block's rows
+    assert call(pS=64, cap=64 + 32 + 63) == sp.SPIFFY_ESHAPE
+    assert call(pk=None) == sp.SPIFFY_EINVAL
+    assert call(L=0) == sp.SPIFFY_EINVAL
+    assert call(G=0) == sp.SPIFFY_EINVAL
+    assert call(G=512) == sp.SPIFFY_ESHAPE                      # (G + 1) * B rows exceed the row limit
+    assert sp.lib.spiffy_workspace_bytes_commit(C.byref(cfg), 4, 32, 64) > sp.lib.spiffy_workspace_bytes(C.byref(cfg), 4, 32, 96)
+    assert sp.lib.spiffy_workspace_bytes_commit(C.byref(cfg), 512, 32, 64) == 0
+
+
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     import importlib
     monkeypatch.setattr(sp, "LIB_PATH", str(tmp_path / "nope.so"))

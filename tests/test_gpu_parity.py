@@ -1391,3 +1391,74 @@ def test_decode_full_sequence_matches_the_oracle_loop(sp):
         for got_c, want in ((ck[l], pre[l][0]), (cv[l], pre[l][1])):
             e_max, _ = rel_err(to_np(got_c.cpu()), want)
             assert e_max < 1e-4, (l, e_max)
+
+
+# ------------------------------------------------------------------ commit of the finished block folded into the next block's first pass
+
+@pytest.mark.parametrize("key", ["c1", "bf16_generic", "bf16_mfma", "bf16_mfma_long", "bf16_mfma_dual"])
+def test_step_commit_is_commit_block_then_step(sp, key):
+    """spiffy_verify_step_commit = spiffy_commit_block of the finished block, then spiffy_verify_step of the next
+    block's states with the prefix grown by B: same cache rows and same outputs, bit for bit (a row's arithmetic
+    does not depend on what is verified with it); and the oracle's two steps within the usual bounds."""
+    S = 0
+    if key == "c1":
+        cfg = synth.CONFIGS["c1"]
+    elif key == "bf16_generic":
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", P=37, B=5)
+    elif key == "bf16_mfma_long":
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=640, P=2040, B=32)
+    else:
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=4, Hkv=2, hd=128, F=320, V=640, P=70, B=32)
+        S = 3 * cfg.B if key == "bf16_mfma_dual" else 0
+    seed, scale, tau = 9, 8.0, 0.5
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
+    caches = [_full_cache(cfg, S + cfg.B, seed, layer=l) for l in range(cfg.L)]     # room for both blocks (and the suffix)
+    hw, we = synth.head_weights(cfg, seed), synth.embed_weights(cfg, seed)
+    states, edges = synth.draft_graph("c1", cfg.scaled(G=4), seed)
+    d_states = torch.from_numpy(states).to(DEV)
+    d_edges = torch.from_numpy(np.ascontiguousarray(edges)).to(DEV)
+    prev = torch.from_numpy(np.random.default_rng(4).integers(0, cfg.V - 1, size=cfg.B).astype(np.int32)).to(DEV)
+
+    def make():
+        dk = [c[0].clone().to(DEV) for c in caches]
+        dv = [c[1].clone().to(DEV) for c in caches]
+        plan = sp.StepPlan(sp.cfg_from_synth(cfg), [sp.layer_weights(dev_weights(w)) for w in layers],
+                           [sp.prefix_kv(k, v, cfg.P, S) for k, v in zip(dk, dv)], we.to(DEV), hw["final_norm"].to(DEV),
+                           hw["w_vocab"].to(DEV), len(states), cfg.B, cfg.P, tau, logit_scale=scale, device=DEV)
+        return plan, dk, dv
+
+    plan_a, ka, va = make()
+    plan_a.workspace = sp.alloc_workspace(plan_a.cfg, len(states), cfg.B, cfg.P + cfg.B + S, DEV)
+    plan_a.commit_block(prev)
+    plan_a.set_prefix_len(cfg.P + cfg.B, S=max(0, S - cfg.B))
+    a = {k: v.clone() for k, v in plan_a.run(d_states, d_edges).items()}
+    plan_b, kb, vb = make()
+    b = plan_b.run_commit(prev, d_states, d_edges)
+    torch.cuda.synchronize()
+    for k in ("hidden", "argmax", "conf", "unmask", "margin", "target_states", "result", "accepted_state"):
+        assert torch.equal(a[k], b[k]), k
+    for l in range(cfg.L):
+        assert torch.equal(ka[l], kb[l]) and torch.equal(va[l], vb[l]), l
+    # the oracle: forward of the finished block (its keys / values join the prefix), then the step
+    lw = [np_weights(w) for w in layers]
+    pre = [(to_np(c[2]), to_np(c[3])) for c in caches]
+    suf = [(to_np(c[4])[:, :S], to_np(c[5])[:, :S]) for c in caches]
+    h = O().embed(to_np(we), prev.cpu().numpy()[None, :])
+    new_pre = []
+    for l in range(cfg.L):
+        h, ks, vs = O().verify_layer(lw[l], pre[l][0], pre[l][1], h, suffix_k=suf[l][0] if S else None,
+                                     suffix_v=suf[l][1] if S else None, return_kv=True, **oracle_kw(cfg))
+        new_pre.append((np.concatenate([pre[l][0], ks[0]], axis=1), np.concatenate([pre[l][1], vs[0]], axis=1)))
+    e_prev, _ = rel_err(to_np(b["hidden_prev"].cpu()), h[0])
+    bound = 1e-4 if cfg.dtype == "f32" else (2e-2 if cfg.L == 1 else 4e-2)
+    assert e_prev < bound, e_prev
+    ref = O().verify_step(lw, new_pre, to_np(we), to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states, edges,
+                          n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P + cfg.B, mask_id=cfg.mask_id,
+                          threshold=tau, rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, logit_scale=scale,
+                          suffix=[(k[:, cfg.B:], v[:, cfg.B:]) for k, v in suf] if S else None)
+    e_max, _ = rel_err(to_np(b["hidden"].cpu()), ref["hidden"])
+    assert e_max < bound, e_max
+    if cfg.dtype == "f32":
+        safe = (states == cfg.mask_id) & (ref["margin"] > 1e-3 * scale)
+        np.testing.assert_array_equal(b["argmax"].cpu().numpy()[safe], ref["argmax"][safe])
+        assert tuple(b["result"].cpu().tolist()[:3]) == (ref["node"], ref["depth"], ref["n_steps"])

@@ -106,29 +106,33 @@ class BlockDecoder:
         mask_id = self.cfg.mask_id
         state = block0.to(torch.int32).reshape(1, self.B).contiguous()
         states, edges = state, None
-        nfe, depths, n_states, traj = 0, [], [], [state[0].cpu().numpy().copy()]
-        while nfe < max_steps:
-            cur = states[0].cpu().numpy()
-            if not (cur == mask_id).any():
-                break
+        cur = state[0].cpu().numpy()
+        nfe, depths, n_states, traj = 0, [], [], [cur.copy()]
+        drafting = self.graph is not None and self.d_star > 0
+        while nfe < max_steps and (cur == mask_id).any():
             out = self._step(states.contiguous(), edges)
             nfe += 1
             n_states.append(int(states.shape[0]))
-            res = out["result"].cpu().tolist()
-            depths.append(int(res[1]))
             new_state = out["accepted_state"].clone()
-            new_np = new_state.cpu().numpy()
-            traj.append(new_np.copy())
-            if not (new_np == mask_id).any() or self.graph is None or self.d_star == 0:
+            parts = [out["result"], new_state]
+            if drafting:
+                # the next pass's drafts, from the distribution of the accepted node (read on the device); enqueued
+                # before the host looks at anything, so that one read per pass brings back all it needs
+                tok, prob = sp.head_topk(self.cfg, self.plan.w_vocab, states.contiguous(), self.graph.K,
+                                         self.logit_scale, self.plan.workspace, result=out["result"], after_step=True)
+                dp = sp.draft_prune(new_state, mask_id, tok, prob, self.graph.offsets, self.graph.pairs,
+                                    self.graph.edges, self.d_star)
+                parts.append(dp["counts"])
+            host = torch.cat(parts).cpu().numpy()           # accept result (4), accepted block (B), pruned sizes (2)
+            depths.append(int(host[1]))
+            cur = host[4:4 + self.B].copy()
+            traj.append(cur.copy())
+            if drafting and (cur == mask_id).any():
+                n_kept, n_edges = int(host[4 + self.B]), int(host[5 + self.B])
+                states = dp["states"][:n_kept]
+                edges = dp["edges"][:n_edges].contiguous() if n_edges else None
+            else:
                 states, edges = new_state.reshape(1, self.B), None
-                continue
-            tok, prob = sp.head_topk(self.cfg, self.plan.w_vocab, states.contiguous(), self.graph.K, self.logit_scale,
-                                     self.plan.workspace, result=out["result"], after_step=True)
-            dp = sp.draft_prune(new_state, mask_id, tok, prob, self.graph.offsets, self.graph.pairs, self.graph.edges,
-                                self.d_star)
-            n_kept, n_edges = [int(x) for x in dp["counts"].cpu().tolist()]
-            states = dp["states"][:n_kept]
-            edges = dp["edges"][:n_edges].contiguous() if n_edges else None
         return dict(final=states[0].clone(), nfe=nfe, depths=depths, n_states=n_states, trajectory=traj)
 
     def commit(self, block: torch.Tensor, defer: bool = False) -> None:

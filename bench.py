@@ -387,7 +387,43 @@ def full_sequence_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, d
         plan.run(d_states, suffix, d_edges)
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
-    return {"suffix_rows": S, "rows_per_layer": cfg.G * cfg.B + S, "ms_per_step": ms, "states_per_s": cfg.G / (ms * 1e-3)}
+    out = {"suffix_rows": S, "rows_per_layer": cfg.G * cfg.B + S, "ms_per_step": ms, "states_per_s": cfg.G / (ms * 1e-3)}
+    del plan, pf
+
+    # a whole generation in this regime: S / B + 1 blocks, the MASK tokens behind the current block recomputed in
+    # every pass; vanilla decoding with and without the commit pass standing in for the next block's first pass
+    from paper_2509_18085_amd import decode
+    n_blocks = S // cfg.B + 1
+
+    def generate(reuse):
+        ck, cv = [], []
+        for k, v in prefix:
+            kk = torch.zeros((cfg.Hkv, cfg.P + n_blocks * cfg.B, cfg.hd), dtype=k.dtype, device=dev)
+            vv = torch.zeros_like(kk)
+            kk[:, :cfg.P], vv[:, :cfg.P] = k, v
+            ck.append(kk)
+            cv.append(vv)
+        dec = decode.BlockDecoder(sp.cfg_from_synth(cfg), layers, ck, cv, cfg.P, w_embed, hw["final_norm"], hw["w_vocab"],
+                                  cfg.B, cfg.threshold, logit_scale=LOGIT_SCALE, device=dev, seq_S0=S,
+                                  reuse_commit_pass=reuse)
+        dec.decode_block(torch.full((cfg.B,), cfg.mask_id, dtype=torch.int32, device=dev), max_steps=1)   # warm-up
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g = dec.generate(n_blocks)
+        torch.cuda.synchronize()
+        return g, (time.perf_counter() - t0) * 1e3
+
+    g0, ms0 = generate(False)
+    g1, ms1 = generate(True)
+    out["vanilla_generation"] = {
+        "blocks": n_blocks, "tokens": n_blocks * cfg.B,
+        "first_pass_of_its_own": {"forward_passes": sum(g0["nfe"]) + n_blocks - 1, "ms": ms0},
+        "first_pass_from_the_commit_pass": {"forward_passes": sum(g1["nfe"]) + n_blocks - 1, "ms": ms1},
+        "tokens_that_differ": int((g0["tokens"] != g1["tokens"]).sum()),
+        "note": "forward passes include the commit pass of every block but the last; the two ways compute the same "
+                "function with different bf16 rounding, and with random weights (flat logits, confidences next to each "
+                "other) near-ties fall either way, so the token sequences part at the first such tie"}
+    return out
 
 
 def stored_traffic(config):

@@ -47,13 +47,19 @@ class BlockDecoder:
     hold fixed keys / values of the tokens after the first block; every committed block takes B rows off it.
     seq_S0 > 0 (instead of S0): full-sequence model with a prefix cache only: seq_S0 MASK tokens after the first
     block are recomputed in every pass (spiffy_verify_step_seq); a finished block is committed by one more such
-    pass on its final tokens, which leaves its keys / values in its slot of the cache.
+    pass on its final tokens, which leaves its keys / values in its slot of the cache.  That pass also ran the
+    next block's positions, as all-MASK suffix rows over the very sequence that block's first pass would see: with
+    reuse_commit_pass the next block's first step takes its hidden states from there and only runs the head
+    (one forward pass less per block; saved_passes counts them).  The two ways compute the same function with
+    different rounding (suffix rows read the block's keys from the cache and split their keys differently), so
+    in bf16 a near-tie can fall the other way: off by default.
     """
 
     def __init__(self, cfg: sp.ModelCfg, layers: Sequence[Dict[str, torch.Tensor]], cache_k: Sequence[torch.Tensor],
                  cache_v: Sequence[torch.Tensor], P0: int, w_embed: torch.Tensor, final_norm: torch.Tensor,
                  w_vocab: torch.Tensor, B: int, threshold: float, logit_scale: float = 1.0, force_one: bool = True,
-                 graph: Optional[DraftGraph] = None, d_star: int = 0, device="cuda", S0: int = 0, seq_S0: int = 0):
+                 graph: Optional[DraftGraph] = None, d_star: int = 0, device="cuda", S0: int = 0, seq_S0: int = 0,
+                 reuse_commit_pass: bool = False):
         self.cfg, self.B, self.graph, self.device = cfg, B, graph, device
         self.d_star = d_star if graph is not None else 0
         self.logit_scale = logit_scale
@@ -61,7 +67,11 @@ class BlockDecoder:
         self.capacity = int(cache_k[0].shape[1])
         prefix = [sp.prefix_kv(k, v, P0, S0) for k, v in zip(cache_k, cache_v)]
         self.seq_S = seq_S0
+        self.reuse_commit_pass = reuse_commit_pass
         self._pending = None
+        self._next_hidden = None      # full-sequence model: hidden states of the next block's positions from the commit pass
+        self.saved_passes = 0
+        self._zero_result = torch.zeros(4, dtype=torch.int32, device=device)   # accept result of a pass with one state
         if seq_S0:
             if S0:
                 raise sp.SpiffyError(sp.SPIFFY_EINVAL, "BlockDecoder: a cached suffix and a recomputed one exclude each other")
@@ -109,21 +119,20 @@ class BlockDecoder:
         cur = state[0].cpu().numpy()
         nfe, depths, n_states, traj = 0, [], [], [cur.copy()]
         drafting = self.graph is not None and self.d_star > 0
-        while nfe < max_steps and (cur == mask_id).any():
-            out = self._step(states.contiguous(), edges)
-            nfe += 1
-            n_states.append(int(states.shape[0]))
-            new_state = out["accepted_state"].clone()
-            parts = [out["result"], new_state]
+
+        def finish_pass(result, new_state, after_step):
+            """Enqueue the next pass's drafts (top-K of the accepted node, read on the device, then drafting and
+            pruning) before the host looks at anything; ONE host read then brings back the accept result (4), the
+            accepted block (B) and the pruned sizes (2)."""
+            nonlocal cur, states, edges
+            parts = [result, new_state]
             if drafting:
-                # the next pass's drafts, from the distribution of the accepted node (read on the device); enqueued
-                # before the host looks at anything, so that one read per pass brings back all it needs
                 tok, prob = sp.head_topk(self.cfg, self.plan.w_vocab, states.contiguous(), self.graph.K,
-                                         self.logit_scale, self.plan.workspace, result=out["result"], after_step=True)
+                                         self.logit_scale, self.plan.workspace, result=result, after_step=after_step)
                 dp = sp.draft_prune(new_state, mask_id, tok, prob, self.graph.offsets, self.graph.pairs,
                                     self.graph.edges, self.d_star)
                 parts.append(dp["counts"])
-            host = torch.cat(parts).cpu().numpy()           # accept result (4), accepted block (B), pruned sizes (2)
+            host = torch.cat(parts).cpu().numpy()
             depths.append(int(host[1]))
             cur = host[4:4 + self.B].copy()
             traj.append(cur.copy())
@@ -133,6 +142,24 @@ class BlockDecoder:
                 edges = dp["edges"][:n_edges].contiguous() if n_edges else None
             else:
                 states, edges = new_state.reshape(1, self.B), None
+
+        if self._next_hidden is not None:
+            # Full-sequence model: the pass that committed the previous block ran this block's positions as all-MASK
+            # suffix rows over exactly the sequence this block's first pass would see, so that pass only needs the
+            # head: no forward pass is spent on it.
+            hidden, self._next_hidden = self._next_hidden, None
+            if bool((cur == mask_id).all()):
+                dh = sp.decode_head(self.cfg, hidden, self.plan.final_norm, self.plan.w_vocab, states.contiguous(),
+                                    self.plan.threshold, self.plan.workspace, logit_scale=self.logit_scale,
+                                    force_one=bool(self.plan.force_one))
+                n_states.append(1)
+                self.saved_passes += 1
+                finish_pass(self._zero_result, dh["target_states"][0].clone(), False)
+        while nfe < max_steps and (cur == mask_id).any():
+            out = self._step(states.contiguous(), edges)
+            nfe += 1
+            n_states.append(int(states.shape[0]))
+            finish_pass(out["result"], out["accepted_state"].clone(), True)
         return dict(final=states[0].clone(), nfe=nfe, depths=depths, n_states=n_states, trajectory=traj)
 
     def commit(self, block: torch.Tensor, defer: bool = False) -> None:
@@ -146,7 +173,9 @@ class BlockDecoder:
             if self.seq_S:
                 # one pass on the finished block: every pass with a suffix writes the true block's keys / values
                 # (which depend on the suffix) into its slot
-                self._step(block.to(torch.int32).reshape(1, self.B).contiguous(), None)
+                out = self._step(block.to(torch.int32).reshape(1, self.B).contiguous(), None)
+                if self.seq_S >= self.B and self.reuse_commit_pass:
+                    self._next_hidden = out["hidden"][self.B:2 * self.B].clone().reshape(1, self.B, self.cfg.d)
             else:
                 self.plan.commit_block(block.to(torch.int32).contiguous())
             self.P += self.B

@@ -1323,10 +1323,14 @@ def test_step_full_sequence_without_suffix_is_the_step(sp):
         assert torch.equal(a[k].reshape(b[k].shape), b[k]), k
 
 
-def test_decode_full_sequence_matches_the_oracle_loop(sp):
+@pytest.mark.parametrize("reuse", [False, True])
+def test_decode_full_sequence_matches_the_oracle_loop(sp, reuse):
     """Configuration 1 (fp32), three blocks, the first with 2B MASK tokens behind it that every pass recomputes:
     device loop = oracle loop (tokens, forward passes, depths), and the same tokens as vanilla decoding.  A
-    finished block's keys / values come from one more pass on its final tokens, with the suffix still behind it."""
+    finished block's keys / values come from one more pass on its final tokens, with the suffix still behind it.
+    reuse: that pass also saw the next block's positions as MASK rows of the same sequence, so the next block's
+    first step runs the head on its hidden states and spends no forward pass (same tokens and depths, one pass
+    less per later block)."""
     from paper_2509_18085_amd import decode
     cfg = synth.CONFIGS["c1"]
     scale, tau, d_star, seed, S0, n_blocks = 12.0, 0.5, 3, synth.DEFAULT_SEED, 2 * cfg.B, 3
@@ -1345,8 +1349,10 @@ def test_decode_full_sequence_matches_the_oracle_loop(sp):
             cv.append(vv.to(DEV))
         dec = decode.BlockDecoder(sp.cfg_from_synth(cfg), [dev_weights(w) for w in layers], ck, cv, cfg.P, we.to(DEV),
                                   hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), cfg.B, tau, logit_scale=scale,
-                                  graph=graph, d_star=d, device=DEV, seq_S0=S0)
-        return dec.generate(n_blocks), ck, cv
+                                  graph=graph, d_star=d, device=DEV, seq_S0=S0, reuse_commit_pass=reuse)
+        g = dec.generate(n_blocks)
+        assert dec.saved_passes == (n_blocks - 1 if reuse else 0)
+        return g, ck, cv
 
     graph = decode.DraftGraph(formulas, device=DEV)
     (got, ck, cv), (van, _, _) = run(graph, d_star), run(None, 0)
@@ -1385,7 +1391,7 @@ def test_decode_full_sequence_matches_the_oracle_loop(sp):
         pre = new_pre
         P, S = P + cfg.B, max(0, S - cfg.B)
     np.testing.assert_array_equal(got["tokens"], np.concatenate(tokens))
-    assert got["nfe"] == nfes and got["depths"] == depths
+    assert got["nfe"] == ([nfes[0]] + [n - 1 for n in nfes[1:]] if reuse else nfes) and got["depths"] == depths
     # the caches now hold the oracle's prefix: context and the three committed blocks
     for l in range(cfg.L):
         for got_c, want in ((ck[l], pre[l][0]), (cv[l], pre[l][1])):
@@ -1462,3 +1468,38 @@ def test_step_commit_is_commit_block_then_step(sp, key):
         safe = (states == cfg.mask_id) & (ref["margin"] > 1e-3 * scale)
         np.testing.assert_array_equal(b["argmax"].cpu().numpy()[safe], ref["argmax"][safe])
         assert tuple(b["result"].cpu().tolist()[:3]) == (ref["node"], ref["depth"], ref["n_steps"])
+
+
+def test_decode_full_sequence_is_lossless_on_the_mfma_path(sp):
+    """bf16 MFMA kernels, full-sequence model (3B MASK tokens recomputed behind the first block), four blocks:
+    speculative decoding reproduces vanilla decoding token for token, with and without the commit pass standing
+    in for the next block's first pass; that shortcut changes no token here and saves one pass per later block."""
+    from paper_2509_18085_amd import decode
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=1280, P=100, B=32, G=1)
+    formulas = [[(i, 1) for i in range(1, n + 1)] for n in (1, 2, 3, 4, 6, 8, 12, 16)] + [[(1, 2)], [(1, 1), (2, 2)]]
+    seed, n_blocks = 11, 4
+    layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
+    prefix = [synth.prefix_kv(cfg, l, seed) for l in range(cfg.L)]
+    hw, we = synth.head_weights(cfg, seed), synth.embed_weights(cfg, seed)
+
+    def run(graph, d, reuse):
+        ck, cv = [], []
+        for k, v in prefix:
+            kk = torch.zeros((cfg.Hkv, cfg.P + n_blocks * cfg.B, cfg.hd), dtype=k.dtype)
+            vv = torch.zeros_like(kk)
+            kk[:, :cfg.P], vv[:, :cfg.P] = k, v
+            ck.append(kk.to(DEV))
+            cv.append(vv.to(DEV))
+        dec = decode.BlockDecoder(sp.cfg_from_synth(cfg), [dev_weights(w) for w in layers], ck, cv, cfg.P, we.to(DEV),
+                                  hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), cfg.B, 0.7, logit_scale=16.0,
+                                  graph=graph, d_star=d, device=DEV, seq_S0=(n_blocks - 1) * cfg.B, reuse_commit_pass=reuse)
+        return dec.generate(n_blocks)
+
+    graph = decode.DraftGraph(formulas, device=DEV)
+    res = {(spec, reuse): run(graph if spec else None, 5 if spec else 0, reuse) for spec in (0, 1) for reuse in (0, 1)}
+    for reuse in (0, 1):
+        np.testing.assert_array_equal(res[(1, reuse)]["tokens"], res[(0, reuse)]["tokens"])
+        assert sum(res[(1, reuse)]["nfe"]) < sum(res[(0, reuse)]["nfe"])
+    assert not (res[(1, 1)]["tokens"] == cfg.mask_id).any()
+    np.testing.assert_array_equal(res[(0, 1)]["tokens"], res[(0, 0)]["tokens"])
+    assert sum(res[(0, 1)]["nfe"]) == sum(res[(0, 0)]["nfe"]) - (n_blocks - 1)

@@ -1309,6 +1309,28 @@ def test_step_full_sequence(sp, key, S):
             assert (ck[:, cfg.P:cfg.P + cfg.B + S].float().abs().cpu() < 1e3).all()
 
 
+def test_step_full_sequence_at_the_suffix_limit(sp):
+    """S = SPIFFY_MAX_SUFFIX = 4096 recomputed suffix rows (three key splits for the suffix queries, 128 row tiles
+    of suffix rows through every projection), one narrow layer so the oracle finishes in seconds."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=1, d=256, Hq=2, Hkv=1, hd=128, F=256, V=640, P=70, B=32)
+    S, scale, tau = 4096, 8.0, 0.5
+    plan, layers, prefix, hw, we, states, edges, suffix, caches = _seq_setup(sp, cfg, S, 9, scale, tau)
+    out = plan.run(torch.from_numpy(states).to(DEV), torch.from_numpy(suffix).to(DEV),
+                   torch.from_numpy(np.ascontiguousarray(edges)).to(DEV))
+    torch.cuda.synchronize()
+    G = len(states)
+    ref = O().verify_step_fullseq([np_weights(w) for w in layers], [(to_np(k), to_np(v)) for k, v in prefix], to_np(we),
+                                  to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states, suffix, edges, n_q_heads=cfg.Hq,
+                                  n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P, mask_id=cfg.mask_id, threshold=tau,
+                                  rms_eps=cfg.rms_eps, rope_base=cfg.rope_base, logit_scale=scale)
+    hid = to_np(out["hidden"].cpu())
+    e_b, _ = rel_err(hid[:G * cfg.B].reshape(G, cfg.B, cfg.d), ref["hidden"])
+    e_s, _ = rel_err(hid[G * cfg.B:], ref["hidden_suffix"])
+    assert e_b < 2e-2 and e_s < 2e-2, (e_b, e_s)
+    for ck, cv in caches:
+        assert (ck[:, cfg.P + cfg.B + S:].cpu() == 1e4).all() and (cv[:, cfg.P + cfg.B + S:].cpu() == 1e4).all()
+
+
 def test_step_full_sequence_without_suffix_is_the_step(sp):
     cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=4, Hkv=2, hd=128, F=320, V=640, P=70, B=32)
     plan, layers, prefix, hw, we, states, edges, suffix, caches = _seq_setup(sp, cfg, 0, 9, 8.0, 0.5)

@@ -2,9 +2,11 @@
 
 One iteration = one forward pass: spiffy_verify_step over the current block and its drafts, then, while
 MASK tokens remain, the next step's draft graph on the device (spiffy_head_topk + spiffy_draft_prune).
-When a block is complete its keys / values are appended to the prefix cache (spiffy_commit_block,
-prefix caching of Sec. 3.1) and the next block starts.  Per forward pass the host reads back 4 + B + 2
-integers (accept result, accepted block, sizes of the pruned graph); everything else stays on the device.
+When a block is complete its keys / values are appended to the prefix cache (prefix caching of Sec. 3.1:
+spiffy_commit_block, or, when another block follows, inside that block's first pass with
+spiffy_verify_step_commit) and the next block starts.  Per forward pass the host reads back 4 + B + 2
+integers in one transfer (accept result, accepted block, sizes of the pruned graph); everything else stays
+on the device.
 Only argument marshalling and the loop live here: every step of the path runs in the library's kernels.
 """
 from __future__ import annotations

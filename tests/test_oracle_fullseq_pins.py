@@ -125,7 +125,8 @@ def test_decode_loop_of_a_full_sequence_model():
     """The block loop with a recomputed suffix: without a suffix it is the cached loop; with one, every pass is
     verify_step_fullseq on the current state, and the result does not depend on drafts (App. A)."""
     cfg, layers, w_embed, prefix_tok, states, suffix_tok = _setup(G=1, B=4)
-    r = np.random.default_rng(2)
+    r = np.random.default_rng(0)
+    rand_suffix = r.integers(0, cfg.V - 1, size=6)           # tokens that matter: the block decodes differently
     kw = dict(_kw(cfg), pos0=cfg.P, mask_id=cfg.mask_id, threshold=0.95, logit_scale=2.0, force_one=True)
     _, Kp, Vp = O.masked_forward(layers, w_embed[prefix_tok], np.arange(cfg.P), np.ones((cfg.P, cfg.P), bool), **_kw(cfg))
     model = dict(layers=layers, prefix=list(zip(Kp, Vp)), w_embed=w_embed, final_norm=np.ones(cfg.d),
@@ -135,8 +136,10 @@ def test_decode_loop_of_a_full_sequence_model():
     empty = O.decode_block(dict(model, suffix_tokens=suffix_tok[:0]), block0)
     np.testing.assert_array_equal(plain[0], empty[0])
     assert plain[2] == empty[2]
+    suffix_tok = rand_suffix
     seq_model = dict(model, suffix_tokens=suffix_tok)
     van = O.decode_block(seq_model, block0)
+    assert not np.array_equal(van[0], plain[0])
     # every state of the trajectory is one full-sequence step from the one before
     for a, b in zip(van[1][:-1], van[1][1:]):
         step = O.verify_step_fullseq(layers, model["prefix"], w_embed, model["final_norm"], model["w_vocab"], a[None],

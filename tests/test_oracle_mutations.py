@@ -114,6 +114,10 @@ CASES = [
      [P(fullseq.test_dense_mask_formulation_through_all_layers)]),
     ("full sequence: the suffix is not updated", "out_s = rest(xs, o.reshape(S, Hq * hd)) if S else xs.copy()", "out_s = xs.copy()",
      [P(fullseq.test_one_state_is_a_plain_cached_forward_over_block_and_suffix)]),
+    ("full sequence: values handed back for the cache are the keys", "        return out_b, out_s, k0, v0", "        return out_b, out_s, k0, k0",
+     [P(fullseq.test_dense_mask_formulation_through_all_layers)]),
+    ("full sequence: the decode loop ignores the suffix", '        if "suffix_tokens" in model:', '        if "suffix_tokens_" in model:',
+     [P(fullseq.test_decode_loop_of_a_full_sequence_model)]),
     ("subgraph: only level 1 is a root", "return all(level[q] in (1, 2) or (parents[q] & g) for q in g)", "return all(level[q] in (1,) or (parents[q] & g) for q in g)",
      [P(subgraph.test_hand_worked_example)]),
     ("subgraph: edges reversed", "            parents[q].add(int(p))\n    best, best_mask", "            parents[p].add(int(q))\n    best, best_mask",

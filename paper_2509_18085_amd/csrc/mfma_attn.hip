@@ -101,6 +101,16 @@ __device__ __forceinline__ float max_with_other_half(float x) {
   return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
 }
 
+// Reference value m of the online softmax (probabilities are exp2(s - m), log2 domain).  It only follows the running
+// maximum when that has moved by more than 8: until then exp2(s - m) stays below 2^8, which bf16 and the fp32 sums
+// hold as well as values below 1, and a reference that stays put needs no rescale of O and l (the factor is exactly
+// 1 and the 64 multiplies are skipped).  The choice is made per query, so a row's arithmetic does not depend on the
+// rows that share its wavefront; (m, l, O) stay consistent and every later merge weighs partials by exp2(m - max m).
+__device__ __forceinline__ float next_reference(float m_run, float tile_max) {
+  const float m_cand = fmaxf(m_run, tile_max);
+  return (m_cand - m_run > 8.0f) ? m_cand : m_run;     // first tile: m_run = -inf, the difference is +inf
+}
+
 // S^T of the wavefront's 32-key half of a tile in LDS: 8 MFMAs
 __device__ __forceinline__ void scores(const WaveState& w, f32x16& s, const bf16_t* __restrict__ ks, int st, int lane) {
   const int row = st * 32 + (lane & 31), hh = lane >> 5;
@@ -129,7 +139,7 @@ __device__ __forceinline__ void finish_tile(WaveState& w, f32x16& s, const bf16_
     tmax = fmaxf(tmax, s[v]);
   }
   tmax = max_with_other_half(tmax);
-  const float m_new = fmaxf(w.m_run, tmax);
+  const float m_new = next_reference(w.m_run, tmax);
   const float alpha = (w.m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(w.m_run - m_new);
   const float m_safe = (m_new == -INFINITY) ? 0.f : m_new;
   bf16x8 pf[2];
@@ -196,7 +206,7 @@ __device__ __forceinline__ void pipe_step(WaveState& w, const f32x16& s, f32x16&
 #pragma unroll
   for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, s[v]);
   tmax = max_with_other_half(tmax);
-  const float m_new = fmaxf(w.m_run, tmax);     // finite: a full tile has no masked score
+  const float m_new = next_reference(w.m_run, tmax);     // finite: a full tile has no masked score
   const float alpha = (w.m_run == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(w.m_run - m_new);
   const int g = lane >> 4, j = lane & 15;
   const int vkey = st * 32 + 4 * (g >> 1) + (j >> 2);

@@ -1423,7 +1423,7 @@ def test_decode_full_sequence_matches_the_oracle_loop(sp, reuse):
 
 # ------------------------------------------------------------------ commit of the finished block folded into the next block's first pass
 
-@pytest.mark.parametrize("key", ["c1", "bf16_generic", "bf16_mfma", "bf16_mfma_long", "bf16_mfma_dual"])
+@pytest.mark.parametrize("key", ["c1", "bf16_generic", "bf16_mfma", "bf16_mfma_long", "bf16_mfma_dual", "bf16_mfma_b4"])
 def test_step_commit_is_commit_block_then_step(sp, key):
     """spiffy_verify_step_commit = spiffy_commit_block of the finished block, then spiffy_verify_step of the next
     block's states with the prefix grown by B: same cache rows and same outputs, bit for bit (a row's arithmetic
@@ -1435,6 +1435,8 @@ def test_step_commit_is_commit_block_then_step(sp, key):
         cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", P=37, B=5)
     elif key == "bf16_mfma_long":
         cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=640, P=2040, B=32)
+    elif key == "bf16_mfma_b4":          # small blocks: the finished block and the four states share one 32-row group
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=4, Hkv=2, hd=128, F=320, V=640, P=70, B=4)
     else:
         cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=4, Hkv=2, hd=128, F=320, V=640, P=70, B=32)
         S = 3 * cfg.B if key == "bf16_mfma_dual" else 0

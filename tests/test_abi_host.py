@@ -20,6 +20,19 @@ def test_exports_match_header():
         assert getattr(sp.lib, name) is not None
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C header: it compiles as C99 with no C++ or torch types."""
+    import shutil
+    import subprocess
+    if shutil.which("gcc") is None:
+        pytest.skip("no gcc")
+    src = tmp_path / "t.c"
+    src.write_text('#include "spiffy.h"\nint main(void) { return (int)sizeof(spiffy_model_cfg) == 0; }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only",
+                        "-I", os.path.join(ROOT, "include"), str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def test_status_strings():
     assert sp.status_str(0) == "ok"
     for s in (-1, -2, -3, -4, -5):

@@ -184,6 +184,13 @@ def main():
         line["roofline"].update({"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                                  "frac": gbs / PEAK_HBM_GBS})
 
+    # what this chip sustains on the same units with nothing in the way: a register-only MFMA loop, a read-only stream
+    line["measured_peaks"] = peaks_leg(sp, dev)
+    mp = line["measured_peaks"]
+    line["roofline"]["frac_of_measured_peak"] = (
+        line["roofline"]["achieved"] / mp["hbm_read_GBs"] if line["roofline"]["bound"] == "hbm"
+        else line["roofline"]["achieved"] / mp["mfma_bf16_random_operands_tflops"])
+
     if not args.step_only:
         line["next_step_drafting"] = drafting_leg(sp, cfg, plan, d_states, dev)
         line["decode_loop"] = decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev)
@@ -194,6 +201,49 @@ def main():
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(cfg, layers, prefix, hw, states, edges)
     print(json.dumps(line))
+
+
+def peaks_leg(sp, dev):
+    """Measured peaks beside the published ones: dense bf16 matrix instructions on register operands (all zero, and
+    pseudo-random in (-1, 1): the chip clocks lower when the operands switch), one read-only pass over 4 GiB, and a
+    device-to-device copy of 1 GiB (bytes read + bytes written)."""
+    import torch
+    sink = torch.empty(1024, dtype=torch.float32, device=dev)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def mfma(rand):
+        sp.probe_mfma(20000, rand, sink)
+        torch.cuda.synchronize()
+        e0.record()
+        flop = sp.probe_mfma(100000, rand, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        return flop / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+    out = {"mfma_bf16_zero_operands_tflops": mfma(False), "mfma_bf16_random_operands_tflops": mfma(True)}
+    src = torch.empty(4 << 30, dtype=torch.uint8, device=dev).fill_(1)
+    sink32 = torch.zeros(1, dtype=torch.int32, device=dev)
+    sp.probe_hbm_read(src, sink32)
+    torch.cuda.synchronize()
+    e0.record()
+    n = 0
+    for _ in range(3):
+        n += sp.probe_hbm_read(src, sink32)
+    e1.record()
+    torch.cuda.synchronize()
+    out["hbm_read_GBs"] = n / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    a, b = src[:1 << 30], src[1 << 30:2 << 30]
+    b.copy_(a)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(3):
+        b.copy_(a)
+    e1.record()
+    torch.cuda.synchronize()
+    out["hbm_copy_GBs"] = 3 * 2.0 * (1 << 30) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    out["note"] = ("register-only v_mfma_f32_32x32x16_bf16 loop on every SIMD (spiffy_probe_mfma) and a read-only pass over "
+                   "4 GiB (spiffy_probe_hbm_read); published peaks: 2500 TFLOP/s, 8000 GB/s")
+    return out
 
 
 def drafting_leg(sp, cfg, plan, d_states, dev, iters=50):

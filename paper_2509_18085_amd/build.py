@@ -14,7 +14,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspiffy.so")
-SOURCES = ["api.hip", "generic_kernels.hip", "graph_accept.hip", "draft_prune.hip", "head_topk.hip", "subgraph_search.hip", "mfma_gemm.hip", "mfma_attn.hip"]
+SOURCES = ["api.hip", "generic_kernels.hip", "graph_accept.hip", "draft_prune.hip", "head_topk.hip", "subgraph_search.hip", "mfma_gemm.hip", "mfma_attn.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

@@ -308,6 +308,17 @@ def test_verify_step_commit_argument_errors():
     assert sp.lib.spiffy_workspace_bytes_commit(C.byref(cfg), 512, 32, 64) == 0
 
 
+def test_probe_argument_errors():
+    flop = C.c_double(0.0)
+    assert sp.lib.spiffy_probe_mfma(0, 0, DUMMY, C.byref(flop), None) == sp.SPIFFY_EINVAL
+    assert sp.lib.spiffy_probe_mfma(1 << 25, 0, DUMMY, C.byref(flop), None) == sp.SPIFFY_EINVAL
+    assert sp.lib.spiffy_probe_mfma(10, 0, None, C.byref(flop), None) == sp.SPIFFY_EINVAL
+    assert sp.lib.spiffy_probe_mfma(10, 0, DUMMY, None, None) == sp.SPIFFY_EINVAL
+    assert sp.lib.spiffy_probe_hbm_read(None, 1024, DUMMY, None) == sp.SPIFFY_EINVAL
+    assert sp.lib.spiffy_probe_hbm_read(DUMMY, 8, DUMMY, None) == sp.SPIFFY_EINVAL
+    assert sp.lib.spiffy_probe_hbm_read(DUMMY + 8, 1024, DUMMY, None) == sp.SPIFFY_EALIGN
+
+
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):
     import importlib
     monkeypatch.setattr(sp, "LIB_PATH", str(tmp_path / "nope.so"))

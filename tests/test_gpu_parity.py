@@ -1527,3 +1527,18 @@ def test_decode_full_sequence_is_lossless_on_the_mfma_path(sp):
     assert not (res[(1, 1)]["tokens"] == cfg.mask_id).any()
     np.testing.assert_array_equal(res[(0, 1)]["tokens"], res[(0, 0)]["tokens"])
     assert sum(res[(0, 1)]["nfe"]) == sum(res[(0, 0)]["nfe"]) - (n_blocks - 1)
+
+
+def test_machine_probes_run(sp):
+    """The roofline probes launch, finish, and report the work they did (their rates are bench.py's business)."""
+    sink = torch.full((1024,), -1.0, dtype=torch.float32, device=DEV)
+    flop = sp.probe_mfma(100, False, sink)
+    torch.cuda.synchronize()
+    assert flop == 1024 * 4 * 100 * 4 * 2.0 * 32 * 32 * 16
+    assert (sink == 0).all()                                   # zero operands: every accumulator stays zero
+    sp.probe_mfma(100, True, sink)
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink).all() and (sink != 0).any()
+    src = torch.ones(3 * (1 << 20) + 48, dtype=torch.uint8, device=DEV)
+    assert sp.probe_hbm_read(src, torch.zeros(1, dtype=torch.int32, device=DEV)) == src.numel()
+    torch.cuda.synchronize()

@@ -362,27 +362,35 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   bf16_t* C = reinterpret_cast<bf16_t*>(a.C);
   if (EPI == EPI_SWIGLU) {
     // lanes 0-15 of a half hold gate values, lanes 16-31 the up values of the same features.  For every
-    // pair of rows (v, v+1) the two lanes swap one value: the gate lane keeps row v and receives up(v), the up
-    // lane keeps row v+1 and receives gate(v+1); each then finishes and stores one row
-    const bool up_lane = (l32 & 16) != 0;
-    const int up = up_lane ? 1 : 0;
+    // pair of rows (v, v+1) the two lanes swap one value (v_permlane16_swap): the gate lane keeps row v and
+    // receives up(v), the up lane keeps row v+1 and receives gate(v+1); each then finishes one row.  Two such
+    // row pairs (v, v+1), (v+2, v+3) are stored together: neighbouring lanes (features f, f+1) trade one result,
+    // the even lane stores both features of the first pair's row, the odd lane those of the second pair's row.
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    const int up = (l32 & 16) ? 1 : 0, odd = l32 & 1;
     // per-lane part of the address once; the row part below is the same for every lane of the half
-    bf16_t* Cl = C + (size_t)up * a.ldc + tj * (BN / 2) + wn * TN * 16 + (l32 & 15);
+    bf16_t* Cl = C + (size_t)(up + 2 * odd) * a.ldc + tj * (BN / 2) + wn * TN * 16 + (l32 & 15) - odd;
+    auto silu_mul = [](float g, float u) { return g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u; };
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
-      for (int v = 0; v < 16; v += 2) {
-        const int r = i0 + wm * RW + i * 32 + 8 * (v >> 2) + 4 * hh + (v & 3);   // the gate lane's row
+      for (int v = 0; v < 16; v += 4) {
+        const int r = i0 + wm * RW + i * 32 + 8 * (v >> 2) + 4 * hh;   // row of accumulator element v in the gate lanes
+        const bool ok = r + up + 2 * odd < i_max;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
-          float a0 = acc[i][j][v], a1 = acc[i][j][v + 1];
-          asm volatile("" : "+v"(a0), "+v"(a1));   // two plain selects below, not a lane-indexed element extract
-          const float keep = up_lane ? a1 : a0;
-          const float give = up_lane ? a0 : a1;
-          const float got = __shfl_xor(give, 16, 64);
-          const float g = up_lane ? got : keep, u = up_lane ? keep : got;
-          if (r + up < i_max)
-            Cl[(size_t)r * a.ldc + j * 16] = static_cast<bf16_t>(g * __builtin_amdgcn_rcpf(1.f + __expf(-g)) * u);
+          const u32x2 s0 = __builtin_amdgcn_permlane16_swap(__float_as_uint(acc[i][j][v]), __float_as_uint(acc[i][j][v + 1]),
+                                                            false, false);
+          const u32x2 s1 = __builtin_amdgcn_permlane16_swap(__float_as_uint(acc[i][j][v + 2]), __float_as_uint(acc[i][j][v + 3]),
+                                                            false, false);
+          const float h0 = silu_mul(__uint_as_float(s0[0]), __uint_as_float(s0[1]));   // row r + up
+          const float h1 = silu_mul(__uint_as_float(s1[0]), __uint_as_float(s1[1]));   // row r + 2 + up
+          const float keep = odd ? h1 : h0;
+          const float got = __shfl_xor(odd ? h0 : h1, 1, 64);
+          bf16x2 out2;
+          out2[0] = static_cast<bf16_t>(odd ? got : keep);
+          out2[1] = static_cast<bf16_t>(odd ? keep : got);
+          if (ok) *reinterpret_cast<bf16x2*>(Cl + (size_t)r * a.ldc + j * 16) = out2;
         }
       }
     return;

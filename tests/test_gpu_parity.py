@@ -1542,3 +1542,24 @@ def test_machine_probes_run(sp):
     src = torch.ones(3 * (1 << 20) + 48, dtype=torch.uint8, device=DEV)
     assert sp.probe_hbm_read(src, torch.zeros(1, dtype=torch.int32, device=DEV)) == src.numel()
     torch.cuda.synchronize()
+
+
+def test_attention_with_scores_that_jump(sp):
+    """Keys late in the prefix that dwarf everything before them (rows scaled 25x, spread over tiles and over both
+    key halves of a tile), a prefix that starts with such a key, and one in the very last, ragged tile: the
+    online-softmax reference has to move (by far more than the 2^8 it tolerates without moving) at arbitrary
+    points of the stream, and small probabilities before the jump must vanish as in the oracle."""
+    cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=1, d=256, Hq=2, Hkv=1, hd=128, F=256, V=640, P=2300, B=32, G=5)
+    w = synth.layer_weights(cfg, 0, 21)
+    pk, pv = synth.prefix_kv(cfg, 0, 21)
+    x = synth.hidden_states(cfg, 21)
+    cases = [([0], 25.0), ([300, 345, 1000, 1500, 2047, 2048, 2299], 25.0), ([64 * 7 + 31, 64 * 7 + 32], 25.0),
+             (list(range(100, 2300, 37)), 4.0)]      # the last: maxima that creep up, below and beyond 2^8 in turn
+    for big, factor in cases:
+        k = pk.clone()
+        for i, r in enumerate(big):
+            k[:, r] = (k[:, r].float() * (factor if factor > 5 else 1.0 + (factor - 1.0) * (i + 1) / len(big))).to(k.dtype)
+        got = run_layer(sp, cfg, w, k, pv, x)
+        ref = O().verify_layer(np_weights(w), to_np(k), to_np(pv), to_np(x), **oracle_kw(cfg))
+        e_max, e_norm = rel_err(to_np(got), ref)
+        assert e_max < tol(cfg), (big, e_max, e_norm)

@@ -460,6 +460,25 @@ def full_sequence_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, d
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / steps
     out = {"suffix_rows": S, "rows_per_layer": cfg.G * cfg.B + S, "ms_per_step": ms, "states_per_s": cfg.G / (ms * 1e-3)}
+
+    # what three draft blocks add to a forward pass in this regime (the paper's own operating point, D* = 3): the step
+    # with the true block alone against the step with three drafts beside it
+    def timed(g):
+        st, ed = d_states[:g].contiguous(), None
+        for _ in range(2):
+            plan.run(st, suffix, ed)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            plan.run(st, suffix, ed)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / steps
+
+    ms1, ms4 = timed(1), timed(4)
+    out["three_drafts_vs_none"] = {
+        "ms_true_block_only": ms1, "ms_with_three_drafts": ms4, "ratio": ms4 / ms1,
+        "note": "for context, not the same measurement: the paper's Table 4 has 1.2485 for LLaDA-8B on an A100 with its whole "
+                "sequence in the forward pass and attention through a dense mask"}
     del plan, pf
 
     # a whole generation in this regime: S / B + 1 blocks, the MASK tokens behind the current block recomputed in

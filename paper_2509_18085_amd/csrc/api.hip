@@ -258,7 +258,9 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
                                    prev ? prefix->P : prefix->P + B, ldp, st))))
       return rc;
   }
-  if ((rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st)))) return rc;
+  if (!(S_seq && mf && mfma_attn_supported(a)) &&      // with rows riding along, the MFMA path runs both groups in one launch below
+      (rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st))))
+    return rc;
   if (S_seq) {      // the suffix rows: queries at positions pos0+B .., keys = cache rows 0 .. P+B+S_seq-1, no block of their own
     const size_t es = esize(dt);
     AttnArgs b = a;
@@ -270,7 +272,9 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
     if (prev) {     // the finished block: one state at the positions before pos0, over the rows in front of it
       b.P = prefix->P; b.S = prefix->S; b.own = 1; b.pos0 = pos0 - B;
     }
-    if ((rc = dev(mf && mfma_attn_supported(b) ? launch_attn_mfma(b, st) : launch_attn_generic(dt, b, st)))) return rc;
+    if (mf && mfma_attn_supported(a)) {       // (b differs from a in row counts and lengths only)
+      if ((rc = dev(launch_attn_mfma_pair(a, b, st)))) return rc;
+    } else if ((rc = dev(launch_attn_generic(dt, b, st)))) return rc;
   }
 
   // output projection + residual (+ RMSNorm-2 fused into the split-K reduction when K is sliced)

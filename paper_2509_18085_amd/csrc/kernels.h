@@ -113,6 +113,7 @@ hipError_t launch_splitk_reduce(const float* P, int ksplit, const void* R, void*
 bool mfma_attn_supported(const AttnArgs& a);
 size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P);
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st);
+hipError_t launch_attn_mfma_pair(const AttnArgs& a, const AttnArgs& b, hipStream_t st);   // two problems, one launch
 
 // Calibration, part 3 (Alg. 2; App. D.1): best connected node set of size D.  All pointers device memory.
 struct SubgraphArgs {

@@ -302,12 +302,12 @@ __device__ __forceinline__ void rotate_frags(bf16x8 (&f)[8], const float2* __res
 
 // DUAL: the cache also holds rows of the tokens after the block (a.S > 0)
 template <bool DUAL>
-__global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
+__device__ __forceinline__ void attn_prefix_body(const AttnKArgs& a, int bid) {
   extern __shared__ __align__(16) unsigned char smem_raw[];
   bf16_t* smem = reinterpret_cast<bf16_t*>(smem_raw);
 
   const int total = a.nQ * a.nS * a.Hq;
-  const int L = xcd_contiguous(blockIdx.x, total);
+  const int L = xcd_contiguous(bid, total);
   const int qt = L % a.nQ;
   const int sp = (L / a.nQ) % a.nS;
   const int h = L / (a.nQ * a.nS);
@@ -548,6 +548,19 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
   }
 }
 
+template <bool DUAL>
+__global__ __launch_bounds__(NT) void attn_prefix_mfma_kernel(AttnKArgs a) {
+  attn_prefix_body<DUAL>(a, (int)blockIdx.x);
+}
+
+// Two independent attention problems in one launch (the G states and, beside them, the rows that ride along with a
+// step: the recomputed suffix, or the block being committed): the first n_a workgroups take `a`, the rest `b`.
+// Each part alone would leave most CUs idle when there are few states.
+__global__ __launch_bounds__(NT) void attn_prefix_mfma_pair_kernel(AttnKArgs a, AttnKArgs b, int n_a) {
+  if ((int)blockIdx.x < n_a) attn_prefix_body<true>(a, (int)blockIdx.x);
+  else attn_prefix_body<true>(b, (int)blockIdx.x - n_a);
+}
+
 // merge the prefix splits of each (row, head): weights 2^(m_s - max m)
 __global__ __launch_bounds__(128) void attn_combine_kernel(const float* __restrict__ opart,
                                                            const float* __restrict__ mlpart, bf16_t* __restrict__ out,
@@ -596,12 +609,10 @@ size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P) {
   return bytes;
 }
 
-hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
-  static std::atomic<unsigned long long> lds_ok[2];
-  hipError_t e = allow_dynamic_lds((const void*)attn_prefix_mfma_kernel<false>, (int)kAttnSmem, lds_ok[0]);
-  if (e != hipSuccess) return e;
-  e = allow_dynamic_lds((const void*)attn_prefix_mfma_kernel<true>, (int)kAttnSmem, lds_ok[1]);
-  if (e != hipSuccess) return e;
+namespace {
+
+// kernel arguments of one attention problem; launches the rotary table kernel when the table is not in place yet
+AttnKArgs prepare_attn(const AttnArgs& a, hipStream_t st) {
   const int M = a.G * a.B;
   const int nS = n_splits(a.P + a.S);
   unsigned char* ws = reinterpret_cast<unsigned char*>(a.partial);
@@ -628,9 +639,40 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   k.nQ = cdiv(M, QTILE);
   k.nS = nS;
   k.split = (int)align_up(cdiv(a.P + a.S, nS), KTILE);      // at most SPLIT_KEYS; a function of P + S only
-  if (a.S > 0) attn_prefix_mfma_kernel<true><<<k.nQ * nS * a.Hq, NT, kAttnSmem, st>>>(k);
-  else attn_prefix_mfma_kernel<false><<<k.nQ * nS * a.Hq, NT, kAttnSmem, st>>>(k);
-  if (nS > 1) attn_combine_kernel<<<M * a.Hq, 128, 0, st>>>(opart, mlpart, (bf16_t*)a.out, M, a.Hq, nS);
+  return k;
+}
+
+hipError_t attn_lds_limits() {
+  static std::atomic<unsigned long long> lds_ok[3];
+  hipError_t e = allow_dynamic_lds((const void*)attn_prefix_mfma_kernel<false>, (int)kAttnSmem, lds_ok[0]);
+  if (e != hipSuccess) return e;
+  e = allow_dynamic_lds((const void*)attn_prefix_mfma_kernel<true>, (int)kAttnSmem, lds_ok[1]);
+  if (e != hipSuccess) return e;
+  return allow_dynamic_lds((const void*)attn_prefix_mfma_pair_kernel, (int)kAttnSmem, lds_ok[2]);
+}
+
+}  // namespace
+
+hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
+  const hipError_t e = attn_lds_limits();
+  if (e != hipSuccess) return e;
+  const AttnKArgs k = prepare_attn(a, st);
+  const int grid = k.nQ * k.nS * a.Hq;
+  if (a.S > 0) attn_prefix_mfma_kernel<true><<<grid, NT, kAttnSmem, st>>>(k);
+  else attn_prefix_mfma_kernel<false><<<grid, NT, kAttnSmem, st>>>(k);
+  if (k.nS > 1) attn_combine_kernel<<<k.M * a.Hq, 128, 0, st>>>(k.opart, k.mlpart, k.out, k.M, a.Hq, k.nS);
+  return hipGetLastError();
+}
+
+// two independent problems (different query rows, outputs and scratch; they may read the same cache) in one launch
+hipError_t launch_attn_mfma_pair(const AttnArgs& a, const AttnArgs& b, hipStream_t st) {
+  const hipError_t e = attn_lds_limits();
+  if (e != hipSuccess) return e;
+  const AttnKArgs ka = prepare_attn(a, st), kb = prepare_attn(b, st);
+  const int n_a = ka.nQ * ka.nS * a.Hq, n_b = kb.nQ * kb.nS * b.Hq;
+  attn_prefix_mfma_pair_kernel<<<n_a + n_b, NT, kAttnSmem, st>>>(ka, kb, n_a);
+  if (ka.nS > 1) attn_combine_kernel<<<ka.M * a.Hq, 128, 0, st>>>(ka.opart, ka.mlpart, ka.out, ka.M, a.Hq, ka.nS);
+  if (kb.nS > 1) attn_combine_kernel<<<kb.M * b.Hq, 128, 0, st>>>(kb.opart, kb.mlpart, kb.out, kb.M, b.Hq, kb.nS);
   return hipGetLastError();
 }
 

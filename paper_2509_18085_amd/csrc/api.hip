@@ -246,17 +246,25 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   a.own = 1;
   a.pos0 = pos0; a.rope_base = cfg->rope_base; a.rope_ready = chain && chain->rope_ready;
   const int ldp = prefix->capacity ? prefix->capacity : prefix->P;
-  if (chain && (chain->append_kv || (S_seq && !prev)) &&
-      (rc = dev(launch_kv_append(dt, ws.qkv, a.Hq, a.Hkv, a.hd, B, pos0, cfg->rope_base,
-                                 const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st))))
-    return rc;
-  if (S_seq) {
-    const size_t es = esize(dt);
-    const char* qkv_seq = reinterpret_cast<const char*>(ws.qkv) + (size_t)G * B * g.N * es;
-    if ((rc = dev(launch_kv_append(dt, qkv_seq, a.Hq, a.Hkv, a.hd, S_seq, prev ? pos0 - B : pos0 + B, cfg->rope_base,
-                                   const_cast<void*>(prefix->k), const_cast<void*>(prefix->v),
-                                   prev ? prefix->P : prefix->P + B, ldp, st))))
+  if (S_seq && !prev) {
+    // the true block (state 0: qkv rows 0 .. B-1) and the suffix (qkv rows G*B ..) land next to each other in the cache,
+    // at consecutive positions: one launch over the two runs of rows
+    if ((rc = dev(launch_kv_append(dt, ws.qkv, a.Hq, a.Hkv, a.hd, B + S_seq, pos0, cfg->rope_base,
+                                   const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st, B,
+                                   (G - 1) * B))))
       return rc;
+  } else {
+    if (chain && chain->append_kv &&
+        (rc = dev(launch_kv_append(dt, ws.qkv, a.Hq, a.Hkv, a.hd, B, pos0, cfg->rope_base,
+                                   const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st))))
+      return rc;
+    if (S_seq) {     // the finished block in front of the states
+      const size_t es = esize(dt);
+      const char* qkv_seq = reinterpret_cast<const char*>(ws.qkv) + (size_t)G * B * g.N * es;
+      if ((rc = dev(launch_kv_append(dt, qkv_seq, a.Hq, a.Hkv, a.hd, S_seq, pos0 - B, cfg->rope_base,
+                                     const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st))))
+        return rc;
+    }
   }
   if (!(S_seq && mf && mfma_attn_supported(a)) &&      // with rows riding along, the MFMA path runs both groups in one launch below
       (rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st))))

@@ -350,14 +350,15 @@ hipError_t launch_compact_rows(const int32_t* tok, const uint8_t* mask, int mask
 template <typename T>
 __global__ __launch_bounds__(256) void kv_append_kernel(const T* __restrict__ qkv, int Hq, int Hkv, int hd, int B,
                                                         int pos0, float base, T* __restrict__ ck, T* __restrict__ cv,
-                                                        int P, int ldp) {
+                                                        int P, int ldp, int B0, int skip) {
   const int half = hd / 2;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B * Hkv * half) return;
   const int f = i % half, kvh = (i / half) % Hkv, b = i / (half * Hkv);
   const int ld = (Hq + 2 * Hkv) * hd;
-  const T* kr = qkv + (size_t)b * ld + (Hq + kvh) * hd;
-  const T* vr = qkv + (size_t)b * ld + (Hq + Hkv + kvh) * hd;
+  const int src = b < B0 ? b : b + skip;      // the rows may come in two runs: B0 rows, `skip` rows that are not appended, the rest
+  const T* kr = qkv + (size_t)src * ld + (Hq + kvh) * hd;
+  const T* vr = qkv + (size_t)src * ld + (Hq + Hkv + kvh) * hd;
   // same table values as the attention kernels use: angle in double, cos / sin rounded to float
   const double inv_freq = pow((double)base, -2.0 * (double)f / (double)hd);
   const double ang = (double)(pos0 + b) * inv_freq;
@@ -372,14 +373,15 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const T* __restrict__ qk
 }
 
 hipError_t launch_kv_append(int dtype, const void* qkv, int Hq, int Hkv, int hd, int B, int pos0, float rope_base,
-                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st) {
+                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st, int B0, int skip) {
+  if (B0 <= 0) { B0 = B; skip = 0; }
   const int n = B * Hkv * (hd / 2);
   if (dtype == SPIFFY_F32)
     kv_append_kernel<float><<<cdiv(n, 256), 256, 0, st>>>((const float*)qkv, Hq, Hkv, hd, B, pos0, rope_base,
-                                                          (float*)cache_k, (float*)cache_v, P, ldp);
+                                                          (float*)cache_k, (float*)cache_v, P, ldp, B0, skip);
   else
     kv_append_kernel<bf16_t><<<cdiv(n, 256), 256, 0, st>>>((const bf16_t*)qkv, Hq, Hkv, hd, B, pos0, rope_base,
-                                                           (bf16_t*)cache_k, (bf16_t*)cache_v, P, ldp);
+                                                           (bf16_t*)cache_k, (bf16_t*)cache_v, P, ldp, B0, skip);
   return hipGetLastError();
 }
 

@@ -31,8 +31,9 @@ hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t st);
 // Prefix-cache extension (Sec. 3.1): the K rows (rotated at positions pos0 .. pos0+B-1) and V rows of the
 // first B rows of the fused qkv activations go to rows P .. P+B-1 of every KV head of the cache
 // ([Hkv][ldp][hd]).  Must run before the attention of the same layer reads the cache only up to row P.
+// rows 0 .. B-1 of the appended range come from qkv rows 0 .. B0-1 and B0+skip .. (B0 <= 0: one run of B rows)
 hipError_t launch_kv_append(int dtype, const void* qkv, int Hq, int Hkv, int hd, int B, int pos0, float rope_base,
-                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st);
+                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st, int B0 = 0, int skip = 0);
 
 // masked-row list: row_idx[0..count) = flattened (g,b) with mask set, ascending; *count.
 hipError_t launch_compact_rows(const int32_t* tokens, const uint8_t* mask, int mask_id, int M,

@@ -246,23 +246,45 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
   a.own = 1;
   a.pos0 = pos0; a.rope_base = cfg->rope_base; a.rope_ready = chain && chain->rope_ready;
   const int ldp = prefix->capacity ? prefix->capacity : prefix->P;
+  // The appends rotate keys with the tables the attention kernels use (built here, once per step, when the MFMA
+  // attention will run; otherwise the append computes the same values itself).
+  const bool mfa = mf && mfma_attn_supported(a);
+  const int tail_pos0 = prev ? pos0 - B : pos0 + B;
+  bool tail_rope_ready = chain && chain->rope_ready_seq;
+  const void *tab = nullptr, *tab_tail = nullptr;
+  if (mfa && chain && (chain->append_kv || S_seq)) {
+    if (!a.rope_ready) {
+      launch_rope_table(ws.attn_partial, B, pos0, cfg->rope_base, st);
+      a.rope_ready = 1;
+    }
+    tab = ws.attn_partial;
+    if (S_seq) {
+      if (!tail_rope_ready) {
+        launch_rope_table(ws.attn_partial_seq, S_seq, tail_pos0, cfg->rope_base, st);
+        tail_rope_ready = true;
+      }
+      tab_tail = ws.attn_partial_seq;
+    }
+  }
   if (S_seq && !prev) {
     // the true block (state 0: qkv rows 0 .. B-1) and the suffix (qkv rows G*B ..) land next to each other in the cache,
     // at consecutive positions: one launch over the two runs of rows
     if ((rc = dev(launch_kv_append(dt, ws.qkv, a.Hq, a.Hkv, a.hd, B + S_seq, pos0, cfg->rope_base,
                                    const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st, B,
-                                   (G - 1) * B))))
+                                   (G - 1) * B, tab, tab_tail))))
       return rc;
   } else {
     if (chain && chain->append_kv &&
         (rc = dev(launch_kv_append(dt, ws.qkv, a.Hq, a.Hkv, a.hd, B, pos0, cfg->rope_base,
-                                   const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st))))
+                                   const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st, 0, 0,
+                                   tab))))
       return rc;
     if (S_seq) {     // the finished block in front of the states
       const size_t es = esize(dt);
       const char* qkv_seq = reinterpret_cast<const char*>(ws.qkv) + (size_t)G * B * g.N * es;
-      if ((rc = dev(launch_kv_append(dt, qkv_seq, a.Hq, a.Hkv, a.hd, S_seq, pos0 - B, cfg->rope_base,
-                                     const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st))))
+      if ((rc = dev(launch_kv_append(dt, qkv_seq, a.Hq, a.Hkv, a.hd, S_seq, tail_pos0, cfg->rope_base,
+                                     const_cast<void*>(prefix->k), const_cast<void*>(prefix->v), prefix->P, ldp, st, 0, 0,
+                                     tab_tail))))
         return rc;
     }
   }
@@ -276,9 +298,9 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
     b.out = reinterpret_cast<char*>(ws.attn) + (size_t)G * B * qd * es;
     b.partial = ws.attn_partial_seq;
     b.G = 1; b.B = S_seq; b.P = prefix->P + B + S_seq; b.S = 0; b.own = 0;
-    b.pos0 = pos0 + B; b.rope_ready = chain->rope_ready_seq;
+    b.pos0 = tail_pos0; b.rope_ready = tail_rope_ready;
     if (prev) {     // the finished block: one state at the positions before pos0, over the rows in front of it
-      b.P = prefix->P; b.S = prefix->S; b.own = 1; b.pos0 = pos0 - B;
+      b.P = prefix->P; b.S = prefix->S; b.own = 1;
     }
     if (mf && mfma_attn_supported(a)) {       // (b differs from a in row counts and lengths only)
       if ((rc = dev(launch_attn_mfma_pair(a, b, st)))) return rc;

@@ -350,7 +350,9 @@ hipError_t launch_compact_rows(const int32_t* tok, const uint8_t* mask, int mask
 template <typename T>
 __global__ __launch_bounds__(256) void kv_append_kernel(const T* __restrict__ qkv, int Hq, int Hkv, int hd, int B,
                                                         int pos0, float base, T* __restrict__ ck, T* __restrict__ cv,
-                                                        int P, int ldp, int B0, int skip) {
+                                                        int P, int ldp, int B0, int skip,
+                                                        const float2* __restrict__ tab_a,
+                                                        const float2* __restrict__ tab_b) {
   const int half = hd / 2;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= B * Hkv * half) return;
@@ -360,9 +362,17 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const T* __restrict__ qk
   const T* kr = qkv + (size_t)src * ld + (Hq + kvh) * hd;
   const T* vr = qkv + (size_t)src * ld + (Hq + Hkv + kvh) * hd;
   // same table values as the attention kernels use: angle in double, cos / sin rounded to float
-  const double inv_freq = pow((double)base, -2.0 * (double)f / (double)hd);
-  const double ang = (double)(pos0 + b) * inv_freq;
-  const float c = (float)cos(ang), s = (float)sin(ang);
+  float c, s;
+  if (tab_a) {      // the table the attention kernels rotate with: [f][row]
+    const float2 cs = b < B0 ? tab_a[(size_t)f * B0 + b] : tab_b[(size_t)f * (B - B0) + (b - B0)];
+    c = cs.x;
+    s = cs.y;
+  } else {
+    const double inv_freq = pow((double)base, -2.0 * (double)f / (double)hd);
+    const double ang = (double)(pos0 + b) * inv_freq;
+    c = (float)cos(ang);
+    s = (float)sin(ang);
+  }
   const float x1 = to_f32(kr[f]), x2 = to_f32(kr[f + half]);
   T* kd = ck + ((size_t)kvh * ldp + P + b) * hd;
   T* vd = cv + ((size_t)kvh * ldp + P + b) * hd;
@@ -373,15 +383,19 @@ __global__ __launch_bounds__(256) void kv_append_kernel(const T* __restrict__ qk
 }
 
 hipError_t launch_kv_append(int dtype, const void* qkv, int Hq, int Hkv, int hd, int B, int pos0, float rope_base,
-                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st, int B0, int skip) {
+                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st, int B0, int skip,
+                            const void* tab_a, const void* tab_b) {
   if (B0 <= 0) { B0 = B; skip = 0; }
+  if (!tab_a || (B0 < B && !tab_b)) tab_a = tab_b = nullptr;
   const int n = B * Hkv * (hd / 2);
   if (dtype == SPIFFY_F32)
     kv_append_kernel<float><<<cdiv(n, 256), 256, 0, st>>>((const float*)qkv, Hq, Hkv, hd, B, pos0, rope_base,
-                                                          (float*)cache_k, (float*)cache_v, P, ldp, B0, skip);
+                                                          (float*)cache_k, (float*)cache_v, P, ldp, B0, skip,
+                                                          (const float2*)tab_a, (const float2*)tab_b);
   else
     kv_append_kernel<bf16_t><<<cdiv(n, 256), 256, 0, st>>>((const bf16_t*)qkv, Hq, Hkv, hd, B, pos0, rope_base,
-                                                           (bf16_t*)cache_k, (bf16_t*)cache_v, P, ldp, B0, skip);
+                                                           (bf16_t*)cache_k, (bf16_t*)cache_v, P, ldp, B0, skip,
+                                                           (const float2*)tab_a, (const float2*)tab_b);
   return hipGetLastError();
 }
 

@@ -31,9 +31,12 @@ hipError_t launch_attn_generic(int dtype, const AttnArgs& a, hipStream_t st);
 // Prefix-cache extension (Sec. 3.1): the K rows (rotated at positions pos0 .. pos0+B-1) and V rows of the
 // first B rows of the fused qkv activations go to rows P .. P+B-1 of every KV head of the cache
 // ([Hkv][ldp][hd]).  Must run before the attention of the same layer reads the cache only up to row P.
-// rows 0 .. B-1 of the appended range come from qkv rows 0 .. B0-1 and B0+skip .. (B0 <= 0: one run of B rows)
+// rows 0 .. B-1 of the appended range come from qkv rows 0 .. B0-1 and B0+skip .. (B0 <= 0: one run of B rows).
+// tab_a / tab_b: optional rotary tables [hd/2][n] (cos, sin) for the first B0 rows (n = B0) and for the rest
+// (n = B - B0), as the attention kernels use them; NULL = the same values computed in the kernel.
 hipError_t launch_kv_append(int dtype, const void* qkv, int Hq, int Hkv, int hd, int B, int pos0, float rope_base,
-                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st, int B0 = 0, int skip = 0);
+                            void* cache_k, void* cache_v, int P, int ldp, hipStream_t st, int B0 = 0, int skip = 0,
+                            const void* tab_a = nullptr, const void* tab_b = nullptr);
 
 // masked-row list: row_idx[0..count) = flattened (g,b) with mask set, ascending; *count.
 hipError_t launch_compact_rows(const int32_t* tokens, const uint8_t* mask, int mask_id, int M,
@@ -114,6 +117,7 @@ hipError_t launch_splitk_reduce(const float* P, int ksplit, const void* R, void*
 bool mfma_attn_supported(const AttnArgs& a);
 size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P);
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st);
+const void* launch_rope_table(void* partial, int B, int pos0, float rope_base, hipStream_t st);   // head_dim 128 only
 hipError_t launch_attn_mfma_pair(const AttnArgs& a, const AttnArgs& b, hipStream_t st);   // two problems, one launch
 
 // Calibration, part 3 (Alg. 2; App. D.1): best connected node set of size D.  All pointers device memory.

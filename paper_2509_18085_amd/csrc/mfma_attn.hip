@@ -609,6 +609,15 @@ size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P) {
   return bytes;
 }
 
+// The rotary table of an attention problem with B rows per state at positions pos0 ..: [hd/2][B] (cos, sin), at the start
+// of that problem's scratch.  Callers that need it before the attention launch (the cache append) build it here and
+// pass rope_ready = 1 to the attention launch.
+const void* launch_rope_table(void* partial, int B, int pos0, float rope_base, hipStream_t st) {
+  const int nrope = B * (HD / 2);
+  rope_table_kernel<<<cdiv(nrope, 256), 256, 0, st>>>(reinterpret_cast<float2*>(partial), B, HD / 2, HD, pos0, rope_base);
+  return partial;
+}
+
 namespace {
 
 // kernel arguments of one attention problem; launches the rotary table kernel when the table is not in place yet

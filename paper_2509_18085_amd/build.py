@@ -15,7 +15,10 @@ CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspiffy.so")
 SOURCES = ["api.hip", "generic_kernels.hip", "graph_accept.hip", "draft_prune.hip", "head_topk.hip", "subgraph_search.hip", "mfma_gemm.hip", "mfma_attn.hip", "probe.hip"]
-FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
+# -ffp-contract=on: a multiply and an add are fused only where the source writes them in one expression, so the
+# rounding of a kernel does not depend on how the optimiser inlined or ordered it (different instantiations of one
+# kernel body have to agree bit for bit)
+FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden", "-ffp-contract=on",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 

@@ -272,6 +272,7 @@ struct AttnKArgs {
   int M, B, Hq, Hkv, P, S, ldp, ld, nQ, nS;   // ldp = rows allocated per KV head of the cache; S = suffix rows
   int own;                                     // 0: no own-block keys (queries that only read the cache)
   int split;                                   // cached rows per split: the P + S rows shared out evenly, whole tiles
+  int qrows;                                   // query rows a workgroup owns: 128, or 64 / 32 when there are few workgroups (scheduling only)
 };
 
 // the lane's 8 MFMA operand fragments of LDS tile row `row` (K layout): hd = 16*kk + 8*hh + e
@@ -316,12 +317,13 @@ __device__ __forceinline__ void attn_prefix_body(const AttnKArgs& a, int bid) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int l32 = lane & 31, hh = lane >> 5;
   const int qw = wave >> 1, st = wave & 1;    // query group of the wavefront pair, key half of this wavefront
-  const int m0 = qt * QTILE;
+  const int m0 = qt * a.qrows;
+  const int m_end = min(a.M, m0 + a.qrows);     // the workgroup's query rows are m0 .. m_end-1
   const int m0w = m0 + qw * 32;
   const int qrow = min(m0w + l32, a.M - 1);
   // A wavefront pair whose 32 query rows all lie beyond M (one or two states in a 128-row tile) takes part in the
   // transfers and barriers only: the pairs that do have rows then keep their SIMDs to themselves.
-  const bool active = __builtin_amdgcn_readfirstlane(m0w) < a.M;
+  const bool active = __builtin_amdgcn_readfirstlane(m0w) < m_end;
 
   WaveState w;
   w.m_run = -INFINITY;
@@ -366,7 +368,7 @@ __device__ __forceinline__ void attn_prefix_body(const AttnKArgs& a, int bid) {
   // own-block rows c0 .. c0+127 (K and V columns of the fused activations) into stages 1 and 2
   const bool has_own = a.own && sp == a.nS - 1;
   const int own_lo = (m0 / a.B) * a.B;
-  const int own_hi = min(a.M, ((min(m0 + QTILE, a.M) - 1) / a.B + 1) * a.B);
+  const int own_hi = min(a.M, ((m_end - 1) / a.B + 1) * a.B);
   auto issue_own = [&](int c0) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
@@ -516,7 +518,7 @@ __device__ __forceinline__ void attn_prefix_body(const AttnKArgs& a, int bid) {
 
   // ---- write ----------------------------------------------------------------------------------
   const float l_tot = w.l_run + __shfl_xor(w.l_run, 32, 64);
-  if (m0w + l32 >= a.M) return;
+  if (m0w + l32 >= m_end) return;
   if (a.nS == 1) {
     const float inv = 1.0f / l_tot;
     bf16_t* op = a.out + (size_t)qrow * (a.Hq * HD) + h * HD + 4 * hh;
@@ -645,7 +647,16 @@ AttnKArgs prepare_attn(const AttnArgs& a, hipStream_t st) {
   k.M = M; k.B = a.B; k.Hq = a.Hq; k.Hkv = a.Hkv; k.P = a.P; k.S = a.S; k.ldp = a.ldp ? a.ldp : a.P;
   k.own = a.own;
   k.ld = (a.Hq + 2 * a.Hkv) * HD;
-  k.nQ = cdiv(M, QTILE);
+  // With few workgroups (one to eight states) a workgroup takes 64 or 32 query rows instead of 128, so that more CUs
+  // stream the keys; the wavefront pairs without rows only move data.  A row's arithmetic is the same (own-block keys
+  // are visited in 32-row groups counted from a multiple of 32 either way) as long as B divides 32 or 32 divides B.
+  k.qrows = QTILE;
+  if (32 % a.B == 0 || a.B % 32 == 0) {
+    const int wgs = cdiv(M, QTILE) * nS * a.Hq;
+    if (wgs <= 64) k.qrows = 32;
+    else if (wgs <= 128) k.qrows = 64;
+  }
+  k.nQ = cdiv(M, k.qrows);
   k.nS = nS;
   k.split = (int)align_up(cdiv(a.P + a.S, nS), KTILE);      // at most SPLIT_KEYS; a function of P + S only
   return k;

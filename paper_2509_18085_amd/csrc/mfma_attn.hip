@@ -649,9 +649,10 @@ AttnKArgs prepare_attn(const AttnArgs& a, hipStream_t st) {
   k.ld = (a.Hq + 2 * a.Hkv) * HD;
   // With few workgroups (one to eight states) a workgroup takes 64 or 32 query rows instead of 128, so that more CUs
   // stream the keys; the wavefront pairs without rows only move data.  A row's arithmetic is the same (own-block keys
-  // are visited in 32-row groups counted from a multiple of 32 either way) as long as B divides 32 or 32 divides B.
+  // are visited in 32-row groups counted from a multiple of 32 either way) as long as B divides 32 or 32 divides B,
+  // and always when there are no own-block keys.
   k.qrows = QTILE;
-  if (32 % a.B == 0 || a.B % 32 == 0) {
+  if (!a.own || 32 % a.B == 0 || a.B % 32 == 0) {
     const int wgs = cdiv(M, QTILE) * nS * a.Hq;
     if (wgs <= 64) k.qrows = 32;
     else if (wgs <= 128) k.qrows = 64;

@@ -64,6 +64,33 @@ __device__ __forceinline__ float dot_row<float>(const float* __restrict__ x, con
   return wave_sum(acc);
 }
 
+// dot products of x with four consecutive rows of w (row stride d): the same per-lane order and wavefront sum as dot_row
+template <typename T>
+__device__ __forceinline__ void dot_rows4(const T* __restrict__ x, const T* __restrict__ w, int d, int lane, float (&out)[4]);
+template <>
+__device__ __forceinline__ void dot_rows4<bf16_t>(const bf16_t* __restrict__ x, const bf16_t* __restrict__ w, int d, int lane,
+                                                  float (&out)[4]) {
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int e = lane * 8; e < d; e += 512) {
+    const bf16x8 a = *reinterpret_cast<const bf16x8*>(x + e);
+    bf16x8 b[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) b[u] = *reinterpret_cast<const bf16x8*>(w + (size_t)u * d + e);
+#pragma unroll
+    for (int u = 0; u < 4; ++u)
+#pragma unroll
+      for (int t = 0; t < 8; ++t) acc[u] = fmaf(static_cast<float>(a[t]), static_cast<float>(b[u][t]), acc[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) out[u] = wave_sum(acc[u]);
+}
+template <>
+__device__ __forceinline__ void dot_rows4<float>(const float* __restrict__ x, const float* __restrict__ w, int d, int lane,
+                                                 float (&out)[4]) {
+#pragma unroll
+  for (int u = 0; u < 4; ++u) out[u] = dot_row<float>(x, w + (size_t)u * d, d, lane);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void topk_refine_kernel(HeadTopkArgs a) {
   __shared__ float s_val[4];
@@ -122,11 +149,26 @@ __global__ __launch_bounds__(256) void topk_refine_kernel(HeadTopkArgs a) {
   // ---- its 128 logits: wavefront w takes vocabulary rows v0 + 32w .. v0 + 32w + 31
   const int v0 = chunk * 128;
   const T* x = reinterpret_cast<const T*>(a.nf) + (size_t)r * a.d;
-  for (int i = 0; i < 32; ++i) {
-    const int v = v0 + w * 32 + i;
-    float l = -INFINITY;
-    if (v < a.V) l = dot_row<T>(x, reinterpret_cast<const T*>(a.w_vocab) + (size_t)v * a.d, a.d, lane) * a.scale;
-    if (lane == 0) s_logit[w * 32 + i] = l;
+  // four vocabulary rows at a time, so that their loads are in flight together (every row keeps its own accumulation
+  // order: the logits are those of one row after the other)
+  for (int i = 0; i < 32; i += 4) {
+    float l[4];
+    if (v0 + w * 32 + i + 3 < a.V) {
+      dot_rows4<T>(x, reinterpret_cast<const T*>(a.w_vocab) + (size_t)(v0 + w * 32 + i) * a.d, a.d, lane, l);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) l[u] *= a.scale;
+    } else {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int v = v0 + w * 32 + i + u;
+        l[u] = -INFINITY;
+        if (v < a.V) l[u] = dot_row<T>(x, reinterpret_cast<const T*>(a.w_vocab) + (size_t)v * a.d, a.d, lane) * a.scale;
+      }
+    }
+    if (lane == 0) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) s_logit[w * 32 + i + u] = l[u];
+    }
   }
   __syncthreads();
   // ---- the chunk's K best

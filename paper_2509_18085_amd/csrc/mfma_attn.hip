@@ -9,7 +9,10 @@
 // A prefix K/V tile of 64 keys is staged in LDS once and used by all 128 query rows (4 states of
 // 32 tokens, or 32 states of 4); workgroups of the same head run next to each other on one XCD
 // so the tile comes from HBM once and from L2 afterwards.  The number of prefix splits depends on
-// P only, so a row's arithmetic does not depend on G.
+// P only, so a row's arithmetic does not depend on G.  With few states (at most 128 such workgroups) a
+// workgroup owns 64 or 32 of the 128 rows instead and the other wavefront pairs only move data: more CUs
+// stream, nothing else changes.  A step that carries a second group of rows (the recomputed suffix of a
+// full-sequence model, or the block being committed) runs both attention problems in one launch.
 //
 // Everything the workgroup reads travels global -> LDS directly as whole 256-byte rows (LDS-DMA loads, no
 // registers): the 128 Q rows and the own-block K/V rows once at the start, the prefix tiles into a ring of

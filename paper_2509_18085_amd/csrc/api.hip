@@ -288,8 +288,8 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
         return rc;
     }
   }
-  if (!(S_seq && mf && mfma_attn_supported(a)) &&      // with rows riding along, the MFMA path runs both groups in one launch below
-      (rc = dev(mf && mfma_attn_supported(a) ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st))))
+  if (!(S_seq && mfa) &&      // with rows riding along, the MFMA path runs both groups in one launch below
+      (rc = dev(mfa ? launch_attn_mfma(a, st) : launch_attn_generic(dt, a, st))))
     return rc;
   if (S_seq) {      // the suffix rows: queries at positions pos0+B .., keys = cache rows 0 .. P+B+S_seq-1, no block of their own
     const size_t es = esize(dt);
@@ -302,7 +302,7 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
     if (prev) {     // the finished block: one state at the positions before pos0, over the rows in front of it
       b.P = prefix->P; b.S = prefix->S; b.own = 1;
     }
-    if (mf && mfma_attn_supported(a)) {       // (b differs from a in row counts and lengths only)
+    if (mfa) {       // (b differs from a in row counts and lengths only)
       if ((rc = dev(launch_attn_mfma_pair(a, b, st)))) return rc;
     } else if ((rc = dev(launch_attn_generic(dt, b, st)))) return rc;
   }

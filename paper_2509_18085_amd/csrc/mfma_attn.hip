@@ -38,7 +38,7 @@
 //                  8-byte pieces addressed by lanes q, q+4, q+8, q+12), B operand = P^T straight from
 //                  the S^T accumulators (no trip through LDS); the rescale factor is per lane.
 // Own-block keys (the block diagonal) come first, handled by the last prefix split: they always go to the
-// first wavefront of a pair, 32 keys at a time in row order, so a state's arithmetic does not depend on
+// wavefront of a pair that takes the first key half, 32 keys at a time in row order, so a state's arithmetic does not depend on
 // where its rows sit in the tile; the mask is applied per element (any B works).
 // Rotary embedding (positions pos0..pos0+B-1 for every state, Sec. 4.3) is applied to the Q and own-block K
 // fragments in registers, on their way from LDS to the matrix pipe; the cached prefix K arrives rotated.
@@ -319,7 +319,10 @@ __device__ __forceinline__ void attn_prefix_body(const AttnKArgs& a, int bid) {
 
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int l32 = lane & 31, hh = lane >> 5;
-  const int qw = wave >> 1, st = wave & 1;    // query group of the wavefront pair, key half of this wavefront
+  // query group of the wavefront pair, and this wavefront's role in it: the key half it takes (role 0 also takes the
+  // own-block keys and finishes the pair's rows).  Role 0 sits on wavefronts 0, 2, 5, 7, one per SIMD when wavefronts go
+  // round the four SIMDs in order: the four pairs' own-block phases and final merges then do not share SIMDs two by two.
+  const int qw = wave >> 1, st = (wave ^ (wave >> 2)) & 1;
   const int m0 = qt * a.qrows;
   const int m_end = min(a.M, m0 + a.qrows);     // the workgroup's query rows are m0 .. m_end-1
   const int m0w = m0 + qw * 32;
@@ -394,7 +397,7 @@ __device__ __forceinline__ void attn_prefix_body(const AttnKArgs& a, int bid) {
   load_frags(w.qf, smem + 3 * STAGE_ELEMS, qw * 32 + l32, hh);
   rotate_frags(w.qf, a.rope, a.B, qrow, hh, 1.4426950408889634f * 0.08838834764831845f);
 
-  // ---- own-block keys: the block diagonal, handled by the last split.  They always go to the first wavefront
+  // ---- own-block keys: the block diagonal, handled by the last split.  They always go to the role-0 wavefront
   // of the pair, 32 keys at a time in row order, so a state's arithmetic does not depend on where its rows sit
   // in the 128-row tile.  K fragments are rotated in registers on their way from LDS to the matrix pipe.
   if (has_own) {

@@ -53,15 +53,19 @@ __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F
 
 // 64-row tiles, and 128-row tiles up to 128 columns wide, are weight-streaming shapes: both operand rings SD deep
 constexpr bool uniform_rings(int epi, int bn, int bmt) { return epi != EPI_LMHEAD && (bmt <= 64 || (bmt == 128 && bn <= 128)); }
-// wavefronts of a workgroup: a 2 x 2 grid over the tile; a 32-row or 32-column tile has one wavefront along that side
-constexpr int waves_m(int bmt) { return bmt >= 64 ? 2 : 1; }
-constexpr int waves_n(int bn) { return bn >= 64 ? 2 : 1; }
+// wavefronts of a workgroup: a 2 x 2 grid over the tile; a 32-row or 32-column tile has one wavefront along that side.
+// A 96-column tile (three 32-column blocks: what gives 256 workgroups when 128 columns give 192) has a 1 x 4 grid whose
+// first three wavefronts own one block each; the fourth only takes its share of the loads.
+constexpr int waves_m(int bmt, int bn) { return bn == 96 ? 1 : (bmt >= 64 ? 2 : 1); }
+constexpr int waves_n(int bn) { return bn == 96 ? 4 : (bn >= 64 ? 2 : 1); }
+constexpr int wave_cols(int bn) { return bn == 96 ? 32 : bn / waves_n(bn); }
 
 template <int EPI, int BN, int SD, int BMT = 256>
 __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int tiles_i, int tiles_j) {
   constexpr int BM = BMT;                         // rows of the output tile: 256, or 128 / 64 / 32 when there are few rows
-  constexpr int WM = waves_m(BMT), WN = waves_n(BN), NW = WM * WN;
-  constexpr int RW = BM / WM, CW = BN / WN;       // rows and columns of the tile that one wavefront owns
+  constexpr int WM = waves_m(BMT, BN), WN = waves_n(BN), NW = WM * WN;
+  constexpr int RW = BM / WM, CW = wave_cols(BN);  // rows and columns of the tile that one wavefront owns
+  constexpr int NW_MATH = WM * (BN / CW);          // wavefronts that own a part of the tile (all but one of a 96-column tile's)
   static_assert(EPI != EPI_LMHEAD || NW == 4, "the LM-head epilogue assumes the 2 x 2 wavefront grid");
   // which operand is the weight matrix (deep ring): Y for the projections, X for the LM head
   constexpr bool XDEEP = (EPI == EPI_LMHEAD);
@@ -85,6 +89,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = wave / WN, wn = wave % WN;
   const int l32 = lane & 31, hh = lane >> 5;
+  const bool math = NW_MATH == NW || wave < NW_MATH;    // wavefront-uniform
 
   int i_max, j_max, kz, ti, tj;
   if (EPI == EPI_LMHEAD) {
@@ -226,6 +231,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   const int yrow = (wn * CW + l32) * BKK;
   bf16x8 fx[2][TM], fy[2][TN];
   auto ldfrag = [&](int buf, const bf16_t* xs, const bf16_t* ys, int kk, int r) {
+    if (!math) return;
     const int slot = ((kk * 2 + hh) ^ sw_r) * 8;
     if (r < TM) fx[buf][r] = *reinterpret_cast<const bf16x8*>(xs + xrow + r * 32 * BKK + slot);
     else fy[buf][r - TM] = *reinterpret_cast<const bf16x8*>(ys + yrow + (r - TM) * 32 * BKK + slot);
@@ -258,7 +264,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 #pragma unroll
       for (int m = 0; m < NMF; ++m) {
         const int i = m / TN, j = m % TN;
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kk & 1][i], fy[kk & 1][j], acc[i][j], 0, 0, 0);
+        if (math) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[kk & 1][i], fy[kk & 1][j], acc[i][j], 0, 0, 0);
 #pragma unroll
         for (int r = frag_lo(m); r < frag_lo(m + 1); ++r) ldfrag((kk + 1) & 1, xs, ys, kk + 1, r);
         const int slot = NMF + kk * NMF + m;      // position among the NSLOT MFMAs that follow barrier kt-1
@@ -278,7 +284,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 #pragma unroll
     for (int m = 0; m < NMF; ++m) {
       const int i = m / TN, j = m % TN;
-      acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[1][i], fy[1][j], acc[i][j], 0, 0, 0);
+      if (math) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fx[1][i], fy[1][j], acc[i][j], 0, 0, 0);
 #pragma unroll
       for (int r = frag_lo(m); r < frag_lo(m + 1); ++r) ldfrag(0, xs1, ys1, 0, r);
 #pragma unroll
@@ -293,6 +299,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     for (kt = 1; kt + SD < KT; ++kt) k_tile(kt, std::true_type{});
   }
   for (; kt < KT; ++kt) k_tile(kt, std::false_type{});
+  if (!math) return;      // (no barrier follows the K loop)
 
   // accumulator element (i,j,v) of this lane: row  = i0 + wm*RW + i*32 + 8*(v/4) + 4*hh + v%4
   //                                           col  = wn*CW + j*32 + l32   (within the tile)
@@ -461,7 +468,7 @@ hipError_t launch_t(const GemmArgs& a, int tiles_i, int tiles_j, hipStream_t st)
   const hipError_t e = allow_dynamic_lds((const void*)gemm_bf16_mfma_kernel<EPI, BN, SD, BMT>,
                                          (int)smem_bytes<EPI, BN, SD, BMT>(), lds_ok);
   if (e != hipSuccess) return e;
-  gemm_bf16_mfma_kernel<EPI, BN, SD, BMT><<<tiles_i * tiles_j * a.ksplit, 64 * waves_m(BMT) * waves_n(BN), smem_bytes<EPI, BN, SD, BMT>(), st>>>(a, tiles_i, tiles_j);
+  gemm_bf16_mfma_kernel<EPI, BN, SD, BMT><<<tiles_i * tiles_j * a.ksplit, 64 * waves_m(BMT, BN) * waves_n(BN), smem_bytes<EPI, BN, SD, BMT>(), st>>>(a, tiles_i, tiles_j);
   return hipGetLastError();
 }
 
@@ -541,21 +548,23 @@ int mfma_lmhead_partials_per_row(int V) { return cdiv(V, BM) * 2; }
 // (one or a few states) the projections are weight-streaming problems: 64- and 128-row tiles spend a quarter
 // or half of the matrix work of a 256-row tile on them and cover more CUs.
 struct TileShape { int bm, bn; };
-static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow192, bool allow32 = false) {
+static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow192, bool allow32 = false, bool allow96 = false) {
   const int heights[4] = {256, 128, 64, 32};
-  const int widths[4] = {192, 128, 64, 32};
-  const float eff[4] = {1.0f, 0.85f, 0.55f, 0.4f};
+  const int widths[5] = {192, 128, 96, 64, 32};
+  const float eff[5] = {1.0f, 0.85f, 0.6f, 0.55f, 0.4f};
   TileShape best = {256, 0};
   float best_cost = 1e30f;
   for (int h = 0; h < 4; ++h)
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 5; ++i) {
       const int bm = heights[h], bn = widths[i];
       const int cols = bn / unit;                 // output columns (or SwiGLU features) per tile
       if ((bn == 192 && (!allow192 || bm <= 64)) || (bn == 64 && bm == 128) || n_cols % cols != 0) continue;
+      // 96-wide tiles: one row of tiles over few rows (weight streaming), where they turn 192 workgroups into 256
+      if (bn == 96 && !(allow96 && (bm == 64 || bm == 128) && M <= bm)) continue;
       // 32-wide tiles (one or two wavefronts per workgroup) exist for the split-K projections of one or two states
       if ((bn == 32 || bm == 32) && !(allow32 && bn == 32 && bm <= 64)) continue;
       const int tiles = cdiv(M, bm) * (n_cols / cols) * ksplit;
-      const float mfma = (float)(bm / 64) * (float)(bn / 64) * 128.0f / eff[i];
+      const float mfma = (float)(bm / 64) * ((float)bn / 64.0f) * 128.0f / eff[i];
       const float load = (float)(bm + bn) * 3.2f;
       const float cost = (float)cdiv(tiles, 256) * (mfma > load ? mfma : load);
       if (cost < best_cost) { best_cost = cost; best = {bm, bn}; }
@@ -573,6 +582,9 @@ static hipError_t launch_shape(const GemmArgs& a, TileShape t, int unit, hipStre
     return launch_t<EPI, 64, 4>(a, mt, nt, st);
   }
   // few rows: the weight ring is as deep as the LDS allows (bytes in flight are what sets the streaming rate)
+  if constexpr (EPI == EPI_SWIGLU) {
+    if (t.bn == 96) return t.bm == 128 ? launch_t<EPI, 96, 5, 128>(a, mt, nt, st) : launch_t<EPI, 96, 7, 64>(a, mt, nt, st);
+  }
   if (t.bm == 128) {
     if constexpr (W192) if (t.bn == 192) return launch_t<EPI, 192, 4, 128>(a, mt, nt, st);
     return launch_t<EPI, 128, 4, 128>(a, mt, nt, st);
@@ -600,7 +612,7 @@ hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
     case EPI_PARTIAL:
       return launch_shape<EPI_PARTIAL>(a, choose_tile(a.M, a.N, 1, a.ksplit, false, true), 1, st);
     case EPI_SWIGLU:
-      return launch_shape<EPI_SWIGLU>(a, choose_tile(a.M, a.N, 2, 1, true), 2, st);   // a tile of width w holds w/2 features
+      return launch_shape<EPI_SWIGLU>(a, choose_tile(a.M, a.N, 2, 1, true, false, true), 2, st);   // a tile of width w holds w/2 features
     case EPI_LMHEAD:
       return launch_t<EPI_LMHEAD, 192, 3>(a, cdiv(a.N, BM), cdiv(a.M, 192), st);
     default:

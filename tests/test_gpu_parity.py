@@ -442,6 +442,8 @@ def test_step_accept_follows_device_targets(sp):
     (256, 128, 64, "resid"),        # single K tile
     (520, 384, 512, "swiglu"),      # gate/up interleave, 192-wide tiles (96 features per tile)
     (129, 320, 640, "swiglu"),      # 128-wide tiles (64 features per tile)
+    (40, 12288, 1024, "swiglu"),    # few rows: 96-wide tiles (48 features, 256 workgroups), three of four wavefronts compute
+    (100, 3072, 256, "swiglu"),     # 128 x 96 tiles, K shorter than the ring
 ])
 def test_gemm_against_float64_matmul(sp, M, N, K, epi):
     g = torch.Generator().manual_seed(M * 7 + N)

@@ -8,7 +8,9 @@
 //     With few rows (one to eight states) the projections only stream weights: the same kernel with
 //     128- or 64-row tiles does half or a quarter of the matrix work per tile and covers more CUs; the
 //     narrow split-K projections of one or two states take 32-column tiles with one wavefront along a
-//     32-wide side (64 x 32: two wavefronts, 32 x 32: one), so 256 workgroups stream instead of 128.
+//     32-wide side (64 x 32: two wavefronts, 32 x 32: one), so 256 workgroups stream instead of 128;
+//     the gate/up projection of up to 128 rows takes 96-column tiles (256 workgroups instead of 192):
+//     a 1 x 4 wavefront grid, three wavefronts own a 32-column block each, the fourth only loads.
 //   * K advances in steps of 64 so every row segment is one full 128-byte line; operands go
 //     global -> LDS directly (LDS-DMA loads, no register staging), rows XOR-swizzled so the
 //     16-byte fragment reads are conflict-free.

@@ -10,8 +10,8 @@
  *
  * Conventions for every call
  *   - Kernel choice is by shape: bf16 with head_dim 128, d % 128 == 0, ffn % 64 == 0 runs the MFMA
- *     kernels (LM head: d % 64 == 0); anything else, and every shape when the
- *     environment variable SPIFFY_FORCE_GENERIC=1 is set, runs shape-agnostic fp32-math kernels.
+ *     kernels (LM head: d % 64 == 0); anything else runs shape-agnostic fp32-math kernels.  The
+ *     choice depends on the arguments of the call only (no environment variable, no global state).
  *   - All data pointers are DEVICE pointers owned by the caller unless a parameter says "host".
  *     The library never frees or keeps them.  Structs (cfg, weights, prefix) are HOST structs
  *     that hold device pointers.
@@ -134,7 +134,9 @@ int spiffy_verify_layer(const spiffy_model_cfg *cfg, const spiffy_layer_weights 
  * At positions that are not masked: argmax = the token, conf = 0, unmask = 0, margin = +inf.
  * Logits are never written to memory.  final_norm [d]; w_vocab [V,d];
  * argmax/target_states [G,B] int32; conf/top2_margin [G,B] float; unmask [G,B] uint8.
- * top2_margin and target_states may be NULL. */
+ * top2_margin and target_states may be NULL.  The bf16 matrix-core head (d % 64 == 0) addresses the vocabulary
+ * matrix with 32-bit byte offsets and keeps at most 2048 chunk summaries per row: vocab * d * 2 >= 2^32 or
+ * vocab > 262144 -> SPIFFY_ESHAPE. */
 int spiffy_decode_head(const spiffy_model_cfg *cfg, const void *hidden, const void *final_norm,
                        const void *w_vocab, const int32_t *block_tokens, const uint8_t *mask,
                        int32_t G, int32_t B, float threshold, float logit_scale, int32_t force_one, int32_t *argmax,
@@ -144,7 +146,7 @@ int spiffy_decode_head(const spiffy_model_cfg *cfg, const void *hidden, const vo
 /* The projection GEMM that verify_layer is made of, exposed for unit tests and for kernel-level
  * timing.  A [M,K], weights [N,K] row-major, C [M,N] (SPIFFY_GEMM_SWIGLU: W0 = gate, W1 = up,
  * both [N,K], C = silu(A W0^T) * (A W1^T)); SPIFFY_GEMM_RESID: C = R + A W0^T with R [M,N];
- * SPIFFY_GEMM_STORE: C = A W0^T.  bf16 with K % 64 == 0 and N % 128 == 0 (SWIGLU: N % 64 == 0)
+ * SPIFFY_GEMM_STORE: C = A W0^T.  bf16 with K % 64 == 0 and N % 64 == 0 (SWIGLU: N % 32 == 0)
  * runs the MFMA kernel, anything else the generic kernel.  workspace (256-byte aligned, at least
  * 4*M*N*sizeof(float) bytes) may be NULL; with it, SPIFFY_GEMM_RESID slices K exactly as
  * verify_layer does for its output and down projections (the slice count depends on N and K only). */

@@ -1,7 +1,6 @@
 // C ABI of the verification library: argument checks, workspace carving, kernel selection by
 // shape, launch order.  No kernel lives here.  Every check runs before the first launch.
 #include <cmath>
-#include <cstdlib>
 #include <cstring>
 
 #include "kernels.h"
@@ -12,15 +11,6 @@ namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 inline size_t esize(int dtype) { return dtype == SPIFFY_F32 ? 4 : 2; }
-
-bool force_generic() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = std::getenv("SPIFFY_FORCE_GENERIC");
-    v = (e && e[0] == '1') ? 1 : 0;
-  }
-  return v == 1;
-}
 
 int check_cfg(const spiffy_model_cfg* c) {
   if (!c) return SPIFFY_EINVAL;
@@ -42,12 +32,21 @@ int check_gb(int32_t G, int32_t B) {
 }
 
 bool layer_mfma(const spiffy_model_cfg* c) {
-  if (force_generic() || c->dtype != SPIFFY_BF16 || c->head_dim != 128) return false;
+  if (c->dtype != SPIFFY_BF16 || c->head_dim != 128) return false;
   return c->d % 128 == 0 && c->ffn % 64 == 0;
 }
 bool head_mfma(const spiffy_model_cfg* c) {
-  if (force_generic() || c->dtype != SPIFFY_BF16) return false;
+  if (c->dtype != SPIFFY_BF16) return false;
   return c->d % 64 == 0;
+}
+
+// Limits of the MFMA LM head: per-lane byte offsets into the vocabulary matrix and into the gathered rows are 32-bit,
+// and the top-K refinement holds at most 2048 per-chunk summaries of a row (V <= 262144).
+bool head_shape_ok(const spiffy_model_cfg* c) {
+  if (!head_mfma(c)) return true;
+  const size_t lim = (size_t)1 << 32;
+  if ((size_t)c->vocab * c->d * 2 >= lim || (size_t)SPIFFY_MAX_ROWS * c->d * 2 >= lim) return false;
+  return mfma_lmhead_partials_per_row(c->vocab) <= 2048;
 }
 
 // generic attention keeps all scores of one row in LDS
@@ -387,7 +386,7 @@ int check_head_args(const spiffy_model_cfg* cfg, const void* hidden, const void*
     return SPIFFY_EINVAL;
   if (!aligned16(hidden) || !aligned16(final_norm) || !aligned16(w_vocab)) return SPIFFY_EALIGN;
   if ((size_t)cfg->d * sizeof(float) > 64 * 1024 && !head_mfma(cfg)) return SPIFFY_ESHAPE;
-  return SPIFFY_OK;
+  return head_shape_ok(cfg) ? SPIFFY_OK : SPIFFY_ESHAPE;
 }
 
 int check_accept_args(const int32_t* edges, int32_t E, const int32_t* draft, const int32_t* target, int32_t G,
@@ -482,7 +481,7 @@ int spiffy_gemm(int32_t dtype, int32_t epilogue, const void* A, const void* W0, 
   g.A = A; g.lda = K; g.M = M; g.K = K; g.N = N; g.C = C; g.ldc = N; g.R = R; g.scale = 1.f;
   g.W[0] = W0;
   if (epilogue == SPIFFY_GEMM_SWIGLU) g.W[1] = W1; else g.Nseg[0] = N;
-  const bool mf = !force_generic() && dtype == SPIFFY_BF16 && mfma_gemm_supported(epilogue, g);
+  const bool mf = dtype == SPIFFY_BF16 && mfma_gemm_supported(epilogue, g);
   hipStream_t st = (hipStream_t)stream;
   if (mf && epilogue == SPIFFY_GEMM_RESID) {     // same K slicing as verify_layer when scratch is given
     const int ks = mfma_ksplit(N, K);
@@ -518,6 +517,7 @@ int spiffy_head_topk(const spiffy_model_cfg* cfg, const void* w_vocab, const int
   if (!result && (node < 0 || node >= G)) return SPIFFY_EINVAL;
   if (K < 1 || K > SPIFFY_MAX_TOPK) return SPIFFY_ESHAPE;
   if (cfg->dtype == SPIFFY_BF16 && cfg->d % 8 != 0) return SPIFFY_ESHAPE;
+  if (!head_shape_ok(cfg)) return SPIFFY_ESHAPE;
   if (!aligned16(w_vocab)) return SPIFFY_EALIGN;
   if (reinterpret_cast<uintptr_t>(workspace) & 255u) return SPIFFY_EALIGN;
   // a step keeps its layer / head scratch at the start of its workspace, so the head's leftovers are found at the

@@ -20,7 +20,7 @@ __global__ __launch_bounds__(64) void graph_accept_kernel(const int32_t* __restr
   for (int e = lane; e < E; e += 64) {
     const int p = edges[2 * e], c = edges[2 * e + 1];
     if (p < 0 || p >= G || c < 0 || c >= G) {
-      bad = 1;
+      atomicOr(&bad, 1);
     } else {
       atomicOr(&child[p], 1ull << c);
     }

@@ -250,6 +250,12 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(HeadTopkArgs a) {
     return;
   }
   const TopPartial top = a.row_top[r];
+  // Column 0 is the head's own argmax with the confidence it reported, whatever the recomputed candidates say
+  // (their logits are summed in another order, so on a near-tie the head's token could otherwise drop out of its
+  // chunk's K best, or come second).  The other K-1 places go to the best candidates other than that token; a
+  // candidate whose recomputed logit exceeds the head's top logit is held at it, so probabilities never increase
+  // along a row.
+  if (lane == 0) { ot[0] = top.idx; op[0] = 1.0f / top.s; }
   // lane = k * K + j of the candidate table
   float v = -INFINITY;
   int i = -1;
@@ -258,11 +264,10 @@ __global__ __launch_bounds__(64) void topk_merge_kernel(HeadTopkArgs a) {
     v = a.cand_val[((size_t)b * KMAX + k) * KMAX + j];
     i = a.cand_idx[((size_t)b * KMAX + k) * KMAX + j];
   }
-  if (i < 0) v = -INFINITY;
-  const bool is_top = i == top.idx;
-  float key = is_top ? INFINITY : v;                // the head's argmax stays first
-  float val = is_top ? top.m : v;
-  for (int j = 0; j < a.K; ++j) {
+  if (i < 0 || i == top.idx) { v = -INFINITY; i = -1; }
+  float key = v;
+  const float val = fminf(v, top.m);
+  for (int j = 1; j < a.K; ++j) {
     float bk = key;
     int bi = (i < 0) ? 0x7fffffff : i;
     wave_best(bk, bi);

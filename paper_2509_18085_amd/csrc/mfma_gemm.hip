@@ -606,9 +606,10 @@ hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
     case EPI_STORE:
       return launch_shape<EPI_STORE>(a, choose_tile(a.M, a.N, 1, 1, true), 1, st);
     case EPI_RESID: {
+      // 256-row tiles only; 128 columns wide unless N is an odd multiple of 64 or the narrower tile fills the chip better
       const int mt = cdiv(a.M, BM);
-      TileShape t = choose_tile(a.M, a.N, 1, 1, false);
-      if (t.bm == 256 && t.bn == 64) return launch_t<EPI_RESID, 64, 4>(a, mt, a.N / 64, st);
+      const TileShape t = choose_tile(a.M, a.N, 1, 1, false);
+      if (a.N % 128 != 0 || (t.bm == 256 && t.bn == 64)) return launch_t<EPI_RESID, 64, 4>(a, mt, a.N / 64, st);
       return launch_t<EPI_RESID, 128, 4>(a, mt, a.N / 128, st);
     }
     case EPI_PARTIAL:

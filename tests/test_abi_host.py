@@ -127,6 +127,24 @@ def test_decode_head_argument_errors():
     assert call(G=-3) == sp.SPIFFY_EINVAL
 
 
+def test_matrix_core_head_refuses_what_its_32_bit_offsets_cannot_address():
+    """V * d * 2 bytes >= 4 GiB, or more than 2048 chunk summaries per row (V > 262144): a shape error from the
+    host checks of spiffy_decode_head and spiffy_head_topk, never a wrapped offset or a failed launch."""
+    big = _cfg("c3")
+    big.vocab, big.d, big.mask_id = 262144, 8192, 5
+    wide = _cfg("c3")
+    wide.vocab, wide.d, wide.mask_id = 300000, 1024, 5
+    for cfg in (big, wide):
+        assert sp.lib.spiffy_decode_head(C.byref(cfg), DUMMY, DUMMY, DUMMY, DUMMY, None, 4, 32, 0.9, 1.0, 1, DUMMY, DUMMY,
+                                         DUMMY, None, None, 0x100000, 1 << 40, None) == sp.SPIFFY_ESHAPE
+        assert sp.lib.spiffy_head_topk(C.byref(cfg), DUMMY, DUMMY, 4, 32, None, 0, 2, 1.0, 0, DUMMY, DUMMY, 0x100000,
+                                       1 << 40, None) == sp.SPIFFY_ESHAPE
+    ok = _cfg("c3")
+    ok.vocab, ok.d, ok.mask_id = 262144, 4096, 5            # 2 GiB of vocabulary matrix, 2048 chunks: the largest that runs
+    assert sp.lib.spiffy_decode_head(C.byref(ok), DUMMY, DUMMY, DUMMY, DUMMY, None, 4, 32, 0.9, 1.0, 1, DUMMY, DUMMY,
+                                     DUMMY, None, None, 0x100000, 16, None) == sp.SPIFFY_EWORKSPACE
+
+
 def test_graph_accept_argument_errors():
     call = lambda **k: sp.lib.spiffy_graph_accept(
         k.get("edges", DUMMY), k.get("E", 3), k.get("ds", DUMMY), k.get("ts", DUMMY), k.get("G", 4), 8,

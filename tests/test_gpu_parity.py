@@ -440,6 +440,8 @@ def test_step_accept_follows_device_targets(sp):
     (70, 256, 192, "store"),        # 128-wide tiles, K of three tiles
     (513, 512, 2048, "resid"),      # sliced K (split-K) with residual, ragged rows
     (256, 128, 64, "resid"),        # single K tile
+    (64, 192, 512, "resid"),        # N an odd multiple of 64: the unsliced launch must take 64-column tiles
+    (300, 320, 1024, "resid"),      # the same with ragged rows and a K that is sliced when scratch is given
     (520, 384, 512, "swiglu"),      # gate/up interleave, 192-wide tiles (96 features per tile)
     (129, 320, 640, "swiglu"),      # 128-wide tiles (64 features per tile)
     (40, 12288, 1024, "swiglu"),    # few rows: 96-wide tiles (48 features, 256 workgroups), three of four wavefronts compute

@@ -29,6 +29,142 @@ PEAK_HBM_GBS = 8000.0         # MI355X HBM3E
 LOGIT_SCALE = 8.0             # synthetic knob: random-init logits are flat, this makes ~1/3 of positions pass tau
 
 
+def step_work(cfg, n_masked):
+    """Algorithmic flop and HBM bytes of one step (per state per layer: 2*B*params flop + the attention's
+    4*B*(P+B)*hd*Hq; weights and cached keys / values once per step; the head on the masked rows only)."""
+    M = cfg.G * cfg.B
+    params_layer = cfg.d * cfg.Hq * cfg.hd * 2 + cfg.d * cfg.Hkv * cfg.hd * 2 + 3 * cfg.d * cfg.F
+    flop = cfg.L * (2.0 * M * params_layer + 4.0 * cfg.B * (cfg.P + cfg.B) * cfg.hd * cfg.Hq * cfg.G) \
+        + 2.0 * n_masked * cfg.V * cfg.d
+    nbytes = cfg.L * (2.0 * params_layer + 2.0 * 2 * cfg.P * cfg.Hkv * cfg.hd) + 2.0 * cfg.V * cfg.d + 2.0 * M * cfg.d
+    return flop, nbytes
+
+
+def build_workload(sp, synth, key, dev, seed, n_states=0):
+    """Synthetic model and inputs of one workload configuration, generated on the device from the seed."""
+    import numpy as np
+    import torch
+    cfg = synth.CONFIGS[key]
+    layers = [synth.layer_weights(cfg, l, seed, device=dev) for l in range(cfg.L)]
+    prefix = [synth.prefix_kv(cfg, l, seed, device=dev) for l in range(cfg.L)]
+    hw = synth.head_weights(cfg, seed, device=dev)
+    w_embed = synth.embed_weights(cfg, seed, device=dev)
+    states, edges = synth.draft_graph(key, cfg, seed)
+    if n_states:
+        states = states[:n_states]
+        edges = edges[(edges < n_states).all(axis=1)].reshape(-1, 2)
+        cfg = cfg.scaled(G=n_states)
+    # target states "sampled from seed" for the acceptance measurement: a planted path of seeded depth
+    depth = int(np.random.default_rng(seed).integers(1, 5))
+    planted, path = synth.planted_targets(states, edges, cfg.V, depth, seed)
+    w = dict(cfg=cfg, key=key, layers=layers, prefix=prefix, hw=hw, w_embed=w_embed, states=states, edges=edges,
+             planted=planted, planted_path=path)
+    w["d_states"] = torch.from_numpy(states).to(dev)
+    w["d_edges"] = torch.from_numpy(np.ascontiguousarray(edges)).to(dev) if len(edges) else None
+    w["d_planted"] = torch.from_numpy(planted).to(dev)
+    w["plan"] = sp.StepPlan(sp.cfg_from_synth(cfg), [sp.layer_weights(x) for x in layers],
+                            [sp.prefix_kv(k, v) for k, v in prefix], w_embed, hw["final_norm"], hw["w_vocab"], cfg.G,
+                            cfg.B, cfg.P, cfg.threshold, logit_scale=LOGIT_SCALE, device=dev)
+    w["walk_res"] = torch.empty(4, dtype=torch.int32, device=dev)
+    w["walk_state"] = torch.empty(cfg.B, dtype=torch.int32, device=dev)
+    return w
+
+
+def one_step(sp, w):
+    """The timed unit: the whole step in one call (its walk runs on the step's own next states), then the
+    acceptance walk against the planted target states of the workload (one more one-wavefront launch)."""
+    w["plan"].run(w["d_states"], w["d_edges"])
+    sp.graph_accept(w["d_edges"], w["d_states"], w["d_planted"], 0, res=w["walk_res"], state=w["walk_state"])
+
+
+def time_steps(sp, w, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        one_step(sp, w)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    w0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        one_step(sp, w)
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - w0
+    return wall * 1e3 / steps, sorted(a.elapsed_time(b) for a, b in ev)
+
+
+def time_dominant_kernel(sp, w, dev, iters):
+    """The gate/up SwiGLU GEMM alone: same shapes as in the step, weights rotating over the layers, HIP events on the
+    launch stream around back-to-back launches."""
+    import torch
+    cfg, layers = w["cfg"], w["layers"]
+    M = cfg.G * cfg.B
+    x = torch.randn((M, cfg.d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    act = torch.empty((M, cfg.F), device=dev, dtype=torch.bfloat16)
+    for lw in layers[:2]:
+        sp.gemm(sp.GEMM_SWIGLU, x, lw["w_gate"], lw["w_up"], out=act)
+    torch.cuda.synchronize()
+    k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_launch = 0
+    k0.record()
+    for _ in range(iters):
+        for lw in layers:
+            sp.gemm(sp.GEMM_SWIGLU, x, lw["w_gate"], lw["w_up"], out=act)
+            n_launch += 1
+    k1.record()
+    torch.cuda.synchronize()
+    return k0.elapsed_time(k1) / n_launch, n_launch
+
+
+def roofline_of(cfg, k_ms, n_launch, traffic):
+    """Roofline object of the SwiGLU GEMM: against the bf16 MFMA peak, or against the HBM peak when the launch moves
+    more bytes per flop than the chip's balance point (few rows: the small-block workload, --states)."""
+    M = cfg.G * cfg.B
+    flop_launch = 2.0 * M * cfg.d * 2 * cfg.F
+    alg_bytes = 2.0 * (2 * cfg.F * cfg.d + M * cfg.d + M * cfg.F)
+    achieved = flop_launch / (k_ms * 1e-3) / 1e12
+    r = {"kernel": "gemm_bf16_mfma_kernel<EPI_SWIGLU> (gate/up projection)", "bound": "mfma", "achieved": achieved,
+         "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+         "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": k_ms, "flop_per_launch": flop_launch,
+         "launches_timed": n_launch}
+    if flop_launch / alg_bytes < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
+        gbs = alg_bytes / (k_ms * 1e-3) / 1e9
+        r.update({"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS})
+    return r
+
+
+def other_config_leg(sp, synth, key, dev, seed, steps, warmup, kernel_iters):
+    """One of the other workload configurations on the same build: the whole step and its dominant kernel, measured
+    the same way as the headline; everything is freed before the next one."""
+    import torch
+    w = build_workload(sp, synth, key, dev, seed)
+    cfg = w["cfg"]
+    ms, per = time_steps(sp, w, steps, warmup)
+    k_ms, n_launch = time_dominant_kernel(sp, w, dev, kernel_iters)
+    n_masked = int((w["states"] == cfg.mask_id).sum())
+    flop, nbytes = step_work(cfg, n_masked)
+    out = {"workload": cfg.name, "G": cfg.G, "B": cfg.B, "P": cfg.P, "L": cfg.L, "ms_per_step": ms,
+           "states_per_s": cfg.G / (ms * 1e-3), "step_latency_ms_p50": per[len(per) // 2],
+           "step_flop": flop, "step_algorithmic_bytes": nbytes,
+           "step_frac_of_bf16_peak": flop / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "step_frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+           "step_bound": "hbm" if nbytes / (PEAK_HBM_GBS * 1e9) > flop / (PEAK_BF16_TFLOPS * 1e12) else "mfma",
+           "roofline": roofline_of(cfg, k_ms, n_launch, stored_traffic(key)),
+           "planted_walk": walk_outcome(w)}
+    del w
+    torch.cuda.empty_cache()
+    return out
+
+
+def walk_outcome(w):
+    res = w["walk_res"].cpu().tolist()
+    own = w["plan"].out["result"].cpu().tolist()
+    return {"planted_depth": len(w["planted_path"]) - 1, "accepted_depth": res[1], "accepted_node": res[0],
+            "planted_path": [int(x) for x in w["planted_path"]],
+            "walk_on_the_steps_own_next_states": {"accepted_node": own[0], "depth": own[1]}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -38,7 +174,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--kernel-iters", type=int, default=5)
     ap.add_argument("--step-only", action="store_true",
-                    help="skip the legs outside the timed step (drafting, decode loop, dual cache): for profiles")
+                    help="skip the legs outside the timed step (drafting, decode loop, dual cache, other configurations): "
+                         "for profiles")
     ap.add_argument("--states", type=int, default=0,
                     help="verify only the first G states of the workload's draft graph (the paper's own operating point "
                          "is G = 4); implies --step-only")
@@ -59,29 +196,15 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = "cuda:0"
     torch.cuda.set_device(0)
-    cfg = synth.CONFIGS[args.config]
     seed = synth.DEFAULT_SEED
-    scfg = sp.cfg_from_synth(cfg)
-    t0 = time.time()
-
-    # ---- synthetic model and inputs, generated on the device from the seed ---------------------
-    layers = [synth.layer_weights(cfg, l, seed, device=dev) for l in range(cfg.L)]
-    prefix = [synth.prefix_kv(cfg, l, seed, device=dev) for l in range(cfg.L)]
-    hw = synth.head_weights(cfg, seed, device=dev)
-    w_embed = synth.embed_weights(cfg, seed, device=dev)
-    states, edges = synth.draft_graph(args.config, cfg, seed)
     if args.states:
-        if not 1 <= args.states <= cfg.G:
-            sys.exit("bench.py: --states must lie in 1..%d for %s" % (cfg.G, args.config))
-        states = states[:args.states]
-        edges = edges[(edges < args.states).all(axis=1)].reshape(-1, 2)
-        cfg = cfg.scaled(G=args.states)
+        if not 1 <= args.states <= synth.CONFIGS[args.config].G:
+            sys.exit("bench.py: --states must lie in 1..%d for %s" % (synth.CONFIGS[args.config].G, args.config))
         args.step_only = True
-    d_states = torch.from_numpy(states).to(dev)
-    d_edges = torch.from_numpy(np.ascontiguousarray(edges)).to(dev) if len(edges) else None
-    plan = sp.StepPlan(scfg, [sp.layer_weights(w) for w in layers], [sp.prefix_kv(k, v) for k, v in prefix],
-                       w_embed, hw["final_norm"], hw["w_vocab"], cfg.G, cfg.B, cfg.P, cfg.threshold,
-                       logit_scale=LOGIT_SCALE, device=dev)
+    t0 = time.time()
+    w = build_workload(sp, synth, args.config, dev, seed, args.states)
+    cfg, layers, prefix, hw, w_embed = w["cfg"], w["layers"], w["prefix"], w["hw"], w["w_embed"]
+    states, edges, d_states, d_edges, plan = w["states"], w["edges"], w["d_states"], w["d_edges"], w["plan"]
     torch.cuda.synchronize()
     t_setup = time.time() - t0
 
@@ -94,51 +217,15 @@ def main():
         del src, dst
 
     # ---- whole step ------------------------------------------------------------------------------
-    for _ in range(args.warmup):
-        plan.run(d_states, d_edges)
-    torch.cuda.synchronize()
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
-    torch.cuda.synchronize()
-    w0 = time.perf_counter()
-    for a, b in ev:
-        a.record()
-        plan.run(d_states, d_edges)
-        b.record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - w0
-    per = sorted(a.elapsed_time(b) for a, b in ev)
-    ms_per_step = wall * 1e3 / args.steps
+    ms_per_step, per = time_steps(sp, w, args.steps, args.warmup)
     out = plan.out
     res = out["result"].cpu().tolist()
     m = states == cfg.mask_id
+    n_masked = int(m.sum())
 
     # ---- dominant kernel in isolation: gate/up SwiGLU GEMM, same shapes, weights rotating over layers
-    M = cfg.G * cfg.B
-    x = torch.randn((M, cfg.d), device=dev, dtype=torch.float32).to(torch.bfloat16)
-    act = torch.empty((M, cfg.F), device=dev, dtype=torch.bfloat16)
-    for w in layers[:2]:
-        sp.gemm(sp.GEMM_SWIGLU, x, w["w_gate"], w["w_up"], out=act)
-    torch.cuda.synchronize()
-    k0, k1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    n_launch = 0
-    k0.record()
-    for _ in range(args.kernel_iters):
-        for w in layers:
-            sp.gemm(sp.GEMM_SWIGLU, x, w["w_gate"], w["w_up"], out=act)
-            n_launch += 1
-    k1.record()
-    torch.cuda.synchronize()
-    k_ms = k0.elapsed_time(k1) / n_launch
-    flop_launch = 2.0 * M * cfg.d * 2 * cfg.F
-    achieved = flop_launch / (k_ms * 1e-3) / 1e12
-
-    # algorithmic work of the whole step
-    params_layer = cfg.d * cfg.Hq * cfg.hd * 2 + cfg.d * cfg.Hkv * cfg.hd * 2 + 3 * cfg.d * cfg.F
-    n_masked = int(m.sum())
-    flop_step = cfg.L * (2.0 * M * params_layer + 4.0 * cfg.B * (cfg.P + cfg.B) * cfg.hd * cfg.Hq * cfg.G) \
-        + 2.0 * n_masked * cfg.V * cfg.d
-    bytes_step = cfg.L * (2.0 * params_layer + 2.0 * 2 * cfg.P * cfg.Hkv * cfg.hd) + 2.0 * cfg.V * cfg.d \
-        + 2.0 * M * cfg.d
+    k_ms, n_launch = time_dominant_kernel(sp, w, dev, args.kernel_iters)
+    flop_step, bytes_step = step_work(cfg, n_masked)
 
     line = {
         "metric": "draft_states_verified_per_s",
@@ -162,27 +249,14 @@ def main():
         "step_algorithmic_bytes": bytes_step,
         "step_tflops": flop_step / (ms_per_step * 1e-3) / 1e12,
         "step_frac_of_bf16_peak": flop_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
-        "outcome": {"accepted_node": res[0], "depth": res[1], "unmasked": int(out["unmask"].sum().item())},
-        "roofline": {"kernel": "gemm_bf16_mfma_kernel<EPI_SWIGLU> (gate/up projection)", "bound": "mfma",
-                     "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS,
-                     "traffic": stored_traffic(args.config) if not args.states else None,
-                     "traffic_source": "profiles/hbm_traffic_c3_gemm_kernels.txt (rocprofv3 --pmc FETCH_SIZE / "
-                                       "WRITE_SIZE, scaled by a 1 GiB copy probe; bytes per launch)",
-                     "algorithmic_bytes_per_launch": 2.0 * (2 * cfg.F * cfg.d + M * cfg.d + M * cfg.F),
-                     "avg_launch_ms": k_ms, "flop_per_launch": flop_launch, "launches_timed": n_launch},
+        "outcome": {"accepted_node": res[0], "depth": res[1], "unmasked": int(out["unmask"].sum().item()),
+                    "planted_walk": walk_outcome(w)},
+        "roofline": roofline_of(cfg, k_ms, n_launch, stored_traffic(args.config) if not args.states else None),
         "setup_s": t_setup,
     }
-
-    # few rows (config 5, --states): the launch moves more bytes per flop than the chip's balance point, so the
-    # bound that applies to the same kernel is HBM
-    alg_bytes = line["roofline"]["algorithmic_bytes_per_launch"]
-    if args.states:
-        del line["roofline"]["traffic_source"]        # the stored counters are those of the full workload
-    if flop_launch / alg_bytes < PEAK_BF16_TFLOPS * 1e12 / (PEAK_HBM_GBS * 1e9):
-        gbs = alg_bytes / (k_ms * 1e-3) / 1e9
-        line["roofline"].update({"bound": "hbm", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                 "frac": gbs / PEAK_HBM_GBS})
+    if not args.states:
+        line["roofline"]["traffic_source"] = ("profiles/hbm_traffic_%s_gemm_kernels.txt (rocprofv3 --pmc FETCH_SIZE / "
+                                              "WRITE_SIZE, scaled by a 1 GiB copy probe; bytes per launch)" % args.config)
 
     # what this chip sustains on the same units with nothing in the way: a register-only MFMA loop, a read-only stream
     line["measured_peaks"] = peaks_leg(sp, dev)
@@ -199,7 +273,18 @@ def main():
         line["calibration_subgraph_search"] = subgraph_leg(sp, dev, seed)
 
     if not args.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(cfg, layers, prefix, hw, states, edges)
+        one_step(sp, w)                     # the legs above reused the plan's buffers: the step's own outputs again
+        torch.cuda.synchronize()
+        line["cpu_baseline"], line["decision_check"] = cpu_baseline(cfg, layers, prefix, hw, states, edges, plan.out)
+
+    if not args.step_only:
+        # the other workload configurations, one after the other, each freed before the next; the headline stays above
+        del w, layers, prefix, hw, w_embed, plan, out, d_states, d_edges
+        torch.cuda.empty_cache()
+        line["other_configs"] = {}
+        for key in ("c2", "c4", "c5"):
+            if key != args.config:
+                line["other_configs"][key] = other_config_leg(sp, synth, key, dev, seed, 10, 2, 2)
     print(json.dumps(line))
 
 
@@ -530,10 +615,13 @@ def stored_traffic(config):
     return None
 
 
-def cpu_baseline(cfg, layers, prefix, hw, states, edges):
+def cpu_baseline(cfg, layers, prefix, hw, states, edges, gpu_out):
     """The oracle as it stands, on this host, on a bounded sample of the same workload: the first
     layers on all G states + the head on all G states + the walk, scaled to the full depth.
-    A baseline for context, not a target."""
+    A baseline for context, not a target.  The head runs on the device step's own final hidden states, so its
+    decisions are the ones the step had to take: the second result counts how they compare (near-ties, near-threshold
+    confidences, excluded states, mismatches; then the same against the plain oracle that does not round the
+    normalised row to bf16, at the literal 1e-3 margin)."""
     import numpy as np
     from threadpoolctl import threadpool_info
     from oracle import spiffy_oracle as O
@@ -552,20 +640,54 @@ def cpu_baseline(cfg, layers, prefix, hw, states, edges):
         t_layers += time.perf_counter() - t0
         del w, pk, pv
     wv, fn = f64(hw["w_vocab"]), f64(hw["final_norm"])
+    hid = f64(gpu_out["hidden"])
     t0 = time.perf_counter()
-    _, _, _, _, tgt = O.decode_head(x, fn, wv, states, cfg.mask_id, cfg.threshold, rms_eps=cfg.rms_eps,
-                                    logit_scale=LOGIT_SCALE, operand_dtype="bf16")
+    amax, conf, unmask, margin, tgt = O.decode_head(hid, fn, wv, states, cfg.mask_id, cfg.threshold, rms_eps=cfg.rms_eps,
+                                                    logit_scale=LOGIT_SCALE, operand_dtype="bf16")
     t_head = time.perf_counter() - t0
     t0 = time.perf_counter()
     O.graph_accept(edges, states, tgt, 0)
     t_walk = time.perf_counter() - t0
     step_s = t_layers * cfg.L / n_layers + t_head + t_walk
     threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
-    return {"value": cfg.G / step_s, "unit": "states/s", "cores": threads, "kind": "oracle",
+    base = {"value": cfg.G / step_s, "unit": "states/s", "cores": threads, "kind": "oracle",
             "sample": "oracle.verify_layer on all %d states for %d of %d layers (%.2f s), oracle.decode_head on all "
                       "states (%.2f s), oracle.graph_accept (%.4f s); layer time scaled by %d/%d"
                       % (cfg.G, n_layers, cfg.L, t_layers, t_head, t_walk, cfg.L, n_layers),
             "measured_s": t_layers + t_head + t_walk, "extrapolated_step_s": step_s}
+
+    # ---- decisions of the device step against the oracle on the same hidden states
+    g = {k: gpu_out[k].cpu().numpy() for k in ("argmax", "conf", "unmask", "target_states")}
+    m = states == cfg.mask_id
+    tie = 1e-3 * max(1.0, LOGIT_SCALE)
+    near_tie = m & (margin < tie)
+    near_tau = m & (np.abs(conf.astype(np.float64) - cfg.threshold) < 1e-4 * cfg.threshold)
+    ok_state = np.ones(cfg.G, bool)
+    for s in range(cfg.G):
+        c = np.sort(conf[s][m[s]])[::-1]
+        if near_tie[s].any() or near_tau[s].any() or (c.size > 1 and c[0] - c[1] < 1e-5 * c[0]):
+            ok_state[s] = False
+    clear = m & ~near_tie
+    p_amax, p_conf, p_unmask, p_margin, _ = O.decode_head(hid, fn, wv, states, cfg.mask_id, cfg.threshold,
+                                                          rms_eps=cfg.rms_eps, logit_scale=LOGIT_SCALE)
+    lit = m & (p_margin >= 1e-3)
+    far = lit & (np.abs(p_conf.astype(np.float64) - cfg.threshold) >= 2e-2 * cfg.threshold)
+    node, depth = O.graph_accept(edges, states, g["target_states"], 0)[:2]
+    res = gpu_out["result"].cpu().tolist()
+    check = {"masked": int(m.sum()), "logit_scale": LOGIT_SCALE, "tie_margin": tie,
+             "near_tie": int(near_tie.sum()), "near_tie_literal_1e_3": int((m & (margin < 1e-3)).sum()),
+             "near_threshold": int(near_tau.sum()), "excluded_states": int((~ok_state).sum()),
+             "mismatches": {"argmax_outside_near_ties": int((g["argmax"] != amax)[clear].sum()),
+                            "unmask_in_compared_states": int((g["unmask"] != unmask)[ok_state].sum()),
+                            "next_state_in_compared_states": int((g["target_states"] != tgt)[ok_state].sum()),
+                            "conf_max_rel_err": float(np.max(np.abs(g["conf"][m] - conf[m]) / np.maximum(conf[m], 1e-30))),
+                            "walk_on_own_next_states": int([res[0], res[1]] != [node, depth])},
+             "plain_float64_oracle": {"argmax_mismatch_outside_1e_3": int((g["argmax"] != p_amax)[lit].sum()),
+                                      "unmask_mismatch_away_from_tau": int((g["unmask"] != p_unmask)[far].sum()),
+                                      "conf_max_rel_err": float(np.max(np.abs(g["conf"][m] - p_conf[m]) / np.maximum(p_conf[m], 1e-30)))},
+             "note": "oracle.decode_head on the device step's own final hidden states; first block: operands rounded to "
+                     "bf16 as on the matrix cores (the gated comparison of the tests), second: no rounding"}
+    return base, check
 
 
 if __name__ == "__main__":

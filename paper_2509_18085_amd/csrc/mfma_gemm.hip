@@ -55,6 +55,8 @@ __device__ __forceinline__ void wait_lgkm0() { __builtin_amdgcn_s_waitcnt(0xC07F
 
 // 64-row tiles, and 128-row tiles up to 128 columns wide, are weight-streaming shapes: both operand rings SD deep
 constexpr bool uniform_rings(int epi, int bn, int bmt) { return epi != EPI_LMHEAD && (bmt <= 64 || (bmt == 128 && bn <= 128)); }
+// stages of the shallow operand's ring = how many K-tiles ahead it is loaded; SA = 0 picks the default of the shape
+constexpr int shallow_stages(int epi, int bn, int bmt, int sd, int sa) { return sa ? sa : (uniform_rings(epi, bn, bmt) ? sd : 2); }
 // wavefronts of a workgroup: a 2 x 2 grid over the tile; a 32-row or 32-column tile has one wavefront along that side.
 // A 96-column tile (three 32-column blocks: what gives 256 workgroups when 128 columns give 192) has a 1 x 4 grid whose
 // first three wavefronts own one block each; the fourth only takes its share of the loads.
@@ -62,7 +64,7 @@ constexpr int waves_m(int bmt, int bn) { return bn == 96 ? 1 : (bmt >= 64 ? 2 : 
 constexpr int waves_n(int bn) { return bn == 96 ? 4 : (bn >= 64 ? 2 : 1); }
 constexpr int wave_cols(int bn) { return bn == 96 ? 32 : bn / waves_n(bn); }
 
-template <int EPI, int BN, int SD, int BMT = 256>
+template <int EPI, int BN, int SD, int BMT = 256, int SA = 0>
 __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int tiles_i, int tiles_j) {
   constexpr int BM = BMT;                         // rows of the output tile: 256, or 128 / 64 / 32 when there are few rows
   constexpr int WM = waves_m(BMT, BN), WN = waves_n(BN), NW = WM * WN;
@@ -71,12 +73,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   static_assert(EPI != EPI_LMHEAD || NW == 4, "the LM-head epilogue assumes the 2 x 2 wavefront grid");
   // which operand is the weight matrix (deep ring): Y for the projections, X for the LM head
   constexpr bool XDEEP = (EPI == EPI_LMHEAD);
-  // UNI (64-row and narrow 128-row tiles, weight-streaming problems): both operands ride rings of SD stages and every load runs
-  // SD tiles ahead, so SD-2 whole tiles stay in flight across a barrier.  Otherwise the activation operand has
-  // two stages and is loaded two tiles ahead; its loads sit behind the weight loads in the in-order counter,
-  // so only the newest weight tile can stay in flight.
-  constexpr bool UNI = uniform_rings(EPI, BN, BMT);
-  constexpr int SX = XDEEP ? SD : (UNI ? SD : 2), SY = XDEEP ? 2 : SD;
+  // The deep operand (weights) rides a ring of SD stages and is loaded SD tiles ahead; the shallow one (activations)
+  // a ring of SH stages, SH tiles ahead.  The load counter retires in order, so waiting for the shallow operand of
+  // the next tile also waits for every older load: across a barrier stay in flight the deep loads issued with that
+  // shallow tile and the SH-2 whole groups after it (SH = 2: only the newest weight tile, whatever SD; SH = SD, the
+  // weight-streaming shapes with few rows: SD-2 whole tiles).
+  constexpr int SH = shallow_stages(EPI, BN, BMT, SD, SA);
+  static_assert(SH >= 2 && SH <= SD, "the shallow ring is at most as deep as the deep one");
+  constexpr int SX = XDEEP ? SD : SH, SY = XDEEP ? SH : SD;
   constexpr int TM = RW / 32, TN = CW / 32;
   constexpr int LX = BM / (8 * NW), LY = BN / (8 * NW);   // 1-KB wave-loads (8 rows x 128 B) per wavefront per K-tile
   constexpr int NL = LX + LY;
@@ -190,9 +194,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   constexpr int LS = XDEEP ? LY : LX, LD = XDEEP ? LX : LY;   // wave-loads of the shallow / deep operand
   auto load_sh = [&](int q, int t) { if (XDEEP) load_y(q, t); else load_x(q, t); };
   auto load_dp = [&](int q, int t) { if (XDEEP) load_x(q, t); else load_y(q, t); };
-  // load `idx` of group g (the loads issued after barrier g): shallow operand of tile g+2 first, then
+  // load `idx` of group g (the loads issued after barrier g): shallow operand of tile g+SH first, then
   // the deep operand of tile g+SD
-  constexpr int SH_AHEAD = UNI ? SD : 2;
+  constexpr int SH_AHEAD = SH;
   auto group_load = [&](int idx, int g, bool checked = true) {
     if (idx < LS) { if (!checked || g + SH_AHEAD < KT) load_sh(idx, g + SH_AHEAD); }
     else { if (!checked || g + SD < KT) load_dp(idx - LS, g + SD); }
@@ -208,8 +212,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
 
   // short K: not enough tiles for the steady-state wait counts, wait for everything each time
   const bool short_k = KT <= SD;
-  // prologue, in the order the partial waits rely on: D0 S0 | D1 .. D(SD-2) | first quarter of group -1
-  // (the part of S1 that a "K step 3 of tile -1" would have issued); the loop issues the rest
+  // prologue, in the order the partial waits rely on: D0 S0 | D1 [S1] .. D(SD-2) [S(SD-2)] (shallow tiles up to SH-2)
+  // | first quarter of group -1 (what a "K step 3 of tile -1" would have issued); the loop issues the rest
   static_assert(SD >= 3, "the steady-state wait keeps one deep-operand tile in flight across the barrier");
 #pragma unroll
   for (int q = 0; q < LD; ++q) load_dp(q, 0);
@@ -220,7 +224,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     if (t < KT) {
 #pragma unroll
       for (int q = 0; q < LD; ++q) load_dp(q, t);
-      if (UNI) {
+      if (t < SH - 1) {
 #pragma unroll
         for (int q = 0; q < LS; ++q) load_sh(q, t);
       }
@@ -238,9 +242,11 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
     if (r < TM) fx[buf][r] = *reinterpret_cast<const bf16x8*>(xs + xrow + r * 32 * BKK + slot);
     else fy[buf][r - TM] = *reinterpret_cast<const bf16x8*>(ys + yrow + (r - TM) * 32 * BKK + slot);
   };
-  // loads younger than tile 0's: the whole tiles 1 .. SD-2 (UNI) or their weight halves, and the start of group -1
-  constexpr int W_FIRST = (SD - 2) * (UNI ? NL : LD) + NL / 4;
-  constexpr int W_STEADY = UNI ? (SD - 2) * NL : LD;
+  // loads younger than tile 0's: the deep halves of tiles 1 .. SD-2, the shallow halves of tiles 1 .. SH-2, and the
+  // start of group -1.  Steady state: younger than the shallow operand of the next tile are the deep loads of its
+  // own group and the SH-2 groups after it (every group when both rings have the same depth).
+  constexpr int W_FIRST = (SD - 2) * LD + (SH - 2) * LS + NL / 4;
+  constexpr int W_STEADY = SH == SD ? (SD - 2) * NL : LD + (SH - 2) * NL;
   static_assert(W_FIRST <= 63 && W_STEADY <= 63, "vmcnt is a 6-bit counter");
   if (short_k) wait_vmcnt<0>(); else wait_vmcnt<W_FIRST>();   // tile 0 is in LDS
   __builtin_amdgcn_s_barrier();
@@ -459,18 +465,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_mfma_kernel(GemmArgs a, int til
   if (i0 + BM <= i_max) store_all(std::false_type{}); else store_all(std::true_type{});
 }
 
-template <int EPI, int BN, int SD, int BMT>
+template <int EPI, int BN, int SD, int BMT, int SA>
 constexpr size_t smem_bytes() {
-  return sizeof(bf16_t) * (size_t)(EPI == EPI_LMHEAD ? SD * BMT + 2 * BN : (uniform_rings(EPI, BN, BMT) ? SD : 2) * BMT + SD * BN) * BKK;
+  constexpr int SH = shallow_stages(EPI, BN, BMT, SD, SA);
+  return sizeof(bf16_t) * (size_t)(EPI == EPI_LMHEAD ? SD * BMT + SH * BN : SH * BMT + SD * BN) * BKK;
 }
 
-template <int EPI, int BN, int SD, int BMT = 256>
+template <int EPI, int BN, int SD, int BMT = 256, int SA = 0>
 hipError_t launch_t(const GemmArgs& a, int tiles_i, int tiles_j, hipStream_t st) {
+  static_assert(smem_bytes<EPI, BN, SD, BMT, SA>() <= 160 * 1024, "a workgroup has 160 KB of LDS");
   static std::atomic<unsigned long long> lds_ok{0};
-  const hipError_t e = allow_dynamic_lds((const void*)gemm_bf16_mfma_kernel<EPI, BN, SD, BMT>,
-                                         (int)smem_bytes<EPI, BN, SD, BMT>(), lds_ok);
+  const hipError_t e = allow_dynamic_lds((const void*)gemm_bf16_mfma_kernel<EPI, BN, SD, BMT, SA>,
+                                         (int)smem_bytes<EPI, BN, SD, BMT, SA>(), lds_ok);
   if (e != hipSuccess) return e;
-  gemm_bf16_mfma_kernel<EPI, BN, SD, BMT><<<tiles_i * tiles_j * a.ksplit, 64 * waves_m(BMT, BN) * waves_n(BN), smem_bytes<EPI, BN, SD, BMT>(), st>>>(a, tiles_i, tiles_j);
+  gemm_bf16_mfma_kernel<EPI, BN, SD, BMT, SA><<<tiles_i * tiles_j * a.ksplit, 64 * waves_m(BMT, BN) * waves_n(BN), smem_bytes<EPI, BN, SD, BMT, SA>(), st>>>(a, tiles_i, tiles_j);
   return hipGetLastError();
 }
 

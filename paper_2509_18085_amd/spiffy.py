@@ -251,12 +251,16 @@ def gemm(epilogue: int, A: torch.Tensor, W0: torch.Tensor, W1: Optional[torch.Te
 
 
 def graph_accept(graph_edges: torch.Tensor, draft_states: torch.Tensor, target_states: torch.Tensor,
-                 root: int = 0, stream=None) -> Tuple[torch.Tensor, torch.Tensor]:
-    """Returns (result int32[4] = node, depth, n_steps, flags ; accepted_state int32[B]), on device."""
+                 root: int = 0, stream=None, res: Optional[torch.Tensor] = None,
+                 state: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Returns (result int32[4] = node, depth, n_steps, flags ; accepted_state int32[B]), on device (written into
+    `res` / `state` when the caller passes them)."""
     G, B = draft_states.shape
     E = int(graph_edges.shape[0]) if graph_edges is not None else 0
-    res = torch.empty(4, dtype=torch.int32, device=draft_states.device)
-    state = torch.empty(B, dtype=torch.int32, device=draft_states.device)
+    if res is None:
+        res = torch.empty(4, dtype=torch.int32, device=draft_states.device)
+    if state is None:
+        state = torch.empty(B, dtype=torch.int32, device=draft_states.device)
     _check(lib.spiffy_graph_accept(_ptr(graph_edges) if E else None, E, _ptr(draft_states), _ptr(target_states),
                                    G, B, root, _ptr(res), _ptr(state), _stream(stream)), "spiffy_graph_accept")
     return res, state

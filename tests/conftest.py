@@ -19,3 +19,20 @@ def pytest_sessionstart(session):
     if not os.path.exists(lib):
         from paper_2509_18085_amd import build
         build.build()
+
+
+def pytest_terminal_summary(terminalreporter):
+    """Reported, not gated: the counts the tests collected (see helpers.REPORT)."""
+    import json
+    helpers = sys.modules.get("helpers")
+    records = getattr(helpers, "REPORT", []) if helpers else []
+    if not records:
+        return
+    terminalreporter.section("reported counts (near-ties, excluded states, plain-oracle disagreements, error growth)")
+    for r in records:
+        terminalreporter.write_line(json.dumps(r))
+    path = os.environ.get("SPIFFY_TEST_REPORT")
+    if path:
+        with open(path, "w") as f:
+            for r in records:
+                f.write(json.dumps(r) + "\n")

@@ -8,6 +8,12 @@ import torch
 from paper_2509_18085_amd import synth
 
 
+# Counts the parity bar asks to be reported (near-ties, excluded states, disagreements with the plain oracle, error
+# growth over the layers): tests append dictionaries here, the session prints them at its end (also under -q) and
+# writes them, one JSON line each, to the file named by SPIFFY_TEST_REPORT when that is set.
+REPORT = []
+
+
 def to_np(t):
     if isinstance(t, torch.Tensor):
         return t.detach().cpu().to(torch.float64).numpy()

@@ -15,6 +15,7 @@ import pytest
 import torch
 
 from paper_2509_18085_amd import synth
+import helpers
 from helpers import np_weights, to_np
 
 pytestmark = pytest.mark.gpu
@@ -278,6 +279,68 @@ def test_step_two_layers_at_config3_size(sp):
     assert out["accepted_state"].cpu().tolist() == ref[3].tolist()
 
 
+def test_step_all_32_layers_end_to_end_report(sp):
+    """End-to-end chaining at configuration 3: the whole step (32 bf16 layers, head, walk) on the device against the
+    float64 oracle carried through all 32 layers on three sampled states (a state's rows depend on no other state).
+    Weights are made on the device layer by layer and handed to the oracle one layer at a time.  Reported: the
+    normwise error after every layer and the argmax / unmask agreement at the end (a 1e-2 hidden error moves
+    logits by far more than the 1e-3 margin, so end-to-end decisions are not gated at bf16).  Gated: everything
+    finite, and the error after L layers at most sqrt(L) times the one-layer figure (independent roundings add
+    in quadrature; anything faster would be a systematic error)."""
+    cfg = synth.CONFIGS["c3"]
+    seed, scale = synth.DEFAULT_SEED, 8.0
+    states, edges = synth.draft_graph("c3", cfg, seed)
+    sample = [0, 13, cfg.G - 1]
+    scfg = sp.cfg_from_synth(cfg)
+    w_embed = synth.embed_weights(cfg, seed, device=DEV)
+    hw = synth.head_weights(cfg, seed, device=DEV)
+    d_states = torch.from_numpy(states).to(DEV)
+    ws = sp.alloc_workspace(scfg, cfg.G, cfg.B, cfg.P, DEV)
+    h_gpu = sp.embed(scfg, w_embed, d_states)
+    h_ref = O().embed(to_np(w_embed[torch.from_numpy(np.unique(states)).to(DEV).long()]),
+                      np.searchsorted(np.unique(states), states[sample]))      # only the rows in use leave the device
+    d_layers, d_prefix, growth = [], [], []
+    for l in range(cfg.L):
+        w = synth.layer_weights(cfg, l, seed, device=DEV)
+        pk, pv = synth.prefix_kv(cfg, l, seed, device=DEV)
+        d_layers.append(w)
+        d_prefix.append((pk, pv))
+        h_gpu = sp.verify_layer(scfg, sp.layer_weights(w), sp.prefix_kv(pk, pv), h_gpu, cfg.P, ws)
+        h_ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), h_ref, **oracle_kw(cfg))
+        e_max, e_norm = rel_err(to_np(h_gpu[sample]), h_ref)
+        growth.append(e_norm)
+        print("layer %2d: normwise %.3e  max-rel %.3e" % (l + 1, e_norm, e_max), flush=True)
+    assert np.isfinite(growth).all() and torch.isfinite(h_gpu.float()).all()
+    # the whole step in one call (its normalised rows are rounded at another place than in the layer-by-layer chain)
+    plan = sp.StepPlan(scfg, [sp.layer_weights(w) for w in d_layers], [sp.prefix_kv(k, v) for k, v in d_prefix],
+                       w_embed, hw["final_norm"], hw["w_vocab"], cfg.G, cfg.B, cfg.P, cfg.threshold, logit_scale=scale,
+                       device=DEV)
+    out = plan.run(d_states, torch.from_numpy(edges).to(DEV))
+    torch.cuda.synchronize()
+    e_step = rel_err(to_np(out["hidden"][sample]), h_ref)
+    amax, conf, unmask, margin, target = O().decode_head(
+        h_ref, to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states[sample], cfg.mask_id, cfg.threshold,
+        rms_eps=cfg.rms_eps, logit_scale=scale, force_one=True)
+    m = states[sample] == cfg.mask_id
+    g_amax, g_unmask = out["argmax"][sample].cpu().numpy(), out["unmask"][sample].cpu().numpy()
+    g_conf = out["conf"][sample].cpu().numpy()
+    rec = dict(kind="end_to_end_32_layers", config=cfg.name, states=sample, logit_scale=scale,
+               normwise_error_per_layer=[float("%.4g" % e) for e in growth],
+               step_call_normwise_error=float("%.4g" % e_step[1]), step_call_max_rel=float("%.4g" % e_step[0]),
+               masked=int(m.sum()), argmax_agree=int((g_amax == amax)[m].sum()),
+               unmask_agree=int((g_unmask == unmask)[m].sum()), oracle_unmasked=int(unmask.sum()),
+               conf_median_rel_err=float(np.median(np.abs(g_conf[m] - conf[m]) / np.maximum(conf[m], 1e-30))),
+               sqrt_L_times_first_layer=float("%.4g" % (np.sqrt(cfg.L) * growth[0])))
+    helpers.REPORT.append(rec)
+    print(rec)
+    assert np.isfinite(g_conf).all() and np.isfinite(e_step).all()
+    assert growth[-1] <= np.sqrt(cfg.L) * growth[0], (growth[0], growth[-1])
+    assert e_step[1] <= 1.25 * np.sqrt(cfg.L) * growth[0], e_step
+    # the walk is an integer procedure: exact on the step's own next states whatever the hidden error
+    ref = O().graph_accept(edges, states, out["target_states"].cpu().numpy(), 0)
+    assert tuple(out["result"].cpu().tolist()[:3]) == ref[:3]
+
+
 # ------------------------------------------------------------------ head parity
 
 def run_head(sp, cfg, hidden, hw, states, threshold, logit_scale, force_one):
@@ -290,12 +353,17 @@ def run_head(sp, cfg, hidden, hw, states, threshold, logit_scale, force_one):
     return {k: v.cpu().numpy() for k, v in out.items()}
 
 
-def check_head(sp, cfg, states, hidden, hw, threshold, logit_scale, force_one=True):
+def check_head(sp, cfg, states, hidden, hw, threshold, logit_scale, force_one=True, max_excluded=0):
+    """Decisions of the head against the oracle.  Gated: argmax where the oracle's top-2 logit margin is at least
+    the tie margin; confidences; unmask and next state of every state that holds no near-tie, no confidence next to
+    the threshold and no near-tie of the forced position; `max_excluded` is the stated ceiling on the states that
+    drop out of that comparison.  Reported, not gated (bf16): the decisions that differ from the plain float64
+    oracle, whose operands are not rounded to bf16, outside the literal margin of 1e-3."""
     got = run_head(sp, cfg, hidden, hw, states, threshold, logit_scale, force_one)
+    kw = dict(rms_eps=cfg.rms_eps, logit_scale=logit_scale, force_one=force_one)
     amax, conf, unmask, margin, target = O().decode_head(
         to_np(hidden), to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states, cfg.mask_id, threshold,
-        rms_eps=cfg.rms_eps, logit_scale=logit_scale, force_one=force_one,
-        operand_dtype="bf16" if cfg.dtype == "bf16" else None)
+        operand_dtype="bf16" if cfg.dtype == "bf16" else None, **kw)
     m = states == cfg.mask_id
     tie = 1e-3 * max(1.0, logit_scale)
     near_tie = m & (margin < tie)
@@ -307,8 +375,23 @@ def check_head(sp, cfg, states, hidden, hw, threshold, logit_scale, force_one=Tr
         c = np.sort(conf[g][m[g]])[::-1]
         if near_tie[g].any() or near_tau[g].any() or (c.size > 1 and c[0] - c[1] < 1e-5 * c[0]):
             ok_state[g] = False
-    print("head %s: masked %d, near-tie (margin<1e-3) %d, near-threshold %d, states excluded %d/%d, unmasked %d"
-          % (cfg.name, m.sum(), near_tie.sum(), near_tau.sum(), (~ok_state).sum(), len(ok_state), unmask.sum()))
+    rec = dict(config=cfg.name, d=cfg.d, V=cfg.V, states=int(states.shape[0]), logit_scale=logit_scale, tau=threshold,
+               masked=int(m.sum()), near_tie=int(near_tie.sum()), near_tie_literal_1e_3=int((m & (margin < 1e-3)).sum()),
+               near_threshold=int(near_tau.sum()), excluded_states=int((~ok_state).sum()), unmasked=int(unmask.sum()),
+               argmax_mismatch_in_near_ties=int((got["argmax"] != amax)[near_tie].sum()))
+    if cfg.dtype == "bf16":
+        # the plain oracle: float64 all the way, the normalised row NOT rounded to the matrix cores' bf16
+        p_amax, p_conf, p_unmask, p_margin, _ = O().decode_head(
+            to_np(hidden), to_np(hw["final_norm"]), to_np(hw["w_vocab"]), states, cfg.mask_id, threshold,
+            operand_dtype=None, **kw)
+        lit = m & (p_margin >= 1e-3)
+        far = m & (np.abs(p_conf.astype(np.float64) - threshold) >= 2e-2 * threshold)
+        rec.update(plain_oracle_argmax_mismatch_outside_1e_3=int((got["argmax"] != p_amax)[lit].sum()),
+                   plain_oracle_unmask_mismatch_away_from_tau=int((got["unmask"] != p_unmask)[far & lit].sum()),
+                   plain_oracle_conf_max_rel=float(np.max(np.abs(got["conf"][m] - p_conf[m]) / np.maximum(p_conf[m], 1e-30)))
+                   if m.any() else 0.0)
+    helpers.REPORT.append(dict(kind="head_decisions", **rec))
+    print("head decisions:", rec)
     clear = m & ~near_tie
     np.testing.assert_array_equal(got["argmax"][clear], amax[clear])
     np.testing.assert_array_equal(got["argmax"][~m], states[~m])
@@ -321,7 +404,8 @@ def check_head(sp, cfg, states, hidden, hw, threshold, logit_scale, force_one=Tr
         np.testing.assert_allclose(got["margin"][big], margin[big], rtol=2e-3, atol=tie)
     np.testing.assert_array_equal(got["unmask"][ok_state], unmask[ok_state])
     np.testing.assert_array_equal(got["target_states"][ok_state], target[ok_state])
-    assert ok_state.mean() >= 0.5
+    assert (~ok_state).sum() <= max_excluded, rec
+    got["report"] = rec
     return got
 
 
@@ -340,16 +424,16 @@ def test_head_generic_bf16_and_edge_masks(sp):
     check_head(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 0.5, 30.0)
 
 
-@pytest.mark.parametrize("shape,scale", [
-    (dict(d=256, V=1280, B=32, G=5), 40.0),         # ragged row tile
-    (dict(d=512, V=128 * 9, B=4, G=70), 25.0),      # several row tiles, small blocks
-    (dict(d=256, V=128, B=16, G=6), 20.0),          # a single vocabulary tile
+@pytest.mark.parametrize("shape,scale,max_excluded", [
+    (dict(d=256, V=1280, B=32, G=5), 40.0, 2),      # ragged row tile (at scale 40 the tie margin is 0.04: one near-tie, one forced position next to another)
+    (dict(d=512, V=128 * 9, B=4, G=70), 25.0, 2),   # several row tiles, small blocks
+    (dict(d=256, V=128, B=16, G=6), 20.0, 0),       # a single vocabulary tile
 ])
-def test_head_mfma_shapes(sp, shape, scale):
+def test_head_mfma_shapes(sp, shape, scale, max_excluded):
     cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", Hq=2, Hkv=2, hd=128, F=256, **shape)
     st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.1, 0.9, 6)
     st[0, :] = 7                    # a state with nothing masked
-    check_head(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 0.6, scale)
+    check_head(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 0.6, scale, max_excluded=max_excluded)
 
 
 def test_head_nothing_masked_anywhere(sp):
@@ -359,12 +443,25 @@ def test_head_nothing_masked_anywhere(sp):
     assert (got["unmask"] == 0).all() and (got["target_states"] == st).all()
 
 
-def test_head_config3_shape_sampled_rows(sp):
-    """Full vocabulary (126464) and width of configuration 3; 320 masked rows checked one by one."""
+@pytest.mark.parametrize("logit_scale", [8.0, 1.0])
+def test_head_config3_shape_sampled_rows(sp, logit_scale):
+    """Full vocabulary (126464) and width of configuration 3; 320 masked rows checked one by one, with the synthetic
+    logit scale of the benchmark and at 1.0, the paper's own setting (Alg. 1 steps 1-3 on the raw logits: with
+    random-init weights every confidence is then about 1/V and each state unmasks its single best position)."""
     cfg = synth.CONFIGS["c3"].scaled(G=12)
     st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.8, 0.9, 8)
     hw = synth.head_weights(cfg)
-    check_head(sp, cfg, st, synth.hidden_states(cfg), hw, cfg.threshold, 8.0)
+    check_head(sp, cfg, st, synth.hidden_states(cfg), hw, cfg.threshold, logit_scale, max_excluded=1)
+
+
+@pytest.mark.parametrize("logit_scale", [8.0, 1.0])
+def test_head_config4_shape_sampled_rows(sp, logit_scale):
+    """The head of configuration 4 (Dream-7B-shaped: d = 3584, V = 152064 = 594 vocabulary tiles of 256 rows), eight
+    states, every masked row against the oracle."""
+    cfg = synth.CONFIGS["c4"].scaled(G=8)
+    st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.7, 0.9, 9)
+    hw = synth.head_weights(cfg)
+    check_head(sp, cfg, st, synth.hidden_states(cfg), hw, cfg.threshold, logit_scale, max_excluded=2)
 
 
 # ------------------------------------------------------------------ whole step
@@ -429,7 +526,7 @@ def test_step_accept_follows_device_targets(sp):
     e_max, _ = rel_err(to_np(out["hidden"]), h)
     assert e_max < 4e-2, e_max       # two chained bf16 layers
     # and the head on the step's own hidden
-    check_head(sp, cfg, states, out["hidden"].cpu(), hw, cfg.threshold, 30.0)
+    check_head(sp, cfg, states, out["hidden"].cpu(), hw, cfg.threshold, 30.0, max_excluded=5)   # 32 states, 6 near-ties at margin 0.03
 
 
 # ------------------------------------------------------------------ projection GEMM on its own
@@ -799,7 +896,8 @@ def test_layer_and_head_at_the_row_limit(sp):
     assert cfg.G * cfg.B == 16384
     check_layer(sp, cfg)
     st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.05, 0.3, 9)
-    check_head(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 0.9, 6.0)
+    # 64 fully masked states, 2924 rows over a 640-token vocabulary at margin 6e-3: 21 near-ties in 16 states
+    check_head(sp, cfg, st, synth.hidden_states(cfg), synth.head_weights(cfg), 0.9, 6.0, max_excluded=18)
 
 
 def test_single_token_blocks(sp):

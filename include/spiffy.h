@@ -42,7 +42,8 @@ typedef enum {
   SPIFFY_ESHAPE = -2,
   SPIFFY_EALIGN = -3,
   SPIFFY_EWORKSPACE = -4,
-  SPIFFY_EDEVICE = -5
+  SPIFFY_EDEVICE = -5,
+  SPIFFY_ELIMIT = -6   /* spiffy_decode_head_static only: the call needs more scratch than the library holds */
 } spiffy_status;
 
 enum { SPIFFY_BF16 = 0, SPIFFY_F32 = 1 };
@@ -142,6 +143,24 @@ int spiffy_decode_head(const spiffy_model_cfg *cfg, const void *hidden, const vo
                        int32_t G, int32_t B, float threshold, float logit_scale, int32_t force_one, int32_t *argmax,
                        float *conf, uint8_t *unmask, float *top2_margin, int32_t *target_states,
                        void *workspace, size_t workspace_bytes, void *stream);
+
+/* spiffy_decode_head for callers that cannot allocate and have no workspace to pass: code recorded into a HIP
+ * graph, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (without the workspace), same
+ * kernels and bit-identical outputs; the scratch is a device array of SPIFFY_STATIC_SCRATCH_BYTES that the library
+ * holds on every GPU it runs on until the process ends.  The call allocates nothing and frees nothing.  Limits:
+ * G*B <= SPIFFY_STATIC_MAX_ROWS (the paper's operating point, four states of a 32-token block, Sec. 5) and a head
+ * scratch (gathered rows G*B x d, one 16-byte summary per row and 128-token chunk of the vocabulary) within the
+ * array: bf16 with d <= 8192 and vocab <= 262144 always fits.  Anything larger returns SPIFFY_ELIMIT before any
+ * launch.  All calls on one GPU share that GPU's array (each call overwrites what the last one left; nothing in it
+ * has to be cleared), so calls that overlap on one GPU, on different streams or from different threads, race:
+ * serialise them.  The first call on a device looks up the array's address (not inside a graph capture). */
+#define SPIFFY_STATIC_SCRATCH_BYTES (8u << 20)
+#define SPIFFY_STATIC_MAX_ROWS 128
+int spiffy_decode_head_static(const spiffy_model_cfg *cfg, const void *hidden, const void *final_norm,
+                              const void *w_vocab, const int32_t *block_tokens, const uint8_t *mask,
+                              int32_t G, int32_t B, float threshold, float logit_scale, int32_t force_one,
+                              int32_t *argmax, float *conf, uint8_t *unmask, float *top2_margin,
+                              int32_t *target_states, void *stream);
 
 /* The projection GEMM that verify_layer is made of, exposed for unit tests and for kernel-level
  * timing.  A [M,K], weights [N,K] row-major, C [M,N] (SPIFFY_GEMM_SWIGLU: W0 = gate, W1 = up,

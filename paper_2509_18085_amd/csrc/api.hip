@@ -3,9 +3,16 @@
 #include <cmath>
 #include <cstring>
 
+#include <mutex>
+
 #include "kernels.h"
 
 using namespace spiffy;
+
+// Scratch of the allocation-free entry point (spiffy_decode_head_static): every GPU the library runs on holds its own
+// copy of this array until the process ends.  In host code the name is only a handle for hipGetSymbolAddress; kernels
+// get the device address that call returns.
+static __device__ __align__(256) unsigned char scratch[SPIFFY_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -397,6 +404,22 @@ int check_accept_args(const int32_t* edges, int32_t E, const int32_t* draft, con
   return SPIFFY_OK;
 }
 
+// Device address of `scratch` on the current device: looked up once per device, with that device current.
+int static_scratch_ptr(void** out) {
+  static std::mutex mu;
+  static void* ptr[64] = {};
+  int d = 0;
+  if (hipGetDevice(&d) != hipSuccess || d < 0 || d >= 64) return SPIFFY_EDEVICE;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[d]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SPIFFY_EDEVICE;
+    ptr[d] = p;
+  }
+  *out = ptr[d];
+  return SPIFFY_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -410,6 +433,7 @@ const char* spiffy_status_str(int s) {
     case SPIFFY_EALIGN: return "pointer not 16-byte aligned";
     case SPIFFY_EWORKSPACE: return "workspace too small";
     case SPIFFY_EDEVICE: return "device launch failed";
+    case SPIFFY_ELIMIT: return "size beyond the limit of the allocation-free entry point";
     default: return "unknown status";
   }
 }
@@ -464,6 +488,25 @@ int spiffy_decode_head(const spiffy_model_cfg* cfg, const void* hidden, const vo
   if (workspace_bytes < carve_head(cfg, G, B, nullptr).bytes) return SPIFFY_EWORKSPACE;
   return run_head(cfg, hidden, final_norm, w_vocab, block_tokens, mask, G, B, threshold, logit_scale, force_one,
                   argmax, conf, unmask, top2_margin, target_states, workspace, (hipStream_t)stream);
+}
+
+int spiffy_decode_head_static(const spiffy_model_cfg* cfg, const void* hidden, const void* final_norm,
+                              const void* w_vocab, const int32_t* block_tokens, const uint8_t* mask, int32_t G,
+                              int32_t B, float threshold, float logit_scale, int32_t force_one, int32_t* argmax,
+                              float* conf, uint8_t* unmask, float* top2_margin, int32_t* target_states, void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(G, B))) return rc;
+  if ((rc = check_head_args(cfg, hidden, final_norm, w_vocab, block_tokens, threshold, logit_scale, argmax, conf,
+                            unmask)))
+    return rc;
+  if ((int64_t)G * B > SPIFFY_STATIC_MAX_ROWS) return SPIFFY_ELIMIT;
+  if (carve_head(cfg, G, B, nullptr).bytes > (size_t)SPIFFY_STATIC_SCRATCH_BYTES) return SPIFFY_ELIMIT;
+  void* ws = nullptr;
+  if ((rc = static_scratch_ptr(&ws))) return rc;
+  // every kernel of the head writes what it later reads (row list and count, gathered rows, summaries): nothing in
+  // the scratch has to start at zero, and what the previous call left there is never read
+  return run_head(cfg, hidden, final_norm, w_vocab, block_tokens, mask, G, B, threshold, logit_scale, force_one,
+                  argmax, conf, unmask, top2_margin, target_states, ws, (hipStream_t)stream);
 }
 
 int spiffy_gemm(int32_t dtype, int32_t epilogue, const void* A, const void* W0, const void* W1, const void* R,

@@ -17,6 +17,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libspiffy.so")
 
 SPIFFY_OK, SPIFFY_EINVAL, SPIFFY_ESHAPE, SPIFFY_EALIGN, SPIFFY_EWORKSPACE, SPIFFY_EDEVICE = 0, -1, -2, -3, -4, -5
+SPIFFY_ELIMIT = -6
+STATIC_SCRATCH_BYTES, STATIC_MAX_ROWS = 8 << 20, 128
 SPIFFY_BF16, SPIFFY_F32 = 0, 1
 MAX_G = 64
 
@@ -24,7 +26,7 @@ EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "s
            "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk", "spiffy_commit_block",
            "spiffy_subgraph_search_workspace_bytes", "spiffy_subgraph_search", "spiffy_verify_step",
            "spiffy_workspace_bytes_seq", "spiffy_verify_step_seq", "spiffy_workspace_bytes_commit",
-           "spiffy_verify_step_commit", "spiffy_probe_mfma", "spiffy_probe_hbm_read"]
+           "spiffy_verify_step_commit", "spiffy_probe_mfma", "spiffy_probe_hbm_read", "spiffy_decode_head_static"]
 GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
 
@@ -75,6 +77,8 @@ def _load() -> C.CDLL:
     lib.spiffy_decode_head.restype = C.c_int
     lib.spiffy_decode_head.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp,
                                        vp, sz, vp]
+    lib.spiffy_decode_head_static.restype = C.c_int
+    lib.spiffy_decode_head_static.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp]
     lib.spiffy_gemm.restype = C.c_int
     lib.spiffy_gemm.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     lib.spiffy_graph_accept.restype = C.c_int
@@ -233,6 +237,21 @@ def decode_head(cfg: ModelCfg, hidden: torch.Tensor, final_norm: torch.Tensor, w
                                   _ptr(mask), G, B, threshold, logit_scale, int(force_one), _ptr(out["argmax"]),
                                   _ptr(out["conf"]), _ptr(out["unmask"]), _ptr(out["margin"]),
                                   _ptr(out["target_states"]), wp, wn, _stream(stream)), "spiffy_decode_head")
+    return out
+
+
+def decode_head_static(cfg: ModelCfg, hidden: torch.Tensor, final_norm: torch.Tensor, w_vocab: torch.Tensor,
+                       block_tokens: torch.Tensor, threshold: float, out: Dict[str, torch.Tensor], *,
+                       mask: Optional[torch.Tensor] = None, logit_scale: float = 1.0, force_one: bool = True,
+                       stream=None) -> Dict[str, torch.Tensor]:
+    """spiffy_decode_head_static: decode_head on the library's own device scratch.  Nothing is allocated, here or
+    in the library: `out` holds the caller's output tensors (argmax, conf, unmask, margin, target_states: the
+    dictionary decode_head returns has the right shapes)."""
+    G, B = block_tokens.shape
+    _check(lib.spiffy_decode_head_static(C.byref(cfg), _ptr(hidden), _ptr(final_norm), _ptr(w_vocab), _ptr(block_tokens),
+                                         _ptr(mask), G, B, threshold, logit_scale, int(force_one), _ptr(out["argmax"]),
+                                         _ptr(out["conf"]), _ptr(out["unmask"]), _ptr(out.get("margin")),
+                                         _ptr(out.get("target_states")), _stream(stream)), "spiffy_decode_head_static")
     return out
 
 

@@ -4,9 +4,12 @@
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--config c3|c2|c4|c5] [--no-cpu-baseline]
 
 One step = the whole hot path over one batch of synthetic input: embedding of G block states,
-L transformer layers (shared-prefix attention + projections), LM head reduced to
-top-1/confidence/unmask, next-state build and the acceptance walk, all in one C-ABI call with
-weights, prefix KV and inputs already resident in HBM.  Prints ONE JSON line.
+L transformer layers (shared-prefix attention + projections; the last one computes only the rows of
+masked positions behind its attention), LM head reduced to top-1/confidence/unmask, next-state build
+and the acceptance walk, all in one C-ABI call with weights, prefix KV and inputs already resident in
+HBM, followed by the acceptance walk against the workload's planted target states (one more
+one-wavefront launch).  Prints ONE JSON line; `other_configs` holds the other workload configurations
+measured the same way, `decision_check` the device step's decisions against the oracle.
 
 metric  = draft states verified per second (G / step latency), whole job on one GPU
 roofline= the dominant kernel (the SwiGLU gate/up MFMA GEMM): algorithmic flop of one launch /
@@ -34,8 +37,11 @@ def step_work(cfg, n_masked):
     4*B*(P+B)*hd*Hq; weights and cached keys / values once per step; the head on the masked rows only)."""
     M = cfg.G * cfg.B
     params_layer = cfg.d * cfg.Hq * cfg.hd * 2 + cfg.d * cfg.Hkv * cfg.hd * 2 + 3 * cfg.d * cfg.F
+    # the last layer computes its output projection and FFN on the masked rows only (exact: nothing else is read
+    # afterwards), so the algorithmic count takes n_masked rows for that part
+    params_behind_attention = cfg.d * cfg.Hq * cfg.hd + 3 * cfg.d * cfg.F
     flop = cfg.L * (2.0 * M * params_layer + 4.0 * cfg.B * (cfg.P + cfg.B) * cfg.hd * cfg.Hq * cfg.G) \
-        + 2.0 * n_masked * cfg.V * cfg.d
+        - 2.0 * (M - n_masked) * params_behind_attention + 2.0 * n_masked * cfg.V * cfg.d
     nbytes = cfg.L * (2.0 * params_layer + 2.0 * 2 * cfg.P * cfg.Hkv * cfg.hd) + 2.0 * cfg.V * cfg.d + 2.0 * M * cfg.d
     return flop, nbytes
 
@@ -64,7 +70,7 @@ def build_workload(sp, synth, key, dev, seed, n_states=0):
     w["d_planted"] = torch.from_numpy(planted).to(dev)
     w["plan"] = sp.StepPlan(sp.cfg_from_synth(cfg), [sp.layer_weights(x) for x in layers],
                             [sp.prefix_kv(k, v) for k, v in prefix], w_embed, hw["final_norm"], hw["w_vocab"], cfg.G,
-                            cfg.B, cfg.P, cfg.threshold, logit_scale=LOGIT_SCALE, device=dev)
+                            cfg.B, cfg.P, cfg.threshold, logit_scale=LOGIT_SCALE, device=dev, keep_hidden=False)
     w["walk_res"] = torch.empty(4, dtype=torch.int32, device=dev)
     w["walk_state"] = torch.empty(cfg.B, dtype=torch.int32, device=dev)
     return w
@@ -273,7 +279,8 @@ def main():
         line["calibration_subgraph_search"] = subgraph_leg(sp, dev, seed)
 
     if not args.no_cpu_baseline:
-        one_step(sp, w)                     # the legs above reused the plan's buffers: the step's own outputs again
+        plan.keep_hidden = True             # once more with the hidden states written out: the oracle's head reads them
+        one_step(sp, w)
         torch.cuda.synchronize()
         line["cpu_baseline"], line["decision_check"] = cpu_baseline(cfg, layers, prefix, hw, states, edges, plan.out)
 

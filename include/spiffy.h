@@ -124,6 +124,19 @@ int spiffy_verify_layer(const spiffy_model_cfg *cfg, const spiffy_layer_weights 
                         int32_t pos0, void *hidden_out, void *workspace, size_t workspace_bytes,
                         void *stream);
 
+/* The last layer of a step.  Only masked positions are decoded (Alg. 1 steps 1-4 rank and fill masked positions
+ * only; Sec. 3.1), so behind the attention, where every row of a state still supplies keys and values to the
+ * others, only the rows of masked positions are computed: output projection, FFN and residuals run on those rows.
+ * mask [G,B] uint8 (1 = masked) may be NULL, then mask = (block_tokens == cfg.mask_id).  hidden_out rows of
+ * masked positions receive exactly what spiffy_verify_layer writes there (bit for bit: a row's arithmetic does
+ * not depend on the rows computed with it); the other rows of hidden_out are not written.  Other arguments,
+ * workspace and errors as for spiffy_verify_layer.  spiffy_verify_step runs its last layer this way when
+ * the caller passes hidden_out = NULL. */
+int spiffy_verify_layer_last(const spiffy_model_cfg *cfg, const spiffy_layer_weights *w,
+                             const spiffy_prefix_kv *prefix, const void *hidden_in, const int32_t *block_tokens,
+                             const uint8_t *mask, int32_t G, int32_t B, int32_t pos0, void *hidden_out,
+                             void *workspace, size_t workspace_bytes, void *stream);
+
 /* LM head reduced to decisions (Alg. 1 steps 1-4 with the threshold rule of Sec. 3.1), for all G
  * states.  mask [G,B] uint8 (1 = masked) may be NULL, then mask = (block_tokens == cfg.mask_id).
  * For every masked position: logits = logit_scale *
@@ -233,7 +246,9 @@ int spiffy_draft_prune(const int32_t *state, int32_t B, int32_t mask_id, const i
 
 /* The whole step on one stream with no host synchronisation: embed, n_layers x verify_layer,
  * decode_head, graph_accept.  layers / prefix are HOST arrays of n_layers structs.
- * hidden_out [G,B,d] receives the last layer's output (may be NULL: kept in the workspace). */
+ * hidden_out [G,B,d] receives the last layer's output.  It may be NULL: the hidden states then stay in the
+ * workspace, and the last layer computes only the rows of masked positions behind its attention (see
+ * spiffy_verify_layer_last; every output of the step is the same, bit for bit). */
 int spiffy_verify_step(const spiffy_model_cfg *cfg, int32_t n_layers,
                        const spiffy_layer_weights *layers, const spiffy_prefix_kv *prefix,
                        const void *w_embed, const void *final_norm, const void *w_vocab,

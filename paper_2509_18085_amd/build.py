@@ -53,6 +53,30 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def build_host_sanitized() -> tuple:
+    """The same library with the HOST code of the launcher (csrc/api.hip: argument checks, workspace carving, kernel
+    selection) compiled under AddressSanitizer and UndefinedBehaviorSanitizer; device code and the kernel translation
+    units are the normal ones.  Returns (library path, sanitizer runtime to preload).  For the CPU tests only."""
+    if not all(os.path.exists(os.path.join(OBJ, s.replace(".hip", ".o"))) for s in SOURCES):
+        build()
+    out_dir = os.path.join(OBJ, "asan")
+    os.makedirs(out_dir, exist_ok=True)
+    hipcc = _hipcc()
+    api_o = os.path.join(out_dir, "api.o")
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=undefined"]
+    flags = [f if f != "-O3" else "-O1" for f in FLAGS] + ["-g"]
+    _run([hipcc] + flags + san + ["-c", os.path.join(CSRC, "api.hip"), "-o", api_o])
+    objs = [api_o] + [os.path.join(OBJ, s.replace(".hip", ".o")) for s in SOURCES if s != "api.hip"]
+    lib = os.path.join(out_dir, "libspiffy_asan.so")
+    _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-fsanitize=address,undefined", "-o", lib] + objs)
+    clang = os.path.join(os.path.dirname(os.path.realpath(hipcc)), "..", "lib", "llvm", "bin", "clang")
+    if not os.path.exists(clang):
+        clang = "/opt/rocm/lib/llvm/bin/clang"
+    rt = subprocess.run([clang, "-print-file-name=libclang_rt.asan-x86_64.so"], stdout=subprocess.PIPE, text=True).stdout.strip()
+    return lib, rt
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
     sys.exit(0)

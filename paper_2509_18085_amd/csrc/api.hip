@@ -77,6 +77,8 @@ struct Carve {
 
 struct LayerWs {
   void *n, *qkv, *attn, *h, *act, *attn_partial, *attn_partial_seq, *splitk;
+  void *gat_attn, *gat_x;        // last layer, masked rows only: gathered attention rows and residual rows
+  int32_t *rows, *count;         // ... and their row list
   size_t bytes;
 };
 // P = cached rows (prefix and suffix together).  S_seq > 0: full-sequence step, S_seq true suffix rows ride along
@@ -94,6 +96,10 @@ LayerWs carve_layer(const spiffy_model_cfg* c, int G, int B, int P, void* base, 
   w.attn_partial = cv.take(layer_mfma(c) ? mfma_attn_partial_bytes(G, B, c->n_q_heads, c->head_dim, P + S_seq) : 0);
   w.attn_partial_seq = cv.take(layer_mfma(c) && S_seq ? mfma_attn_partial_bytes(1, S_seq, c->n_q_heads, c->head_dim, P + B + S_seq) : 0);
   w.splitk = cv.take(layer_mfma(c) ? sizeof(float) * 4 * M * c->d : 0);   // up to 4 K slices of [M,d] fp32
+  w.gat_attn = cv.take(M * (size_t)c->n_q_heads * c->head_dim * es);
+  w.gat_x = cv.take(M * c->d * es);
+  w.rows = (int32_t*)cv.take(sizeof(int32_t) * M);
+  w.count = (int32_t*)cv.take(sizeof(int32_t) * 4);
   w.bytes = cv.off;
   return w;
 }
@@ -182,6 +188,13 @@ struct LayerChain {
   // prefix->P counts the rows in front of that finished block; its keys / values are written to cache rows
   // P .. P+B-1 and the G states (positions pos0 = that block's + B) attend to P + B cached rows.
   bool tail_is_prev_block = false;
+  // Last layer of a step: only masked positions are decoded (Alg. 1 steps 1-4 look at masked positions only), so
+  // beyond the attention, where every row still supplies keys and values, only their rows are computed.  rows /
+  // count: the device-side list of those rows (ascending) in the layer scratch; the other rows of hidden_out are
+  // left as they are.
+  bool masked_rows_only = false;
+  const int32_t* tokens = nullptr;    // [G,B] block tokens and optional explicit mask, for the row list
+  const uint8_t* mask = nullptr;
 };
 
 // The same product as two launches over the row ranges [0, rows_a) and [rows_a, rows_a + rows_b): each range gets the
@@ -313,36 +326,55 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
     } else if ((rc = dev(launch_attn_generic(dt, b, st)))) return rc;
   }
 
+  // Masked rows only (last layer): from here on row r of every matrix is row ws.rows[r] of the block rows, r < *ws.count.
+  // The row count is known on the device only: the launches cover all M rows and skip what lies beyond it.  A row's
+  // arithmetic does not depend on where it sits, so the results are those of the full layer, bit for bit.
+  const bool cm = chain && chain->masked_rows_only && !S_seq;
+  const int32_t* n_rows = cm ? ws.count : nullptr;
+  const void* attn_rows = ws.attn;
+  const void* resid = hidden_in;
+  if (cm) {
+    const size_t es = esize(dt);
+    if ((rc = dev(launch_compact_rows(chain->tokens, chain->mask, cfg->mask_id, M, ws.rows, ws.count, st)))) return rc;
+    if ((rc = dev(launch_gather_rows2(ws.attn, (size_t)qd * es, hidden_in, (size_t)d * es, ws.rows, ws.count, M, ws.gat_attn,
+                                      ws.gat_x, st))))
+      return rc;
+    attn_rows = ws.gat_attn;
+    resid = ws.gat_x;
+  }
+
   // output projection + residual (+ RMSNorm-2 fused into the split-K reduction when K is sliced)
   std::memset(&g, 0, sizeof(g));
-  g.A = ws.attn; g.lda = qd; g.M = M; g.K = qd; g.W[0] = w->wo; g.Nseg[0] = d; g.N = d;
-  g.C = ws.h; g.ldc = d; g.R = hidden_in; g.scale = 1.f;
+  g.A = attn_rows; g.lda = qd; g.M = M; g.M_dev = n_rows; g.K = qd; g.W[0] = w->wo; g.Nseg[0] = d; g.N = d;
+  g.C = ws.h; g.ldc = d; g.R = resid; g.scale = 1.f;
   bool normed = false;
   if (mf && mfma_gemm_supported(EPI_RESID, g)) {
     const int ks = mfma_ksplit(d, qd);
     if (ks > 1) {
       g.C = ws.splitk; g.ksplit = ks;
       if ((rc = dev(mfma_rows(EPI_PARTIAL, g)))) return rc;
-      if ((rc = dev(launch_splitk_reduce((const float*)ws.splitk, ks, hidden_in, ws.h, w->norm2, cfg->rms_eps, ws.n, M,
-                                         d, st))))
+      if ((rc = dev(launch_splitk_reduce((const float*)ws.splitk, ks, resid, ws.h, w->norm2, cfg->rms_eps, ws.n, M,
+                                         d, st, n_rows))))
         return rc;
       normed = true;
     } else if ((rc = dev(mfma_rows(EPI_RESID, g)))) return rc;
   } else if ((rc = dev(launch_gemm_generic(dt, EPI_RESID, g, st)))) return rc;
 
-  if (!normed && (rc = dev(launch_rmsnorm(dt, ws.h, w->norm2, cfg->rms_eps, M, d, nullptr, nullptr, ws.n, st))))
+  if (!normed && (rc = dev(launch_rmsnorm(dt, ws.h, w->norm2, cfg->rms_eps, M, d, nullptr, n_rows, ws.n, st))))
     return rc;
 
   std::memset(&g, 0, sizeof(g));
-  g.A = ws.n; g.lda = d; g.M = M; g.K = d; g.W[0] = w->w_gate; g.W[1] = w->w_up; g.N = cfg->ffn;
+  g.A = ws.n; g.lda = d; g.M = M; g.M_dev = n_rows; g.K = d; g.W[0] = w->w_gate; g.W[1] = w->w_up; g.N = cfg->ffn;
   g.C = ws.act; g.ldc = cfg->ffn; g.scale = 1.f;
   if ((rc = dev(mf && mfma_gemm_supported(EPI_SWIGLU, g) ? mfma_rows(EPI_SWIGLU, g)
                                                           : launch_gemm_generic(dt, EPI_SWIGLU, g, st))))
     return rc;
 
+  // down projection + residual; compacted rows go back to their places in hidden_out (by the reduction when K is
+  // sliced, else through ws.gat_x, which is free once the output projection has read it)
   std::memset(&g, 0, sizeof(g));
-  g.A = ws.act; g.lda = cfg->ffn; g.M = M; g.K = cfg->ffn; g.W[0] = w->w_down; g.Nseg[0] = d; g.N = d;
-  g.C = hidden_out; g.ldc = d; g.R = ws.h; g.scale = 1.f;
+  g.A = ws.act; g.lda = cfg->ffn; g.M = M; g.M_dev = n_rows; g.K = cfg->ffn; g.W[0] = w->w_down; g.Nseg[0] = d; g.N = d;
+  g.C = cm ? ws.gat_x : hidden_out; g.ldc = d; g.R = ws.h; g.scale = 1.f;
   if (mf && mfma_gemm_supported(EPI_RESID, g)) {
     const int ks = mfma_ksplit(d, cfg->ffn);
     if (ks > 1) {
@@ -351,11 +383,12 @@ int run_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const 
       const void* ng = chain ? chain->next_norm1 : nullptr;
       if (chain && ng) chain->normed_out = true;
       return dev(launch_splitk_reduce((const float*)ws.splitk, ks, ws.h, hidden_out, ng, cfg->rms_eps,
-                                      ng ? ws.n : nullptr, M, d, st));
+                                      ng ? ws.n : nullptr, M, d, st, n_rows, cm ? ws.rows : nullptr));
     }
-    return dev(mfma_rows(EPI_RESID, g));
-  }
-  return dev(launch_gemm_generic(dt, EPI_RESID, g, st));
+    if ((rc = dev(mfma_rows(EPI_RESID, g)))) return rc;
+  } else if ((rc = dev(launch_gemm_generic(dt, EPI_RESID, g, st)))) return rc;
+  if (cm) return dev(launch_scatter_rows(ws.gat_x, (size_t)d * esize(dt), ws.rows, ws.count, M, hidden_out, st));
+  return SPIFFY_OK;
 }
 
 int run_head(const spiffy_model_cfg* cfg, const void* hidden, const void* final_norm, const void* w_vocab,
@@ -471,6 +504,23 @@ int spiffy_verify_layer(const spiffy_model_cfg* cfg, const spiffy_layer_weights*
     return SPIFFY_EALIGN;
   if (workspace_bytes < carve_layer(cfg, G, B, prefix->P + prefix->S, nullptr).bytes) return SPIFFY_EWORKSPACE;
   return run_layer(cfg, w, prefix, hidden_in, G, B, pos0, hidden_out, workspace, (hipStream_t)stream);
+}
+
+int spiffy_verify_layer_last(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w, const spiffy_prefix_kv* prefix,
+                             const void* hidden_in, const int32_t* block_tokens, const uint8_t* mask, int32_t G, int32_t B,
+                             int32_t pos0, void* hidden_out, void* workspace, size_t workspace_bytes, void* stream) {
+  int rc;
+  if ((rc = check_cfg(cfg)) || (rc = check_gb(G, B))) return rc;
+  if (!hidden_in || !hidden_out || !workspace || !block_tokens || pos0 < 0) return SPIFFY_EINVAL;
+  if ((rc = check_layer_args(cfg, w, prefix, G, B))) return rc;
+  if (!aligned16(hidden_in) || !aligned16(hidden_out) || (reinterpret_cast<uintptr_t>(workspace) & 255u))
+    return SPIFFY_EALIGN;
+  if (workspace_bytes < carve_layer(cfg, G, B, prefix->P + prefix->S, nullptr).bytes) return SPIFFY_EWORKSPACE;
+  LayerChain chain;
+  chain.masked_rows_only = true;
+  chain.tokens = block_tokens;
+  chain.mask = mask;
+  return run_layer(cfg, w, prefix, hidden_in, G, B, pos0, hidden_out, workspace, (hipStream_t)stream, &chain);
 }
 
 int spiffy_decode_head(const spiffy_model_cfg* cfg, const void* hidden, const void* final_norm, const void* w_vocab,
@@ -628,9 +678,13 @@ int spiffy_verify_step(const spiffy_model_cfg* cfg, int32_t n_layers, const spif
   int32_t* tgt = target_states ? target_states : ws.target;
   if ((rc = dev(launch_embed(cfg->dtype, w_embed, block_tokens, G * B, cfg->d, cfg->vocab, hid, st)))) return rc;
   LayerChain chain;
+  chain.tokens = block_tokens;
   for (int l = 0; l < n_layers; ++l) {
     chain.normed_in = chain.normed_out;
     chain.next_norm1 = (l + 1 < n_layers) ? layers[l + 1].norm1 : nullptr;
+    // a caller that does not ask for the hidden states gets the last layer on the masked rows only: the head reads
+    // nothing else
+    chain.masked_rows_only = !hidden_out && l + 1 == n_layers;
     if ((rc = run_layer(cfg, &layers[l], &prefix[l], hid, G, B, pos0, hid, ws.rest, st, &chain))) return rc;
     chain.rope_ready = true;      // same pos0 / B / base for every layer: the table is computed once
   }

@@ -31,6 +31,44 @@ hipError_t launch_embed(int dtype, const void* w, const int32_t* tok, int M, int
 }
 
 // ---------------------------------------------------------------------------------------------
+// row gather of two matrices with one row list: a_out[r,:] = a[row_idx[r],:], b_out[r,:] = b[row_idx[r],:]
+// for r < *count (the masked rows of the last layer: attention output and residual stream)
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_rows2_kernel(const uint4* __restrict__ a, int a16, const uint4* __restrict__ b,
+                                                           int b16, const int32_t* __restrict__ row_idx,
+                                                           const int32_t* __restrict__ count, uint4* __restrict__ a_out,
+                                                           uint4* __restrict__ b_out) {
+  const int r = blockIdx.x;
+  if (r >= *count) return;
+  const size_t src = (size_t)row_idx[r];
+  for (int i = threadIdx.x; i < a16; i += 256) a_out[(size_t)r * a16 + i] = a[src * a16 + i];
+  for (int i = threadIdx.x; i < b16; i += 256) b_out[(size_t)r * b16 + i] = b[src * b16 + i];
+}
+
+// out[row_idx[r],:] = in[r,:] for r < *count
+__global__ __launch_bounds__(256) void scatter_rows_kernel(const uint4* __restrict__ in, int n16, const int32_t* __restrict__ row_idx,
+                                                           const int32_t* __restrict__ count, uint4* __restrict__ out) {
+  const int r = blockIdx.x;
+  if (r >= *count) return;
+  const size_t dst = (size_t)row_idx[r];
+  for (int i = threadIdx.x; i < n16; i += 256) out[dst * n16 + i] = in[(size_t)r * n16 + i];
+}
+
+hipError_t launch_scatter_rows(const void* in, size_t row_bytes, const int32_t* row_idx, const int32_t* count, int M,
+                               void* out, hipStream_t st) {
+  scatter_rows_kernel<<<M, 256, 0, st>>>((const uint4*)in, (int)(row_bytes / 16), row_idx, count, (uint4*)out);
+  return hipGetLastError();
+}
+
+hipError_t launch_gather_rows2(const void* a, size_t a_row_bytes, const void* b, size_t b_row_bytes,
+                               const int32_t* row_idx, const int32_t* count, int M, void* a_out, void* b_out,
+                               hipStream_t st) {
+  gather_rows2_kernel<<<M, 256, 0, st>>>((const uint4*)a, (int)(a_row_bytes / 16), (const uint4*)b, (int)(b_row_bytes / 16),
+                                         row_idx, count, (uint4*)a_out, (uint4*)b_out);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // RMSNorm with optional row gather
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ float block_sum_256(float v, float* red) {

@@ -13,6 +13,12 @@ hipError_t launch_embed(int dtype, const void* w_embed, const int32_t* tokens, i
 hipError_t launch_rmsnorm(int dtype, const void* x, const void* gain, float eps, int M, int d,
                           const int32_t* row_idx, const int32_t* n_rows_dev, void* out, hipStream_t st);
 hipError_t launch_gemm_generic(int dtype, int epi, const GemmArgs& a, hipStream_t st);
+// a_out[r,:] = a[row_idx[r],:] and b_out[r,:] = b[row_idx[r],:] for r < *count; row sizes in bytes, multiples of 16
+hipError_t launch_scatter_rows(const void* in, size_t row_bytes, const int32_t* row_idx, const int32_t* count, int M,
+                               void* out, hipStream_t st);     // out[row_idx[r],:] = in[r,:] for r < *count
+hipError_t launch_gather_rows2(const void* a, size_t a_row_bytes, const void* b, size_t b_row_bytes,
+                               const int32_t* row_idx, const int32_t* count, int M, void* a_out, void* b_out,
+                               hipStream_t st);
 
 struct AttnArgs {
   const void* qkv;       // [M, (Hq+2Hkv)*hd]: q | k | v columns, not yet rotated
@@ -111,9 +117,12 @@ bool mfma_gemm_supported(int epi, const GemmArgs& a);
 hipError_t launch_gemm_mfma(int epi, const GemmArgs& a, hipStream_t st);
 int mfma_lmhead_partials_per_row(int V);
 int mfma_ksplit(int N, int K);          // K slices used for a [M,K]x[N,K] projection with residual (depends on N, K only)
-// out = R + sum of the K-slice partials P[ksplit][M][N] (fixed order); if normed != NULL also RMSNorm(out)*gain
+// out = R + sum of the K-slice partials P[ksplit][M][N] (fixed order); if normed != NULL also RMSNorm(out)*gain.
+// n_rows_dev (optional): only rows below *n_rows_dev exist; out_rows (optional): row m of the result goes to row
+// out_rows[m] of `out` (the partials, R and normed keep row m).
 hipError_t launch_splitk_reduce(const float* P, int ksplit, const void* R, void* out, const void* gain, float eps,
-                                void* normed, int M, int N, hipStream_t st);  // partial summaries per row written by EPI_LMHEAD
+                                void* normed, int M, int N, hipStream_t st, const int32_t* n_rows_dev = nullptr,
+                                const int32_t* out_rows = nullptr);
 bool mfma_attn_supported(const AttnArgs& a);
 size_t mfma_attn_partial_bytes(int G, int B, int Hq, int hd, int P);
 hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st);

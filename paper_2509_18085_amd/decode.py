@@ -84,7 +84,7 @@ class BlockDecoder:
         else:
             self.plan = sp.StepPlan(cfg, [sp.layer_weights(w) for w in layers], prefix, w_embed, final_norm, w_vocab,
                                     1 + self.d_star, B, P0, threshold, logit_scale=logit_scale, force_one=force_one,
-                                    device=device)
+                                    device=device, keep_hidden=False)     # the loop reads decisions only: the last layer runs on masked rows
             # the workspace must also fit the longest prefix the cache can hold
             self.plan.workspace = sp.alloc_workspace(cfg, 1 + self.d_star, B, self.capacity, device)
 

@@ -14,7 +14,8 @@ from typing import Dict, List, Optional, Sequence, Tuple
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libspiffy.so")
+# SPIFFY_LIB names another build of the same library (the host-sanitizer build of the tests); default: the in-tree one
+LIB_PATH = os.environ.get("SPIFFY_LIB") or os.path.join(_HERE, "libspiffy.so")
 
 SPIFFY_OK, SPIFFY_EINVAL, SPIFFY_ESHAPE, SPIFFY_EALIGN, SPIFFY_EWORKSPACE, SPIFFY_EDEVICE = 0, -1, -2, -3, -4, -5
 SPIFFY_ELIMIT = -6
@@ -23,7 +24,7 @@ SPIFFY_BF16, SPIFFY_F32 = 0, 1
 MAX_G = 64
 
 EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "spiffy_embed",
-           "spiffy_verify_layer", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk", "spiffy_commit_block",
+           "spiffy_verify_layer", "spiffy_verify_layer_last", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk", "spiffy_commit_block",
            "spiffy_subgraph_search_workspace_bytes", "spiffy_subgraph_search", "spiffy_verify_step",
            "spiffy_workspace_bytes_seq", "spiffy_verify_step_seq", "spiffy_workspace_bytes_commit",
            "spiffy_verify_step_commit", "spiffy_probe_mfma", "spiffy_probe_hbm_read", "spiffy_decode_head_static"]
@@ -74,6 +75,9 @@ def _load() -> C.CDLL:
     lib.spiffy_verify_layer.restype = C.c_int
     lib.spiffy_verify_layer.argtypes = [cfgp, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, i32, i32, i32,
                                         vp, vp, sz, vp]
+    lib.spiffy_verify_layer_last.restype = C.c_int
+    lib.spiffy_verify_layer_last.argtypes = [cfgp, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, i32, i32,
+                                             i32, vp, vp, sz, vp]
     lib.spiffy_decode_head.restype = C.c_int
     lib.spiffy_decode_head.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp,
                                        vp, sz, vp]
@@ -218,6 +222,18 @@ def verify_layer(cfg: ModelCfg, w: LayerWeights, prefix: PrefixKV, hidden_in: to
     wp, wn = _ws(workspace)
     _check(lib.spiffy_verify_layer(C.byref(cfg), C.byref(w), C.byref(prefix), _ptr(hidden_in), G, B, pos0,
                                    _ptr(out), wp, wn, _stream(stream)), "spiffy_verify_layer")
+    return out
+
+
+def verify_layer_last(cfg: ModelCfg, w: LayerWeights, prefix: PrefixKV, hidden_in: torch.Tensor,
+                      block_tokens: torch.Tensor, pos0: int, workspace: torch.Tensor, out: torch.Tensor,
+                      mask: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """The last layer of a step: rows of masked positions of `out` are written, the others are left as they are."""
+    G, B, _ = hidden_in.shape
+    wp, wn = _ws(workspace)
+    _check(lib.spiffy_verify_layer_last(C.byref(cfg), C.byref(w), C.byref(prefix), _ptr(hidden_in), _ptr(block_tokens),
+                                        _ptr(mask), G, B, pos0, _ptr(out), wp, wn, _stream(stream)),
+           "spiffy_verify_layer_last")
     return out
 
 
@@ -373,8 +389,9 @@ class StepPlan:
     def __init__(self, cfg: ModelCfg, layers: Sequence[LayerWeights], prefix: Sequence[PrefixKV],
                  w_embed: torch.Tensor, final_norm: torch.Tensor, w_vocab: torch.Tensor, G: int, B: int,
                  pos0: int, threshold: float, logit_scale: float = 1.0, force_one: bool = True,
-                 root: int = 0, device="cuda"):
+                 root: int = 0, device="cuda", keep_hidden: bool = True):
         self.cfg, self.G, self.G_cap, self.B, self.pos0 = cfg, G, G, B, pos0
+        self.keep_hidden = keep_hidden      # False: hidden_out = NULL, the last layer runs on the masked rows only
         self.threshold, self.logit_scale, self.force_one, self.root = threshold, logit_scale, int(force_one), root
         self.n_layers = len(layers)
         self._layers = (LayerWeights * max(1, self.n_layers))(*layers)
@@ -421,9 +438,9 @@ class StepPlan:
         _check(lib.spiffy_verify_step(
             C.byref(self.cfg), self.n_layers, self._layers, self._prefix, _ptr(self.w_embed), _ptr(self.final_norm),
             _ptr(self.w_vocab), _ptr(block_tokens), self.G, self.B, self.pos0, _ptr(graph_edges) if E else None, E,
-            self.root, self.threshold, self.logit_scale, self.force_one, _ptr(o["hidden"]), _ptr(o["argmax"]),
-            _ptr(o["conf"]), _ptr(o["unmask"]), _ptr(o["margin"]), _ptr(o["target_states"]), _ptr(o["result"]),
-            _ptr(o["accepted_state"]), wp, wn, _stream(stream)), "spiffy_verify_step")
+            self.root, self.threshold, self.logit_scale, self.force_one, _ptr(o["hidden"]) if self.keep_hidden else None,
+            _ptr(o["argmax"]), _ptr(o["conf"]), _ptr(o["unmask"]), _ptr(o["margin"]), _ptr(o["target_states"]),
+            _ptr(o["result"]), _ptr(o["accepted_state"]), wp, wn, _stream(stream)), "spiffy_verify_step")
         return o
 
 

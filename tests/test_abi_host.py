@@ -110,6 +110,20 @@ def test_verify_layer_argument_errors():
     assert call(cfg=bad) == sp.SPIFFY_EINVAL
 
 
+def test_verify_layer_last_argument_errors():
+    cfg = _cfg("c3")
+    w, p = _layer_structs()
+    call = lambda **k: sp.lib.spiffy_verify_layer_last(
+        C.byref(cfg), C.byref(w), C.byref(p), k.get("hin", DUMMY), k.get("tok", DUMMY), None, k.get("G", 4), 32, 64,
+        k.get("hout", DUMMY), k.get("ws", 0x100000), k.get("wsn", 16), None)
+    assert call() == sp.SPIFFY_EWORKSPACE
+    assert call(tok=None) == sp.SPIFFY_EINVAL
+    assert call(hin=None) == sp.SPIFFY_EINVAL
+    assert call(G=0) == sp.SPIFFY_EINVAL
+    assert call(hout=DUMMY + 2) == sp.SPIFFY_EALIGN
+    assert call(ws=0x100010) == sp.SPIFFY_EALIGN
+
+
 def test_decode_head_argument_errors():
     cfg = _cfg("c3")
     call = lambda **k: sp.lib.spiffy_decode_head(

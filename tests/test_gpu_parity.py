@@ -259,6 +259,76 @@ def test_layer_full_size_in_the_bench_launch_configuration(sp, key):
     assert torch.isfinite(got.float()).all()
 
 
+@pytest.mark.parametrize("kind", ["mfma", "mfma_gqa_small_blocks", "generic_f32", "generic_bf16"])
+def test_last_layer_computes_masked_rows_only(sp, kind):
+    """spiffy_verify_layer_last: behind the attention only the rows of masked positions are computed.  Those rows equal
+    spiffy_verify_layer's bit for bit (a row's arithmetic does not depend on the rows around it) and the oracle's
+    within the layer tolerance; rows of unmasked positions are not written; a state with nothing masked, a fully
+    masked state and a ragged row count are in the batch."""
+    if kind == "mfma":
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=512, Hq=4, Hkv=4, hd=128, F=768, P=300, B=32, G=9, V=1280)
+    elif kind == "mfma_gqa_small_blocks":
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=256, Hq=2, Hkv=1, hd=128, F=320, P=2100, B=4, G=70, V=1280)
+    elif kind == "generic_f32":
+        cfg = synth.CONFIGS["c1"].scaled(G=5)
+    else:
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", d=96, Hq=6, Hkv=2, hd=16, F=72, P=37, B=7, G=4)
+    st = synth.random_states(cfg.G, cfg.B, cfg.V, 0.2, 0.8, 21)
+    st[1, :] = 3                     # nothing masked
+    st[2, :] = cfg.mask_id           # everything masked
+    w = synth.layer_weights(cfg, 0, bias=True)
+    pk, pv = synth.prefix_kv(cfg, 0)
+    x = synth.hidden_states(cfg)
+    full = run_layer(sp, cfg, w, pk, pv, x)
+    scfg = sp.cfg_from_synth(cfg)
+    ws = sp.alloc_workspace(scfg, cfg.G, cfg.B, cfg.P, DEV)
+    out = torch.full_like(x, 777.0).to(DEV)
+    sp.verify_layer_last(scfg, sp.layer_weights(dev_weights(w)), sp.prefix_kv(pk.to(DEV), pv.to(DEV)), x.to(DEV),
+                         torch.from_numpy(st).to(DEV), cfg.P, ws, out)
+    torch.cuda.synchronize()
+    out = out.cpu()
+    m = torch.from_numpy(st == cfg.mask_id)
+    assert torch.equal(out[m], full[m])
+    assert (out[~m] == 777.0).all()
+    # an explicit mask selects the rows instead of the tokens
+    mask = torch.zeros((cfg.G, cfg.B), dtype=torch.uint8)
+    mask[0, 0] = mask[cfg.G - 1, cfg.B - 1] = 1
+    out2 = torch.full_like(x, 777.0).to(DEV)
+    sp.verify_layer_last(scfg, sp.layer_weights(dev_weights(w)), sp.prefix_kv(pk.to(DEV), pv.to(DEV)), x.to(DEV),
+                         torch.from_numpy(st).to(DEV), cfg.P, ws, out2, mask=mask.to(DEV))
+    torch.cuda.synchronize()
+    out2 = out2.cpu()
+    assert torch.equal(out2[mask.bool()], full[mask.bool()]) and (out2[~mask.bool()] == 777.0).all()
+    g = 2
+    ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), to_np(x[g:g + 1]), **oracle_kw(cfg))
+    e_max, _ = rel_err(to_np(out[g:g + 1]), ref)
+    assert e_max < tol(cfg), e_max
+
+
+@pytest.mark.parametrize("kind", ["mfma", "fp32"])
+def test_step_without_hidden_output_decides_the_same(sp, kind):
+    """spiffy_verify_step with hidden_out = NULL runs its last layer on the masked rows only: every decision, the
+    confidences and the walk are those of the call that returns the hidden states, bit for bit."""
+    if kind == "mfma":
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=1280, P=100, B=32, G=32)
+        key, scale = "c3", 30.0
+    else:
+        cfg, key, scale = synth.CONFIGS["c1"], "c1", 40.0
+    plan, layers, prefix, hw, w_embed, states, edges = build_step(sp, cfg, key, 5, scale)
+    d_states, d_edges = torch.from_numpy(states).to(DEV), torch.from_numpy(edges).to(DEV)
+    ref = {k: v.clone() for k, v in plan.run(d_states, d_edges).items()}
+    torch.cuda.synchronize()
+    for v in plan.out.values():
+        v.fill_(0)
+    plan.keep_hidden = False
+    out = plan.run(d_states, d_edges)
+    torch.cuda.synchronize()
+    for k in ("argmax", "conf", "unmask", "margin", "target_states", "result", "accepted_state"):
+        assert torch.equal(out[k], ref[k]), k
+    assert (out["hidden"] == 0).all()          # not written
+    assert int((states == cfg.mask_id).sum()) > 0
+
+
 def test_step_two_layers_at_config3_size(sp):
     """The chained whole-step path at configuration 3's full row count, prefix length and widths (two layers to
     keep the oracle in seconds): hidden states of sampled states, and the walk on the step's own next states."""

@@ -404,10 +404,11 @@ def decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev, n_blocks=8):
             cv.append(vv)
         return ck, cv
 
-    def run(graph, d_star):
+    def run(graph, d_star, replay=False):
         ck, cv = caches()
         dec = decode.BlockDecoder(sp.cfg_from_synth(cfg), layers, ck, cv, cfg.P, w_embed, hw["final_norm"], hw["w_vocab"],
-                                  cfg.B, cfg.threshold, logit_scale=LOGIT_SCALE, graph=graph, d_star=d_star, device=dev)
+                                  cfg.B, cfg.threshold, logit_scale=LOGIT_SCALE, graph=graph, d_star=d_star, device=dev,
+                                  graph_replay=replay)
         block0 = torch.full((cfg.B,), cfg.mask_id, dtype=torch.int32, device=dev)
         dec.decode_block(block0, max_steps=2)                   # warm-up (nothing is committed)
         torch.cuda.synchronize()
@@ -420,6 +421,7 @@ def decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev, n_blocks=8):
     graph = decode.DraftGraph([[(i, 1) for i in range(1, (n % cfg.B) + 2)] for n in range(D)], device=dev)
     g, ms, dec = run(graph, D)
     v, v_ms, _ = run(None, 0)
+    vr, vr_ms, vr_dec = run(None, 0, replay=True)      # the same vanilla generation, passes replayed from HIP graphs
     nfe, v_nfe = sum(g["nfe"]), sum(v["nfe"])
     states = sum(sum(x) for x in g["n_states"])
     block = torch.randint(0, cfg.V - 1, (cfg.B,), dtype=torch.int32, device=dev)
@@ -461,6 +463,9 @@ def decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev, n_blocks=8):
             "vanilla": {"forward_passes": v_nfe, "ms": v_ms, "ms_per_forward_pass": v_ms / max(1, v_nfe),
                         "tokens_per_s": tokens / (v_ms * 1e-3)},
             "same_tokens_as_vanilla": bool((g["tokens"] == v["tokens"]).all()),
+            "vanilla_passes_from_hip_graphs": {"forward_passes": sum(vr["nfe"]), "graph_launches": vr_dec.graph_launches,
+                                               "ms": vr_ms, "tokens_per_s": tokens / (vr_ms * 1e-3),
+                                               "same_tokens_as_eager": bool((vr["tokens"] == v["tokens"]).all())},
             "commit_block_ms": e0.elapsed_time(e1) / 3,
             "block_start_ms": {"commit_then_first_pass": sep_ms, "one_fused_pass": fused_ms},
             "note": "each time includes the commits (folded into the next block's first pass, the last one a pass of its own), top-K, drafting, pruning and the host reads of the accept result; "

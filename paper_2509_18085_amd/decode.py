@@ -55,14 +55,22 @@ class BlockDecoder:
     (one forward pass less per block; saved_passes counts them).  The two ways compute the same function with
     different rounding (suffix rows read the block's keys from the cache and split their keys differently), so
     in bf16 a near-tie can fall the other way: off by default.
+    graph_replay (cached-prefix models): every pass after a block's first is one HIP-graph launch: verify, top-K,
+    drafting, pruning and the next pass's inputs are recorded once per block (the prefix length is a kernel
+    argument) at the fixed shape of 1 + d_star states and replayed; the host only reads 4 + B + 2 integers per
+    pass.  Same tokens, forward passes and accepted depths as the eager loop.
     """
 
     def __init__(self, cfg: sp.ModelCfg, layers: Sequence[Dict[str, torch.Tensor]], cache_k: Sequence[torch.Tensor],
                  cache_v: Sequence[torch.Tensor], P0: int, w_embed: torch.Tensor, final_norm: torch.Tensor,
                  w_vocab: torch.Tensor, B: int, threshold: float, logit_scale: float = 1.0, force_one: bool = True,
                  graph: Optional[DraftGraph] = None, d_star: int = 0, device="cuda", S0: int = 0, seq_S0: int = 0,
-                 reuse_commit_pass: bool = False):
+                 reuse_commit_pass: bool = False, graph_replay: bool = False):
         self.cfg, self.B, self.graph, self.device = cfg, B, graph, device
+        self.graph_replay = bool(graph_replay) and not seq_S0
+        self._pass_graph = None       # (prefix length it was recorded for, HIP graph) of the fixed-shape pass
+        self._g_dirty = True          # the static inputs of the fixed-shape pass do not hold the current states yet
+        self.graph_launches = 0
         self.d_star = d_star if graph is not None else 0
         self.logit_scale = logit_scale
         self.P, self.S = P0, S0
@@ -87,6 +95,55 @@ class BlockDecoder:
                                     device=device, keep_hidden=False)     # the loop reads decisions only: the last layer runs on masked rows
             # the workspace must also fit the longest prefix the cache can hold
             self.plan.workspace = sp.alloc_workspace(cfg, 1 + self.d_star, B, self.capacity, device)
+            if self.graph_replay:
+                self._init_fixed_pass()
+
+    # ---- a forward pass of fixed shape, recorded once per block into a HIP graph and replayed for every further pass ----
+    def _init_fixed_pass(self) -> None:
+        """Static buffers of the fixed-shape pass: always 1 + d_star states and the whole edge list.  States that the
+        pruning did not keep are copies of the current block and edges that did not survive are (0, 0): neither can be
+        reached by the walk, and a state's rows do not depend on the states verified with it, so every result equals
+        that of the variable-shape pass."""
+        dev, G, B = self.device, 1 + self.d_star, self.B
+        E = int(self.graph.edges.shape[0]) if (self.graph is not None and self.graph.edges is not None) else 0
+        self._g_states = torch.full((G, B), self.cfg.mask_id, dtype=torch.int32, device=dev)
+        self._g_edges = torch.zeros((max(E, 1), 2), dtype=torch.int32, device=dev)
+        self._g_pack = torch.zeros(4 + B + 2, dtype=torch.int32, device=dev)      # accept result, accepted block, pruned sizes
+        self._g_rows = torch.arange(G, device=dev).reshape(G, 1)
+        self._g_erows = torch.arange(max(E, 1), device=dev).reshape(-1, 1)
+        self._fixed_pass()            # once outside any capture: one-time kernel attributes of every tile shape it uses
+        torch.cuda.synchronize()
+        self._g_states.fill_(self.cfg.mask_id)
+        self._g_edges.zero_()
+
+    def _fixed_pass(self) -> None:
+        """verify -> top-K of the accepted node -> drafting and pruning -> the next pass's inputs, all on the device."""
+        drafting = self.graph is not None and self.d_star > 0
+        E = int(self.graph.edges.shape[0]) if (drafting and self.graph.edges is not None) else 0
+        out = self.plan.run(self._g_states, self._g_edges if E else None)
+        new_state = out["accepted_state"]
+        if drafting:
+            tok, prob = sp.head_topk(self.cfg, self.plan.w_vocab, self._g_states, self.graph.K, self.logit_scale,
+                                     self.plan.workspace, result=out["result"], after_step=True)
+            dp = sp.draft_prune(new_state, self.cfg.mask_id, tok, prob, self.graph.offsets, self.graph.pairs,
+                                self.graph.edges, self.d_star)
+            counts = dp["counts"]
+            self._g_states.copy_(torch.where(self._g_rows < counts[0], dp["states"], new_state.reshape(1, self.B)))
+            if E:
+                self._g_edges.copy_(torch.where(self._g_erows < counts[1], dp["edges"], torch.zeros_like(dp["edges"])))
+            self._g_pack.copy_(torch.cat([out["result"], new_state, counts]))
+        else:
+            self._g_states.copy_(new_state.reshape(1, self.B))
+            self._g_pack[:4 + self.B].copy_(torch.cat([out["result"], new_state]))
+
+    def _replay_pass(self) -> None:
+        if self._pass_graph is None or self._pass_graph[0] != (self.P, self.S):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                self._fixed_pass()
+            self._pass_graph = ((self.P, self.S), g)
+        self._pass_graph[1].replay()
+        self.graph_launches += 1
 
     def _step(self, states, edges):
         if isinstance(self.plan, sp.SeqStepPlan):
@@ -158,10 +215,33 @@ class BlockDecoder:
                 self.saved_passes += 1
                 finish_pass(self._zero_result, dh["target_states"][0].clone(), False)
         while nfe < max_steps and (cur == mask_id).any():
+            if self.graph_replay and nfe > 0 and self._pending is None:
+                # every pass after the block's first: the fixed-shape pass, replayed from the graph recorded for this
+                # block's prefix length; the host reads the same 4 + B + 2 integers
+                if nfe == 1 or self._g_dirty:
+                    G_cap = self._g_states.shape[0]
+                    self._g_states.copy_(cur_dev.reshape(1, self.B).expand(G_cap, self.B))
+                    self._g_states[:states.shape[0]].copy_(states)
+                    self._g_edges.zero_()
+                    if edges is not None:
+                        self._g_edges[:edges.shape[0]].copy_(edges)
+                    self._g_dirty = False
+                n_states.append(int(states.shape[0]))
+                self._replay_pass()
+                nfe += 1
+                host = self._g_pack.cpu().numpy()
+                depths.append(int(host[1]))
+                cur = host[4:4 + self.B].copy()
+                traj.append(cur.copy())
+                n_kept = int(host[4 + self.B]) if drafting else 1
+                states = self._g_states[:max(1, n_kept)]            # what the next pass verifies (the rest is padding)
+                continue
             out = self._step(states.contiguous(), edges)
             nfe += 1
             n_states.append(int(states.shape[0]))
-            finish_pass(out["result"], out["accepted_state"].clone(), True)
+            cur_dev = out["accepted_state"].clone()
+            finish_pass(out["result"], cur_dev, True)
+            self._g_dirty = True
         return dict(final=states[0].clone(), nfe=nfe, depths=depths, n_states=n_states, trajectory=traj)
 
     def commit(self, block: torch.Tensor, defer: bool = False) -> None:

@@ -990,7 +990,7 @@ def _oracle_commit(m, kw, block, P):
     return new_prefix
 
 
-def _decoder_setup(sp, cfg, seed, n_blocks, threshold, scale, graph, d_star):
+def _decoder_setup(sp, cfg, seed, n_blocks, threshold, scale, graph, d_star, graph_replay=False):
     from paper_2509_18085_amd import decode
     layers = [synth.layer_weights(cfg, l, seed) for l in range(cfg.L)]
     prefix = [synth.prefix_kv(cfg, l, seed) for l in range(cfg.L)]
@@ -1007,7 +1007,7 @@ def _decoder_setup(sp, cfg, seed, n_blocks, threshold, scale, graph, d_star):
         cv.append(vv)
     dec = decode.BlockDecoder(sp.cfg_from_synth(cfg), [dev_weights(w) for w in layers], ck, cv, cfg.P, we.to(DEV),
                               hw["final_norm"].to(DEV), hw["w_vocab"].to(DEV), cfg.B, threshold, logit_scale=scale,
-                              graph=graph, d_star=d_star, device=DEV)
+                              graph=graph, d_star=d_star, device=DEV, graph_replay=graph_replay)
     m = dict(layers=[np_weights(w) for w in layers], prefix=[(to_np(k), to_np(v)) for k, v in prefix],
              w_embed=to_np(we), final_norm=to_np(hw["final_norm"]), w_vocab=to_np(hw["w_vocab"]))
     kw = dict(n_q_heads=cfg.Hq, n_kv_heads=cfg.Hkv, head_dim=cfg.hd, pos0=cfg.P, mask_id=cfg.mask_id,
@@ -1091,6 +1091,31 @@ def test_decode_is_lossless_on_the_mfma_path(sp):
     assert not (got["tokens"] == cfg.mask_id).any()
     assert sum(got["nfe"]) < sum(van["nfe"])
     assert sum(sum(d) for d in got["depths"]) >= sum(van["nfe"]) - sum(got["nfe"])
+
+
+@pytest.mark.parametrize("key", ["c1", "bf16_mfma"])
+@pytest.mark.parametrize("drafting", [True, False])
+def test_decode_passes_replayed_from_a_graph_equal_the_eager_loop(sp, key, drafting):
+    """graph_replay: every pass after a block's first is one launch of a HIP graph recorded for that block (verify,
+    top-K, drafting, pruning and the next pass's inputs at the fixed shape of 1 + d_star states).  Tokens, forward
+    passes, accepted depths and the number of states the pruning kept equal the eager loop's, with and without
+    drafts, over three blocks (a new recording per block: the prefix grows)."""
+    from paper_2509_18085_amd import decode
+    if key == "c1":
+        cfg, tau, scale = synth.CONFIGS["c1"].scaled(G=1), 0.6, 40.0
+    else:
+        cfg = synth.CONFIGS["c1"].scaled(dtype="bf16", L=2, d=256, Hq=2, Hkv=2, hd=128, F=320, V=1280, P=100, B=32, G=1)
+        tau, scale = 0.7, 16.0
+    n_max = min(cfg.B, 8)
+    formulas = [[(i, 1) for i in range(1, n + 1)] for n in range(1, n_max + 1)] + [[(1, 2)], [(1, 1), (2, 2)]]
+    mk = lambda replay: _decoder_setup(sp, cfg, 11, 3, tau, scale, decode.DraftGraph(formulas, device=DEV) if drafting else None,
+                                       5 if drafting else 0, graph_replay=replay)[0]
+    eager, replay = mk(False), mk(True)
+    a, b = eager.generate(3), replay.generate(3)
+    np.testing.assert_array_equal(a["tokens"], b["tokens"])
+    assert a["nfe"] == b["nfe"] and a["depths"] == b["depths"] and a["n_states"] == b["n_states"]
+    assert replay.graph_launches == sum(n - 1 for n in b["nfe"]) and replay.graph_launches > 0
+    assert not (b["tokens"] == cfg.mask_id).any()
 
 
 # ------------------------------------------------------------------ dual cache: fixed K/V of the tokens after the block

@@ -314,16 +314,6 @@ int spiffy_verify_step_commit(const spiffy_model_cfg *cfg, int32_t n_layers, con
                               int32_t *target_states, spiffy_accept_result *result, int32_t *accepted_state,
                               void *workspace, size_t workspace_bytes, void *stream);
 
-/* Measured peaks of the machine, for the roofline figures of the benchmark (not part of the paper's method).
- * spiffy_probe_mfma: every SIMD of the chip runs iters x 4 dense bf16 matrix instructions (32x32x16, fp32
- * accumulation) on operands held in registers, all zero or (random_operands != 0) pseudo-random in (-1, 1); no
- * memory traffic.  *flop (host) receives the floating-point operations of the launch; sink is device memory
- * for at least 1024 floats (overwritten).  1 <= iters <= 2^24.
- * spiffy_probe_hbm_read: one read-only pass over bytes of device memory at src (16-byte aligned); sink is device
- * memory for one uint32.  Time either call with events on the stream. */
-int spiffy_probe_mfma(int32_t iters, int32_t random_operands, float *sink, double *flop, void *stream);
-int spiffy_probe_hbm_read(const void *src, size_t bytes, uint32_t *sink, void *stream);
-
 /* Offline calibration, part 3 (Alg. 2; App. D.1): the optimal subgraph of the candidate graph.  The graph has
  * N <= 64 nodes (draft formulas q_kv); count [N] is each node's frequency, level [N] its 1-based level k, edges
  * [E,2] rows (p, q): p is a parent of q (rows with an end outside 0..N-1 are ignored).  A node is connected to a

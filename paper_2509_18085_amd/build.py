@@ -14,7 +14,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libspiffy.so")
-SOURCES = ["api.hip", "generic_kernels.hip", "graph_accept.hip", "draft_prune.hip", "head_topk.hip", "subgraph_search.hip", "mfma_gemm.hip", "mfma_attn.hip", "probe.hip"]
+SOURCES = ["api.hip", "generic_kernels.hip", "graph_accept.hip", "draft_prune.hip", "head_topk.hip", "subgraph_search.hip", "mfma_gemm.hip", "mfma_attn.hip"]
+PROBE_LIB = os.path.join(HERE, "libspiffy_probe.so")     # bench-only: measured peaks of the machine (csrc/probe.hip)
 # -ffp-contract=on: a multiply and an add are fused only where the source writes them in one expression, so the
 # rounding of a kernel does not depend on how the optimiser inlined or ordered it (different instantiations of one
 # kernel body have to agree bit for bit)
@@ -48,6 +49,7 @@ def build(verbose: bool = False) -> str:
     with ThreadPoolExecutor(max_workers=min(8, len(SOURCES))) as ex:
         outs = list(ex.map(one, range(len(SOURCES))))
     outs.append(_run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB] + objs))
+    outs.append(_run([hipcc] + FLAGS + ["-shared", "-o", PROBE_LIB, os.path.join(CSRC, "probe.hip")]))
     if verbose:
         print("\n".join(o for o in outs if o.strip()))
     return LIB

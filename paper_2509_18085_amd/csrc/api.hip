@@ -845,18 +845,6 @@ int spiffy_commit_block(const spiffy_model_cfg* cfg, int32_t n_layers, const spi
   return SPIFFY_OK;
 }
 
-int spiffy_probe_mfma(int32_t iters, int32_t random_operands, float* sink, double* flop, void* stream) {
-  if (iters < 1 || iters > (1 << 24) || !sink || !flop) return SPIFFY_EINVAL;
-  *flop = probe_mfma_flop(iters);
-  return dev(launch_probe_mfma(iters, random_operands ? 1 : 0, sink, (hipStream_t)stream));
-}
-
-int spiffy_probe_hbm_read(const void* src, size_t bytes, uint32_t* sink, void* stream) {
-  if (!src || !sink || bytes < 16) return SPIFFY_EINVAL;
-  if (!aligned16(src)) return SPIFFY_EALIGN;
-  return dev(launch_probe_hbm_read(src, bytes, sink, (hipStream_t)stream));
-}
-
 size_t spiffy_subgraph_search_workspace_bytes(void) { return subgraph_search_workspace_bytes(); }
 
 int spiffy_subgraph_search(const int64_t* count, const int32_t* level, int32_t N, const int32_t* edges, int32_t E,

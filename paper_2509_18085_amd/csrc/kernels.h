@@ -103,11 +103,6 @@ struct DraftPruneArgs {
 };
 hipError_t launch_draft_prune(const DraftPruneArgs& a, hipStream_t st);
 
-// machine probes for the roofline figures (probe.hip)
-double probe_mfma_flop(int iters);
-hipError_t launch_probe_mfma(int iters, int random_operands, float* sink, hipStream_t st);
-hipError_t launch_probe_hbm_read(const void* src, size_t bytes, unsigned* sink, hipStream_t st);
-
 hipError_t launch_graph_accept(const int32_t* edges, int E, const int32_t* draft, const int32_t* target,
                                int G, int B, int root, spiffy_accept_result* res, int32_t* state,
                                hipStream_t st);

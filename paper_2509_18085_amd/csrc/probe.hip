@@ -1,6 +1,8 @@
-// Measured peaks of the machine the library runs on, for the roofline figures (not part of the verification path):
+// Measured peaks of the machine, for the roofline figures of the benchmark (not part of the verification path, and not
+// part of libspiffy.so: this file is a library of its own, libspiffy_probe.so, that only bench.py and one test load):
 // a register-only loop of v_mfma_f32_32x32x16_bf16 on every SIMD, and a read-only stream over a device buffer.
-#include "kernels.h"
+#include "common.h"
+#include "../../include/spiffy_probe.h"
 
 namespace spiffy {
 
@@ -62,18 +64,28 @@ __global__ __launch_bounds__(256) void probe_hbm_read_kernel(const uint4* __rest
   if (x == 0x9e3779b9u) sink[0] = x;       // keeps the loads alive; practically never true
 }
 
-}  // namespace
-
 double probe_mfma_flop(int iters) { return (double)kProbeWgs * 4.0 * (double)iters * kChains * 2.0 * 32 * 32 * 16; }
 
-hipError_t launch_probe_mfma(int iters, int random_operands, float* sink, hipStream_t st) {
-  probe_mfma_kernel<<<kProbeWgs, 256, 0, st>>>(iters, random_operands, sink);
-  return hipGetLastError();
-}
-
-hipError_t launch_probe_hbm_read(const void* src, size_t bytes, unsigned* sink, hipStream_t st) {
-  probe_hbm_read_kernel<<<2048, 256, 0, st>>>(reinterpret_cast<const uint4*>(src), bytes / 16, sink);
-  return hipGetLastError();
-}
+}  // namespace
 
 }  // namespace spiffy
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+int spiffy_probe_mfma(int32_t iters, int32_t random_operands, float* sink, double* flop, void* stream) {
+  if (iters < 1 || iters > (1 << 24) || !sink || !flop) return SPIFFY_EINVAL;
+  *flop = spiffy::probe_mfma_flop(iters);
+  spiffy::probe_mfma_kernel<<<spiffy::kProbeWgs, 256, 0, (hipStream_t)stream>>>(iters, random_operands ? 1 : 0, sink);
+  return hipGetLastError() == hipSuccess ? SPIFFY_OK : SPIFFY_EDEVICE;
+}
+
+int spiffy_probe_hbm_read(const void* src, size_t bytes, uint32_t* sink, void* stream) {
+  if (!src || !sink || bytes < 16) return SPIFFY_EINVAL;
+  if (reinterpret_cast<uintptr_t>(src) & 15u) return SPIFFY_EALIGN;
+  spiffy::probe_hbm_read_kernel<<<2048, 256, 0, (hipStream_t)stream>>>(reinterpret_cast<const uint4*>(src), bytes / 16, sink);
+  return hipGetLastError() == hipSuccess ? SPIFFY_OK : SPIFFY_EDEVICE;
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -27,7 +27,7 @@ EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "s
            "spiffy_verify_layer", "spiffy_verify_layer_last", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk", "spiffy_commit_block",
            "spiffy_subgraph_search_workspace_bytes", "spiffy_subgraph_search", "spiffy_verify_step",
            "spiffy_workspace_bytes_seq", "spiffy_verify_step_seq", "spiffy_workspace_bytes_commit",
-           "spiffy_verify_step_commit", "spiffy_probe_mfma", "spiffy_probe_hbm_read", "spiffy_decode_head_static"]
+           "spiffy_verify_step_commit", "spiffy_decode_head_static"]
 GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
 
@@ -111,10 +111,6 @@ def _load() -> C.CDLL:
     lib.spiffy_verify_step_commit.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp, vp,
                                               i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
                                               vp, vp, sz, vp]
-    lib.spiffy_probe_mfma.restype = C.c_int
-    lib.spiffy_probe_mfma.argtypes = [i32, i32, vp, C.POINTER(C.c_double), vp]
-    lib.spiffy_probe_hbm_read.restype = C.c_int
-    lib.spiffy_probe_hbm_read.argtypes = [vp, sz, vp, vp]
     lib.spiffy_verify_step.restype = C.c_int
     lib.spiffy_verify_step.argtypes = [cfgp, i32, C.POINTER(LayerWeights), C.POINTER(PrefixKV), vp, vp, vp, vp,
                                        i32, i32, i32, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp, vp,
@@ -365,21 +361,6 @@ def subgraph_search(count: torch.Tensor, level: torch.Tensor, edges: Optional[to
                                       _stream(stream)), "spiffy_subgraph_search")
     out["_workspace"] = workspace
     return out
-
-
-def probe_mfma(iters: int, random_operands: bool, sink: torch.Tensor, stream=None) -> float:
-    """Launch the register-only MFMA loop; returns the flop of the launch (time it with events)."""
-    flop = C.c_double(0.0)
-    _check(lib.spiffy_probe_mfma(iters, 1 if random_operands else 0, _ptr(sink), C.byref(flop), _stream(stream)),
-           "spiffy_probe_mfma")
-    return flop.value
-
-
-def probe_hbm_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> int:
-    """Launch one read-only pass over src; returns the bytes read."""
-    n = src.numel() * src.element_size()
-    _check(lib.spiffy_probe_hbm_read(_ptr(src), n, _ptr(sink), _stream(stream)), "spiffy_probe_hbm_read")
-    return n
 
 
 class StepPlan:

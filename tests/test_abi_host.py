@@ -340,15 +340,22 @@ def test_verify_step_commit_argument_errors():
     assert sp.lib.spiffy_workspace_bytes_commit(C.byref(cfg), 512, 32, 64) == 0
 
 
-def test_probe_argument_errors():
-    flop = C.c_double(0.0)
-    assert sp.lib.spiffy_probe_mfma(0, 0, DUMMY, C.byref(flop), None) == sp.SPIFFY_EINVAL
-    assert sp.lib.spiffy_probe_mfma(1 << 25, 0, DUMMY, C.byref(flop), None) == sp.SPIFFY_EINVAL
-    assert sp.lib.spiffy_probe_mfma(10, 0, None, C.byref(flop), None) == sp.SPIFFY_EINVAL
-    assert sp.lib.spiffy_probe_mfma(10, 0, DUMMY, None, None) == sp.SPIFFY_EINVAL
-    assert sp.lib.spiffy_probe_hbm_read(None, 1024, DUMMY, None) == sp.SPIFFY_EINVAL
-    assert sp.lib.spiffy_probe_hbm_read(DUMMY, 8, DUMMY, None) == sp.SPIFFY_EINVAL
-    assert sp.lib.spiffy_probe_hbm_read(DUMMY + 8, 1024, DUMMY, None) == sp.SPIFFY_EALIGN
+def test_probe_library_is_separate_and_checks_its_arguments():
+    """The machine probes live in libspiffy_probe.so: the verification library does not export them."""
+    from paper_2509_18085_amd import probe
+    with pytest.raises(AttributeError):
+        sp.lib.spiffy_probe_mfma
+    flop = C.c_double(0)
+    assert probe.lib.spiffy_probe_mfma(0, 0, DUMMY, C.byref(flop), None) == sp.SPIFFY_EINVAL
+    assert probe.lib.spiffy_probe_mfma(1 << 25, 0, DUMMY, C.byref(flop), None) == sp.SPIFFY_EINVAL
+    assert probe.lib.spiffy_probe_mfma(10, 0, None, C.byref(flop), None) == sp.SPIFFY_EINVAL
+    assert probe.lib.spiffy_probe_mfma(10, 0, DUMMY, None, None) == sp.SPIFFY_EINVAL
+    assert probe.lib.spiffy_probe_hbm_read(None, 1024, DUMMY, None) == sp.SPIFFY_EINVAL
+    assert probe.lib.spiffy_probe_hbm_read(DUMMY, 8, DUMMY, None) == sp.SPIFFY_EINVAL
+    assert probe.lib.spiffy_probe_hbm_read(DUMMY + 8, 1024, DUMMY, None) == sp.SPIFFY_EALIGN
+    hdr = open(os.path.join(ROOT, "include", "spiffy_probe.h")).read()
+    assert set(re.findall(r"\b(spiffy_probe_[a-z_]+)\s*\(", hdr)) == {"spiffy_probe_mfma", "spiffy_probe_hbm_read"}
+
 
 
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):

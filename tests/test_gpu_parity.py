@@ -1729,15 +1729,16 @@ def test_decode_full_sequence_is_lossless_on_the_mfma_path(sp):
 def test_machine_probes_run(sp):
     """The roofline probes launch, finish, and report the work they did (their rates are bench.py's business)."""
     sink = torch.full((1024,), -1.0, dtype=torch.float32, device=DEV)
-    flop = sp.probe_mfma(100, False, sink)
+    from paper_2509_18085_amd import probe
+    flop = probe.probe_mfma(100, False, sink)
     torch.cuda.synchronize()
     assert flop == 1024 * 4 * 100 * 4 * 2.0 * 32 * 32 * 16
     assert (sink == 0).all()                                   # zero operands: every accumulator stays zero
-    sp.probe_mfma(100, True, sink)
+    probe.probe_mfma(100, True, sink)
     torch.cuda.synchronize()
     assert torch.isfinite(sink).all() and (sink != 0).any()
     src = torch.ones(3 * (1 << 20) + 48, dtype=torch.uint8, device=DEV)
-    assert sp.probe_hbm_read(src, torch.zeros(1, dtype=torch.int32, device=DEV)) == src.numel()
+    assert probe.probe_hbm_read(src, torch.zeros(1, dtype=torch.int32, device=DEV)) == src.numel()
     torch.cuda.synchronize()
 
 

@@ -140,11 +140,12 @@ def roofline_of(cfg, k_ms, n_launch, traffic):
     return r
 
 
-def other_config_leg(sp, synth, key, dev, seed, steps, warmup, kernel_iters):
+def other_config_leg(sp, synth, key, dev, seed, steps, warmup, kernel_iters, n_states=0):
     """One of the other workload configurations on the same build: the whole step and its dominant kernel, measured
-    the same way as the headline; everything is freed before the next one."""
+    the same way as the headline; everything is freed before the next one.  n_states: only the first states of the
+    workload's draft graph (the paper's own operating point is one true block and three drafts)."""
     import torch
-    w = build_workload(sp, synth, key, dev, seed)
+    w = build_workload(sp, synth, key, dev, seed, n_states)
     cfg = w["cfg"]
     ms, per = time_steps(sp, w, steps, warmup)
     k_ms, n_launch = time_dominant_kernel(sp, w, dev, kernel_iters)
@@ -156,7 +157,7 @@ def other_config_leg(sp, synth, key, dev, seed, steps, warmup, kernel_iters):
            "step_frac_of_bf16_peak": flop / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
            "step_frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
            "step_bound": "hbm" if nbytes / (PEAK_HBM_GBS * 1e9) > flop / (PEAK_BF16_TFLOPS * 1e12) else "mfma",
-           "roofline": roofline_of(cfg, k_ms, n_launch, stored_traffic(key)),
+           "roofline": roofline_of(cfg, k_ms, n_launch, None if n_states else stored_traffic(key)),
            "planted_walk": walk_outcome(w)}
     del w
     torch.cuda.empty_cache()
@@ -292,6 +293,8 @@ def main():
         for key in ("c2", "c4", "c5"):
             if key != args.config:
                 line["other_configs"][key] = other_config_leg(sp, synth, key, dev, seed, 10, 2, 2)
+        # the paper's own operating point (D* = 3: the true block and three drafts) at the headline model shape
+        line["other_configs"]["c3_four_states"] = other_config_leg(sp, synth, "c3", dev, seed, 10, 2, 2, n_states=4)
     print(json.dumps(line))
 
 

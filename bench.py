@@ -621,13 +621,13 @@ def full_sequence_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, d
 def stored_traffic(config):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary
     (counters cannot be collected from inside this process); None if there is none for the workload."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s_gemm_kernels.txt" % config)
-    try:
-        for ln in open(path):
-            if ln.startswith("traffic_bytes_per_launch_swiglu_gemm:"):
-                return float(ln.split(":")[1])
-    except OSError:
-        pass
+    for name in ("hbm_traffic_%s_gemm_kernels.txt" % config, "hbm_traffic_%s_kernels.txt" % config):
+        try:
+            for ln in open(os.path.join(ROOT, "profiles", name)):
+                if ln.startswith("traffic_bytes_per_launch_swiglu_gemm:"):
+                    return float(ln.split(":")[1])
+        except OSError:
+            pass
     return None
 
 

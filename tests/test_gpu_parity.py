@@ -305,6 +305,25 @@ def test_last_layer_computes_masked_rows_only(sp, kind):
     assert e_max < tol(cfg), e_max
 
 
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_last_layer_with_nothing_masked_writes_nothing(sp, dtype):
+    """Degenerate case: no masked position in the whole batch: the row count on the device is zero, every launch behind the
+    attention finds nothing to do and hidden_out keeps what it held."""
+    cfg = (synth.CONFIGS["c1"].scaled(dtype="bf16", d=256, Hq=2, Hkv=2, hd=128, F=320, P=70, B=32, G=3, V=1280)
+           if dtype == "bf16" else synth.CONFIGS["c1"].scaled(G=3))
+    st = np.full((cfg.G, cfg.B), 5, np.int32)
+    w = synth.layer_weights(cfg, 0)
+    pk, pv = synth.prefix_kv(cfg, 0)
+    x = synth.hidden_states(cfg)
+    scfg = sp.cfg_from_synth(cfg)
+    ws = sp.alloc_workspace(scfg, cfg.G, cfg.B, cfg.P, DEV)
+    out = torch.full_like(x, 777.0).to(DEV)
+    sp.verify_layer_last(scfg, sp.layer_weights(dev_weights(w)), sp.prefix_kv(pk.to(DEV), pv.to(DEV)), x.to(DEV),
+                         torch.from_numpy(st).to(DEV), cfg.P, ws, out)
+    torch.cuda.synchronize()
+    assert (out == 777.0).all()
+
+
 @pytest.mark.parametrize("kind", ["mfma", "fp32"])
 def test_step_without_hidden_output_decides_the_same(sp, kind):
     """spiffy_verify_step with hidden_out = NULL runs its last layer on the masked rows only: every decision, the

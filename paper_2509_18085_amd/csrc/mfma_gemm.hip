@@ -562,7 +562,8 @@ int mfma_lmhead_partials_per_row(int V) { return cdiv(V, BM) * 2; }
 // (one or a few states) the projections are weight-streaming problems: 64- and 128-row tiles spend a quarter
 // or half of the matrix work of a 256-row tile on them and cover more CUs.
 struct TileShape { int bm, bn; };
-static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow192, bool allow32 = false, bool allow96 = false) {
+static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow192, bool allow32 = false, bool allow96 = false,
+                             bool allow96_two_rows = false) {
   const int heights[4] = {256, 128, 64, 32};
   const int widths[5] = {192, 128, 96, 64, 32};
   const float eff[5] = {1.0f, 0.85f, 0.6f, 0.55f, 0.4f};
@@ -574,7 +575,9 @@ static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow
       const int cols = bn / unit;                 // output columns (or SwiGLU features) per tile
       if ((bn == 192 && (!allow192 || bm <= 64)) || (bn == 64 && bm == 128) || n_cols % cols != 0) continue;
       // 96-wide tiles: one row of tiles over few rows (weight streaming), where they turn 192 workgroups into 256
-      if (bn == 96 && !(allow96 && (bm == 64 || bm == 128) && M <= bm)) continue;
+      // (the QKV projection also takes them over two rows of 128-row tiles: 256 workgroups at 256 rows where 128 columns
+      // give 192; 41.4 against 43.3 us in interleaved runs)
+      if (bn == 96 && !((allow96 && (bm == 64 || bm == 128) && M <= bm) || (allow96_two_rows && bm == 128 && M <= 2 * bm))) continue;
       // 32-wide tiles (one or two wavefronts per workgroup) exist for the split-K projections of one or two states
       if ((bn == 32 || bm == 32) && !(allow32 && bn == 32 && bm <= 64)) continue;
       const int tiles = cdiv(M, bm) * (n_cols / cols) * ksplit;
@@ -592,15 +595,17 @@ static hipError_t launch_shape(const GemmArgs& a, TileShape t, int unit, hipStre
   constexpr bool W192 = EPI != EPI_PARTIAL;       // the split-K projections never take the 192-wide tile
   if (t.bm == 256) {
     if constexpr (W192) if (t.bn == 192) return launch_t<EPI, 192, 3>(a, mt, nt, st);
-    // 256 x 128: room for a third activation stage beside four weight stages (160 KB); measured 2-4% faster than two on
-    // the gate/up and QKV shapes that cannot take 192 columns, no gain on the split-K projections
-    if constexpr (EPI == EPI_SWIGLU || EPI == EPI_STORE) if (t.bn == 128) return launch_t<EPI, 128, 4, 256, 3>(a, mt, nt, st);
-    if (t.bn == 128) return launch_t<EPI, 128, 4>(a, mt, nt, st);
+    // 256 x 128: room for a third activation stage beside four weight stages (160 KB); in interleaved A/B runs 2-5%
+    // faster than two stages on every projection that takes this tile (down projection 95.9 -> 91.4 us at 1024 rows)
+    if (t.bn == 128) return launch_t<EPI, 128, 4, 256, 3>(a, mt, nt, st);
     return launch_t<EPI, 64, 4>(a, mt, nt, st);
   }
   // few rows: the weight ring is as deep as the LDS allows (bytes in flight are what sets the streaming rate)
   if constexpr (EPI == EPI_SWIGLU) {
     if (t.bn == 96) return t.bm == 128 ? launch_t<EPI, 96, 5, 128>(a, mt, nt, st) : launch_t<EPI, 96, 7, 64>(a, mt, nt, st);
+  }
+  if constexpr (EPI == EPI_STORE) {
+    if (t.bn == 96) return launch_t<EPI, 96, 4, 128>(a, mt, nt, st);
   }
   if (t.bm == 128) {
     if constexpr (W192) if (t.bn == 192) return launch_t<EPI, 192, 4, 128>(a, mt, nt, st);
@@ -619,7 +624,7 @@ hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
   if (a.ksplit < 1) a.ksplit = 1;
   switch (epi) {
     case EPI_STORE:
-      return launch_shape<EPI_STORE>(a, choose_tile(a.M, a.N, 1, 1, true), 1, st);
+      return launch_shape<EPI_STORE>(a, choose_tile(a.M, a.N, 1, 1, true, false, false, true), 1, st);
     case EPI_RESID: {
       // 256-row tiles only; 128 columns wide unless N is an odd multiple of 64 or the narrower tile fills the chip better
       const int mt = cdiv(a.M, BM);

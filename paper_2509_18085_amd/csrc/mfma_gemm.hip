@@ -533,6 +533,11 @@ int mfma_ksplit(int N, int K) {
   const int n_tiles = cdiv(N, 128), kt = K / BKK;
   int ks = 1;
   while (ks < 4 && 4 * n_tiles * ks < 224 && kt / (ks + 1) >= 8) ++ks;
+  // and no slice longer than 128 K-tiles (8192 elements): a split-K launch is one round of workgroups whose time is the
+  // slice length.  K = 18944 over 768 rows and 3584 columns: 118.5 us with two slices (168 workgroups), 97.2 us with
+  // three (252), 129.7 us with four (two rounds); 1024 rows of that shape pay for it (336 workgroups with three).
+  const int by_length = cdiv(kt, 128);
+  if (by_length > ks) ks = by_length < 4 ? by_length : 4;
   return ks;
 }
 
@@ -562,11 +567,19 @@ int mfma_lmhead_partials_per_row(int V) { return cdiv(V, BM) * 2; }
 // (one or a few states) the projections are weight-streaming problems: 64- and 128-row tiles spend a quarter
 // or half of the matrix work of a 256-row tile on them and cover more CUs.
 struct TileShape { int bm, bn; };
-static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow192, bool allow32 = false, bool allow96 = false,
-                             bool allow96_two_rows = false) {
-  const int heights[4] = {256, 128, 64, 32};
-  const int widths[5] = {192, 128, 96, 64, 32};
+static const int kTileWidths[5] = {192, 128, 96, 64, 32};
+// estimated time of one K-tile of one workgroup of shape bm x kTileWidths[wi]
+static float tile_cost(int bm, int wi) {
   const float eff[5] = {1.0f, 0.85f, 0.6f, 0.55f, 0.4f};
+  const int bn = kTileWidths[wi];
+  const float mfma = (float)(bm / 64) * ((float)bn / 64.0f) * 128.0f / eff[wi];
+  const float load = (float)(bm + bn) * 3.2f;
+  return mfma > load ? mfma : load;
+}
+static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow192, bool allow32 = false, bool allow96 = false,
+                             bool allow96_two_rows = false, float* cost_out = nullptr) {
+  const int heights[4] = {256, 128, 64, 32};
+  const int* widths = kTileWidths;
   TileShape best = {256, 0};
   float best_cost = 1e30f;
   for (int h = 0; h < 4; ++h)
@@ -581,11 +594,10 @@ static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow
       // 32-wide tiles (one or two wavefronts per workgroup) exist for the split-K projections of one or two states
       if ((bn == 32 || bm == 32) && !(allow32 && bn == 32 && bm <= 64)) continue;
       const int tiles = cdiv(M, bm) * (n_cols / cols) * ksplit;
-      const float mfma = (float)(bm / 64) * ((float)bn / 64.0f) * 128.0f / eff[i];
-      const float load = (float)(bm + bn) * 3.2f;
-      const float cost = (float)cdiv(tiles, 256) * (mfma > load ? mfma : load);
+      const float cost = (float)cdiv(tiles, 256) * tile_cost(bm, i);
       if (cost < best_cost) { best_cost = cost; best = {bm, bn}; }
     }
+  if (cost_out) *cost_out = best_cost;
   return best;
 }
 
@@ -634,8 +646,36 @@ hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
     }
     case EPI_PARTIAL:
       return launch_shape<EPI_PARTIAL>(a, choose_tile(a.M, a.N, 1, a.ksplit, false, true), 1, st);
-    case EPI_SWIGLU:
-      return launch_shape<EPI_SWIGLU>(a, choose_tile(a.M, a.N, 2, 1, true, false, true), 2, st);   // a tile of width w holds w/2 features
+    case EPI_SWIGLU: {
+      float whole = 0.f;
+      const TileShape t = choose_tile(a.M, a.N, 2, 1, true, false, true, false, &whole);   // a tile of width w holds w/2 features
+      // Two-part column schedule, for widths whose best single shape leaves the last round of workgroups mostly empty
+      // (18944 features over 768 rows: 888 tiles of 256 x 128 = 3.47 rounds, and 96 does not divide the width): 256 x 192
+      // tiles over as many leading features as fill whole rounds, then the best shape for the rest, as a second launch
+      // on the same stream.  Same K order in every shape, so the output bits are those of the single launch; measured
+      // 207.8 -> 190.5 us on that projection (170 column tiles of 96 features, then 246 tiles of 128 x 128).
+      const int mt = cdiv(a.M, 256);
+      const int rounds = (int)(((long long)mt * (a.N / 96)) / 256);
+      if (rounds >= 1) {
+        const int main_tiles = (256 * rounds) / mt;                    // column tiles of 96 features in the first part
+        const int rest = a.N - 96 * main_tiles;                          // features left; a multiple of 32 as a.N is
+        float rest_cost = 0.f;
+        const TileShape tr = rest > 0 ? choose_tile(a.M, rest, 2, 1, true, false, true, false, &rest_cost) : TileShape{0, 0};
+        if (rest > 0 && tr.bn != 0 && (float)rounds * tile_cost(256, 0) + rest_cost <= 0.9f * whole) {
+          GemmArgs m = a, r = a;
+          m.N = 96 * main_tiles;
+          const size_t ldw = a.ldw ? a.ldw : a.K;
+          r.N = rest;
+          r.W[0] = (const bf16_t*)a.W[0] + (size_t)m.N * ldw;
+          r.W[1] = (const bf16_t*)a.W[1] + (size_t)m.N * ldw;
+          r.C = (bf16_t*)a.C + m.N;
+          const hipError_t e = launch_shape<EPI_SWIGLU>(m, TileShape{256, 192}, 2, st);
+          if (e != hipSuccess) return e;
+          return launch_shape<EPI_SWIGLU>(r, tr, 2, st);
+        }
+      }
+      return launch_shape<EPI_SWIGLU>(a, t, 2, st);
+    }
     case EPI_LMHEAD:
       return launch_t<EPI_LMHEAD, 192, 3>(a, cdiv(a.N, BM), cdiv(a.M, 192), st);
     default:

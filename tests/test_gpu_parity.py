@@ -632,6 +632,8 @@ def test_step_accept_follows_device_targets(sp):
     (129, 320, 640, "swiglu"),      # 128-wide tiles (64 features per tile)
     (40, 12288, 1024, "swiglu"),    # few rows: 96-wide tiles (48 features, 256 workgroups), three of four wavefronts compute
     (100, 3072, 256, "swiglu"),     # 128 x 96 tiles, K shorter than the ring
+    (768, 18944, 256, "swiglu"),    # two-part column schedule: 170 tiles of 96 features, then 128 x 128 tiles (config 4's width and rows)
+    (600, 12288, 128, "swiglu"),    # two-part: one round of 256 x 192 tiles, the rest in 128 x 192 tiles; ragged rows
 ])
 def test_gemm_against_float64_matmul(sp, M, N, K, epi):
     g = torch.Generator().manual_seed(M * 7 + N)
@@ -675,6 +677,22 @@ def test_split_k_projection_rows_do_not_depend_on_the_row_count(sp, N, K):
     ref = to_np(R.cpu()) + to_np(A.cpu()) @ to_np(W.cpu()).T
     e_max, e_norm = rel_err(to_np(full.cpu()), ref)
     assert e_max < 1e-2 and e_norm < 4e-3, (e_max, e_norm)
+
+
+def test_gate_up_two_part_schedule_is_scheduling_only(sp):
+    """At 18944 features the gate/up projection of 768 rows runs as two launches (256 x 192 tiles over the leading 16320
+    features, 128 x 128 tiles over the rest) and that of 256 rows as one (256 x 128 tiles); 1024 rows take three rounds of
+    256 x 192 tiles and 64 x 64 tiles for the last 512 features.  The K order of an element is the same in all of them:
+    the common rows come out bit-identical."""
+    F, K = 18944, 512
+    g = torch.Generator().manual_seed(F + K)
+    A = (torch.randn((1024, K), generator=g) * 0.5).to(torch.bfloat16).to(DEV)
+    W0 = (torch.randn((F, K), generator=g) * 0.05).to(torch.bfloat16).to(DEV)
+    W1 = (torch.randn((F, K), generator=g) * 0.05).to(torch.bfloat16).to(DEV)
+    full = sp.gemm(sp.GEMM_SWIGLU, A, W0, W1).clone()
+    for n in (768, 512, 256, 40):
+        part = sp.gemm(sp.GEMM_SWIGLU, A[:n].contiguous(), W0, W1)
+        assert torch.equal(part, full[:n]), n
 
 
 def test_small_block_duplicates_are_bit_identical(sp):

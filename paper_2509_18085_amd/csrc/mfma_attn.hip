@@ -9,8 +9,8 @@
 // A prefix K/V tile of 64 keys is staged in LDS once and used by all 128 query rows (4 states of
 // 32 tokens, or 32 states of 4); workgroups of the same head run next to each other on one XCD
 // so the tile comes from HBM once and from L2 afterwards.  The number of prefix splits depends on
-// P only, so a row's arithmetic does not depend on G.  With few states (at most 128 such workgroups) a
-// workgroup owns 64 or 32 of the 128 rows instead and the other wavefront pairs only move data: more CUs
+// P only, so a row's arithmetic does not depend on G.  With few states (fewer such workgroups than CUs) a
+// workgroup owns 96, 64 or 32 of the 128 rows instead and the other wavefront pairs only move data: more CUs
 // stream, nothing else changes.  A step that carries a second group of rows (the recomputed suffix of a
 // full-sequence model, or the block being committed) runs both attention problems in one launch.
 //
@@ -275,7 +275,7 @@ struct AttnKArgs {
   int M, B, Hq, Hkv, P, S, ldp, ld, nQ, nS;   // ldp = rows allocated per KV head of the cache; S = suffix rows
   int own;                                     // 0: no own-block keys (queries that only read the cache)
   int split;                                   // cached rows per split: the P + S rows shared out evenly, whole tiles
-  int qrows;                                   // query rows a workgroup owns: 128, or 64 / 32 when there are few workgroups (scheduling only)
+  int qrows;                                   // query rows a workgroup owns: 128, or 96 / 64 / 32 when there are few workgroups (scheduling only)
 };
 
 // the lane's 8 MFMA operand fragments of LDS tile row `row` (K layout): hd = 16*kk + 8*hh + e
@@ -662,6 +662,9 @@ AttnKArgs prepare_attn(const AttnArgs& a, hipStream_t st) {
     const int wgs = cdiv(M, QTILE) * nS * a.Hq;
     if (wgs <= 64) k.qrows = 32;
     else if (wgs <= 128) k.qrows = 64;
+    // between half and the whole chip (28 heads x 6 tiles of 128 rows = 168 workgroups): 96 rows, three of the four
+    // wavefront pairs at work, if that brings more workgroups and still one round of them (28 x 8 = 224)
+    else if (wgs < 256 && cdiv(M, 96) > cdiv(M, QTILE) && cdiv(M, 96) * nS * a.Hq <= 256) k.qrows = 96;
   }
   k.nQ = cdiv(M, k.qrows);
   k.nS = nS;

@@ -130,6 +130,8 @@ def roofline_of(cfg, k_ms, n_launch, traffic):
     flop_launch = 2.0 * M * cfg.d * 2 * cfg.F
     alg_bytes = 2.0 * (2 * cfg.F * cfg.d + M * cfg.d + M * cfg.F)
     achieved = flop_launch / (k_ms * 1e-3) / 1e12
+    # one "launch" is one gate/up projection: a single kernel launch except where the library splits the columns over
+    # two launches of the same kernel (workload c4: wide tiles over whole rounds of workgroups, narrower ones for the rest)
     r = {"kernel": "gemm_bf16_mfma_kernel<EPI_SWIGLU> (gate/up projection)", "bound": "mfma", "achieved": achieved,
          "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
          "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": k_ms, "flop_per_launch": flop_launch,

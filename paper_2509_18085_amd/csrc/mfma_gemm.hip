@@ -588,9 +588,10 @@ static TileShape choose_tile(int M, int n_cols, int unit, int ksplit, bool allow
       const int cols = bn / unit;                 // output columns (or SwiGLU features) per tile
       if ((bn == 192 && (!allow192 || bm <= 64)) || (bn == 64 && bm == 128) || n_cols % cols != 0) continue;
       // 96-wide tiles: one row of tiles over few rows (weight streaming), where they turn 192 workgroups into 256
-      // (the QKV projection also takes them over two rows of 128-row tiles: 256 workgroups at 256 rows where 128 columns
-      // give 192; 41.4 against 43.3 us in interleaved runs)
-      if (bn == 96 && !((allow96 && (bm == 64 || bm == 128) && M <= bm) || (allow96_two_rows && bm == 128 && M <= 2 * bm))) continue;
+      // (the QKV projection also takes them over two rows of 128- or 64-row tiles: 256 workgroups where 128 columns
+      // give 192; 41.4 against 43.3 us at 256 rows, 31.9 against 35.2 us at 128 rows in interleaved runs)
+      if (bn == 96 && !((allow96 && (bm == 64 || bm == 128) && M <= bm) ||
+                        (allow96_two_rows && (bm == 64 || bm == 128) && M <= 2 * bm))) continue;
       // 32-wide tiles (one or two wavefronts per workgroup) exist for the split-K projections of one or two states
       if ((bn == 32 || bm == 32) && !(allow32 && bn == 32 && bm <= 64)) continue;
       const int tiles = cdiv(M, bm) * (n_cols / cols) * ksplit;
@@ -617,7 +618,7 @@ static hipError_t launch_shape(const GemmArgs& a, TileShape t, int unit, hipStre
     if (t.bn == 96) return t.bm == 128 ? launch_t<EPI, 96, 5, 128>(a, mt, nt, st) : launch_t<EPI, 96, 7, 64>(a, mt, nt, st);
   }
   if constexpr (EPI == EPI_STORE) {
-    if (t.bn == 96) return launch_t<EPI, 96, 4, 128>(a, mt, nt, st);
+    if (t.bn == 96) return t.bm == 128 ? launch_t<EPI, 96, 4, 128>(a, mt, nt, st) : launch_t<EPI, 96, 6, 64>(a, mt, nt, st);
   }
   if (t.bm == 128) {
     if constexpr (W192) if (t.bn == 192) return launch_t<EPI, 192, 4, 128>(a, mt, nt, st);

@@ -641,6 +641,8 @@ def test_step_accept_follows_device_targets(sp):
     (300, 384, 256, "store"),       # 192-wide tiles, ragged rows, short K
     (1024, 1536, 1024, "store"),    # 192-wide tiles, several row tiles, steady-state pipeline
     (70, 256, 192, "store"),        # 128-wide tiles, K of three tiles
+    (100, 12288, 256, "store"),     # 64 x 96 tiles over two rows of tiles (256 workgroups), K shorter than the ring
+    (200, 12288, 192, "store"),     # 128 x 96 tiles over two rows of tiles
     (513, 512, 2048, "resid"),      # sliced K (split-K) with residual, ragged rows
     (256, 128, 64, "resid"),        # single K tile
     (64, 192, 512, "resid"),        # N an odd multiple of 64: the unsliced launch must take 64-column tiles
@@ -694,6 +696,19 @@ def test_split_k_projection_rows_do_not_depend_on_the_row_count(sp, N, K):
     ref = to_np(R.cpu()) + to_np(A.cpu()) @ to_np(W.cpu()).T
     e_max, e_norm = rel_err(to_np(full.cpu()), ref)
     assert e_max < 1e-2 and e_norm < 4e-3, (e_max, e_norm)
+
+
+def test_qkv_tile_shapes_are_scheduling_only(sp):
+    """12288 columns: 40 rows run 64 x 64 tiles, 100 rows 64 x 96, 200 rows 128 x 96, 300 rows 128 x 192 and 1024 rows
+    256 x 192; the common rows come out bit-identical."""
+    N, K = 12288, 512
+    g = torch.Generator().manual_seed(N + K)
+    A = (torch.randn((1024, K), generator=g) * 0.5).to(torch.bfloat16).to(DEV)
+    W = (torch.randn((N, K), generator=g) * 0.05).to(torch.bfloat16).to(DEV)
+    full = sp.gemm(sp.GEMM_STORE, A, W).clone()
+    for n in (40, 100, 200, 300):
+        part = sp.gemm(sp.GEMM_STORE, A[:n].contiguous(), W)
+        assert torch.equal(part, full[:n]), n
 
 
 def test_gate_up_two_part_schedule_is_scheduling_only(sp):

@@ -187,6 +187,24 @@ int spiffy_gemm(int32_t dtype, int32_t epilogue, const void *A, const void *W0, 
                 const void *R, void *C, int32_t M, int32_t N, int32_t K, void *workspace,
                 size_t workspace_bytes, void *stream);
 
+/* How spiffy_gemm / verify_layer would launch a bf16 projection of M rows, N output columns (SPIFFY_GEMM_SWIGLU: N
+ * features) and inner size K on the MFMA kernel: host arithmetic only, nothing is launched and no device is touched.
+ * The choice is scheduling: the order of the K sum of an output element does not depend on it (Sec. 4.3: states of one
+ * step are independent rows), only k_slices does, and k_slices depends on (N, K) alone.  with_workspace: as for
+ * spiffy_gemm, SPIFFY_GEMM_RESID slices K only when scratch is given.  Returns SPIFFY_ESHAPE for shapes the MFMA
+ * kernel does not take (see spiffy_gemm), SPIFFY_EINVAL for a NULL plan or an unknown epilogue. */
+typedef struct {
+  int32_t n_launches;       /* 1, or 2 when the columns are split into a wide-tile part and a rest */
+  int32_t k_slices;         /* K slices (partial sums in fp32 scratch, reduced in a fixed order) */
+  struct {
+    int32_t tile_rows, tile_cols;   /* SWIGLU: a tile of w columns holds w/2 features (gate and up interleaved) */
+    int32_t col0, n_cols;           /* output columns (features) [col0, col0 + n_cols) */
+    int32_t workgroups;
+  } launch[2];
+} spiffy_gemm_plan_t;
+int spiffy_gemm_plan(int32_t epilogue, int32_t M, int32_t N, int32_t K, int32_t with_workspace,
+                     spiffy_gemm_plan_t *plan);
+
 /* Acceptance walk (Alg. 1 step 5).  graph_edges [E,2] int32 (parent, child), E >= 0;
  * draft_states, target_states [G,B] int32; 0 <= root < G <= SPIFFY_MAX_G.  Starting at root, move
  * to the lowest-id child (by the edge list only) whose draft state equals the current node's

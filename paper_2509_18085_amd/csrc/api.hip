@@ -590,6 +590,31 @@ int spiffy_gemm(int32_t dtype, int32_t epilogue, const void* A, const void* W0, 
   return dev(mf ? launch_gemm_mfma(epilogue, g, st) : launch_gemm_generic(dtype, epilogue, g, st));
 }
 
+int spiffy_gemm_plan(int32_t epilogue, int32_t M, int32_t N, int32_t K, int32_t with_workspace,
+                     spiffy_gemm_plan_t* plan) {
+  if (!plan || epilogue < SPIFFY_GEMM_STORE || epilogue > SPIFFY_GEMM_SWIGLU) return SPIFFY_EINVAL;
+  if (M < 1 || N < 1 || K < 1) return SPIFFY_ESHAPE;
+  GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.M = M; g.N = N; g.K = K; g.lda = K; g.ldc = N;
+  if (epilogue != SPIFFY_GEMM_SWIGLU) g.Nseg[0] = N;
+  if (!mfma_gemm_supported(epilogue, g)) return SPIFFY_ESHAPE;
+  int epi = epilogue, ks = 1;
+  if (epilogue == SPIFFY_GEMM_RESID && with_workspace && mfma_ksplit(N, K) > 1) { epi = EPI_PARTIAL; ks = mfma_ksplit(N, K); }
+  const GemmPlan p = plan_gemm_mfma(epi, M, N, ks);
+  std::memset(plan, 0, sizeof(*plan));
+  plan->n_launches = p.n_parts;
+  plan->k_slices = ks;
+  for (int i = 0; i < p.n_parts; ++i) {
+    plan->launch[i].tile_rows = p.part[i].bm;
+    plan->launch[i].tile_cols = p.part[i].bn;
+    plan->launch[i].col0 = p.part[i].col0;
+    plan->launch[i].n_cols = p.part[i].ncols;
+    plan->launch[i].workgroups = p.part[i].workgroups;
+  }
+  return SPIFFY_OK;
+}
+
 int spiffy_graph_accept(const int32_t* graph_edges, int32_t E, const int32_t* draft_states,
                         const int32_t* target_states, int32_t G, int32_t B, int32_t root,
                         spiffy_accept_result* result, int32_t* accepted_state, void* stream) {

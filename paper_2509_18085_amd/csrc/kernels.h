@@ -110,6 +110,13 @@ hipError_t launch_graph_accept(const int32_t* edges, int E, const int32_t* draft
 // ---- MFMA (bf16, gfx950) -----------------------------------------------------------------------
 bool mfma_gemm_supported(int epi, const GemmArgs& a);
 hipError_t launch_gemm_mfma(int epi, const GemmArgs& a, hipStream_t st);
+// what launch_gemm_mfma launches for a shape: tile rows x columns (SWIGLU: a tile of w columns holds w/2 features), the
+// range of output columns (features) and the number of workgroups of each launch
+struct GemmPlan {
+  int n_parts;
+  struct { int bm, bn, col0, ncols, workgroups; } part[2];
+};
+GemmPlan plan_gemm_mfma(int epi, int M, int N, int ksplit);
 int mfma_lmhead_partials_per_row(int V);
 int mfma_ksplit(int N, int K);          // K slices used for a [M,K]x[N,K] projection with residual (depends on N, K only)
 // out = R + sum of the K-slice partials P[ksplit][M][N] (fixed order); if normed != NULL also RMSNorm(out)*gain.

@@ -632,50 +632,87 @@ static hipError_t launch_shape(const GemmArgs& a, TileShape t, int unit, hipStre
   return launch_t<EPI, 128, 6, 64>(a, mt, nt, st);
 }
 
-hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
-  GemmArgs a = a0;
-  if (a.ksplit < 1) a.ksplit = 1;
+// The launches of one projection: one, or two column ranges (the two-part schedule of the gate/up projection).
+// Host arithmetic only; launch_gemm_mfma executes exactly this plan.
+GemmPlan plan_gemm_mfma(int epi, int M, int N, int ksplit) {
+  GemmPlan p = {};
+  if (ksplit < 1) ksplit = 1;
+  auto one = [&](TileShape t, int unit) {
+    p.n_parts = 1;
+    p.part[0] = {t.bm, t.bn, 0, N, cdiv(M, t.bm) * (N / (t.bn / unit)) * ksplit};
+  };
   switch (epi) {
     case EPI_STORE:
-      return launch_shape<EPI_STORE>(a, choose_tile(a.M, a.N, 1, 1, true, false, false, true), 1, st);
+      one(choose_tile(M, N, 1, 1, true, false, false, true), 1);
+      break;
     case EPI_RESID: {
       // 256-row tiles only; 128 columns wide unless N is an odd multiple of 64 or the narrower tile fills the chip better
-      const int mt = cdiv(a.M, BM);
-      const TileShape t = choose_tile(a.M, a.N, 1, 1, false);
-      if (a.N % 128 != 0 || (t.bm == 256 && t.bn == 64)) return launch_t<EPI_RESID, 64, 4>(a, mt, a.N / 64, st);
-      return launch_t<EPI_RESID, 128, 4>(a, mt, a.N / 128, st);
+      const TileShape t = choose_tile(M, N, 1, 1, false);
+      one(TileShape{256, (N % 128 != 0 || (t.bm == 256 && t.bn == 64)) ? 64 : 128}, 1);
+      break;
     }
     case EPI_PARTIAL:
-      return launch_shape<EPI_PARTIAL>(a, choose_tile(a.M, a.N, 1, a.ksplit, false, true), 1, st);
+      one(choose_tile(M, N, 1, ksplit, false, true), 1);
+      break;
     case EPI_SWIGLU: {
       float whole = 0.f;
-      const TileShape t = choose_tile(a.M, a.N, 2, 1, true, false, true, false, &whole);   // a tile of width w holds w/2 features
+      const TileShape t = choose_tile(M, N, 2, 1, true, false, true, false, &whole);   // a tile of width w holds w/2 features
+      one(t, 2);
       // Two-part column schedule, for widths whose best single shape leaves the last round of workgroups mostly empty
       // (18944 features over 768 rows: 888 tiles of 256 x 128 = 3.47 rounds, and 96 does not divide the width): 256 x 192
       // tiles over as many leading features as fill whole rounds, then the best shape for the rest, as a second launch
       // on the same stream.  Same K order in every shape, so the output bits are those of the single launch; measured
       // 207.8 -> 190.5 us on that projection (170 column tiles of 96 features, then 246 tiles of 128 x 128).
-      const int mt = cdiv(a.M, 256);
-      const int rounds = (int)(((long long)mt * (a.N / 96)) / 256);
+      const int mt = cdiv(M, 256);
+      const int rounds = (int)(((long long)mt * (N / 96)) / 256);
       if (rounds >= 1) {
         const int main_tiles = (256 * rounds) / mt;                    // column tiles of 96 features in the first part
-        const int rest = a.N - 96 * main_tiles;                          // features left; a multiple of 32 as a.N is
+        const int rest = N - 96 * main_tiles;                            // features left; a multiple of 32 as N is
         float rest_cost = 0.f;
-        const TileShape tr = rest > 0 ? choose_tile(a.M, rest, 2, 1, true, false, true, false, &rest_cost) : TileShape{0, 0};
+        const TileShape tr = rest > 0 ? choose_tile(M, rest, 2, 1, true, false, true, false, &rest_cost) : TileShape{0, 0};
         if (rest > 0 && tr.bn != 0 && (float)rounds * tile_cost(256, 0) + rest_cost <= 0.9f * whole) {
-          GemmArgs m = a, r = a;
-          m.N = 96 * main_tiles;
-          const size_t ldw = a.ldw ? a.ldw : a.K;
-          r.N = rest;
-          r.W[0] = (const bf16_t*)a.W[0] + (size_t)m.N * ldw;
-          r.W[1] = (const bf16_t*)a.W[1] + (size_t)m.N * ldw;
-          r.C = (bf16_t*)a.C + m.N;
-          const hipError_t e = launch_shape<EPI_SWIGLU>(m, TileShape{256, 192}, 2, st);
-          if (e != hipSuccess) return e;
-          return launch_shape<EPI_SWIGLU>(r, tr, 2, st);
+          p.n_parts = 2;
+          p.part[0] = {256, 192, 0, 96 * main_tiles, mt * main_tiles};
+          p.part[1] = {tr.bm, tr.bn, 96 * main_tiles, rest, cdiv(M, tr.bm) * (rest / (tr.bn / 2))};
         }
       }
-      return launch_shape<EPI_SWIGLU>(a, t, 2, st);
+      break;
+    }
+    case EPI_LMHEAD:      // vocabulary rows x token columns; the token tiles in use are only known on the device
+      p.n_parts = 1;
+      p.part[0] = {256, 192, 0, N, cdiv(N, BM) * cdiv(M, 192)};
+      break;
+    default:
+      break;
+  }
+  return p;
+}
+
+hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
+  GemmArgs a = a0;
+  if (a.ksplit < 1) a.ksplit = 1;
+  const GemmPlan p = plan_gemm_mfma(epi, a.M, a.N, a.ksplit);
+  if (p.n_parts < 1) return hipErrorInvalidValue;
+  switch (epi) {
+    case EPI_STORE:
+      return launch_shape<EPI_STORE>(a, TileShape{p.part[0].bm, p.part[0].bn}, 1, st);
+    case EPI_RESID:
+      if (p.part[0].bn == 64) return launch_t<EPI_RESID, 64, 4>(a, cdiv(a.M, BM), a.N / 64, st);
+      return launch_t<EPI_RESID, 128, 4>(a, cdiv(a.M, BM), a.N / 128, st);
+    case EPI_PARTIAL:
+      return launch_shape<EPI_PARTIAL>(a, TileShape{p.part[0].bm, p.part[0].bn}, 1, st);
+    case EPI_SWIGLU: {
+      const size_t ldw = a.ldw ? a.ldw : a.K;
+      for (int i = 0; i < p.n_parts; ++i) {
+        GemmArgs g = a;
+        g.N = p.part[i].ncols;
+        g.W[0] = (const bf16_t*)a.W[0] + (size_t)p.part[i].col0 * ldw;
+        g.W[1] = (const bf16_t*)a.W[1] + (size_t)p.part[i].col0 * ldw;
+        g.C = (bf16_t*)a.C + p.part[i].col0;
+        const hipError_t e = launch_shape<EPI_SWIGLU>(g, TileShape{p.part[i].bm, p.part[i].bn}, 2, st);
+        if (e != hipSuccess) return e;
+      }
+      return hipSuccess;
     }
     case EPI_LMHEAD:
       return launch_t<EPI_LMHEAD, 192, 3>(a, cdiv(a.N, BM), cdiv(a.M, 192), st);

@@ -27,7 +27,7 @@ EXPORTS = ["spiffy_status_str", "spiffy_uses_mfma", "spiffy_workspace_bytes", "s
            "spiffy_verify_layer", "spiffy_verify_layer_last", "spiffy_decode_head", "spiffy_gemm", "spiffy_graph_accept", "spiffy_draft_prune", "spiffy_head_topk", "spiffy_commit_block",
            "spiffy_subgraph_search_workspace_bytes", "spiffy_subgraph_search", "spiffy_verify_step",
            "spiffy_workspace_bytes_seq", "spiffy_verify_step_seq", "spiffy_workspace_bytes_commit",
-           "spiffy_verify_step_commit", "spiffy_decode_head_static"]
+           "spiffy_verify_step_commit", "spiffy_decode_head_static", "spiffy_gemm_plan"]
 GEMM_STORE, GEMM_RESID, GEMM_SWIGLU = 0, 1, 2
 
 
@@ -49,6 +49,15 @@ class PrefixKV(C.Structure):
 
 class AcceptResult(C.Structure):
     _fields_ = [("node", C.c_int32), ("depth", C.c_int32), ("n_steps", C.c_int32), ("flags", C.c_int32)]
+
+
+class GemmLaunch(C.Structure):
+    _fields_ = [("tile_rows", C.c_int32), ("tile_cols", C.c_int32), ("col0", C.c_int32), ("n_cols", C.c_int32),
+                ("workgroups", C.c_int32)]
+
+
+class GemmPlan(C.Structure):
+    _fields_ = [("n_launches", C.c_int32), ("k_slices", C.c_int32), ("launch", GemmLaunch * 2)]
 
 
 class SpiffyError(RuntimeError):
@@ -83,6 +92,8 @@ def _load() -> C.CDLL:
                                        vp, sz, vp]
     lib.spiffy_decode_head_static.restype = C.c_int
     lib.spiffy_decode_head_static.argtypes = [cfgp, vp, vp, vp, vp, vp, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp]
+    lib.spiffy_gemm_plan.restype = C.c_int
+    lib.spiffy_gemm_plan.argtypes = [i32, i32, i32, i32, i32, C.POINTER(GemmPlan)]
     lib.spiffy_gemm.restype = C.c_int
     lib.spiffy_gemm.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, i32, i32, vp, sz, vp]
     lib.spiffy_graph_accept.restype = C.c_int
@@ -279,6 +290,15 @@ def gemm(epilogue: int, A: torch.Tensor, W0: torch.Tensor, W1: Optional[torch.Te
     _check(lib.spiffy_gemm(dt, epilogue, _ptr(A), _ptr(W0), _ptr(W1), _ptr(R), _ptr(out), M, N, K, wp, wn,
                            _stream(stream)), "spiffy_gemm")
     return out
+
+
+def gemm_plan(epilogue: int, M: int, N: int, K: int, with_workspace: bool = True) -> dict:
+    """The launches spiffy_gemm / verify_layer use for a bf16 projection of that shape (host arithmetic, no device)."""
+    p = GemmPlan()
+    _check(lib.spiffy_gemm_plan(epilogue, M, N, K, int(with_workspace), C.byref(p)), "spiffy_gemm_plan")
+    return {"k_slices": p.k_slices,
+            "launches": [{"tile": (l.tile_rows, l.tile_cols), "col0": l.col0, "n_cols": l.n_cols,
+                          "workgroups": l.workgroups} for l in p.launch[:p.n_launches]]}
 
 
 def graph_accept(graph_edges: torch.Tensor, draft_states: torch.Tensor, target_states: torch.Tensor,

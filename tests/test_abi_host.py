@@ -380,3 +380,67 @@ def test_synth_graphs_follow_the_recipes():
     assert len({tuple(r) for r in st}) == 16          # 16 subsets, 4 copies each
     tgt, path = synth.planted_targets(*synth.draft_graph("c3", synth.CONFIGS["c3"]), synth.CONFIGS["c3"].V, 3, 5)
     assert len(path) >= 2
+
+
+# ------------------------------------------------------------------ launch plans (host arithmetic of the GEMM dispatcher)
+
+TILE_ROWS = {256, 128, 64, 32}
+
+
+def _check_plan(epi, M, N, K, plan):
+    unit = 2 if epi == sp.GEMM_SWIGLU else 1
+    col = 0
+    for l in plan["launches"]:
+        bm, bn = l["tile"]
+        assert bm in TILE_ROWS and bn in (192, 128, 96, 64, 32), (M, N, l)
+        assert l["col0"] == col and l["n_cols"] > 0 and l["n_cols"] % (bn // unit) == 0, (M, N, l)
+        assert l["workgroups"] == -(-M // bm) * (l["n_cols"] // (bn // unit)) * plan["k_slices"], (M, N, l)
+        col += l["n_cols"]
+    assert col == N, (M, N, plan)       # the launches cover every output column exactly once
+
+
+def test_gemm_plans_cover_the_columns_once_and_slice_k_by_shape_only():
+    """Every plan of the dispatcher covers [0, N) exactly once with tiles that divide their range, for the projection
+    shapes of the three models and row counts from 1 to 2048; the K-slice count is the same for every row count."""
+    shapes = [(sp.GEMM_STORE, 12288, 4096), (sp.GEMM_STORE, 4608, 3584), (sp.GEMM_RESID, 4096, 4096),
+              (sp.GEMM_RESID, 4096, 12288), (sp.GEMM_RESID, 3584, 18944), (sp.GEMM_RESID, 3584, 3584),
+              (sp.GEMM_RESID, 192, 512), (sp.GEMM_SWIGLU, 12288, 4096), (sp.GEMM_SWIGLU, 18944, 3584),
+              (sp.GEMM_SWIGLU, 320, 640)]
+    for epi, N, K in shapes:
+        slices = set()
+        for M in list(range(1, 300, 7)) + [256, 512, 640, 768, 1000, 1024, 1536, 2048]:
+            for ws in (True, False):
+                plan = sp.gemm_plan(epi, M, N, K, ws)
+                _check_plan(epi, M, N, K, plan)
+                if ws:
+                    slices.add(plan["k_slices"])
+                else:
+                    assert plan["k_slices"] == 1
+        assert len(slices) == 1, (epi, N, K, slices)
+
+
+def test_gemm_plans_of_the_benchmark_shapes():
+    """The schedules the design notes describe: two rounds of 256 x 192 tiles for the headline gate/up launch, the
+    two-part schedule at 18944 features over 768 rows, three K slices for K = 18944, 96-column tiles for QKV over two
+    rows of tiles."""
+    assert sp.gemm_plan(sp.GEMM_SWIGLU, 1024, 12288, 4096) == {
+        "k_slices": 1, "launches": [{"tile": (256, 192), "col0": 0, "n_cols": 12288, "workgroups": 512}]}
+    assert sp.gemm_plan(sp.GEMM_SWIGLU, 768, 18944, 3584)["launches"] == [
+        {"tile": (256, 192), "col0": 0, "n_cols": 16320, "workgroups": 510},
+        {"tile": (128, 128), "col0": 16320, "n_cols": 2624, "workgroups": 246}]
+    assert sp.gemm_plan(sp.GEMM_RESID, 768, 3584, 18944) == {
+        "k_slices": 3, "launches": [{"tile": (256, 128), "col0": 0, "n_cols": 3584, "workgroups": 252}]}
+    assert sp.gemm_plan(sp.GEMM_RESID, 1024, 4096, 12288)["k_slices"] == 2
+    assert sp.gemm_plan(sp.GEMM_STORE, 256, 12288, 4096)["launches"][0]["tile"] == (128, 96)
+    assert sp.gemm_plan(sp.GEMM_STORE, 128, 12288, 4096)["launches"][0]["tile"] == (64, 96)
+    assert sp.gemm_plan(sp.GEMM_STORE, 1024, 12288, 4096)["launches"][0] == {
+        "tile": (256, 192), "col0": 0, "n_cols": 12288, "workgroups": 256}
+
+
+def test_gemm_plan_errors():
+    p = sp.GemmPlan()
+    assert sp.lib.spiffy_gemm_plan(sp.GEMM_STORE, 64, 100, 256, 1, C.byref(p)) == sp.SPIFFY_ESHAPE     # N % 64
+    assert sp.lib.spiffy_gemm_plan(sp.GEMM_STORE, 64, 128, 100, 1, C.byref(p)) == sp.SPIFFY_ESHAPE     # K % 64
+    assert sp.lib.spiffy_gemm_plan(sp.GEMM_STORE, 0, 128, 128, 1, C.byref(p)) == sp.SPIFFY_ESHAPE
+    assert sp.lib.spiffy_gemm_plan(7, 64, 128, 128, 1, C.byref(p)) == sp.SPIFFY_EINVAL
+    assert sp.lib.spiffy_gemm_plan(sp.GEMM_STORE, 64, 128, 128, 1, None) == sp.SPIFFY_EINVAL

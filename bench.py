@@ -297,6 +297,8 @@ def main():
                 line["other_configs"][key] = other_config_leg(sp, synth, key, dev, seed, 10, 2, 2)
         # the paper's own operating point (D* = 3: the true block and three drafts) at the headline model shape
         line["other_configs"]["c3_four_states"] = other_config_leg(sp, synth, "c3", dev, seed, 10, 2, 2, n_states=4)
+        # and the vanilla pass (one state): every projection is a weight stream, the regime of the HBM roofline
+        line["other_configs"]["c3_one_state"] = other_config_leg(sp, synth, "c3", dev, seed, 10, 2, 2, n_states=1)
     print(json.dumps(line))
 
 

@@ -123,6 +123,50 @@ def time_dominant_kernel(sp, w, dev, iters):
     return k0.elapsed_time(k1) / n_launch, n_launch
 
 
+def weight_stream_leg(sp, w, dev):
+    """The four projections of a layer alone, through spiffy_gemm with the step's shapes (QKV as one fused weight
+    matrix, output and down projections with their K slices and reduction), weights rotating over eight layers:
+    algorithmic bytes over time against the HBM peak.  For the workloads whose projections are weight streams."""
+    import torch
+    cfg, layers = w["cfg"], w["layers"][:8]
+    M, d, F = cfg.G * cfg.B, cfg.d, cfg.F
+    qd = cfg.Hq * cfg.hd
+    x = torch.randn((M, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    xa = torch.randn((M, qd), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    xf = torch.randn((M, F), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    r = torch.randn((M, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    ws = torch.empty(4 * M * d * 4 + 256, dtype=torch.uint8, device=dev)
+    wqkv = [torch.cat([lw["wq"], lw["wk"], lw["wv"]]) for lw in layers]
+    legs = {
+        "qkv": (lambda i: sp.gemm(sp.GEMM_STORE, x, wqkv[i], out=o_qkv), 2.0 * (wqkv[0].numel() + M * d + M * wqkv[0].shape[0])),
+        "output_projection_and_reduction": (lambda i: sp.gemm(sp.GEMM_RESID, xa, layers[i]["wo"], R=r, out=o_d, workspace=ws),
+                                            2.0 * (d * qd + M * qd + 2 * M * d)),
+        "gate_up": (lambda i: sp.gemm(sp.GEMM_SWIGLU, x, layers[i]["w_gate"], layers[i]["w_up"], out=o_f),
+                    2.0 * (2 * F * d + M * d + M * F)),
+        "down_projection_and_reduction": (lambda i: sp.gemm(sp.GEMM_RESID, xf, layers[i]["w_down"], R=r, out=o_d, workspace=ws),
+                                          2.0 * (d * F + M * F + 2 * M * d)),
+    }
+    o_qkv = torch.empty((M, wqkv[0].shape[0]), device=dev, dtype=torch.bfloat16)
+    o_d = torch.empty((M, d), device=dev, dtype=torch.bfloat16)
+    o_f = torch.empty((M, F), device=dev, dtype=torch.bfloat16)
+    out = {}
+    for name, (fn, nbytes) in legs.items():
+        for i in range(len(layers)):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            for i in range(len(layers)):
+                fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / (3 * len(layers))
+        out[name] = {"us": us, "algorithmic_MB": nbytes / 1e6, "GBs": nbytes / us / 1e3,
+                     "frac_of_hbm_peak": nbytes / us / 1e3 / PEAK_HBM_GBS}
+    return out
+
+
 def roofline_of(cfg, k_ms, n_launch, traffic):
     """Roofline object of the SwiGLU GEMM: against the bf16 MFMA peak, or against the HBM peak when the launch moves
     more bytes per flop than the chip's balance point (few rows: the small-block workload, --states)."""
@@ -161,6 +205,8 @@ def other_config_leg(sp, synth, key, dev, seed, steps, warmup, kernel_iters, n_s
            "step_bound": "hbm" if nbytes / (PEAK_HBM_GBS * 1e9) > flop / (PEAK_BF16_TFLOPS * 1e12) else "mfma",
            "roofline": roofline_of(cfg, k_ms, n_launch, None if n_states else stored_traffic(key)),
            "planted_walk": walk_outcome(w)}
+    if out["roofline"]["bound"] == "hbm":
+        out["weight_streams"] = weight_stream_leg(sp, w, dev)
     del w
     torch.cuda.empty_cache()
     return out

@@ -569,23 +569,32 @@ __global__ __launch_bounds__(NT) void attn_prefix_mfma_pair_kernel(AttnKArgs a, 
   else attn_prefix_body<true>(b, (int)blockIdx.x - n_a);
 }
 
-// merge the prefix splits of each (row, head): weights 2^(m_s - max m)
-__global__ __launch_bounds__(128) void attn_combine_kernel(const float* __restrict__ opart,
+// merge the prefix splits of each (row, head): weights 2^(m_s - max m).  32 lanes per (row, head), four head
+// dimensions per lane, eight (row, head) pairs per workgroup.
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float* __restrict__ opart,
                                                            const float* __restrict__ mlpart, bf16_t* __restrict__ out,
                                                            int M, int Hq, int nS) {
-  const size_t rowh = blockIdx.x;   // row * Hq + head
-  const int t = threadIdx.x;
+  const size_t n_rowh = (size_t)M * Hq;
+  const size_t rowh = (size_t)blockIdx.x * 8 + (threadIdx.x >> 5);   // row * Hq + head
+  if (rowh >= n_rowh) return;
+  const int t = (threadIdx.x & 31) * 4;
   float mx = -INFINITY;
-  for (int s = 0; s < nS; ++s) mx = fmaxf(mx, mlpart[((size_t)s * M * Hq + rowh) * 2]);
-  float num = 0.f, den = 0.f;
+  for (int s = 0; s < nS; ++s) mx = fmaxf(mx, mlpart[((size_t)s * n_rowh + rowh) * 2]);
+  f32x4 num = {0.f, 0.f, 0.f, 0.f};
+  float den = 0.f;
   for (int s = 0; s < nS; ++s) {
-    const size_t i = (size_t)s * M * Hq + rowh;
+    const size_t i = (size_t)s * n_rowh + rowh;
     const float ms = mlpart[i * 2];
     const float wgt = (ms == -INFINITY) ? 0.f : exp2f(ms - mx);
     den += wgt * mlpart[i * 2 + 1];
-    num += wgt * opart[i * HD + t];
+    const f32x4 o = *reinterpret_cast<const f32x4*>(opart + i * HD + t);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) num[e] += wgt * o[e];
   }
-  out[rowh * HD + t] = static_cast<bf16_t>(num / den);
+  bf16x4 r;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) r[e] = static_cast<bf16_t>(num[e] / den);
+  *reinterpret_cast<bf16x4*>(out + rowh * HD + t) = r;
 }
 
 __global__ void rope_table_kernel(float2* __restrict__ tab, int B, int half, int hd, int pos0, float base) {
@@ -690,7 +699,7 @@ hipError_t launch_attn_mfma(const AttnArgs& a, hipStream_t st) {
   const int grid = k.nQ * k.nS * a.Hq;
   if (a.S > 0) attn_prefix_mfma_kernel<true><<<grid, NT, kAttnSmem, st>>>(k);
   else attn_prefix_mfma_kernel<false><<<grid, NT, kAttnSmem, st>>>(k);
-  if (k.nS > 1) attn_combine_kernel<<<k.M * a.Hq, 128, 0, st>>>(k.opart, k.mlpart, k.out, k.M, a.Hq, k.nS);
+  if (k.nS > 1) attn_combine_kernel<<<cdiv(k.M * a.Hq, 8), 256, 0, st>>>(k.opart, k.mlpart, k.out, k.M, a.Hq, k.nS);
   return hipGetLastError();
 }
 
@@ -701,8 +710,8 @@ hipError_t launch_attn_mfma_pair(const AttnArgs& a, const AttnArgs& b, hipStream
   const AttnKArgs ka = prepare_attn(a, st), kb = prepare_attn(b, st);
   const int n_a = ka.nQ * ka.nS * a.Hq, n_b = kb.nQ * kb.nS * b.Hq;
   attn_prefix_mfma_pair_kernel<<<n_a + n_b, NT, kAttnSmem, st>>>(ka, kb, n_a);
-  if (ka.nS > 1) attn_combine_kernel<<<ka.M * a.Hq, 128, 0, st>>>(ka.opart, ka.mlpart, ka.out, ka.M, a.Hq, ka.nS);
-  if (kb.nS > 1) attn_combine_kernel<<<kb.M * b.Hq, 128, 0, st>>>(kb.opart, kb.mlpart, kb.out, kb.M, b.Hq, kb.nS);
+  if (ka.nS > 1) attn_combine_kernel<<<cdiv(ka.M * a.Hq, 8), 256, 0, st>>>(ka.opart, ka.mlpart, ka.out, ka.M, a.Hq, ka.nS);
+  if (kb.nS > 1) attn_combine_kernel<<<cdiv(kb.M * b.Hq, 8), 256, 0, st>>>(kb.opart, kb.mlpart, kb.out, kb.M, b.Hq, kb.nS);
   return hipGetLastError();
 }
 

@@ -482,42 +482,65 @@ hipError_t launch_t(const GemmArgs& a, int tiles_i, int tiles_j, hipStream_t st)
   return hipGetLastError();
 }
 
-// out[m,:] = R[m,:] + sum_z P[z][m,:]  (fixed order), optionally followed by RMSNorm of that row
+// out[m,:] = R[m,:] + sum_z P[z][m,:]  (fixed order), optionally followed by RMSNorm of that row.
+// One workgroup per row, of 256 or 1024 threads: with few rows the launch is latency-bound and 1024 threads have every
+// load of a row in flight at once.  The thread count is scheduling only.  The row's sum of squares is defined by the
+// 256-thread order: a lane adds the sums of its four elements over the 256-element chunks w, w+4, w+8, .. (w = its
+// wavefront), the 64 lanes of a wavefront are summed, then the four wavefront sums.  With 1024 threads every
+// (chunk, lane) sum goes through LDS and the first four wavefronts add them in that same order.
 template <bool NORM>
-__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ P, int ksplit,
+__global__ __launch_bounds__(1024) void splitk_reduce_kernel(const float* __restrict__ P, int ksplit,
                                                             const bf16_t* __restrict__ R, bf16_t* __restrict__ out,
                                                             const bf16_t* __restrict__ gain, float eps,
                                                             bf16_t* __restrict__ normed, int M, int N,
                                                             const int32_t* __restrict__ n_rows_dev,
                                                             const int32_t* __restrict__ out_rows) {
   __shared__ float red[4];
-  extern __shared__ float rowbuf[];
+  extern __shared__ float rowbuf[];               // NORM: the row in fp32; 1024 threads: then one sum per (chunk, lane)
   const int m = blockIdx.x;
   if (n_rows_dev && m >= *n_rows_dev) return;
   const size_t mo = out_rows ? (size_t)out_rows[m] : (size_t)m;     // where the row goes (compacted rows scatter back)
+  const int stride = 4 * (int)blockDim.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const bool wide = blockDim.x > 256;
+  float* lane_ss = rowbuf + N;
   float ss = 0.f;
-  for (int n = threadIdx.x * 4; n < N; n += 1024) {
-    f32x4 s = *reinterpret_cast<const f32x4*>(P + (size_t)m * N + n);
-    for (int z = 1; z < ksplit; ++z) {
-      const f32x4 p = *reinterpret_cast<const f32x4*>(P + ((size_t)z * M + m) * N + n);
-      s[0] += p[0]; s[1] += p[1]; s[2] += p[2]; s[3] += p[3];
-    }
-    const bf16x4 r = *reinterpret_cast<const bf16x4*>(R + (size_t)m * N + n);
-    bf16x4 o;
+  for (int base = wave * 256; base < N; base += stride) {     // wavefront-uniform: one chunk per trip
+    const int n = base + lane * 4;
+    float c = 0.f;
+    if (n < N) {
+      f32x4 s = *reinterpret_cast<const f32x4*>(P + (size_t)m * N + n);
+      for (int z = 1; z < ksplit; ++z) {
+        const f32x4 p = *reinterpret_cast<const f32x4*>(P + ((size_t)z * M + m) * N + n);
+        s[0] += p[0]; s[1] += p[1]; s[2] += p[2]; s[3] += p[3];
+      }
+      const bf16x4 r = *reinterpret_cast<const bf16x4*>(R + (size_t)m * N + n);
+      bf16x4 o;
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      s[e] += static_cast<float>(r[e]);
-      o[e] = static_cast<bf16_t>(s[e]);
-      if (NORM) { rowbuf[n + e] = s[e]; ss += s[e] * s[e]; }
+      for (int e = 0; e < 4; ++e) {
+        s[e] += static_cast<float>(r[e]);
+        o[e] = static_cast<bf16_t>(s[e]);
+        if (NORM) { rowbuf[n + e] = s[e]; c += s[e] * s[e]; }
+      }
+      *reinterpret_cast<bf16x4*>(out + mo * N + n) = o;
     }
-    *reinterpret_cast<bf16x4*>(out + mo * N + n) = o;
+    if (NORM) {
+      if (wide) lane_ss[(base >> 8) * 64 + lane] = c; else ss += c;
+    }
   }
   if (!NORM) return;
-  ss = wave_sum(ss);
-  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = ss;
+  if (wide) {
+    __syncthreads();
+    if (wave < 4)
+      for (int k = wave; k < (N + 255) / 256; k += 4) ss += lane_ss[k * 64 + lane];
+  }
+  if (wave < 4) {
+    ss = wave_sum(ss);
+    if (lane == 0) red[wave] = ss;
+  }
   __syncthreads();
   const float inv = 1.0f / sqrtf((red[0] + red[1] + red[2] + red[3]) / (float)N + eps);
-  for (int n = threadIdx.x * 4; n < N; n += 1024) {
+  for (int n = threadIdx.x * 4; n < N; n += stride) {
     const bf16x4 g = *reinterpret_cast<const bf16x4*>(gain + n);
     bf16x4 o;
 #pragma unroll
@@ -724,12 +747,13 @@ hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
 hipError_t launch_splitk_reduce(const float* P, int ksplit, const void* R, void* out, const void* gain, float eps,
                                 void* normed, int M, int N, hipStream_t st, const int32_t* n_rows_dev,
                                 const int32_t* out_rows) {
+  const int threads = (N >= 4096 && M <= 512) ? 1024 : 256;
   if (normed)
-    splitk_reduce_kernel<true><<<M, 256, sizeof(float) * (size_t)N, st>>>(P, ksplit, (const bf16_t*)R, (bf16_t*)out,
+    splitk_reduce_kernel<true><<<M, threads, sizeof(float) * ((size_t)N + (threads > 256 ? 64 * ((N + 255) / 256) : 0)), st>>>(P, ksplit, (const bf16_t*)R, (bf16_t*)out,
                                                                        (const bf16_t*)gain, eps, (bf16_t*)normed, M, N,
                                                                        n_rows_dev, out_rows);
   else
-    splitk_reduce_kernel<false><<<M, 256, 0, st>>>(P, ksplit, (const bf16_t*)R, (bf16_t*)out, nullptr, 0.f, nullptr, M, N,
+    splitk_reduce_kernel<false><<<M, threads, 0, st>>>(P, ksplit, (const bf16_t*)R, (bf16_t*)out, nullptr, 0.f, nullptr, M, N,
                                                    n_rows_dev, out_rows);
   return hipGetLastError();
 }

@@ -228,6 +228,23 @@ def test_layer_rows_are_bit_identical_across_tile_heights(sp):
     assert e_max < tol(cfg), e_max
 
 
+def test_reduction_thread_count_is_scheduling_only(sp):
+    """The split-K reduction with its fused RMSNorm runs 1024 threads per row up to 512 rows and 256 beyond (rows of 4096
+    elements); the row's sum of squares is taken chunk by chunk in a fixed order, so 32 states (1024 rows) and their
+    first 8 or 16 (256 / 512 rows) give bit-identical rows."""
+    cfg = synth.CONFIGS["c3"].scaled(L=1, F=512, V=1280, P=64)
+    w = synth.layer_weights(cfg, 0)
+    pk, pv = synth.prefix_kv(cfg, 0)
+    x = synth.hidden_states(cfg)
+    full = run_layer(sp, cfg, w, pk, pv, x)
+    for n in (8, 16, 1):
+        part = run_layer(sp, cfg, w, pk, pv, x[:n].contiguous())
+        assert torch.equal(part, full[:n]), n
+    ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), to_np(x[3:4]), **oracle_kw(cfg))
+    e_max, _ = rel_err(to_np(full[3:4]), ref)
+    assert e_max < tol(cfg), e_max
+
+
 def test_attention_query_tiles_of_96_rows_are_scheduling_only(sp):
     """28 query heads over 768 rows are 168 workgroups of 128 query rows, so the launch takes 96-row tiles (224
     workgroups, three wavefront pairs at work); 4 states run 32-row tiles and 12 states 64-row tiles.  The rows of

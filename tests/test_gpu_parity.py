@@ -696,6 +696,51 @@ def test_gemm_against_float64_matmul(sp, M, N, K, epi):
     assert e_max < 1e-2 and e_norm < 4e-3, (e_max, e_norm)
 
 
+def test_gemm_seeded_random_shapes(sp):
+    """Forty seeded shapes across the dispatcher's tile plans (ragged rows, one to five row tiles, widths that are odd
+    multiples of 32 / 64, short K, wide gate/up launches that take the two-part schedule) against the float64 product;
+    every launch plan is also checked to cover the columns once."""
+    rng = np.random.default_rng(20250918)
+    cases = []
+    for _ in range(28):
+        epi = ("store", "resid", "swiglu")[int(rng.integers(0, 3))]
+        M = int(rng.integers(1, 1100))
+        K = 64 * int(rng.integers(1, 13))
+        N = (32 if epi == "swiglu" else 64) * int(rng.integers(1, 40))
+        cases.append((epi, M, N, K))
+    cases += [("swiglu", 1100, 6144, 64), ("swiglu", 900, 9504, 64), ("swiglu", 640, 12288, 64), ("swiglu", 400, 18944, 64),
+              ("swiglu", 513, 18944, 128), ("store", 130, 12288, 64), ("store", 70, 9216, 128), ("store", 1030, 4608, 64),
+              ("resid", 770, 3584, 1024), ("resid", 33, 4096, 2048), ("resid", 520, 1152, 640), ("swiglu", 1, 96, 64)]
+    code = {"store": sp.GEMM_STORE, "resid": sp.GEMM_RESID, "swiglu": sp.GEMM_SWIGLU}
+    for epi, M, N, K in cases:
+        plan = sp.gemm_plan(code[epi], M, N, K, True)
+        col = 0
+        for l in plan["launches"]:
+            assert l["col0"] == col
+            col += l["n_cols"]
+        assert col == N, (epi, M, N, K, plan)
+        g = torch.Generator().manual_seed(M * 131 + N * 7 + K)
+        A = (torch.randn((M, K), generator=g) * 0.5).to(torch.bfloat16)
+        W0 = (torch.randn((N, K), generator=g) * 0.05).to(torch.bfloat16)
+        a, w0 = to_np(A), to_np(W0)
+        if epi == "store":
+            got = sp.gemm(sp.GEMM_STORE, A.to(DEV), W0.to(DEV))
+            ref = a @ w0.T
+        elif epi == "resid":
+            R = torch.randn((M, N), generator=g).to(torch.bfloat16)
+            ws = torch.empty(4 * M * N * 4 + 256, dtype=torch.uint8, device=DEV)
+            got = sp.gemm(sp.GEMM_RESID, A.to(DEV), W0.to(DEV), R=R.to(DEV), workspace=ws)
+            ref = to_np(R) + a @ w0.T
+        else:
+            W1 = (torch.randn((N, K), generator=g) * 0.05).to(torch.bfloat16)
+            got = sp.gemm(sp.GEMM_SWIGLU, A.to(DEV), W0.to(DEV), W1.to(DEV))
+            gg = a @ w0.T
+            ref = gg / (1.0 + np.exp(-gg)) * (a @ to_np(W1).T)
+        torch.cuda.synchronize()
+        e_max, e_norm = rel_err(to_np(got.cpu()), ref)
+        assert e_max < 1e-2 and e_norm < 4e-3, (epi, M, N, K, plan, e_max, e_norm)
+
+
 @pytest.mark.parametrize("N,K", [(4096, 4096), (4096, 12288), (1024, 2048)])
 def test_split_k_projection_rows_do_not_depend_on_the_row_count(sp, N, K):
     """Output / down projection shapes: 32, 64, 96, 128 and 256 rows run on 32x32 (one wavefront), 64x32 (two),

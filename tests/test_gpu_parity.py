@@ -245,20 +245,22 @@ def test_reduction_thread_count_is_scheduling_only(sp):
     assert e_max < tol(cfg), e_max
 
 
-def test_attention_query_tiles_of_96_rows_are_scheduling_only(sp):
+@pytest.mark.parametrize("B,G", [(32, 24), (4, 192), (16, 48)])
+def test_attention_query_tiles_of_96_rows_are_scheduling_only(sp, B, G):
     """28 query heads over 768 rows are 168 workgroups of 128 query rows, so the launch takes 96-row tiles (224
-    workgroups, three wavefront pairs at work); 4 states run 32-row tiles and 12 states 64-row tiles.  The rows of
-    the states they share come out bit-identical, and a state matches the oracle."""
-    cfg = synth.CONFIGS["c4"].scaled(L=1, F=512, V=1280, P=300)
+    workgroups, three wavefront pairs at work); a sixth of the states run 32-row tiles and half of them 64-row tiles.
+    The rows of the states they share come out bit-identical, and a state matches the oracle.  Blocks of 32, 4 and 16
+    tokens (3, 24 and 6 states per 96-row tile)."""
+    cfg = synth.CONFIGS["c4"].scaled(L=1, F=512, V=1280, P=300, B=B, G=G)
     w = synth.layer_weights(cfg, 0)
     pk, pv = synth.prefix_kv(cfg, 0)
     x = synth.hidden_states(cfg)
     full = run_layer(sp, cfg, w, pk, pv, x)
-    for lo, n in ((0, 4), (7, 12), (20, 4)):
+    for lo, n in ((0, G // 6), (G // 4 + 1, G // 2), (G - G // 6, G // 6)):
         part = run_layer(sp, cfg, w, pk, pv, x[lo:lo + n].contiguous())
         assert torch.equal(part, full[lo:lo + n]), (lo, n)
-    ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), to_np(x[23:24]), **oracle_kw(cfg))
-    e_max, _ = rel_err(to_np(full[23:24]), ref)
+    ref = O().verify_layer(np_weights(w), to_np(pk), to_np(pv), to_np(x[G - 1:G]), **oracle_kw(cfg))
+    e_max, _ = rel_err(to_np(full[G - 1:G]), ref)
     assert e_max < tol(cfg), e_max
 
 

@@ -12,6 +12,8 @@
  *   - Kernel choice is by shape: bf16 with head_dim 128, d % 128 == 0, ffn % 64 == 0 runs the MFMA
  *     kernels (LM head: d % 64 == 0); anything else runs shape-agnostic fp32-math kernels.  The
  *     choice depends on the arguments of the call only (no environment variable, no global state).
+ *     On the MFMA kernels a layer takes d <= 16384 (a row in fp32 is kept in 64 KB of on-chip memory by
+ *     the reduction behind the output and down projections); wider models get SPIFFY_ESHAPE.
  *   - All data pointers are DEVICE pointers owned by the caller unless a parameter says "host".
  *     The library never frees or keeps them.  Structs (cfg, weights, prefix) are HOST structs
  *     that hold device pointers.

@@ -170,6 +170,8 @@ int check_layer_args(const spiffy_model_cfg* cfg, const spiffy_layer_weights* w,
   for (const void* p : ptrs)
     if (p && !aligned16(p)) return SPIFFY_EALIGN;
   if (!layer_mfma(cfg) && generic_attn_smem(cfg, B, prefix->P + prefix->S) > kMaxGenericSmem) return SPIFFY_ESHAPE;
+  // the reduction behind the split-K projections keeps a row of d fp32 values in 64 KB of LDS for its RMSNorm
+  if (layer_mfma(cfg) && (size_t)cfg->d * sizeof(float) > 64 * 1024) return SPIFFY_ESHAPE;
   return SPIFFY_OK;
 }
 

@@ -747,7 +747,9 @@ hipError_t launch_gemm_mfma(int epi, const GemmArgs& a0, hipStream_t st) {
 hipError_t launch_splitk_reduce(const float* P, int ksplit, const void* R, void* out, const void* gain, float eps,
                                 void* normed, int M, int N, hipStream_t st, const int32_t* n_rows_dev,
                                 const int32_t* out_rows) {
-  const int threads = (N >= 4096 && M <= 512) ? 1024 : 256;
+  // 1024 threads per row with few rows, while the row and its (chunk, lane) sums fit the 64 KB a launch gets by default
+  const bool wide_fits = sizeof(float) * ((size_t)N + 64 * ((N + 255) / 256)) <= 64 * 1024;
+  const int threads = (N >= 4096 && M <= 512 && (!normed || wide_fits)) ? 1024 : 256;
   if (normed)
     splitk_reduce_kernel<true><<<M, threads, sizeof(float) * ((size_t)N + (threads > 256 ? 64 * ((N + 255) / 256) : 0)), st>>>(P, ksplit, (const bf16_t*)R, (bf16_t*)out,
                                                                        (const bf16_t*)gain, eps, (bf16_t*)normed, M, N,

@@ -444,3 +444,20 @@ def test_gemm_plan_errors():
     assert sp.lib.spiffy_gemm_plan(sp.GEMM_STORE, 0, 128, 128, 1, C.byref(p)) == sp.SPIFFY_ESHAPE
     assert sp.lib.spiffy_gemm_plan(7, 64, 128, 128, 1, C.byref(p)) == sp.SPIFFY_EINVAL
     assert sp.lib.spiffy_gemm_plan(sp.GEMM_STORE, 64, 128, 128, 1, None) == sp.SPIFFY_EINVAL
+
+
+def test_layer_width_limit_is_a_host_check():
+    """A bf16 model wider than 16384 would need more than 64 KB of on-chip memory per row in the reduction behind the
+    split-K projections: refused on the host, nothing is launched."""
+    cfg = sp.ModelCfg()
+    cfg.d, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.ffn, cfg.vocab = 16512, 129, 129, 128, 4096, 1000
+    cfg.dtype, cfg.rms_eps, cfg.rope_base, cfg.mask_id = sp.SPIFFY_BF16, 1e-5, 10000.0, 999
+    w = sp.LayerWeights()
+    for f in ("wq", "wk", "wv", "wo", "w_gate", "w_up", "w_down", "norm1", "norm2"):
+        setattr(w, f, DUMMY)
+    pf = sp.PrefixKV()
+    assert sp.lib.spiffy_verify_layer(C.byref(cfg), C.byref(w), C.byref(pf), DUMMY, 2, 32, 0, DUMMY, DUMMY, 1 << 40, None) \
+        == sp.SPIFFY_ESHAPE
+    cfg.d, cfg.n_q_heads, cfg.n_kv_heads = 16384, 128, 128
+    rc = sp.lib.spiffy_verify_layer(C.byref(cfg), C.byref(w), C.byref(pf), DUMMY, 2, 32, 0, DUMMY, DUMMY, 16, None)
+    assert rc == sp.SPIFFY_EWORKSPACE      # the shape itself is accepted; the call stops at the next host check

@@ -321,6 +321,7 @@ def main():
         else line["roofline"]["achieved"] / mp["mfma_bf16_random_operands_tflops"])
 
     if not args.step_only:
+        line["vendor_library_context"] = library_leg(sp, w, dev)
         line["next_step_drafting"] = drafting_leg(sp, cfg, plan, d_states, dev)
         line["decode_loop"] = decode_leg(sp, cfg, layers, prefix, hw, w_embed, dev)
         line["dual_cache_step"] = dual_cache_leg(sp, cfg, layers, prefix, hw, w_embed, d_states, d_edges, dev, seed)
@@ -346,6 +347,57 @@ def main():
         # and the vanilla pass (one state): every projection is a weight stream, the regime of the HBM roofline
         line["other_configs"]["c3_one_state"] = other_config_leg(sp, synth, "c3", dev, seed, 10, 2, 2, n_states=1)
     print(json.dumps(line))
+
+
+def library_leg(sp, w, dev):
+    """Context, not a target and not on the product path: the image's GEMM library (torch.matmul, bf16) on the
+    projection shapes of this workload, weights rotating over four layers, beside the same projections through
+    spiffy_gemm.  The library computes the bare products: no SwiGLU, no residual, no K-slice reduction."""
+    import torch
+    cfg, layers = w["cfg"], w["layers"][:4]
+    M, d, F, qd = cfg.G * cfg.B, cfg.d, cfg.F, cfg.Hq * cfg.hd
+    x = torch.randn((M, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    xa = torch.randn((M, qd), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    xf = torch.randn((M, F), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    r = torch.randn((M, d), device=dev, dtype=torch.float32).to(torch.bfloat16)
+    ws = torch.empty(4 * M * d * 4 + 256, dtype=torch.uint8, device=dev)
+    wqkv = [torch.cat([lw["wq"], lw["wk"], lw["wv"]]) for lw in layers]
+    wgu = [torch.cat([lw["w_gate"], lw["w_up"]]) for lw in layers]
+    o_qkv = torch.empty((M, wqkv[0].shape[0]), device=dev, dtype=torch.bfloat16)
+    o_gu = torch.empty((M, 2 * F), device=dev, dtype=torch.bfloat16)
+    o_d = torch.empty((M, d), device=dev, dtype=torch.bfloat16)
+    o_f = torch.empty((M, F), device=dev, dtype=torch.bfloat16)
+    pairs = {
+        "qkv": (lambda i: torch.matmul(x, wqkv[i].t(), out=o_qkv), lambda i: sp.gemm(sp.GEMM_STORE, x, wqkv[i], out=o_qkv)),
+        "output_projection": (lambda i: torch.matmul(xa, layers[i]["wo"].t(), out=o_d),
+                              lambda i: sp.gemm(sp.GEMM_RESID, xa, layers[i]["wo"], R=r, out=o_d, workspace=ws)),
+        "gate_up": (lambda i: torch.matmul(x, wgu[i].t(), out=o_gu),
+                    lambda i: sp.gemm(sp.GEMM_SWIGLU, x, layers[i]["w_gate"], layers[i]["w_up"], out=o_f)),
+        "down_projection": (lambda i: torch.matmul(xf, layers[i]["w_down"].t(), out=o_d),
+                            lambda i: sp.gemm(sp.GEMM_RESID, xf, layers[i]["w_down"], R=r, out=o_d, workspace=ws)),
+    }
+
+    def timed(fn):
+        for i in range(len(layers)):
+            fn(i)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(4):
+            for i in range(len(layers)):
+                fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (4 * len(layers))
+
+    out = {}
+    for rd in range(2):                 # interleaved: the second pass is the one reported (clocks settled)
+        for name, (lib_fn, own_fn) in pairs.items():
+            out[name] = {"library_us": timed(lib_fn), "spiffy_gemm_us": timed(own_fn)}
+    out["note"] = ("torch.matmul (the image's GEMM library) against spiffy_gemm on the same shapes and weights; the library "
+                   "computes the bare product, spiffy_gemm includes the SwiGLU epilogue or the residual and the reduction "
+                   "of its K slices")
+    return out
 
 
 def peaks_leg(sp_unused, dev):

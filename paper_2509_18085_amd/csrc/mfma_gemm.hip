@@ -682,23 +682,34 @@ GemmPlan plan_gemm_mfma(int epi, int M, int N, int ksplit) {
       const TileShape t = choose_tile(M, N, 2, 1, true, false, true, false, &whole);   // a tile of width w holds w/2 features
       one(t, 2);
       // Two-part column schedule, for widths whose best single shape leaves the last round of workgroups mostly empty
-      // (18944 features over 768 rows: 888 tiles of 256 x 128 = 3.47 rounds, and 96 does not divide the width): 256 x 192
-      // tiles over as many leading features as fill whole rounds, then the best shape for the rest, as a second launch
-      // on the same stream.  Same K order in every shape, so the output bits are those of the single launch; measured
-      // 207.8 -> 190.5 us on that projection (170 column tiles of 96 features, then 246 tiles of 128 x 128).
-      const int mt = cdiv(M, 256);
-      const int rounds = (int)(((long long)mt * (N / 96)) / 256);
-      if (rounds >= 1) {
-        const int main_tiles = (256 * rounds) / mt;                    // column tiles of 96 features in the first part
-        const int rest = N - 96 * main_tiles;                            // features left; a multiple of 32 as N is
+      // (18944 features over 768 rows: 888 tiles of 256 x 128 = 3.47 rounds, and 96 does not divide the width; over 128
+      // rows: 296 tiles of 128 x 128, 1.16 rounds): one shape over as many leading features as fill whole rounds of the
+      // 256 CUs - 256 x 192 tiles, or the best single shape - then the best shape for the rest, as a second launch on
+      // the same stream.  Same K order in every shape, so the output bits are those of the single launch; measured
+      // 207.8 -> 190.5 us at 768 rows (170 column tiles of 256 x 192, then 246 tiles of 128 x 128) and 83.9 -> 69.7 us
+      // at 128 rows (256 tiles of 128 x 128, then 160 of 64 x 64).
+      float best = 0.9f * whole;          // a second launch has to promise at least a tenth
+      auto try_main = [&](TileShape tm) {
+        int wi = 0;
+        while (wi < 5 && kTileWidths[wi] != tm.bn) ++wi;
+        if (wi == 5) return;
+        const int per = tm.bn / 2, mt = cdiv(M, tm.bm);               // features per tile, row tiles
+        const int rounds = (int)(((long long)mt * (N / per)) / 256);
+        if (rounds < 1) return;
+        const int main_tiles = (256 * rounds) / mt;                    // column tiles of the first part
+        const int rest = N - per * main_tiles;                         // features left; a multiple of 32 as N is
+        if (rest <= 0) return;
         float rest_cost = 0.f;
-        const TileShape tr = rest > 0 ? choose_tile(M, rest, 2, 1, true, false, true, false, &rest_cost) : TileShape{0, 0};
-        if (rest > 0 && tr.bn != 0 && (float)rounds * tile_cost(256, 0) + rest_cost <= 0.9f * whole) {
-          p.n_parts = 2;
-          p.part[0] = {256, 192, 0, 96 * main_tiles, mt * main_tiles};
-          p.part[1] = {tr.bm, tr.bn, 96 * main_tiles, rest, cdiv(M, tr.bm) * (rest / (tr.bn / 2))};
-        }
-      }
+        const TileShape tr = choose_tile(M, rest, 2, 1, true, false, true, false, &rest_cost);
+        const float cost = (float)rounds * tile_cost(tm.bm, wi) + rest_cost;
+        if (tr.bn == 0 || cost > best) return;
+        best = cost;
+        p.n_parts = 2;
+        p.part[0] = {tm.bm, tm.bn, 0, per * main_tiles, mt * main_tiles};
+        p.part[1] = {tr.bm, tr.bn, per * main_tiles, rest, cdiv(M, tr.bm) * (rest / (tr.bn / 2))};
+      };
+      try_main(TileShape{256, 192});
+      if (t.bn != 0 && !(t.bm == 256 && t.bn == 192)) try_main(t);
       break;
     }
     case EPI_LMHEAD:      // vocabulary rows x token columns; the token tiles in use are only known on the device

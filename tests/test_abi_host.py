@@ -428,6 +428,9 @@ def test_gemm_plans_of_the_benchmark_shapes():
     assert sp.gemm_plan(sp.GEMM_SWIGLU, 768, 18944, 3584)["launches"] == [
         {"tile": (256, 192), "col0": 0, "n_cols": 16320, "workgroups": 510},
         {"tile": (128, 128), "col0": 16320, "n_cols": 2624, "workgroups": 246}]
+    assert sp.gemm_plan(sp.GEMM_SWIGLU, 128, 18944, 3584)["launches"] == [        # four states of the same model
+        {"tile": (128, 128), "col0": 0, "n_cols": 16384, "workgroups": 256},
+        {"tile": (64, 64), "col0": 16384, "n_cols": 2560, "workgroups": 160}]
     assert sp.gemm_plan(sp.GEMM_RESID, 768, 3584, 18944) == {
         "k_slices": 3, "launches": [{"tile": (256, 128), "col0": 0, "n_cols": 3584, "workgroups": 252}]}
     assert sp.gemm_plan(sp.GEMM_RESID, 1024, 4096, 12288)["k_slices"] == 2
